@@ -1,0 +1,239 @@
+/*
+ * cqa -- certified quantized decode attention for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Everything here is plain C: opaque handle, plain
+ * pointers and sizes.  "dev" pointers are HIP device memory, "host" pointers are
+ * ordinary host memory; streams are hipStream_t passed as void* (NULL = the
+ * default stream).  Every call returns a status (CQA_OK = 0, negative = error);
+ * no C++ exception crosses this boundary.  The library never returns an
+ * uncertified output silently: when a fallback is required and the FP16
+ * originals or the staging buffer are unavailable, the call fails with
+ * CQA_ERR_NO_TIER2 / CQA_ERR_OOM_* and leaves the outputs of the affected heads
+ * untouched (the paper's precondition P4 and its contract).
+ *
+ * Fixed geometry (the paper's defaults): head_dim d = 128, block B = 16 tokens,
+ * value group g = 16 channels.  Other values are rejected with
+ * CQA_ERR_UNSUPPORTED.
+ *
+ * Ownership: the handle owns Tier-1 (packed INT8 keys / INT4 values and their
+ * metadata, in HBM), Tier-2 (FP16 originals in pinned host memory), the trailing
+ * FP16 partial blocks, the split workspace, the fallback staging buffer and one
+ * side stream with its events.  The caller owns q, O, cert, flags, blk_logmass
+ * and the main stream.  All kernels are enqueued on the caller's stream; only
+ * cqa_decode_step and cqa_dense_fallback (when it has to read device-resident
+ * head selectors) may block the host.
+ */
+#ifndef CQA_H
+#define CQA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CQA_VERSION 100
+
+enum {
+  CQA_OK = 0,
+  CQA_ERR_INVALID_ARG = -1,
+  CQA_ERR_OOM_DEVICE = -2,
+  CQA_ERR_OOM_PINNED = -3,
+  CQA_ERR_NO_TIER2 = -4,
+  CQA_ERR_CAPACITY = -5,
+  CQA_ERR_HIP = -6,
+  CQA_ERR_UNSUPPORTED = -7
+};
+
+/* Where the FP16 originals live (the paper's Tier 2). */
+enum {
+  CQA_TIER2_PINNED = 0, /* library-owned pinned host memory (hipHostMalloc)      */
+  CQA_TIER2_NONE = 1    /* not retained: any call that needs a fallback fails   */
+};
+
+/* Flag word written per (batch, query head) by cqa_certified_decode.
+ * Bits 0-4 request more precision; bits 8-10 record the rung that served the
+ * head (0 = fast path, 3 = per-head dense recompute, 4 = whole-layer recompute). */
+#define CQA_FLAG_KEY 0x01u     /* E_key > eps_key                                */
+#define CQA_FLAG_VAL 0x02u     /* E_val > eps_val or max_b rho_b eta_b > v_tol   */
+#define CQA_FLAG_RANK 0x04u    /* top-1 block not certified by the interval test */
+#define CQA_FLAG_PRECOND 0x08u /* a non-finite certificate quantity              */
+#define CQA_FLAG_TOTAL 0x10u   /* E_key + E_val > eps_total                      */
+#define CQA_FLAG_ANY 0x1Fu
+#define CQA_RUNG_SHIFT 8
+
+typedef struct cqa_cache cqa_cache;
+
+typedef struct cqa_cache_desc {
+  int32_t n_layers;
+  int32_t batch;        /* Bt sequences, all of the same length                 */
+  int32_t n_q_heads;    /* Hq, a multiple of n_kv_heads; Hq / Hkv in {1,2,4}     */
+  int32_t n_kv_heads;   /* Hkv                                                  */
+  int32_t head_dim;     /* must be 128                                          */
+  int32_t block_tokens; /* must be 16                                           */
+  int32_t v_group;      /* must be 16                                           */
+  int32_t tier2_mode;   /* CQA_TIER2_*                                          */
+  int64_t max_tokens;   /* capacity per sequence                                */
+} cqa_cache_desc;
+
+/* Thresholds of the runtime certificate policy (the paper's policy table).
+ * +inf disables a threshold; comparisons are strict (>). */
+typedef struct cqa_tolerances {
+  float eps_total;          /* on E_key + E_val                                  */
+  float eps_key;            /* on E_key                                          */
+  float eps_val;            /* on E_val                                          */
+  float v_tol;              /* on max_b rho_b eta_b (per-block value test)       */
+  float rank_min_mass;      /* ranking test only if the top block holds >= this  */
+  float eps_guard;          /* additive slack of the ranking test                */
+  int32_t rank_depth;       /* r: 0 = ranking test off, 1 = top-1 block          */
+  int32_t mass_exp;         /* c in e^{c Delta}: 2 (theorems) or 3 (paper impl.)  */
+  int32_t key_bound_mode;   /* 0 min(tanh, tail), 1 tail form only, 2 tanh only  */
+  int32_t rung4_min_groups; /* >0: that many flagged KV groups => Rung 4         */
+  uint32_t force_flags;     /* OR-ed into every head's flag word (test hook)     */
+} cqa_tolerances;
+
+/* Per-(batch, query head) certificate of one decode step.  40 bytes. */
+typedef struct cqa_head_cert {
+  float E_key;             /* 2 V_max * TV bound (key-quantization term)         */
+  float E_val;             /* sum_b rho_b eta_b (value-reconstruction term)      */
+  float delta_h;           /* max_b Delta_b over sealed blocks                   */
+  float v_max;             /* max value norm over all attended tokens            */
+  float alpha_tail_hat;    /* INT8-estimated mass on INT8-keyed tokens           */
+  float lse;               /* log sum_t exp(s'_t)                                */
+  float max_block_contrib; /* max_b rho_b eta_b                                  */
+  float rank_margin;       /* l_(1) - l_(2) of the block log-masses (+inf if <2) */
+  int32_t top_block;       /* argmax_b l_b (-1 if no sealed block)               */
+  int32_t served_rung;     /* 0, 3 or 4                                          */
+} cqa_head_cert;
+
+/* ---- cache lifetime ------------------------------------------------------ */
+
+/* Allocates every buffer up front on the current HIP device (the paper's
+ * "allocated at load, never released"): Tier-1, Tier-2 (unless NONE), trailing
+ * blocks, split workspace, staging for one layer.  *out is set only on success.
+ * Errors: INVALID_ARG, UNSUPPORTED (geometry), OOM_DEVICE, OOM_PINNED, HIP. */
+int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out);
+int32_t cqa_cache_destroy(cqa_cache* c);
+
+/* Bytes the create call allocates: *device_bytes in HBM, *pinned_bytes in pinned
+ * host memory.  Either pointer may be NULL. */
+int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
+                            int64_t* pinned_bytes);
+
+/* ---- cache write: the paper's quantize-at-block-fill path ---------------- */
+
+/* Appends n_new tokens to every (batch, kv-head) sequence of `layer`.
+ * k_fp16_dev, v_fp16_dev: device, FP16, layout [batch][n_kv_heads][n_new][128]
+ * (post-RoPE keys).  New tokens join the trailing FP16 partial block; every
+ * block that reaches 16 tokens is sealed: per-channel INT8 keys with FP32
+ * (sigma, z) per block, per-token per-16-channel-group INT4 values with FP16
+ * (scale, offset), and the block annotations eta_b, nu_b.  Sealed blocks are
+ * immutable.  The FP16 originals are copied to Tier-2 (pinned host) on the same
+ * stream unless tier2_mode is NONE.  Asynchronous on `stream`; the inputs must
+ * stay valid until the stream has passed this call.
+ * Errors: INVALID_ARG, CAPACITY (length + n_new > max_tokens), HIP. */
+int32_t cqa_cache_append(cqa_cache* c, int32_t layer, const void* k_fp16_dev,
+                         const void* v_fp16_dev, int64_t n_new, void* stream);
+
+/* Tokens currently held per sequence of `layer` (host-side counter). */
+int32_t cqa_cache_length(const cqa_cache* c, int32_t layer, int64_t* n_tokens);
+
+/* Drops every token of `layer` (host counter only; buffers are reused). */
+int32_t cqa_cache_reset(cqa_cache* c, int32_t layer);
+
+/* Canonical logical view of one sealed block, independent of the physical
+ * packing, written to HOST buffers (synchronises the device):
+ *   kcodes[16*128] int8 [token][channel]; sigma[128], z[128] float;
+ *   vcodes[16*128] uint8 in 0..15 [token][channel];
+ *   vscale_bits[16*8], voffset_bits[16*8] raw FP16 bits [token][group];
+ *   *eta, *nu the block annotations.
+ * Errors: INVALID_ARG (indices out of range or block not sealed), HIP. */
+int32_t cqa_cache_export_block(const cqa_cache* c, int32_t layer, int32_t batch,
+                               int32_t kv_head, int64_t block, int8_t* kcodes, float* sigma,
+                               float* z, uint8_t* vcodes, uint16_t* vscale_bits,
+                               uint16_t* voffset_bits, float* eta, float* nu);
+
+/* ---- decode: the paper's fused certified attention + certificate --------- */
+
+/* One decode step of `layer` on the quantized cache, for all (batch, q-head):
+ * split-K pass over Tier-1 (scaled-query scoring identity, block statistics
+ * m_b, S_b, l_b, FP32 online softmax, in-register INT8/INT4 dequantization,
+ * both bound terms accumulated in the same pass; the trailing FP16 tokens are
+ * attended exactly) followed by the cross-split reduction that finalises
+ *   O_dev     float [batch][n_q_heads][128]      (O_quant for EVERY head),
+ *   cert_dev  cqa_head_cert [batch][n_q_heads]   (served_rung = 0),
+ *   flags_dev uint32 [batch][n_q_heads]          (bits 0-4 only),
+ *   blk_logmass_dev float [batch][n_q_heads][n_sealed_blocks], may be NULL.
+ * q_fp16_dev: device FP16 [batch][n_q_heads][128].  tol: host pointer, copied.
+ * Flags only REQUEST a fallback; see cqa_dense_fallback / cqa_decode_step.
+ * Asynchronous on `stream`.  Calls on the same handle must not overlap (they
+ * share the split workspace).  Errors: INVALID_ARG (incl. an empty cache), HIP. */
+int32_t cqa_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                             const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                             uint32_t* flags_dev, float* blk_logmass_dev, void* stream);
+
+/* The paper's Rung 3 / Rung 4 body: recomputes dense FP16 attention (FP32
+ * accumulation) from the Tier-2 originals for the selected heads and overwrites
+ * their rows of O_dev; their certificates become E_key = E_val = 0 with
+ * served_rung = rung, and bits 8-10 of their flag words are set to `rung`.
+ * head_select_host: uint32 [batch][n_q_heads] on the HOST, nonzero = recompute;
+ * ignored (may be NULL) if all_heads != 0.  Originals are paged per (batch,
+ * kv-head) with pinned hipMemcpyAsync on the library's side stream into the
+ * staging buffer, double-buffered against the dense kernel, which runs on
+ * `stream` after an event join.  cert_dev / flags_dev may be NULL.
+ * Errors: NO_TIER2 (tier2_mode NONE; outputs untouched), INVALID_ARG, HIP. */
+int32_t cqa_dense_fallback(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                           const uint32_t* head_select_host, int32_t all_heads, int32_t rung,
+                           float* O_dev, cqa_head_cert* cert_dev, uint32_t* flags_dev,
+                           void* stream);
+
+/* certified_decode, then the ladder: reads the flag words back (one D2H copy
+ * and a stream synchronise), serves flagged heads by Rung 3, or the whole layer
+ * by Rung 4 when any head has PRECOND set or when rung4_min_groups > 0 and at
+ * least that many (batch, kv-head) groups hold a flagged head.  On return O_dev
+ * is final.  *rung_served (host, may be NULL) receives 0, 3 or 4.
+ * Errors: as the two calls above. */
+int32_t cqa_decode_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                        const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                        uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
+                        void* stream);
+
+/* Dense FP16 decode attention on device-resident K, V (the same kernel the
+ * fallback runs after paging): softmax(q K^T / sqrt(128)) V with FP32
+ * accumulation.  q [batch][n_q_heads][128] FP16; k, v [batch][n_kv_heads]
+ * [n_tokens][128] FP16; O float [batch][n_q_heads][128].  `workspace_dev` must
+ * hold cqa_dense_workspace_bytes(batch, n_q_heads, n_tokens) bytes.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+int32_t cqa_dense_attention(const void* q_fp16_dev, const void* k_fp16_dev,
+                            const void* v_fp16_dev, int32_t batch, int32_t n_q_heads,
+                            int32_t n_kv_heads, int64_t n_tokens, float* O_dev,
+                            void* workspace_dev, void* stream);
+int64_t cqa_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int64_t n_tokens);
+
+/* ---- measurement and misc ------------------------------------------------ */
+
+/* Launches cqa_certified_decode `iters` times back to back on `stream`,
+ * bracketed by HIP events recorded on that same stream, synchronises, and
+ * returns the mean duration of one step in milliseconds in *ms_per_step
+ * (host).  For benchmarks; the outputs hold the last iteration's results. */
+int32_t cqa_time_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                                  const cqa_tolerances* tol, float* O_dev,
+                                  cqa_head_cert* cert_dev, uint32_t* flags_dev,
+                                  float* blk_logmass_dev, int32_t iters, float* ms_per_step,
+                                  void* stream);
+
+/* Split count the decode pass uses for the current length of `layer`
+ * (for reporting; chosen from the device's compute-unit count). */
+int32_t cqa_decode_splits(const cqa_cache* c, int32_t layer, int32_t* n_splits);
+/* Overrides the automatic split count (0 restores it).  For tests. */
+int32_t cqa_set_splits(cqa_cache* c, int32_t n_splits);
+
+const char* cqa_strerror(int32_t status);
+int32_t cqa_version(void);
+/* hipError_t of the last failing HIP call on this thread (0 if none). */
+int32_t cqa_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CQA_H */

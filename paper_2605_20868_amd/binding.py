@@ -1,0 +1,254 @@
+"""Thin ctypes binding of libcqa.so: argument marshalling only.
+
+Function names mirror the C ABI in include/cqa.h.  Pointers are accepted as
+Python ints, ctypes pointers or any object with a `data_ptr()` method (e.g. a
+torch tensor used purely as device memory).  Every computation runs in the HIP
+library; there is no CPU fallback: if the library is missing or fails to load,
+importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcqa.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_OOM_DEVICE = -2
+ERR_OOM_PINNED = -3
+ERR_NO_TIER2 = -4
+ERR_CAPACITY = -5
+ERR_HIP = -6
+ERR_UNSUPPORTED = -7
+
+TIER2_PINNED = 0
+TIER2_NONE = 1
+
+FLAG_KEY = 0x01
+FLAG_VAL = 0x02
+FLAG_RANK = 0x04
+FLAG_PRECOND = 0x08
+FLAG_TOTAL = 0x10
+FLAG_ANY = 0x1F
+RUNG_SHIFT = 8
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_tokens", C.c_int32),
+                ("v_group", C.c_int32), ("tier2_mode", C.c_int32), ("max_tokens", C.c_int64)]
+
+
+class Tolerances(C.Structure):
+    _fields_ = [("eps_total", C.c_float), ("eps_key", C.c_float), ("eps_val", C.c_float),
+                ("v_tol", C.c_float), ("rank_min_mass", C.c_float), ("eps_guard", C.c_float),
+                ("rank_depth", C.c_int32), ("mass_exp", C.c_int32), ("key_bound_mode", C.c_int32),
+                ("rung4_min_groups", C.c_int32), ("force_flags", C.c_uint32)]
+
+    def __init__(self, eps_total=math.inf, eps_key=math.inf, eps_val=math.inf, v_tol=math.inf,
+                 rank_min_mass=0.0, eps_guard=1e-6, rank_depth=0, mass_exp=2, key_bound_mode=0,
+                 rung4_min_groups=0, force_flags=0):
+        super().__init__(eps_total, eps_key, eps_val, v_tol, rank_min_mass, eps_guard, rank_depth,
+                         mass_exp, key_bound_mode, rung4_min_groups, force_flags)
+
+
+class HeadCert(C.Structure):
+    _fields_ = [("E_key", C.c_float), ("E_val", C.c_float), ("delta_h", C.c_float),
+                ("v_max", C.c_float), ("alpha_tail_hat", C.c_float), ("lse", C.c_float),
+                ("max_block_contrib", C.c_float), ("rank_margin", C.c_float),
+                ("top_block", C.c_int32), ("served_rung", C.c_int32)]
+
+
+CERT_BYTES = C.sizeof(HeadCert)
+# numpy structured dtype with the same layout, for reading certificates back
+CERT_FIELDS = [("E_key", "<f4"), ("E_val", "<f4"), ("delta_h", "<f4"), ("v_max", "<f4"),
+               ("alpha_tail_hat", "<f4"), ("lse", "<f4"), ("max_block_contrib", "<f4"),
+               ("rank_margin", "<f4"), ("top_block", "<i4"), ("served_rung", "<i4")]
+
+
+class CqaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.cqa_strerror(status).decode() if _lib is not None else "?"
+        hip = _lib.cqa_last_hip_error() if _lib is not None and status == ERR_HIP else 0
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hipError {hip})" if hip else ")"))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_20868_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    sig = {
+        "cqa_cache_create": (i32, [C.POINTER(CacheDesc), C.POINTER(vp)]),
+        "cqa_cache_destroy": (i32, [vp]),
+        "cqa_workspace_bytes": (i32, [C.POINTER(CacheDesc), C.POINTER(i64), C.POINTER(i64)]),
+        "cqa_cache_append": (i32, [vp, i32, vp, vp, i64, vp]),
+        "cqa_cache_length": (i32, [vp, i32, C.POINTER(i64)]),
+        "cqa_cache_reset": (i32, [vp, i32]),
+        "cqa_cache_export_block": (i32, [vp, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "cqa_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp, vp]),
+        "cqa_dense_fallback": (i32, [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "cqa_decode_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
+                                  C.POINTER(i32), vp]),
+        "cqa_dense_attention": (i32, [vp, vp, vp, i32, i32, i32, i64, vp, vp, vp]),
+        "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
+        "cqa_time_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
+                                            i32, C.POINTER(C.c_float), vp]),
+        "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
+        "cqa_set_splits": (i32, [vp, i32]),
+        "cqa_strerror": (C.c_char_p, [i32]),
+        "cqa_version": (i32, []),
+        "cqa_last_hip_error": (i32, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)      # raises AttributeError if the symbol is not exported
+        fn.restype = res
+        fn.argtypes = args
+    return lib, sorted(sig)
+
+
+_lib = None
+_lib, EXPORTED = _load()
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return C.c_void_p(x)
+    if hasattr(x, "data_ptr"):
+        return C.c_void_p(x.data_ptr())
+    if hasattr(x, "ctypes"):
+        return C.c_void_p(x.ctypes.data)
+    return x
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise CqaError(status, where)
+
+
+def cqa_version() -> int:
+    return _lib.cqa_version()
+
+
+def cqa_strerror(status: int) -> str:
+    return _lib.cqa_strerror(status).decode()
+
+
+def cqa_last_hip_error() -> int:
+    return _lib.cqa_last_hip_error()
+
+
+def cqa_workspace_bytes(desc: CacheDesc):
+    dev, pin = C.c_int64(0), C.c_int64(0)
+    _check(_lib.cqa_workspace_bytes(C.byref(desc), C.byref(dev), C.byref(pin)), "cqa_workspace_bytes")
+    return dev.value, pin.value
+
+
+def cqa_cache_create(n_layers, batch, n_q_heads, n_kv_heads, max_tokens, tier2_mode=TIER2_PINNED,
+                     head_dim=128, block_tokens=16, v_group=16):
+    desc = CacheDesc(n_layers, batch, n_q_heads, n_kv_heads, head_dim, block_tokens, v_group,
+                     tier2_mode, max_tokens)
+    h = C.c_void_p(None)
+    _check(_lib.cqa_cache_create(C.byref(desc), C.byref(h)), "cqa_cache_create")
+    return h
+
+
+def cqa_cache_destroy(h) -> None:
+    _check(_lib.cqa_cache_destroy(h), "cqa_cache_destroy")
+
+
+def cqa_cache_append(h, layer, k_dev, v_dev, n_new, stream=None) -> None:
+    _check(_lib.cqa_cache_append(h, layer, _ptr(k_dev), _ptr(v_dev), n_new, _ptr(stream)),
+           "cqa_cache_append")
+
+
+def cqa_cache_length(h, layer) -> int:
+    n = C.c_int64(0)
+    _check(_lib.cqa_cache_length(h, layer, C.byref(n)), "cqa_cache_length")
+    return n.value
+
+
+def cqa_cache_reset(h, layer) -> None:
+    _check(_lib.cqa_cache_reset(h, layer), "cqa_cache_reset")
+
+
+def cqa_cache_export_block(h, layer, batch, kv_head, block):
+    """Returns numpy arrays (kcodes i8[16,128], sigma f32[128], z f32[128], vcodes u8[16,128],
+    vscale f16[16,8], voffset f16[16,8], eta f32, nu f32) -- the canonical logical view."""
+    import numpy as np
+    kc = np.empty((16, 128), np.int8)
+    sg = np.empty(128, np.float32)
+    z = np.empty(128, np.float32)
+    vc = np.empty((16, 128), np.uint8)
+    vs = np.empty((16, 8), np.uint16)
+    vo = np.empty((16, 8), np.uint16)
+    eta = C.c_float(0)
+    nu = C.c_float(0)
+    _check(_lib.cqa_cache_export_block(h, layer, batch, kv_head, block, _ptr(kc), _ptr(sg), _ptr(z),
+                                       _ptr(vc), _ptr(vs), _ptr(vo),
+                                       C.cast(C.byref(eta), C.c_void_p),
+                                       C.cast(C.byref(nu), C.c_void_p)), "cqa_cache_export_block")
+    import numpy as _np
+    return (kc, sg, z, vc, vs.view(_np.float16), vo.view(_np.float16),
+            _np.float32(eta.value), _np.float32(nu.value))
+
+
+def cqa_certified_decode(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                         blk_logmass_dev=None, stream=None) -> None:
+    _check(_lib.cqa_certified_decode(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev),
+                                     _ptr(cert_dev), _ptr(flags_dev), _ptr(blk_logmass_dev),
+                                     _ptr(stream)), "cqa_certified_decode")
+
+
+def cqa_dense_fallback(h, layer, q_dev, head_select_host, all_heads, rung, O_dev, cert_dev=None,
+                       flags_dev=None, stream=None) -> None:
+    _check(_lib.cqa_dense_fallback(h, layer, _ptr(q_dev), _ptr(head_select_host), int(all_heads),
+                                   rung, _ptr(O_dev), _ptr(cert_dev), _ptr(flags_dev),
+                                   _ptr(stream)), "cqa_dense_fallback")
+
+
+def cqa_decode_step(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                    blk_logmass_dev=None, stream=None) -> int:
+    rung = C.c_int32(0)
+    _check(_lib.cqa_decode_step(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev), _ptr(cert_dev),
+                                _ptr(flags_dev), _ptr(blk_logmass_dev), C.byref(rung),
+                                _ptr(stream)), "cqa_decode_step")
+    return rung.value
+
+
+def cqa_dense_workspace_bytes(batch, n_q_heads, n_tokens) -> int:
+    return _lib.cqa_dense_workspace_bytes(batch, n_q_heads, n_tokens)
+
+
+def cqa_dense_attention(q_dev, k_dev, v_dev, batch, n_q_heads, n_kv_heads, n_tokens, O_dev,
+                        workspace_dev, stream=None) -> None:
+    _check(_lib.cqa_dense_attention(_ptr(q_dev), _ptr(k_dev), _ptr(v_dev), batch, n_q_heads,
+                                    n_kv_heads, n_tokens, _ptr(O_dev), _ptr(workspace_dev),
+                                    _ptr(stream)), "cqa_dense_attention")
+
+
+def cqa_time_certified_decode(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                              blk_logmass_dev=None, iters=1, stream=None) -> float:
+    ms = C.c_float(0)
+    _check(_lib.cqa_time_certified_decode(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev),
+                                          _ptr(cert_dev), _ptr(flags_dev), _ptr(blk_logmass_dev),
+                                          iters, C.byref(ms), _ptr(stream)),
+           "cqa_time_certified_decode")
+    return ms.value
+
+
+def cqa_decode_splits(h, layer) -> int:
+    n = C.c_int32(0)
+    _check(_lib.cqa_decode_splits(h, layer, C.byref(n)), "cqa_decode_splits")
+    return n.value
+
+
+def cqa_set_splits(h, n_splits) -> None:
+    _check(_lib.cqa_set_splits(h, n_splits), "cqa_set_splits")

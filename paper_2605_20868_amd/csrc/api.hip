@@ -1,0 +1,485 @@
+// C ABI of the library: cache lifetime, append, decode, fallback ladder, export.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "cqa_internal.h"
+
+struct cqa_cache {
+  cqa::Cache impl;
+};
+
+namespace cqa {
+thread_local int g_last_hip_error = 0;
+
+static int32_t check_desc(const cqa_cache_desc* d) {
+  if (d == nullptr) return CQA_ERR_INVALID_ARG;
+  if (d->n_layers < 1 || d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 ||
+      d->max_tokens < 1)
+    return CQA_ERR_INVALID_ARG;
+  if (d->head_dim != D || d->block_tokens != BLK || d->v_group != VG) return CQA_ERR_UNSUPPORTED;
+  if (d->n_q_heads % d->n_kv_heads != 0) return CQA_ERR_INVALID_ARG;
+  const int g = d->n_q_heads / d->n_kv_heads;
+  if (g != 1 && g != 2 && g != 4) return CQA_ERR_UNSUPPORTED;
+  if (d->tier2_mode != CQA_TIER2_PINNED && d->tier2_mode != CQA_TIER2_NONE)
+    return CQA_ERR_INVALID_ARG;
+  if (d->batch > 65535 || d->n_kv_heads > 65535) return CQA_ERR_UNSUPPORTED;  // grid.y / grid.z
+  if (d->max_tokens > ((int64_t)1 << 30)) return CQA_ERR_UNSUPPORTED;
+  return CQA_OK;
+}
+
+struct Sizes {
+  int64_t nb_cap, heads, kc, km, vc, vm, an, trail, t2, partials, dense_ws, stage, select;
+  int max_splits;
+};
+
+static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
+  Sizes s;
+  s.nb_cap = (d->max_tokens + BLK - 1) / BLK;
+  s.heads = (int64_t)d->n_layers * d->batch * d->n_kv_heads;
+  s.kc = s.heads * s.nb_cap * KC_BYTES;
+  s.km = s.heads * s.nb_cap * KM_BYTES;
+  s.vc = s.heads * s.nb_cap * VC_BYTES;
+  s.vm = s.heads * s.nb_cap * VM_BYTES;
+  s.an = s.heads * s.nb_cap * AN_BYTES;
+  s.trail = s.heads * BLK * D * 2;
+  s.t2 = d->tier2_mode == CQA_TIER2_PINNED ? s.heads * d->max_tokens * D * 2 : 0;
+  int64_t ms = (4 * (int64_t)n_cu) / ((int64_t)d->batch * d->n_kv_heads);
+  if (ms < 64) ms = 64;
+  if (ms > s.nb_cap) ms = s.nb_cap;
+  if (ms < 1) ms = 1;
+  s.max_splits = (int)ms;
+  s.partials = (int64_t)d->batch * d->n_q_heads * s.max_splits * PART_FLOATS * 4;
+  s.dense_ws = dense_ws_floats(d->n_q_heads / d->n_kv_heads, d->max_tokens) * 4;
+  s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
+  s.select = (int64_t)d->batch * d->n_q_heads * 4;
+  return s;
+}
+
+static void release(cqa_cache* h) {
+  if (h == nullptr) return;
+  Cache* c = &h->impl;
+  (void)hipSetDevice(c->device);
+  (void)hipDeviceSynchronize();
+  (void)hipFree(c->kc);
+  (void)hipFree(c->km);
+  (void)hipFree(c->vc);
+  (void)hipFree(c->vm);
+  (void)hipFree(c->an);
+  (void)hipFree(c->trail_k);
+  (void)hipFree(c->trail_v);
+  (void)hipFree(c->partials);
+  (void)hipFree(c->dense_ws);
+  (void)hipFree(c->select_dev);
+  for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
+  if (c->t2_k) (void)hipHostFree(c->t2_k);
+  if (c->t2_v) (void)hipHostFree(c->t2_v);
+  if (c->flags_host) (void)hipHostFree(c->flags_host);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  for (int i = 0; i < 2; ++i) {
+    if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
+    if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+  }
+  if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+  if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
+  if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
+  delete[] c->length;
+  delete h;
+}
+
+#define CQA_ALLOC_DEV(ptr, bytes)                                         \
+  do {                                                                    \
+    hipError_t e__ = hipMalloc((void**)&(ptr), (size_t)((bytes) > 0 ? (bytes) : 16)); \
+    if (e__ != hipSuccess) {                                              \
+      g_last_hip_error = (int)e__;                                        \
+      (void)hipGetLastError();                                            \
+      release(h);                                                         \
+      return e__ == hipErrorOutOfMemory ? CQA_ERR_OOM_DEVICE : CQA_ERR_HIP; \
+    }                                                                     \
+  } while (0)
+
+#define CQA_ALLOC_PIN(ptr, bytes)                                         \
+  do {                                                                    \
+    hipError_t e__ = hipHostMalloc((void**)&(ptr), (size_t)(bytes), hipHostMallocDefault); \
+    if (e__ != hipSuccess) {                                              \
+      g_last_hip_error = (int)e__;                                        \
+      (void)hipGetLastError();                                            \
+      release(h);                                                         \
+      return CQA_ERR_OOM_PINNED;                                          \
+    }                                                                     \
+  } while (0)
+
+#define CQA_TRY(expr)                    \
+  do {                                   \
+    hipError_t e__ = (expr);             \
+    if (e__ != hipSuccess) {             \
+      g_last_hip_error = (int)e__;       \
+      release(h);                        \
+      return CQA_ERR_HIP;                \
+    }                                    \
+  } while (0)
+
+}  // namespace cqa
+
+using namespace cqa;
+
+extern "C" {
+
+int32_t cqa_version(void) { return CQA_VERSION; }
+
+int32_t cqa_last_hip_error(void) { return g_last_hip_error; }
+
+const char* cqa_strerror(int32_t status) {
+  switch (status) {
+    case CQA_OK: return "ok";
+    case CQA_ERR_INVALID_ARG: return "invalid argument";
+    case CQA_ERR_OOM_DEVICE: return "out of device memory";
+    case CQA_ERR_OOM_PINNED: return "out of pinned host memory";
+    case CQA_ERR_NO_TIER2: return "FP16 originals (Tier 2) unavailable: cannot fall back";
+    case CQA_ERR_CAPACITY: return "cache capacity exceeded";
+    case CQA_ERR_HIP: return "HIP runtime error (see cqa_last_hip_error)";
+    case CQA_ERR_UNSUPPORTED: return "unsupported geometry";
+    default: return "unknown status";
+  }
+}
+
+int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
+                            int64_t* pinned_bytes) {
+  const int32_t st = check_desc(desc);
+  if (st != CQA_OK) return st;
+  const Sizes s = compute_sizes(desc, 256);
+  if (device_bytes)
+    *device_bytes = s.kc + s.km + s.vc + s.vm + s.an + 2 * s.trail + s.partials +
+                    2 * s.dense_ws + 4 * s.stage + s.select;
+  if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
+  return CQA_OK;
+}
+
+int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
+  if (out == nullptr) return CQA_ERR_INVALID_ARG;
+  const int32_t st = check_desc(desc);
+  if (st != CQA_OK) return st;
+  cqa_cache* h = new (std::nothrow) cqa_cache;
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  memset(c, 0, sizeof(Cache));
+  c->desc = *desc;
+  c->length = new (std::nothrow) int64_t[desc->n_layers];
+  if (c->length == nullptr) {
+    delete h;
+    return CQA_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < desc->n_layers; ++i) c->length[i] = 0;
+  // from here on release() frees whatever has been set, and the handle itself
+  CQA_TRY(hipGetDevice(&c->device));
+  CQA_TRY(hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device));
+  if (c->n_cu < 1) c->n_cu = 256;
+  const Sizes s = compute_sizes(desc, c->n_cu);
+  c->nb_cap = s.nb_cap;
+  c->heads_total = s.heads;
+  c->max_splits = s.max_splits;
+  CQA_ALLOC_DEV(c->kc, s.kc);
+  CQA_ALLOC_DEV(c->km, s.km);
+  CQA_ALLOC_DEV(c->vc, s.vc);
+  CQA_ALLOC_DEV(c->vm, s.vm);
+  CQA_ALLOC_DEV(c->an, s.an);
+  CQA_ALLOC_DEV(c->trail_k, s.trail);
+  CQA_ALLOC_DEV(c->trail_v, s.trail);
+  CQA_ALLOC_DEV(c->partials, s.partials);
+  CQA_ALLOC_DEV(c->dense_ws, 2 * s.dense_ws);
+  CQA_ALLOC_DEV(c->select_dev, s.select);
+  CQA_ALLOC_PIN(c->flags_host, s.select);
+  if (desc->tier2_mode == CQA_TIER2_PINNED) {
+    for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < 2; ++j) CQA_ALLOC_DEV(c->stage[i][j], s.stage);
+    CQA_ALLOC_PIN(c->t2_k, s.t2);
+    CQA_ALLOC_PIN(c->t2_v, s.t2);
+  }
+  CQA_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  for (int i = 0; i < 2; ++i) {
+    CQA_TRY(hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
+    CQA_TRY(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
+  }
+  CQA_TRY(hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+  CQA_TRY(hipEventCreate(&c->ev_t0));
+  CQA_TRY(hipEventCreate(&c->ev_t1));
+  *out = h;
+  return CQA_OK;
+}
+
+int32_t cqa_cache_destroy(cqa_cache* h) {
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  release(h);
+  return CQA_OK;
+}
+
+int32_t cqa_cache_length(const cqa_cache* h, int32_t layer, int64_t* n_tokens) {
+  if (h == nullptr || n_tokens == nullptr || layer < 0 || layer >= h->impl.desc.n_layers)
+    return CQA_ERR_INVALID_ARG;
+  *n_tokens = h->impl.length[layer];
+  return CQA_OK;
+}
+
+int32_t cqa_cache_reset(cqa_cache* h, int32_t layer) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers) return CQA_ERR_INVALID_ARG;
+  h->impl.length[layer] = 0;
+  return CQA_OK;
+}
+
+int32_t cqa_set_splits(cqa_cache* h, int32_t n_splits) {
+  if (h == nullptr || n_splits < 0) return CQA_ERR_INVALID_ARG;
+  h->impl.forced_splits = n_splits;
+  return CQA_OK;
+}
+
+int32_t cqa_decode_splits(const cqa_cache* h, int32_t layer, int32_t* n_splits) {
+  if (h == nullptr || n_splits == nullptr || layer < 0 || layer >= h->impl.desc.n_layers)
+    return CQA_ERR_INVALID_ARG;
+  *n_splits = pick_splits(&h->impl, h->impl.length[layer] / BLK);
+  return CQA_OK;
+}
+
+int32_t cqa_cache_append(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
+                         const void* v_fp16_dev, int64_t n_new, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || k_fp16_dev == nullptr ||
+      v_fp16_dev == nullptr || n_new < 0)
+    return CQA_ERR_INVALID_ARG;
+  if (n_new == 0) return CQA_OK;
+  Cache* c = &h->impl;
+  const int64_t len = c->length[layer];
+  if (len + n_new > c->desc.max_tokens) return CQA_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  const __half* k = (const __half*)k_fp16_dev;
+  const __half* v = (const __half*)v_fp16_dev;
+  if (c->desc.tier2_mode == CQA_TIER2_PINNED) {
+    // one strided copy per tensor: row = one (batch, kv-head) sequence
+    const int64_t head0 = head_index(c, layer, 0, 0);
+    const size_t rows = (size_t)c->desc.batch * c->desc.n_kv_heads;
+    const size_t width = (size_t)n_new * D * 2;
+    const size_t dpitch = (size_t)c->desc.max_tokens * D * 2;
+    CQA_HIP(hipMemcpy2DAsync(c->t2_k + (head0 * c->desc.max_tokens + len) * D, dpitch, k, width,
+                             width, rows, hipMemcpyDeviceToHost, st));
+    CQA_HIP(hipMemcpy2DAsync(c->t2_v + (head0 * c->desc.max_tokens + len) * D, dpitch, v, width,
+                             width, rows, hipMemcpyDeviceToHost, st));
+  }
+  const int32_t rc = launch_seal(c, layer, k, v, n_new, len, st);
+  if (rc != CQA_OK) return rc;
+  c->length[layer] = len + n_new;
+  return CQA_OK;
+}
+
+int32_t cqa_cache_export_block(const cqa_cache* h, int32_t layer, int32_t batch, int32_t kv_head,
+                               int64_t block, int8_t* kcodes, float* sigma, float* z,
+                               uint8_t* vcodes, uint16_t* vscale_bits, uint16_t* voffset_bits,
+                               float* eta, float* nu) {
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  const Cache* c = &h->impl;
+  if (layer < 0 || layer >= c->desc.n_layers || batch < 0 || batch >= c->desc.batch ||
+      kv_head < 0 || kv_head >= c->desc.n_kv_heads || block < 0 ||
+      block >= c->length[layer] / BLK)
+    return CQA_ERR_INVALID_ARG;
+  CQA_HIP(hipDeviceSynchronize());
+  const int64_t gb = head_index(c, layer, batch, kv_head) * c->nb_cap + block;
+  uint8_t kc[KC_BYTES];
+  float km[KM_BYTES / 4];
+  uint32_t vc[VC_BYTES / 4];
+  uint16_t vm[VM_BYTES / 2];
+  float an[2];
+  CQA_HIP(hipMemcpy(kc, c->kc + gb * KC_BYTES, KC_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(km, c->km + gb * (KM_BYTES / 4), KM_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(vc, c->vc + gb * VC_BYTES, VC_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(vm, c->vm + gb * (VM_BYTES / 2), VM_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(an, c->an + gb * 2, AN_BYTES, hipMemcpyDeviceToHost));
+  for (int t = 0; t < BLK; ++t)
+    for (int ch = 0; ch < D; ++ch) {
+      if (kcodes) kcodes[t * D + ch] = (int8_t)((int)kc[kc_offset(t, ch)] - 128);
+      if (vcodes)
+        vcodes[t * D + ch] =
+            (uint8_t)((vc[vc_dword_offset(t >> 3, ch) / 4] >> (4 * (t & 7))) & 15u);
+    }
+  for (int ch = 0; ch < D; ++ch) {
+    if (sigma) sigma[ch] = km[ch];
+    if (z) z[ch] = km[D + ch];
+  }
+  for (int t = 0; t < BLK; ++t)
+    for (int g = 0; g < NG; ++g) {
+      if (vscale_bits) vscale_bits[t * NG + g] = vm[vm_index(t, g)];
+      if (voffset_bits) voffset_bits[t * NG + g] = vm[BLK * NG + vm_index(t, g)];
+    }
+  if (eta) *eta = an[0];
+  if (nu) *nu = an[1];
+  return CQA_OK;
+}
+
+int32_t cqa_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                             const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                             uint32_t* flags_dev, float* blk_logmass_dev, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
+      tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
+    return CQA_ERR_INVALID_ARG;
+  return launch_certified(&h->impl, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
+                          flags_dev, blk_logmass_dev, (hipStream_t)stream);
+}
+
+int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                                  const cqa_tolerances* tol, float* O_dev,
+                                  cqa_head_cert* cert_dev, uint32_t* flags_dev,
+                                  float* blk_logmass_dev, int32_t iters, float* ms_per_step,
+                                  void* stream) {
+  if (h == nullptr || iters < 1 || ms_per_step == nullptr) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  hipStream_t st = (hipStream_t)stream;
+  CQA_HIP(hipEventRecord(c->ev_t0, st));
+  for (int i = 0; i < iters; ++i) {
+    const int32_t rc = cqa_certified_decode(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev,
+                                            blk_logmass_dev, stream);
+    if (rc != CQA_OK) return rc;
+  }
+  CQA_HIP(hipEventRecord(c->ev_t1, st));
+  CQA_HIP(hipEventSynchronize(c->ev_t1));
+  float ms = 0.0f;
+  CQA_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+  *ms_per_step = ms / (float)iters;
+  return CQA_OK;
+}
+
+int32_t cqa_dense_fallback(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                           const uint32_t* head_select_host, int32_t all_heads, int32_t rung,
+                           float* O_dev, cqa_head_cert* cert_dev, uint32_t* flags_dev,
+                           void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
+      O_dev == nullptr || (!all_heads && head_select_host == nullptr) || rung < 0 || rung > 7)
+    return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  const int64_t len = c->length[layer];
+  if (len <= 0) return CQA_ERR_INVALID_ARG;
+  const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
+  const int g = hq / hkv;
+  hipStream_t st = (hipStream_t)stream;
+  const __half* q = (const __half*)q_fp16_dev;
+
+  std::vector<int> groups;
+  for (int b = 0; b < bt; ++b)
+    for (int kh = 0; kh < hkv; ++kh) {
+      bool any = all_heads != 0;
+      for (int i = 0; i < g && !any; ++i) any = head_select_host[b * hq + kh * g + i] != 0;
+      if (any) groups.push_back(b * hkv + kh);
+    }
+  if (groups.empty()) return CQA_OK;
+  if (!all_heads)
+    CQA_HIP(hipMemcpyAsync(c->select_dev, head_select_host, (size_t)bt * hq * 4,
+                           hipMemcpyHostToDevice, st));
+  // the side stream must see every Tier-2 write queued on the caller's stream so far
+  CQA_HIP(hipEventRecord(c->ev_main, st));
+  CQA_HIP(hipStreamWaitEvent(c->side, c->ev_main, 0));
+  const int64_t ws_floats = dense_ws_floats(g, c->desc.max_tokens);
+  const size_t bytes = (size_t)len * D * 2;
+  for (size_t i = 0; i < groups.size(); ++i) {
+    const int buf = (int)(i & 1);
+    const int b = groups[i] / hkv, kh = groups[i] % hkv;
+    const int64_t head = head_index(c, layer, b, kh);
+    if (c->free_valid[buf]) CQA_HIP(hipStreamWaitEvent(c->side, c->ev_free[buf], 0));
+    CQA_HIP(hipMemcpyAsync(c->stage[buf][0], c->t2_k + head * c->desc.max_tokens * D, bytes,
+                           hipMemcpyHostToDevice, c->side));
+    CQA_HIP(hipMemcpyAsync(c->stage[buf][1], c->t2_v + head * c->desc.max_tokens * D, bytes,
+                           hipMemcpyHostToDevice, c->side));
+    CQA_HIP(hipEventRecord(c->ev_ready[buf], c->side));
+    CQA_HIP(hipStreamWaitEvent(st, c->ev_ready[buf], 0));
+    const int64_t row = (int64_t)b * hq + kh * g;
+    const int32_t rc = launch_dense_group(
+        q + row * D, c->stage[buf][0], c->stage[buf][1], g, len, O_dev + row * D,
+        all_heads ? nullptr : c->select_dev + row, cert_dev ? cert_dev + row : nullptr,
+        flags_dev ? flags_dev + row : nullptr, rung, c->dense_ws + buf * ws_floats, st);
+    if (rc != CQA_OK) return rc;
+    CQA_HIP(hipEventRecord(c->ev_free[buf], st));
+    c->free_valid[buf] = true;
+  }
+  return CQA_OK;
+}
+
+int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                        const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                        uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
+                        void* stream) {
+  int32_t rc = cqa_certified_decode(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev,
+                                    blk_logmass_dev, stream);
+  if (rc != CQA_OK) return rc;
+  Cache* c = &h->impl;
+  hipStream_t st = (hipStream_t)stream;
+  const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
+  const int g = hq / hkv;
+  const int n = bt * hq;
+  CQA_HIP(hipMemcpyAsync(c->flags_host, flags_dev, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+  CQA_HIP(hipStreamSynchronize(st));
+  // ladder policy: PRECOND anywhere, or enough flagged KV groups, escalates to the whole layer
+  bool any = false, precond = false;
+  int flagged_groups = 0;
+  std::vector<uint32_t> need(n, 0u);
+  for (int b = 0; b < bt; ++b)
+    for (int kh = 0; kh < hkv; ++kh) {
+      bool grp = false;
+      for (int i = 0; i < g; ++i) {
+        const int idx = b * hq + kh * g + i;
+        const uint32_t f = c->flags_host[idx];
+        if (f & CQA_FLAG_ANY) {
+          need[idx] = 1u;
+          grp = true;
+        }
+        if (f & CQA_FLAG_PRECOND) precond = true;
+      }
+      if (grp) {
+        any = true;
+        ++flagged_groups;
+      }
+    }
+  int rung = 0;
+  if (any) {
+    rung = 3;
+    if (precond || (tol->rung4_min_groups > 0 && flagged_groups >= tol->rung4_min_groups)) rung = 4;
+  }
+  if (rung_served) *rung_served = rung;
+  if (rung == 0) return CQA_OK;
+  return cqa_dense_fallback(h, layer, q_fp16_dev, need.data(), rung == 4, rung, O_dev, cert_dev,
+                            flags_dev, stream);
+}
+
+int64_t cqa_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int64_t n_tokens) {
+  (void)batch;
+  (void)n_q_heads;
+  if (n_tokens < 1) return 0;
+  return dense_ws_floats(4, n_tokens) * 4;
+}
+
+int32_t cqa_dense_attention(const void* q_fp16_dev, const void* k_fp16_dev,
+                            const void* v_fp16_dev, int32_t batch, int32_t n_q_heads,
+                            int32_t n_kv_heads, int64_t n_tokens, float* O_dev,
+                            void* workspace_dev, void* stream) {
+  if (q_fp16_dev == nullptr || k_fp16_dev == nullptr || v_fp16_dev == nullptr ||
+      O_dev == nullptr || workspace_dev == nullptr || batch < 1 || n_q_heads < 1 ||
+      n_kv_heads < 1 || n_tokens < 1 || n_q_heads % n_kv_heads != 0)
+    return CQA_ERR_INVALID_ARG;
+  const int g = n_q_heads / n_kv_heads;
+  if (g != 1 && g != 2 && g != 4) return CQA_ERR_UNSUPPORTED;
+  const __half* q = (const __half*)q_fp16_dev;
+  const __half* k = (const __half*)k_fp16_dev;
+  const __half* v = (const __half*)v_fp16_dev;
+  for (int b = 0; b < batch; ++b)
+    for (int kh = 0; kh < n_kv_heads; ++kh) {
+      const int64_t row = (int64_t)b * n_q_heads + kh * g;
+      const int64_t kv = ((int64_t)b * n_kv_heads + kh) * n_tokens * D;
+      const int32_t rc =
+          launch_dense_group(q + row * D, k + kv, v + kv, g, n_tokens, O_dev + row * D, nullptr,
+                             nullptr, nullptr, 0, (float*)workspace_dev, (hipStream_t)stream);
+      if (rc != CQA_OK) return rc;
+    }
+  return CQA_OK;
+}
+
+}  // extern "C"

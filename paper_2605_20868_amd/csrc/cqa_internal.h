@@ -1,0 +1,133 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/cqa.h"
+
+namespace cqa {
+
+// ---- fixed geometry (the paper's defaults: d = 128, B = 16, g = 16) ------------
+constexpr int D = 128;          // head dimension
+constexpr int BLK = 16;         // tokens per block
+constexpr int VG = 16;          // value channels per group
+constexpr int NG = D / VG;      // 8 value groups per token
+
+// ---- physical Tier-1 layout, per sealed block ---------------------------------
+// Five block-major streams per (layer, batch, kv-head); block b of a head lives at
+// offset b * <bytes per block> in each stream, so one split of the decode pass
+// reads five contiguous byte ranges.
+//
+// K codes (2048 B): biased bytes u = code + 128, ordered [cq][kg][token][j] with
+//   channel = cq*64 + kg*16 + j  (cq in 0..1, kg in 0..3, j in 0..15), so a wave's
+//   lane l = kg*16 + token reads one aligned 16-byte piece and the whole wave reads
+//   1 KB contiguously per cq.
+// K meta (1024 B): sigma[128] then z[128], FP32, natural channel order.
+// V codes (1024 B): dwords ordered [o][gh][n][gq]; the dword of (o, g = gh*4+gq, n)
+//   holds channel g*16+n of the eight tokens o*8 .. o*8+7, token i in bits 4i..4i+3.
+// V meta (512 B): FP16 scale[o][g][i] (256 B) then FP16 offset[o][g][i] (256 B),
+//   token = o*8 + i.
+// Annotations (8 B): float eta_b, float nu_b.
+constexpr int KC_BYTES = BLK * D;            // 2048
+constexpr int KM_BYTES = 2 * D * 4;          // 1024
+constexpr int VC_BYTES = BLK * D / 2;        // 1024
+constexpr int VM_BYTES = 2 * BLK * NG * 2;   // 512
+constexpr int AN_BYTES = 8;
+
+__host__ __device__ inline int kc_offset(int token, int channel) {
+  const int cq = channel >> 6, kg = (channel >> 4) & 3, j = channel & 15;
+  return cq * 1024 + kg * 256 + token * 16 + j;
+}
+// byte offset of the dword holding (token octet o, channel c); nibble index = token & 7
+__host__ __device__ inline int vc_dword_offset(int o, int channel) {
+  const int g = channel >> 4, n = channel & 15;
+  return o * 512 + (g >> 2) * 256 + n * 16 + (g & 3) * 4;
+}
+// index (in halves) of the scale of (token, group) inside the V-meta block; offsets follow at +128
+__host__ __device__ inline int vm_index(int token, int g) {
+  return (token >> 3) * 64 + g * 8 + (token & 7);
+}
+
+// ---- split partial written by the decode pass, merged by the reduction ---------
+// Per (batch, q-head, split): PART_FLOATS floats.
+constexpr int P_M = 0;      // running max of the split
+constexpr int P_L = 1;      // sum of exp(s - m)
+constexpr int P_EV = 2;     // sum_b S_b e^{m_b - m} eta_b
+constexpr int P_EVMAX = 3;  // max_b S_b e^{m_b - m} eta_b
+constexpr int P_DMAX = 4;   // max_b Delta_b
+constexpr int P_VMAX = 5;   // max_b nu_b
+constexpr int P_T1 = 6;     // largest block log-mass
+constexpr int P_T2 = 7;     // second largest
+constexpr int P_I1 = 8;     // block index of the largest (int bits)
+constexpr int P_O = 16;     // o[128]
+constexpr int PART_FLOATS = 16 + D;  // 144
+
+struct Cache {
+  cqa_cache_desc desc;
+  int device;
+  int n_cu;
+  int64_t nb_cap;            // blocks of capacity per head
+  int64_t heads_total;       // n_layers * batch * n_kv_heads
+  int64_t* length;           // host, per layer
+  int forced_splits;
+  int max_splits;
+  // Tier-1 streams
+  uint8_t* kc;
+  float* km;
+  uint8_t* vc;
+  __half* vm;
+  float* an;
+  // trailing FP16 partial blocks [heads_total][16][128]
+  __half* trail_k;
+  __half* trail_v;
+  // Tier-2 (pinned host) [heads_total][max_tokens][128]
+  __half* t2_k;
+  __half* t2_v;
+  // workspaces
+  float* partials;           // [batch][Hq][max_splits][PART_FLOATS]
+  float* dense_ws;           // dense partials for one (batch, kv-head) group x 2 buffers
+  __half* stage[2][2];       // [buffer][K|V] : max_tokens * 128 halves each
+  uint32_t* select_dev;      // [batch][Hq]
+  uint32_t* flags_host;      // pinned [batch][Hq]
+  hipStream_t side;
+  hipEvent_t ev_ready[2];    // staging buffer filled (recorded on side)
+  hipEvent_t ev_free[2];     // staging buffer consumed (recorded on main)
+  hipEvent_t ev_main;        // main-stream marker the side stream waits on
+  hipEvent_t ev_t0, ev_t1;   // timing
+  bool free_valid[2];
+};
+
+inline int64_t head_index(const Cache* c, int layer, int b, int kvh) {
+  return ((int64_t)layer * c->desc.batch + b) * c->desc.n_kv_heads + kvh;
+}
+
+extern thread_local int g_last_hip_error;
+#define CQA_HIP(expr)                                   \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) {                            \
+      cqa::g_last_hip_error = (int)e__;                 \
+      return CQA_ERR_HIP;                               \
+    }                                                   \
+  } while (0)
+
+// ---- launchers implemented in the kernel translation units ---------------------
+int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in, int64_t n_new,
+                    int64_t len_before, hipStream_t st);
+int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
+                         cqa_head_cert* cert, uint32_t* flags, float* blk_logmass, hipStream_t st);
+int pick_splits(const Cache* c, int64_t n_blocks);
+
+int dense_splits(int64_t n_tokens);
+// Dense FP16 attention for the G query heads of ONE kv group: k, v point at [n_tokens][128];
+// q_group at the group's first query head.  O rows are written only where select (device,
+// indexed from the group's first head; NULL = all) is nonzero.
+int32_t launch_dense_group(const __half* q_group, const __half* k, const __half* v, int group,
+                           int64_t n_tokens, float* O_group, const uint32_t* select_group,
+                           cqa_head_cert* cert_group, uint32_t* flags_group, int rung,
+                           float* ws, hipStream_t st);
+int64_t dense_ws_floats(int group, int64_t n_tokens);
+
+}  // namespace cqa

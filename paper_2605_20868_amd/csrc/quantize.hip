@@ -1,0 +1,221 @@
+// Cache-write kernels: seal a block of 16 tokens into Tier-1.
+//
+// Follows the paper's "Quantization Schemes" section: per-block per-channel INT8
+// keys with sigma_c = (u_c - l_c)/255, z_c = l_c + 128 sigma_c, code =
+// clamp(round((k - z_c)/sigma_c), -128, 127); per-token per-16-channel-group INT4
+// values with an FP16 scale and offset; and the block annotations eta_b =
+// max_t ||v_hat_t - v_t||_2, nu_b = max_t ||v_t||_2.
+//
+// All quantizer arithmetic is IEEE binary32 with one rounding per operation in
+// the order written (subtract, divide; multiply, add; subtract, divide,
+// round-half-even, clamp): contraction into fused multiply-adds is switched off
+// for this file so codes and scales have exactly one correct value.
+// Inputs are assumed finite.
+#pragma clang fp contract(off)
+
+#include "cqa_internal.h"
+
+namespace cqa {
+
+struct SealArgs {
+  const __half* k_in;   // [Bt][Hkv][n_new][128]
+  const __half* v_in;
+  const __half* trail_k;  // [heads][16][128]
+  const __half* trail_v;
+  uint8_t* kc;
+  float* km;
+  uint8_t* vc;
+  __half* vm;
+  float* an;
+  int64_t nb_cap;
+  int64_t nb_old;       // sealed blocks before this append
+  int64_t n_new;
+  int r;                // tokens in the trailing block before this append
+  int layer, batch, n_kv;
+};
+
+__global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
+  const int c = threadIdx.x;            // channel
+  const int j = blockIdx.x;             // new block index
+  const int kvh = blockIdx.y, b = blockIdx.z;
+  const int64_t head = ((int64_t)a.layer * a.batch + b) * a.n_kv + kvh;
+  const int64_t blk = a.nb_old + j;
+  const int64_t in_head = ((int64_t)b * a.n_kv + kvh) * a.n_new;
+
+  __shared__ __align__(16) uint8_t kbuf[KC_BYTES];
+  __shared__ uint8_t vnib[BLK][D];
+  __shared__ __align__(16) __half vmeta[2 * BLK * NG];
+  __shared__ double red[2][BLK][2];
+
+  float kf[BLK], vf[BLK];
+#pragma unroll
+  for (int t = 0; t < BLK; ++t) {
+    const int64_t i = (int64_t)j * BLK + t;
+    if (i < a.r) {
+      kf[t] = __half2float(a.trail_k[(head * BLK + i) * D + c]);
+      vf[t] = __half2float(a.trail_v[(head * BLK + i) * D + c]);
+    } else {
+      kf[t] = __half2float(a.k_in[(in_head + (i - a.r)) * D + c]);
+      vf[t] = __half2float(a.v_in[(in_head + (i - a.r)) * D + c]);
+    }
+  }
+
+  // ---- keys: per-channel affine INT8 over the block's 16 tokens
+  float lo = kf[0], hi = kf[0];
+#pragma unroll
+  for (int t = 1; t < BLK; ++t) {
+    lo = fminf(lo, kf[t]);
+    hi = fmaxf(hi, kf[t]);
+  }
+  const float sigma = (hi - lo) / 255.0f;
+  const float z = lo + 128.0f * sigma;
+#pragma unroll
+  for (int t = 0; t < BLK; ++t) {
+    int code = 0;
+    if (sigma != 0.0f) {
+      float q = rintf((kf[t] - z) / sigma);
+      q = fminf(fmaxf(q, -128.0f), 127.0f);
+      code = (int)q;
+    }
+    kbuf[kc_offset(t, c)] = (uint8_t)(code + 128);
+  }
+  float* km = a.km + (head * a.nb_cap + blk) * (KM_BYTES / 4);
+  km[c] = sigma;
+  km[D + c] = z;
+
+  // ---- values: per-token, per-group asymmetric INT4
+  const int g = c >> 4;
+#pragma unroll
+  for (int t = 0; t < BLK; ++t) {
+    float vlo = vf[t], vhi = vf[t];
+#pragma unroll
+    for (int m = 1; m < VG; m <<= 1) {
+      vlo = fminf(vlo, __shfl_xor(vlo, m));
+      vhi = fmaxf(vhi, __shfl_xor(vhi, m));
+    }
+    const __half sh = __float2half_rn((vhi - vlo) / 15.0f);
+    const float s = __half2float(sh);
+    int code = 0;
+    if (s != 0.0f) {
+      float q = rintf((vf[t] - vlo) / s);
+      q = fminf(fmaxf(q, 0.0f), 15.0f);
+      code = (int)q;
+    }
+    vnib[t][c] = (uint8_t)code;
+    if ((c & 15) == 0) {
+      vmeta[vm_index(t, g)] = sh;
+      vmeta[BLK * NG + vm_index(t, g)] = __float2half_rn(vlo);  // exact: vlo is an FP16 input
+    }
+    // annotations in double: squared reconstruction error and squared norm of this token
+    const double vh = (double)code * (double)s + (double)vlo;
+    double e2 = (vh - (double)vf[t]) * (vh - (double)vf[t]);
+    double n2 = (double)vf[t] * (double)vf[t];
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+      e2 += __shfl_xor(e2, m);
+      n2 += __shfl_xor(n2, m);
+    }
+    if ((c & 63) == 0) {
+      red[c >> 6][t][0] = e2;
+      red[c >> 6][t][1] = n2;
+    }
+  }
+  __syncthreads();
+
+  // ---- write out, 16 bytes per thread where possible
+  uint8_t* kc = a.kc + (head * a.nb_cap + blk) * KC_BYTES;
+  reinterpret_cast<uint4*>(kc)[c] = reinterpret_cast<const uint4*>(kbuf)[c];
+
+  uint32_t* vc = reinterpret_cast<uint32_t*>(a.vc + (head * a.nb_cap + blk) * VC_BYTES);
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int dw = c + rep * 128;
+    const int o = dw >> 7, gh = (dw >> 6) & 1, n = (dw >> 2) & 15, gq = dw & 3;
+    const int ch = (gh * 4 + gq) * 16 + n;
+    uint32_t x = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x |= (uint32_t)vnib[o * 8 + i][ch] << (4 * i);
+    vc[dw] = x;
+  }
+  __half* vm = a.vm + (head * a.nb_cap + blk) * (VM_BYTES / 2);
+  reinterpret_cast<uint32_t*>(vm)[c] = reinterpret_cast<const uint32_t*>(vmeta)[c];
+
+  if (c == 0) {
+    double eta2 = 0.0, nu2 = 0.0;
+    for (int t = 0; t < BLK; ++t) {
+      eta2 = fmax(eta2, red[0][t][0] + red[1][t][0]);
+      nu2 = fmax(nu2, red[0][t][1] + red[1][t][1]);
+    }
+    float* an = a.an + (head * a.nb_cap + blk) * 2;
+    an[0] = (float)sqrt(eta2);
+    an[1] = (float)sqrt(nu2);
+  }
+}
+
+// Moves the tokens that stay unsealed into the trailing FP16 block.
+// src_first: index (within this append's input) of the first token to keep;
+// dst_first: slot of the trailing block it goes to; count tokens.
+__global__ __launch_bounds__(128) void trail_kernel(const __half* k_in, const __half* v_in,
+                                                    __half* trail_k, __half* trail_v,
+                                                    int64_t n_new, int64_t src_first,
+                                                    int dst_first, int count, int layer, int batch,
+                                                    int n_kv) {
+  const int c = threadIdx.x;
+  const int kvh = blockIdx.x, b = blockIdx.y;
+  const int64_t head = ((int64_t)layer * batch + b) * n_kv + kvh;
+  const int64_t in_head = ((int64_t)b * n_kv + kvh) * n_new;
+  for (int t = 0; t < count; ++t) {
+    trail_k[(head * BLK + dst_first + t) * D + c] = k_in[(in_head + src_first + t) * D + c];
+    trail_v[(head * BLK + dst_first + t) * D + c] = v_in[(in_head + src_first + t) * D + c];
+  }
+}
+
+int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in, int64_t n_new,
+                    int64_t len_before, hipStream_t st) {
+  const int r = (int)(len_before % BLK);
+  const int64_t nb_old = len_before / BLK;
+  const int64_t n_seal = (r + n_new) / BLK;
+  const int r_new = (int)((r + n_new) % BLK);
+  const int bt = c->desc.batch, hkv = c->desc.n_kv_heads;
+  if (n_seal > 0) {
+    SealArgs a;
+    a.k_in = k_in;
+    a.v_in = v_in;
+    a.trail_k = c->trail_k;
+    a.trail_v = c->trail_v;
+    a.kc = c->kc;
+    a.km = c->km;
+    a.vc = c->vc;
+    a.vm = c->vm;
+    a.an = c->an;
+    a.nb_cap = c->nb_cap;
+    a.nb_old = nb_old;
+    a.n_new = n_new;
+    a.r = r;
+    a.layer = layer;
+    a.batch = bt;
+    a.n_kv = hkv;
+    // grid.x is limited to 2^31-1 blocks; n_seal <= nb_cap is far below that
+    hipLaunchKernelGGL(seal_kernel, dim3((unsigned)n_seal, hkv, bt), dim3(128), 0, st, a);
+    CQA_HIP(hipGetLastError());
+  }
+  int64_t src_first;
+  int dst_first, count;
+  if (n_seal == 0) {
+    src_first = 0;
+    dst_first = r;
+    count = (int)n_new;
+  } else {
+    src_first = n_new - r_new;
+    dst_first = 0;
+    count = r_new;
+  }
+  if (count > 0) {
+    hipLaunchKernelGGL(trail_kernel, dim3(hkv, bt), dim3(128), 0, st, k_in, v_in, c->trail_k,
+                       c->trail_v, n_new, src_first, dst_first, count, layer, bt, hkv);
+    CQA_HIP(hipGetLastError());
+  }
+  return CQA_OK;
+}
+
+}  // namespace cqa
