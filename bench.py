@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the certified-decode hot path on one MI355X.
+
+A step = one pass of the whole hot path over the 128K single-layer workload:
+append one (k, v) token per KV head (trailing FP16 block, Tier-2 copy, block seal
+when 16 tokens have arrived), the split-K certified decode over the packed
+cache, the cross-split reduction with the certificate, the flag read-back and
+the fallback ladder (tolerances +inf in the headline run, so no head falls back).
+
+Prints ONE JSON line.  `value` is whole-step throughput (steps/s for the one
+layer) with all inputs resident in HBM; `roofline` prices the dominant kernel
+(the split-K decode pass) against HBM bandwidth using its algorithmic bytes and
+its mean duration measured with HIP events on the launch stream inside the
+timed region; `cpu_baseline` is the CPU oracle timed on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+import workloads
+
+PEAK_HBM_GBS = 8000.0
+BYTES_PER_TOKEN = 288.5        # Tier-1 bytes per token per KV head (codes + metadata + eta, nu)
+WORKLOAD = "t128k"
+
+
+def read_traffic_note():
+    """HBM bytes per launch of the split kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", "certified_split_t128k_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(k, v, steps_budget_s=12.0):
+    """Times the oracle (as it stands) on full steps of the same workload, before the GPU is touched."""
+    import oracle
+
+    sh = workloads.SHAPES[WORKLOAD]
+    oc = oracle.OracleLayerCache(sh.batch, sh.n_kv_heads)
+    oc.append(k, v)                                   # prefix build: set-up, not timed
+    tol = oracle.Tolerances()
+    n = 0
+    t0 = time.perf_counter()
+    c0 = os.times()
+    while True:
+        ks, vs = workloads.make_step_kv(WORKLOAD, 1000 + n, seed=0)
+        q = workloads.make_q(WORKLOAD, 1000 + n, seed=0)
+        oc.append(ks, vs)
+        oc.decode_step(q, tol)
+        n += 1
+        if time.perf_counter() - t0 > steps_budget_s or n >= 8:
+            break
+    wall = time.perf_counter() - t0
+    c1 = os.times()
+    cpu = (c1.user + c1.system) - (c0.user + c0.system)
+    return {"value": n / wall, "unit": "steps/s", "cores": max(1, int(round(cpu / wall))),
+            "kind": "oracle",
+            "sample": f"{n} full steps (append 1 token + certified decode of all 32 heads, 128K context) "
+                      f"of the same workload; numpy float64, host has {len(os.sched_getaffinity(0))} cores"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--context", type=int, default=None, help="override the context length (debug)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives or sharding are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+    if int(os.environ.get("RANK", "0")) != 0:
+        return 0
+
+    sh = workloads.SHAPES[WORKLOAD]
+    ctx = args.context or sh.context
+    k, v = workloads.make_kv(WORKLOAD, seed=0, context=ctx)
+
+    base = None
+    if not args.no_cpu_baseline:
+        base = cpu_baseline(k, v)
+
+    import torch
+    from paper_2605_20868_amd import binding as cqa     # raises if libcqa.so is missing
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+    cap = ctx + K + W + 64
+    h = cqa.cqa_cache_create(1, sh.batch, sh.n_q_heads, sh.n_kv_heads, cap)
+    try:
+        kd = torch.from_numpy(k).to(dev)
+        vd = torch.from_numpy(v).to(dev)
+        cqa.cqa_cache_append(h, 0, kd, vd, ctx)
+        torch.cuda.synchronize()
+        del kd, vd
+        rng = np.random.Generator(np.random.Philox(7))
+        n_in = K + W
+        ks = torch.from_numpy(workloads.student_t3_f16(rng, (n_in, sh.batch, sh.n_kv_heads, 1, 128))).to(dev)
+        vs = torch.from_numpy(workloads.normal_f16(rng, (n_in, sh.batch, sh.n_kv_heads, 1, 128))).to(dev)
+        qs = torch.from_numpy(workloads.normal_f16(rng, (n_in, sh.batch, sh.n_q_heads, 128))).to(dev)
+        O = torch.empty((sh.batch, sh.n_q_heads, 128), dtype=torch.float32, device=dev)
+        cert = torch.zeros((sh.batch * sh.n_q_heads, cqa.CERT_BYTES), dtype=torch.uint8, device=dev)
+        flags = torch.zeros((sh.batch * sh.n_q_heads,), dtype=torch.int32, device=dev)
+        tol = cqa.Tolerances()                          # headline: every threshold at +inf
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def step(i):
+            cqa.cqa_cache_append(h, 0, ks[i], vs[i], 1, stream)
+            return cqa.cqa_decode_step(h, 0, qs[i], tol, O, cert, flags, None, stream)
+
+        for i in range(W):
+            step(i)
+        torch.cuda.synchronize()
+        cqa.cqa_profile_begin(h, K)
+        t0 = time.perf_counter()
+        for i in range(W, W + K):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        mean_ms, min_ms, n_timed = cqa.cqa_profile_end(h)
+        assert n_timed == K
+
+        # kernel-only rate: split pass + reduction back to back, no host synchronisation in between
+        ko_ms = cqa.cqa_time_certified_decode(h, 0, qs[0], tol, O, cert, flags, None, 50, stream)
+        splits = cqa.cqa_decode_splits(h, 0)
+        n_tokens = cqa.cqa_cache_length(h, 0)
+    finally:
+        cqa.cqa_cache_destroy(h)
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    nb_mid = (ctx + W + K // 2) // 16
+    alg_bytes = sh.batch * sh.n_kv_heads * nb_mid * 16 * BYTES_PER_TOKEN
+    achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
+    out = {
+        "metric": "certified decode attention steps/s per layer at 128K ctx; HBM GB/s vs peak",
+        "value": K / (t1 - t0),
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"t128k: 1 layer, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
+                        f"d 128, context {ctx}+steps, K ~ Student-t(3), V ~ N(0,1), INT8 K / INT4 V "
+                        f"(B=16, g=16), tolerances +inf, Tier-2 FP16 originals in pinned host RAM",
+            "step": "append 1 token + certified decode + reduce + flag read-back + ladder",
+            "splits": splits,
+            "final_tokens": n_tokens,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": achieved / PEAK_HBM_GBS,
+            "traffic": read_traffic_note(),
+            "kernel": "certified_split_kernel<4>",
+            "kernel_mean_ms": mean_ms,
+            "kernel_min_ms": min_ms,
+            "algorithmic_bytes_per_launch": alg_bytes,
+        },
+        "kernel_only": {
+            "ms_per_step": ko_ms,
+            "steps_per_s": 1e3 / ko_ms,
+            "what": "split pass + reduction, 50 back-to-back launches between two HIP events",
+        },
+        "cpu_baseline": base,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -222,6 +222,15 @@ int32_t cqa_time_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp1
                                   float* blk_logmass_dev, int32_t iters, float* ms_per_step,
                                   void* stream);
 
+/* Per-launch timing of the split-K decode kernel (the dominant kernel), taken
+ * with HIP event pairs recorded on the stream each cqa_certified_decode /
+ * cqa_decode_step call launches it on.  begin arms up to max_launches pairs
+ * (<= 65536); end synchronises on them and returns the mean and minimum kernel
+ * duration in milliseconds and the number of launches timed (host pointers,
+ * any may be NULL).  For benchmarks. */
+int32_t cqa_profile_begin(cqa_cache* c, int32_t max_launches);
+int32_t cqa_profile_end(cqa_cache* c, float* mean_ms, float* min_ms, int32_t* n_launches);
+
 /* Split count the decode pass uses for the current length of `layer`
  * (for reporting; chosen from the device's compute-unit count). */
 int32_t cqa_decode_splits(const cqa_cache* c, int32_t layer, int32_t* n_splits);

@@ -81,6 +81,12 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_20868_amd.build` "
                           "(there is no CPU fallback)")
+    try:
+        # One HIP runtime per process: if torch is around, its bundled runtime must be the one
+        # that gets loaded, and it must be loaded before this library resolves libamdhip64.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     sig = {
@@ -99,6 +105,8 @@ def _load():
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
         "cqa_time_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
                                             i32, C.POINTER(C.c_float), vp]),
+        "cqa_profile_begin": (i32, [vp, i32]),
+        "cqa_profile_end": (i32, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]),
         "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
         "cqa_set_splits": (i32, [vp, i32]),
         "cqa_strerror": (C.c_char_p, [i32]),
@@ -242,6 +250,17 @@ def cqa_time_certified_decode(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev,
                                           iters, C.byref(ms), _ptr(stream)),
            "cqa_time_certified_decode")
     return ms.value
+
+
+def cqa_profile_begin(h, max_launches) -> None:
+    _check(_lib.cqa_profile_begin(h, max_launches), "cqa_profile_begin")
+
+
+def cqa_profile_end(h):
+    """Returns (mean_ms, min_ms, n_launches) of the split-K decode kernel since profile_begin."""
+    mean, mn, n = C.c_float(0), C.c_float(0), C.c_int32(0)
+    _check(_lib.cqa_profile_end(h, C.byref(mean), C.byref(mn), C.byref(n)), "cqa_profile_end")
+    return mean.value, mn.value, n.value
 
 
 def cqa_decode_splits(h, layer) -> int:

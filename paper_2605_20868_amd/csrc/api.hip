@@ -48,6 +48,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.t2 = d->tier2_mode == CQA_TIER2_PINNED ? s.heads * d->max_tokens * D * 2 : 0;
   int64_t ms = (4 * (int64_t)n_cu) / ((int64_t)d->batch * d->n_kv_heads);
   if (ms < 64) ms = 64;
+  if (ms > MAX_SPLITS) ms = MAX_SPLITS;
   if (ms > s.nb_cap) ms = s.nb_cap;
   if (ms < 1) ms = 1;
   s.max_splits = (int)ms;
@@ -86,6 +87,11 @@ static void release(cqa_cache* h) {
   if (c->ev_main) (void)hipEventDestroy(c->ev_main);
   if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
   if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
+  if (c->prof_ev) {
+    for (int i = 0; i < 2 * c->prof_cap; ++i)
+      if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+    delete[] c->prof_ev;
+  }
   delete[] c->length;
   delete h;
 }
@@ -346,6 +352,48 @@ int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp1
   float ms = 0.0f;
   CQA_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
   *ms_per_step = ms / (float)iters;
+  return CQA_OK;
+}
+
+int32_t cqa_profile_begin(cqa_cache* h, int32_t max_launches) {
+  if (h == nullptr || max_launches < 1 || max_launches > 65536) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->prof_ev != nullptr && c->prof_cap < max_launches) {
+    for (int i = 0; i < 2 * c->prof_cap; ++i)
+      if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+    delete[] c->prof_ev;
+    c->prof_ev = nullptr;
+    c->prof_cap = 0;
+  }
+  if (c->prof_ev == nullptr) {
+    c->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
+    if (c->prof_ev == nullptr) return CQA_ERR_INVALID_ARG;
+    for (int i = 0; i < 2 * max_launches; ++i) c->prof_ev[i] = nullptr;
+    c->prof_cap = max_launches;
+    for (int i = 0; i < 2 * max_launches; ++i) CQA_HIP(hipEventCreate(&c->prof_ev[i]));
+  }
+  c->prof_n = 0;
+  return CQA_OK;
+}
+
+int32_t cqa_profile_end(cqa_cache* h, float* mean_ms, float* min_ms, int32_t* n_launches) {
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->prof_ev == nullptr) return CQA_ERR_INVALID_ARG;
+  const int n = c->prof_n;
+  double sum = 0.0;
+  float mn = 0.0f;
+  for (int i = 0; i < n; ++i) {
+    CQA_HIP(hipEventSynchronize(c->prof_ev[2 * i + 1]));
+    float ms = 0.0f;
+    CQA_HIP(hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    sum += ms;
+    mn = (i == 0 || ms < mn) ? ms : mn;
+  }
+  if (mean_ms) *mean_ms = n > 0 ? (float)(sum / n) : 0.0f;
+  if (min_ms) *min_ms = mn;
+  if (n_launches) *n_launches = n;
+  c->prof_n = c->prof_cap;  // stop recording until the next begin
   return CQA_OK;
 }
 

@@ -63,6 +63,7 @@ constexpr int P_T2 = 7;     // second largest
 constexpr int P_I1 = 8;     // block index of the largest (int bits)
 constexpr int P_O = 16;     // o[128]
 constexpr int PART_FLOATS = 16 + D;  // 144
+constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-head)
 
 struct Cache {
   cqa_cache_desc desc;
@@ -97,6 +98,9 @@ struct Cache {
   hipEvent_t ev_main;        // main-stream marker the side stream waits on
   hipEvent_t ev_t0, ev_t1;   // timing
   bool free_valid[2];
+  // optional per-launch timing of the split kernel (pairs of events on the launch stream)
+  hipEvent_t* prof_ev;
+  int prof_cap, prof_n;
 };
 
 inline int64_t head_index(const Cache* c, int layer, int b, int kvh) {

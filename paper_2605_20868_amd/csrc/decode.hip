@@ -281,55 +281,113 @@ struct ReduceArgs {
   int nsplit, nb, r, n_q, n_kv;
 };
 
-__device__ __forceinline__ float block128_sum(float v, float* scratch2) {
+constexpr int RED_THREADS = 256;
+
+// block-wide sum / max over 256 threads; every thread gets the result
+__device__ __forceinline__ float block_sum(float v, float* scratch4) {
 #pragma unroll
   for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
   __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch2[threadIdx.x >> 6] = v;
+  if ((threadIdx.x & 63) == 0) scratch4[threadIdx.x >> 6] = v;
   __syncthreads();
-  return scratch2[0] + scratch2[1];
+  return (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
+}
+__device__ __forceinline__ float block_max(float v, float* scratch4) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(scratch4[0], scratch4[1]), fmaxf(scratch4[2], scratch4[3]));
 }
 
-__global__ __launch_bounds__(128) void certified_reduce_kernel(ReduceArgs a) {
-  const int c = threadIdx.x;
+__global__ __launch_bounds__(RED_THREADS) void certified_reduce_kernel(ReduceArgs a) {
+  const int t = threadIdx.x, w = t >> 6, l = t & 63;
+  const int c = t & (D - 1);            // channel owned by threads 0..127 in the epilogue
+  const bool own = t < D;
   const int hq = blockIdx.x, b = blockIdx.y;
   const int group = a.n_q / a.n_kv;
   const int kvh = hq / group;
   const float inv_sqrt_d = 0.08838834764831845f;
-  __shared__ float scratch2[2];
+  __shared__ float scratch4[4];
+  __shared__ float wsm[MAX_SPLITS];     // per-split max, then per-split weight e^{m_s - M}
+  __shared__ float t2s[4][3];
+  __shared__ __align__(8) float osum[4][D];
 
   const float* part = a.partials + ((int64_t)b * a.n_q + hq) * a.nsplit * PART_FLOATS;
-  float M = -INFINITY;
-  for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, part[s * PART_FLOATS + P_M]);
-  float L = 0.0f, o = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f;
+  // ---- per-split scalars, spread over the threads
+  float m_loc = -INFINITY;
+  for (int s = t; s < a.nsplit; s += RED_THREADS) {
+    const float m = part[s * PART_FLOATS + P_M];
+    wsm[s] = m;
+    m_loc = fmaxf(m_loc, m);
+  }
+  float M = block_max(m_loc, scratch4);
+  float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f;
   float T1 = -INFINITY, T2 = -INFINITY;
   int I1 = -1;
-  for (int s = 0; s < a.nsplit; ++s) {
+  for (int s = t; s < a.nsplit; s += RED_THREADS) {
     const float* ps = part + s * PART_FLOATS;
-    const float f = __expf(ps[P_M] - M);
+    const float f = __expf(wsm[s] - M);
+    wsm[s] = f;
     L += f * ps[P_L];
-    o += f * ps[P_O + c];
     EV += f * ps[P_EV];
     EVM = fmaxf(EVM, f * ps[P_EVMAX]);
     DM = fmaxf(DM, ps[P_DMAX]);
     VM = fmaxf(VM, ps[P_VMAX]);
     top2_merge(T1, I1, T2, ps[P_T1], __float_as_int(ps[P_I1]), ps[P_T2]);
   }
+  L = block_sum(L, scratch4);
+  EV = block_sum(EV, scratch4);
+  EVM = block_max(EVM, scratch4);
+  DM = block_max(DM, scratch4);
+  VM = block_max(VM, scratch4);
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const float u1 = __shfl_xor(T1, m), u2 = __shfl_xor(T2, m);
+    const int j1 = __shfl_xor(I1, m);
+    top2_merge(T1, I1, T2, u1, j1, u2);
+  }
+  if (l == 0) {
+    t2s[w][0] = T1;
+    t2s[w][1] = T2;
+    t2s[w][2] = __int_as_float(I1);
+  }
+  __syncthreads();   // also publishes wsm
+  T1 = t2s[0][0];
+  T2 = t2s[0][1];
+  I1 = __float_as_int(t2s[0][2]);
+#pragma unroll
+  for (int ww = 1; ww < 4; ++ww)
+    top2_merge(T1, I1, T2, t2s[ww][0], __float_as_int(t2s[ww][2]), t2s[ww][1]);
+
+  // ---- weighted sum of the partial outputs: wave w takes splits w, w+4, ...; lane l channels 2l, 2l+1
+  float2 o2 = make_float2(0.0f, 0.0f);
+#pragma unroll 4
+  for (int s = w; s < a.nsplit; s += 4) {
+    const float f = wsm[s];
+    const float2 x = reinterpret_cast<const float2*>(part + s * PART_FLOATS + P_O)[l];
+    o2.x = fmaf(f, x.x, o2.x);
+    o2.y = fmaf(f, x.y, o2.y);
+  }
+  reinterpret_cast<float2*>(&osum[w][0])[l] = o2;
+  __syncthreads();
+  float o = (osum[0][c] + osum[1][c]) + (osum[2][c] + osum[3][c]);
   float L_sealed = L;
 
   // ---- trailing FP16 tokens: exact keys and values, eta = 0
   if (a.r > 0) {
-    const float qc = __half2float(a.q[((int64_t)b * a.n_q + hq) * D + c]);
+    const float qc = own ? __half2float(a.q[((int64_t)b * a.n_q + hq) * D + c]) : 0.0f;
     const __half* tk = a.trail_k + ((int64_t)b * a.n_kv + kvh) * BLK * D;
     const __half* tv = a.trail_v + ((int64_t)b * a.n_kv + kvh) * BLK * D;
     float st[BLK - 1];
     float vt[BLK - 1];
     float mt = -INFINITY;
-    for (int t = 0; t < a.r; ++t) {
-      vt[t] = __half2float(tv[t * D + c]);
-      st[t] = block128_sum(qc * __half2float(tk[t * D + c]), scratch2) * inv_sqrt_d;
-      mt = fmaxf(mt, st[t]);
-      const float n2 = block128_sum(vt[t] * vt[t], scratch2);
+    for (int tt = 0; tt < a.r; ++tt) {
+      vt[tt] = own ? __half2float(tv[tt * D + c]) : 0.0f;
+      st[tt] = block_sum(qc * __half2float(tk[tt * D + c]), scratch4) * inv_sqrt_d;
+      mt = fmaxf(mt, st[tt]);
+      const float n2 = block_sum(vt[tt] * vt[tt], scratch4);
       VM = fmaxf(VM, sqrtf(n2));
     }
     const float M2 = fmaxf(M, mt);
@@ -339,19 +397,19 @@ __global__ __launch_bounds__(128) void certified_reduce_kernel(ReduceArgs a) {
     EV *= fs;
     EVM *= fs;
     L_sealed = L;
-    for (int t = 0; t < a.r; ++t) {
-      const float pt = __expf(st[t] - M2);
+    for (int tt = 0; tt < a.r; ++tt) {
+      const float pt = __expf(st[tt] - M2);
       L += pt;
-      o = fmaf(pt, vt[t], o);
+      o = fmaf(pt, vt[tt], o);
     }
     M = M2;
   }
 
   const float out = o / L;
-  a.O[((int64_t)b * a.n_q + hq) * D + c] = out;
+  if (own) a.O[((int64_t)b * a.n_q + hq) * D + c] = out;
   const int bad = __syncthreads_or(!isfinite(out));
 
-  if (c == 0) {
+  if (t == 0) {
     const double Ld = (double)L;
     const double e_val = (double)EV / Ld;
     const double maxc = (double)EVM / Ld;
@@ -407,6 +465,7 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
                      : (4 * (int64_t)c->n_cu) / ((int64_t)c->desc.batch * c->desc.n_kv_heads);
   if (want < 1) want = 1;
   if (want > c->max_splits) want = c->max_splits;
+  if (want > MAX_SPLITS) want = MAX_SPLITS;
   if (c->forced_splits <= 0) {
     const int64_t cap = (n_blocks + 7) / 8;  // at least two blocks per wave
     if (want > cap) want = cap;
@@ -441,6 +500,8 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.n_q = hq;
     a.n_kv = hkv;
     const dim3 grid(nsplit, hkv, bt);
+    const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
+    if (prof) CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n], st));
     switch (hq / hkv) {
       case 1: hipLaunchKernelGGL(certified_split_kernel<1>, grid, dim3(256), 0, st, a); break;
       case 2: hipLaunchKernelGGL(certified_split_kernel<2>, grid, dim3(256), 0, st, a); break;
@@ -448,6 +509,10 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
       default: return CQA_ERR_UNSUPPORTED;
     }
     CQA_HIP(hipGetLastError());
+    if (prof) {
+      CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st));
+      ++c->prof_n;
+    }
   }
   ReduceArgs ra;
   ra.partials = c->partials;
@@ -463,7 +528,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   ra.r = r;
   ra.n_q = hq;
   ra.n_kv = hkv;
-  hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(128), 0, st, ra);
+  hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(RED_THREADS), 0, st, ra);
   CQA_HIP(hipGetLastError());
   return CQA_OK;
 }
