@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--context", type=int, default=None, help="override the context length (debug)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives or sharding are part of it); "
@@ -127,6 +129,12 @@ def main() -> int:
             cqa.cqa_cache_append(h, 0, ks[i], vs[i], 1, stream)
             return cqa.cqa_decode_step(h, 0, qs[i], tol, O, cert, flags, None, stream)
 
+        if args.copy_probe:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
         for i in range(W):
             step(i)
         torch.cuda.synchronize()
@@ -178,7 +186,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": achieved / PEAK_HBM_GBS,
             "traffic": read_traffic_note(),
-            "kernel": "certified_split_kernel<4>",
+            "kernel": "certified_split_mfma_kernel<4>",
             "kernel_mean_ms": mean_ms,
             "kernel_min_ms": min_ms,
             "algorithmic_bytes_per_launch": alg_bytes,

@@ -237,6 +237,10 @@ int32_t cqa_decode_splits(const cqa_cache* c, int32_t layer, int32_t* n_splits);
 /* Overrides the automatic split count (0 restores it).  For tests. */
 int32_t cqa_set_splits(cqa_cache* c, int32_t n_splits);
 
+/* Chooses the split-K decode kernel: 0 = matrix-core (MFMA) kernel, the default;
+ * 1 = the vector-ALU kernel (same results to rounding; kept as a cross-check).  For tests. */
+int32_t cqa_set_kernel_variant(cqa_cache* c, int32_t variant);
+
 const char* cqa_strerror(int32_t status);
 int32_t cqa_version(void);
 /* hipError_t of the last failing HIP call on this thread (0 if none). */

@@ -109,6 +109,7 @@ def _load():
         "cqa_profile_end": (i32, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]),
         "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
         "cqa_set_splits": (i32, [vp, i32]),
+        "cqa_set_kernel_variant": (i32, [vp, i32]),
         "cqa_strerror": (C.c_char_p, [i32]),
         "cqa_version": (i32, []),
         "cqa_last_hip_error": (i32, []),
@@ -267,6 +268,10 @@ def cqa_decode_splits(h, layer) -> int:
     n = C.c_int32(0)
     _check(_lib.cqa_decode_splits(h, layer, C.byref(n)), "cqa_decode_splits")
     return n.value
+
+
+def cqa_set_kernel_variant(h, variant) -> None:
+    _check(_lib.cqa_set_kernel_variant(h, variant), "cqa_set_kernel_variant")
 
 
 def cqa_set_splits(h, n_splits) -> None:

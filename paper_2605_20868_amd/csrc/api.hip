@@ -241,6 +241,12 @@ int32_t cqa_set_splits(cqa_cache* h, int32_t n_splits) {
   return CQA_OK;
 }
 
+int32_t cqa_set_kernel_variant(cqa_cache* h, int32_t variant) {
+  if (h == nullptr || variant < 0 || variant > 1) return CQA_ERR_INVALID_ARG;
+  h->impl.variant = variant;
+  return CQA_OK;
+}
+
 int32_t cqa_decode_splits(const cqa_cache* h, int32_t layer, int32_t* n_splits) {
   if (h == nullptr || n_splits == nullptr || layer < 0 || layer >= h->impl.desc.n_layers)
     return CQA_ERR_INVALID_ARG;

@@ -101,7 +101,25 @@ struct Cache {
   // optional per-launch timing of the split kernel (pairs of events on the launch stream)
   hipEvent_t* prof_ev;
   int prof_cap, prof_n;
+  int variant;               // 0 = matrix-core split kernel (default), 1 = vector-ALU split kernel
 };
+
+struct DecodeArgs {
+  const uint8_t* kc;   // layer base of each Tier-1 stream
+  const float* km;
+  const uint8_t* vc;
+  const __half* vm;
+  const float* an;
+  const __half* q;     // [Bt][Hq][128]
+  float* partials;     // [Bt][Hq][nsplit][PART_FLOATS]
+  float* blk_logmass;  // [Bt][Hq][nb] or null
+  int64_t nb_cap;
+  int nb;              // sealed blocks
+  int nsplit;
+  int bps;             // blocks per split
+  int n_q, n_kv;
+};
+
 
 inline int64_t head_index(const Cache* c, int layer, int b, int kvh) {
   return ((int64_t)layer * c->desc.batch + b) * c->desc.n_kv_heads + kvh;
@@ -123,6 +141,8 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, float* blk_logmass, hipStream_t st);
 int pick_splits(const Cache* c, int64_t n_blocks);
+void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
+int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipStream_t st);
 
 int dense_splits(int64_t n_tokens);
 // Dense FP16 attention for the G query heads of ONE kv group: k, v point at [n_tokens][128];

