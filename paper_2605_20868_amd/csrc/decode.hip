@@ -44,8 +44,9 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   const int vn = l & 15, vgh = (l >> 4) & 1, vo = l >> 5;  // roles in the value phase
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int64_t base_blk = ((int64_t)b * a.n_kv + kvh) * a.nb_cap;
-  const int b0 = split * a.bps;
-  const int b1 = min(b0 + a.bps, a.nb);
+  // blocks are dealt evenly over the splits (every split gets at least one: nsplit <= nb)
+  const int b0 = (int)(((int64_t)split * a.nb) / a.nsplit);
+  const int b1 = (int)(((int64_t)(split + 1) * a.nb) / a.nsplit);
   const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
 
   __shared__ __align__(16) float qs[4][G][D];     // scaled query of the block in flight, per wave
@@ -443,28 +444,26 @@ __global__ __launch_bounds__(RED_THREADS) void certified_reduce_kernel(ReduceArg
   }
 }
 
-// Splits per (batch, kv-head) and blocks per split.  Each workgroup's four waves take blocks in
-// units of four (the MFMA pass works on quads), so blocks-per-split is rounded to 16 where the
-// sequence is long enough; a ragged last split is masked inside the kernels.
+// Workgroups ("splits") per (batch, kv-head) and, for the vector-ALU kernel, blocks per split.
+// The launch is sized to ONE resident generation: two workgroups of four waves per compute unit
+// (the matrix-core kernel runs at two waves per SIMD), so no workgroup waits for a slot and the
+// per-wave start-up latency is paid once.  The matrix-core kernel deals the head's quads of
+// blocks evenly over all 4 * nsplit waves; short sequences get fewer workgroups so that every
+// wave still has at least one quad.
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps) {
   *nsplit = 0;
   *bps = 0;
   if (n_blocks <= 0) return;
-  int64_t want = c->forced_splits > 0
-                     ? c->forced_splits
-                     : (4 * (int64_t)c->n_cu) / ((int64_t)c->desc.batch * c->desc.n_kv_heads);
+  const int64_t heads = (int64_t)c->desc.batch * c->desc.n_kv_heads;
+  int64_t want = c->forced_splits > 0 ? c->forced_splits : (2 * (int64_t)c->n_cu + heads - 1) / heads;
   if (want < 1) want = 1;
   if (want > c->max_splits) want = c->max_splits;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
-  if (c->forced_splits <= 0) {
-    const int64_t cap = (n_blocks + 15) / 16;  // at least one quad per wave
-    if (want > cap) want = cap;
-  }
-  if (want > n_blocks) want = n_blocks;
-  int64_t per = (n_blocks + want - 1) / want;
-  if (c->forced_splits <= 0) per = (per + 15) / 16 * 16;
-  *bps = (int)per;
-  *nsplit = (int)((n_blocks + per - 1) / per);
+  const int64_t quads = (n_blocks + 3) / 4;
+  const int64_t cap = (quads + 3) / 4;   // at least one quad per wave
+  if (want > cap) want = cap;
+  *nsplit = (int)want;
+  *bps = (int)((n_blocks + want - 1) / want);
 }
 
 int pick_splits(const Cache* c, int64_t n_blocks) {

@@ -19,15 +19,21 @@
 //           folded into  sum_t p_t (offset_{t,g} - 16 scale_{t,g}),  accumulated on the VALU.
 //
 // Lane roles (l = lane, n = l & 15, kg = l >> 4, h = n >> 2, j = g' = n & 3):
-//   score phase : column n = (head h, block j of the quad); kg = 8-channel slice
-//   value phase : row    n = (head h, group g' of the tile set); kg = 8-token slice
-//   accumulators: C[row = 4 kg + v][col = n]  ->  head kg, vgpr v = g', channel n
+//   operand forming: scaled query of row (head h, block j), channels of slice kg;
+//                    value weights of row (head h, group g'), 8-token slice kg
+//   score results  : C_i[row 4 kg + v][col n] -> head kg, block v (v == i kept), token n, so the
+//                    softmax state of head kg lives in row kg and token reductions are DPP row ops
+//   accumulators   : acc_g[row 4 kg + v][col n] -> head kg, group set member v = g & 3, channel n
+// The raw data of the next quad is loaded while the current one is processed; the per-block
+// metadata (sigma, z, scale, offset) is staged through wave-private LDS so that each byte is
+// fetched once although four heads consume it.
 #include "cqa_internal.h"
 
 namespace cqa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 union BF8 {
   bf16x8 v;
@@ -72,76 +78,136 @@ __device__ __forceinline__ void top2_merge_m(float& t1, int& i1, float& t2, floa
   }
 }
 
+// DPP moves inside a row of 16 lanes (no LDS round trip)
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __uint_as_float(
+      (uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true));
+}
+// all-reduce over the 16 lanes of a row: quad xor 1, quad xor 2, half-row mirror, row mirror
+__device__ __forceinline__ float row_max(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));
+  x = fmaxf(x, dpp_mov<0x4E>(x));
+  x = fmaxf(x, dpp_mov<0x141>(x));
+  x = fmaxf(x, dpp_mov<0x140>(x));
+  return x;
+}
+__device__ __forceinline__ float row_sum(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  x += dpp_mov<0x141>(x);
+  x += dpp_mov<0x140>(x);
+  return x;
+}
+
+constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: bank spread over blocks)
+constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
+constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
+
 template <int G>
-__global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a) {
-  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a) {
+  const int l = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
-  const int h = n >> 2, j = n & 3;
-  const bool hvalid = h < G;
+  const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int64_t base_blk = ((int64_t)b * a.n_kv + kvh) * a.nb_cap;
-  const int b0 = split * a.bps;
-  const int b1 = min(b0 + a.bps, a.nb);
+  // This wave's contiguous run of quads: the head's quads are dealt out evenly (sizes differ by
+  // at most one) over all 4 * nsplit waves that work on the head.
+  const int nquads = (a.nb + 3) >> 2;
+  const int gw = split * 4 + w, nw = a.nsplit * 4;
+  const int b0 = 4 * (int)(((int64_t)gw * nquads) / nw);
+  const int b1 = min(4 * (int)(((int64_t)(gw + 1) * nquads) / nw), a.nb);
   const float inv_sqrt_d = 0.08838834764831845f;
 
-  __shared__ __align__(16) float pbuf[4][4][4][BLK];  // [wave][head][block of quad][token]
+  __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
+  __shared__ __align__(16) __half vmbuf[4][4][VM_ROW];   // [wave][block of quad][scale | offset]
+  __shared__ __align__(16) float pbuf[4][4][P_HEAD];     // [wave][head][block of quad][token]
+  __shared__ __align__(16) float cbuf[4][2][4][4];       // [wave][c_b | Delta_b][head][block]
+  __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
+  __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
-  // query of my head, my 32 channels: channel(u, e) = (u>>1)*64 + kg*16 + (u&1)*8 + e
-  float qreg[32];
-  {
-    const __half* qh = a.q + ((int64_t)b * a.n_q + kvh * G + (hvalid ? h : 0)) * D;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint4 x = *reinterpret_cast<const uint4*>(qh + (u >> 1) * 64 + kg * 16 + (u & 1) * 8);
-      const __half2* hh = reinterpret_cast<const __half2*>(&x);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        qreg[u * 8 + 2 * e] = hvalid ? __low2float(hh[e]) : 0.0f;
-        qreg[u * 8 + 2 * e + 1] = hvalid ? __high2float(hh[e]) : 0.0f;
-      }
-    }
+  // queries of the group as FP32 in LDS, rows of absent heads zero; lane (h, kg) reads the
+  // channels (u>>1)*64 + kg*16 + (u&1)*8 + e of head h when it forms slice u
+  for (int idx = threadIdx.x; idx < 4 * D; idx += 256) {
+    const int hh = idx / D, c = idx % D;
+    qbuf[hh][c] = hh < G ? __half2float(a.q[((int64_t)b * a.n_q + kvh * G + hh) * D + c]) : 0.0f;
   }
+  __syncthreads();
 
+  // softmax state of head kg (replicated over the 16 lanes of the row)
   float m_run = -INFINITY, l_run = 0.0f, ev = 0.0f, evmax = 0.0f, dmax = 0.0f, vmax = 0.0f;
   float t1 = -INFINITY, t2 = -INFINITY;
   int i1 = -1;
-  float offacc[2] = {0.0f, 0.0f};
+  float offacc[2] = {0.0f, 0.0f};   // offset sums of (head h, groups g', 4 + g'), operand role
   f32x4 acc[8];
 #pragma unroll
   for (int g = 0; g < 8; ++g) acc[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  for (int qb = b0 + 4 * w; qb < b1; qb += 16) {
-    const int myblk = qb + j;
-    const bool bvalid = myblk < b1;
-    const int64_t gbj = base_blk + min(myblk, a.nb - 1);
+  // Loads of one quad.  Block indices are clamped to the split's last block, so a ragged tail
+  // and the prefetch issued by the last iteration re-read valid (cached) memory; what they
+  // bring in is masked or never used.  The prefetch is unconditional on purpose: guarding it
+  // with a branch makes every prefetched register a phi and costs dozens of spilled VGPRs.
+  //   K codes : block i, channel half cq; lane (token n, kg) takes bytes [16 l, +16) of each KB
+  //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
+  //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
+  //             2r + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
+  const int bl = max(b1 - 1, 0);   // last block of this wave's run
+#define CQA_LOAD_K(QB)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
+    const uint8_t* kcb = a.kc + (base_blk + min((QB) + i, bl)) * KC_BYTES;         \
+    kraw[i][0] = reinterpret_cast<const uint4*>(kcb)[l];                                 \
+    kraw[i][1] = reinterpret_cast<const uint4*>(kcb + 1024)[l];                          \
+  }
+#define CQA_LOAD_V(QB)                                                                   \
+  _Pragma("unroll") for (int P = 0; P < 2; ++P) {                                        \
+    const int64_t gbp = base_blk + min((QB) + 2 * P + (kg >> 1), bl);              \
+    const uint8_t* vcb = a.vc + gbp * VC_BYTES + (kg & 1) * 512 + n * 16;                \
+    vraw[P][0] = *reinterpret_cast<const uint4*>(vcb);                                   \
+    vraw[P][1] = *reinterpret_cast<const uint4*>(vcb + 256);                             \
+  }
+#define CQA_LOAD_META(QB)                                                                \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
+    const int64_t gb = base_blk + min((QB) + i, bl);                               \
+    km_n[i] = reinterpret_cast<const u32x4*>(a.km + gb * (KM_BYTES / 4))[l];             \
+    an_n[i] = *reinterpret_cast<const float2*>(a.an + gb * 2);                           \
+  }                                                                                      \
+  _Pragma("unroll") for (int P = 0; P < 2; ++P) {                                        \
+    const int64_t gbm = base_blk + min((QB) + 2 * P + (l >> 5), bl);               \
+    vm_n[P] = reinterpret_cast<const u32x4*>(a.vm + gbm * (VM_BYTES / 2))[l & 31];       \
+  }
 
-    // ---- loads of the quad
-    uint4 kraw[4][2];
+  // Software pipeline: the K codes of quad k+1 are requested after the score phase of quad k
+  // (into the registers it has just freed), the V codes of quad k at the top of its iteration
+  // (used after the score phase), the metadata of quad k+1 at the top of iteration k.
+  uint4 kraw[4][2], vraw[2][2];
+  u32x4 km_n[4], vm_n[2];
+  float2 an_n[4];
+  int qb = b0;
+  if (qb < b1) {
+    CQA_LOAD_META(qb)   // same issue order as in the loop: metadata, then K codes
+    CQA_LOAD_K(qb)
+  }
+
+  for (; qb < b1; qb += 4) {
+    float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint8_t* kcb = a.kc + (base_blk + min(qb + i, a.nb - 1)) * KC_BYTES;
-#pragma unroll
-      for (int cq = 0; cq < 2; ++cq) kraw[i][cq] = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
+      an[i] = an_n[i];
+      reinterpret_cast<u32x4*>(&kmbuf[w][i][0])[l] = km_n[i];
     }
-    const float* kmb = a.km + gbj * (KM_BYTES / 4);
-    const float2 an = *reinterpret_cast<const float2*>(a.an + gbj * 2);
-    uint4 vraw[2][2], sraw[2][2], oraw[2][2];
 #pragma unroll
-    for (int P = 0; P < 2; ++P) {
-      const int64_t gbp = base_blk + min(qb + 2 * P + (kg >> 1), a.nb - 1);
-      const uint8_t* vcb = a.vc + gbp * VC_BYTES + (kg & 1) * 512 + n * 16;
-      const __half* vmb = a.vm + gbp * (VM_BYTES / 2) + (kg & 1) * 64;
-#pragma unroll
-      for (int gs = 0; gs < 2; ++gs) {
-        vraw[P][gs] = *reinterpret_cast<const uint4*>(vcb + gs * 256);
-        sraw[P][gs] = *reinterpret_cast<const uint4*>(vmb + (4 * gs + j) * 8);
-        oraw[P][gs] = *reinterpret_cast<const uint4*>(vmb + BLK * NG + (4 * gs + j) * 8);
-      }
-    }
+    for (int P = 0; P < 2; ++P)
+      reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
+    CQA_LOAD_V(qb)
+    CQA_LOAD_META(qb + 4)
+    wave_sync_m();
 
-    // ---- scores: B (scaled query, 3 bf16 terms) per channel slice u, A per block
+    // ---- scores.  A operand: scaled query of column-role (h, j), three bf16 terms;
+    //      B operand: the 16 tokens of block i as exact bf16 integers (code + 128).
+    //      C_i[row (head kg, block v)][col token n]: row v == i is the one kept.
     f32x4 C[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -149,16 +215,19 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
-      const float4 s0 = *reinterpret_cast<const float4*>(kmb + c0);
-      const float4 s1 = *reinterpret_cast<const float4*>(kmb + c0 + 4);
-      const float4 z0 = *reinterpret_cast<const float4*>(kmb + D + c0);
-      const float4 z1 = *reinterpret_cast<const float4*>(kmb + D + c0 + 4);
+      const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
+      const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
+      const float4 z0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0]);
+      const float4 z1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0 + 4]);
+      const float4 q0 = *reinterpret_cast<const float4*>(&qbuf[h][c0]);
+      const float4 q1 = *reinterpret_cast<const float4*>(&qbuf[h][c0 + 4]);
       const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
       const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+      const float qq[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
       float qt[8], r1[8], r2[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float qv = qreg[u * 8 + e];
+        const float qv = qq[e];
         qt[e] = qv * sg[e];
         csum = fmaf(qv, zz[e], csum);
         qsum += qt[e];
@@ -166,12 +235,12 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
         r1[e] = qt[e] - trunc_bf16(qt[e]);
         r2[e] = r1[e] - trunc_bf16(r1[e]);
       }
-      BF8 bh, bm, bl;
+      BF8 qh3, qm3, ql3;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        bh.u[p] = pack_hi16(qt[2 * p + 1], qt[2 * p]);
-        bm.u[p] = pack_hi16(r1[2 * p + 1], r1[2 * p]);
-        bl.u[p] = pack_rne(r2[2 * p + 1], r2[2 * p]);
+        qh3.u[p] = pack_hi16(qt[2 * p + 1], qt[2 * p]);
+        qm3.u[p] = pack_hi16(r1[2 * p + 1], r1[2 * p]);
+        ql3.u[p] = pack_rne(r2[2 * p + 1], r2[2 * p]);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -183,100 +252,104 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
           kf[e] = (float)((d0 >> (8 * e)) & 0xffu);
           kf[4 + e] = (float)((d1 >> (8 * e)) & 0xffu);
         }
-        BF8 av;
+        BF8 kv;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) av.u[p] = pack_hi16(kf[2 * p + 1], kf[2 * p]);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, bh.v, C[i], 0, 0, 0);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, bm.v, C[i], 0, 0, 0);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, bl.v, C[i], 0, 0, 0);
+        for (int p = 0; p < 4; ++p) kv.u[p] = pack_hi16(kf[2 * p + 1], kf[2 * p]);
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh3.v, kv.v, C[i], 0, 0, 0);
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qm3.v, kv.v, C[i], 0, 0, 0);
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql3.v, kv.v, C[i], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
     }
-    // per-block constant c_b = q.z - 128 sum(q~) (stored bytes are code + 128) and Delta_b
+    CQA_LOAD_K(qb + 4)
+    // per-block constant c_b = q.z - 128 sum(q~) (stored bytes are code + 128) and Delta_b:
+    // summed over the four channel slices, then handed to the rows that own head kg
     float cb = fmaf(-128.0f, qsum, csum);
     cb += __shfl_xor(cb, 16);
     cb += __shfl_xor(cb, 32);
     dsum += __shfl_xor(dsum, 16);
     dsum += __shfl_xor(dsum, 32);
-
-    // my column's block is j: tokens 4 kg .. 4 kg + 3 of it
-    float s[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const float raw = j == 0 ? C[0][v] : (j == 1 ? C[1][v] : (j == 2 ? C[2][v] : C[3][v]));
-      s[v] = (raw + cb) * inv_sqrt_d;
+    if (kg == 0) {
+      cbuf[w][0][h][j] = cb;
+      cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d);
     }
+    wave_sync_m();
+    const float4 cb4 = *reinterpret_cast<const float4*>(&cbuf[w][0][kg][0]);
+    const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
+    const float cbs[4] = {cb4.x, cb4.y, cb4.z, cb4.w};
+    const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
 
-    // ---- block statistics and online softmax (state replicated over the lanes of a head)
-    float mb = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    mb = fmaxf(mb, __shfl_xor(mb, 16));
-    mb = fmaxf(mb, __shfl_xor(mb, 32));
-    float pt[4];
-    float sb = 0.0f;
+    // ---- block statistics and online softmax of head kg; this lane is token n of each block
+    float mbv[4], ptv[4], sbv[4];
+    float mq = -INFINITY;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      pt[v] = bvalid ? __expf(s[v] - mb) : 0.0f;
-      sb += pt[v];
+    for (int i = 0; i < 4; ++i) {
+      const float s = (C[i][i] + cbs[i]) * inv_sqrt_d;
+      mbv[i] = row_max(s);
+      ptv[i] = __expf(s - mbv[i]);
+      sbv[i] = row_sum(ptv[i]);
+      if (qb + i < b1) mq = fmaxf(mq, mbv[i]);
     }
-    sb += __shfl_xor(sb, 16);
-    sb += __shfl_xor(sb, 32);
-    const float lb = bvalid ? mb + __logf(sb) : -INFINITY;
-    float mq = bvalid ? mb : -INFINITY;
-    mq = fmaxf(mq, __shfl_xor(mq, 1));
-    mq = fmaxf(mq, __shfl_xor(mq, 2));
     const float m_new = fmaxf(m_run, mq);
     const float alpha = __expf(m_run - m_new);
-    const float f = bvalid ? __expf(mb - m_new) : 0.0f;
-    const float sf = sb * f;
-    const float ce = sf * an.x;
-    float sq = sf, ceq = ce, cem = ce;
-    sq += __shfl_xor(sq, 1);
-    ceq += __shfl_xor(ceq, 1);
-    cem = fmaxf(cem, __shfl_xor(cem, 1));
-    sq += __shfl_xor(sq, 2);
-    ceq += __shfl_xor(ceq, 2);
-    cem = fmaxf(cem, __shfl_xor(cem, 2));
-    l_run = fmaf(l_run, alpha, sq);
-    ev = fmaf(ev, alpha, ceq);
-    evmax = fmaxf(evmax * alpha, cem);
+    l_run *= alpha;
+    ev *= alpha;
+    evmax *= alpha;
     m_run = m_new;
-    if (bvalid) {
-      dmax = fmaxf(dmax, dsum * (0.5f * inv_sqrt_d));
-      vmax = fmaxf(vmax, an.y);
-      if (lb > t1) {
-        t2 = t1;
-        t1 = lb;
-        i1 = myblk;
-      } else if (lb > t2) {
-        t2 = lb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float p = 0.0f;
+      if (qb + i < b1) {
+        const float f = __expf(mbv[i] - m_new);
+        p = ptv[i] * f;
+        const float sf = sbv[i] * f;
+        const float ce = sf * an[i].x;
+        const float lb = mbv[i] + __logf(sbv[i]);
+        l_run += sf;
+        ev += ce;
+        evmax = fmaxf(evmax, ce);
+        dmax = fmaxf(dmax, dls[i]);
+        vmax = fmaxf(vmax, an[i].y);
+        if (lb > t1) {
+          t2 = t1;
+          t1 = lb;
+          i1 = qb + i;
+        } else if (lb > t2) {
+          t2 = lb;
+        }
+        if (a.blk_logmass != nullptr && n == 0 && kg < G)
+          a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lb;
       }
-      if (a.blk_logmass != nullptr && kg == 0 && hvalid)
-        a.blk_logmass[((int64_t)b * a.n_q + kvh * G + h) * a.nb + myblk] = lb;
+      pbuf[w][kg][i * BLK + n] = p;
     }
-    *reinterpret_cast<float4*>(&pbuf[w][h][j][kg * 4]) =
-        make_float4(pt[0] * f, pt[1] * f, pt[2] * f, pt[3] * f);
+    if (n == 0) abuf[w][kg] = alpha;
     wave_sync_m();
 
-    // ---- rescale the output accumulators (head of an accumulator lane is kg)
-    const float alpha_acc = __shfl(alpha, kg * 4);
-    if (__any(alpha_acc != 1.0f)) {
+    // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
+    if (__any(alpha != 1.0f)) {
 #pragma unroll
       for (int g = 0; g < 8; ++g)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[g][v] *= alpha_acc;
+        for (int v = 0; v < 4; ++v) acc[g][v] *= alpha;
     }
-    offacc[0] *= alpha;
-    offacc[1] *= alpha;
+    const float alpha_op = abuf[w][h];
+    offacc[0] *= alpha_op;
+    offacc[1] *= alpha_op;
 
-    // ---- values: two pairs of blocks, K = 32 tokens each
+    // ---- values: two pairs of blocks, K = 32 tokens each; operand role (head h, group g' = j)
 #pragma unroll
     for (int P = 0; P < 2; ++P) {
-      const float4 pa = *reinterpret_cast<const float4*>(&pbuf[w][h][2 * P + (kg >> 1)][(kg & 1) * 8]);
-      const float4 pb = *reinterpret_cast<const float4*>(&pbuf[w][h][2 * P + (kg >> 1)][(kg & 1) * 8 + 4]);
+      const int bi = 2 * P + (kg >> 1);
+      const float4 pa = *reinterpret_cast<const float4*>(&pbuf[w][h][bi * BLK + (kg & 1) * 8]);
+      const float4 pb = *reinterpret_cast<const float4*>(&pbuf[w][h][bi * BLK + (kg & 1) * 8 + 4]);
       const float p8[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
 #pragma unroll
       for (int gs = 0; gs < 2; ++gs) {
-        const __half2* sh = reinterpret_cast<const __half2*>(&sraw[P][gs]);
-        const __half2* oh = reinterpret_cast<const __half2*>(&oraw[P][gs]);
+        const __half* vmp = &vmbuf[w][bi][(kg & 1) * 64 + (4 * gs + j) * 8];
+        const uint4 sraw = *reinterpret_cast<const uint4*>(vmp);
+        const uint4 oraw = *reinterpret_cast<const uint4*>(vmp + BLK * NG);
+        const __half2* sh = reinterpret_cast<const __half2*>(&sraw);
+        const __half2* oh = reinterpret_cast<const __half2*>(&oraw);
         float wv[8], wr[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -301,10 +374,10 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
         for (int t = 0; t < 4; ++t) {
           const uint32_t x = xs[t];
           BF8 bv;   // bf16(16 + code): exponent bits 0x4180, code in mantissa bits 6..3
-          bv.u[0] = ((x << 3) & 0x00780078u) | 0x41804180u;
-          bv.u[1] = ((x >> 1) & 0x00780078u) | 0x41804180u;
-          bv.u[2] = ((x >> 5) & 0x00780078u) | 0x41804180u;
-          bv.u[3] = ((x >> 9) & 0x00780078u) | 0x41804180u;
+          bv.u[0] = ((x << 3) & 0x00780078u) | (0x41804180u & ~0x00780078u);
+          bv.u[1] = ((x >> 1) & 0x00780078u) | (0x41804180u & ~0x00780078u);
+          bv.u[2] = ((x >> 5) & 0x00780078u) | (0x41804180u & ~0x00780078u);
+          bv.u[3] = ((x >> 9) & 0x00780078u) | (0x41804180u & ~0x00780078u);
           acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.v, bv.v, acc[4 * gs + t], 0, 0, 0);
           acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, bv.v, acc[4 * gs + t], 0, 0, 0);
         }
@@ -313,37 +386,30 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
     wave_sync_m();
   }
 
-  // ---- per-wave epilogue: fold the offset sums in, reduce the per-lane trackers over the head's lanes
+  // ---- per-wave epilogue: fold the offset sums in; the softmax state of head kg is already
+  //      complete in every lane of row kg
 #pragma unroll
   for (int gs = 0; gs < 2; ++gs) {
     offacc[gs] += __shfl_xor(offacc[gs], 16);
     offacc[gs] += __shfl_xor(offacc[gs], 32);
   }
 #pragma unroll
-  for (int m = 1; m <= 2; m <<= 1) {
-    dmax = fmaxf(dmax, __shfl_xor(dmax, m));
-    vmax = fmaxf(vmax, __shfl_xor(vmax, m));
-    const float u1 = __shfl_xor(t1, m), u2 = __shfl_xor(t2, m);
-    const int j1 = __shfl_xor(i1, m);
-    top2_merge_m(t1, i1, t2, u1, j1, u2);
-  }
-  __syncthreads();
-#pragma unroll
   for (int g = 0; g < 8; ++g) {
     const float off = __shfl(offacc[g >> 2], kg * 4 + (g & 3));
     const float val = (g & 3) == 0 ? acc[g][0] : ((g & 3) == 1 ? acc[g][1] : ((g & 3) == 2 ? acc[g][2] : acc[g][3]));
     if (kg < G) mo[w][kg < G ? kg : 0][g * 16 + n] = val + off;
   }
-  if (kg == 0 && j == 0 && hvalid) {
-    ms[w][h][0] = m_run;
-    ms[w][h][1] = l_run;
-    ms[w][h][2] = ev;
-    ms[w][h][3] = evmax;
-    ms[w][h][4] = dmax;
-    ms[w][h][5] = vmax;
-    ms[w][h][6] = t1;
-    ms[w][h][7] = t2;
-    ms[w][h][8] = __int_as_float(i1);
+  if (n == 0 && kg < G) {
+    float* m = ms[w][kg < G ? kg : 0];
+    m[0] = m_run;
+    m[1] = l_run;
+    m[2] = ev;
+    m[3] = evmax;
+    m[4] = dmax;
+    m[5] = vmax;
+    m[6] = t1;
+    m[7] = t2;
+    m[8] = __int_as_float(i1);
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < G * D; idx += 256) {
@@ -383,6 +449,10 @@ __global__ __launch_bounds__(256) void certified_split_mfma_kernel(DecodeArgs a)
     pp[P_I1] = __int_as_float(I1);
   }
 }
+
+#undef CQA_LOAD_K
+#undef CQA_LOAD_V
+#undef CQA_LOAD_META
 
 int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
   switch (group) {
