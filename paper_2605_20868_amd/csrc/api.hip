@@ -69,6 +69,7 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->vc);
   (void)hipFree(c->vm);
   (void)hipFree(c->an);
+  (void)hipFree(c->sigmax);
   (void)hipFree(c->trail_k);
   (void)hipFree(c->trail_v);
   (void)hipFree(c->partials);
@@ -192,6 +193,8 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   CQA_ALLOC_DEV(c->vc, s.vc);
   CQA_ALLOC_DEV(c->vm, s.vm);
   CQA_ALLOC_DEV(c->an, s.an);
+  CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
+  CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
   CQA_ALLOC_DEV(c->trail_k, s.trail);
   CQA_ALLOC_DEV(c->trail_v, s.trail);
   CQA_ALLOC_DEV(c->partials, s.partials);
@@ -231,7 +234,11 @@ int32_t cqa_cache_length(const cqa_cache* h, int32_t layer, int64_t* n_tokens) {
 
 int32_t cqa_cache_reset(cqa_cache* h, int32_t layer) {
   if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers) return CQA_ERR_INVALID_ARG;
-  h->impl.length[layer] = 0;
+  Cache* c = &h->impl;
+  CQA_HIP(hipDeviceSynchronize());
+  CQA_HIP(hipMemset(c->sigmax + head_index(c, layer, 0, 0), 0,
+                    (size_t)c->desc.batch * c->desc.n_kv_heads * 4));
+  c->length[layer] = 0;
   return CQA_OK;
 }
 
@@ -242,8 +249,9 @@ int32_t cqa_set_splits(cqa_cache* h, int32_t n_splits) {
 }
 
 int32_t cqa_set_kernel_variant(cqa_cache* h, int32_t variant) {
-  if (h == nullptr || variant < 0 || variant > 1) return CQA_ERR_INVALID_ARG;
-  h->impl.variant = variant;
+  if (h == nullptr || variant < 0 || variant > 0x101) return CQA_ERR_INVALID_ARG;
+  h->impl.variant = variant & 1;
+  h->impl.debug = variant >> 8;
   return CQA_OK;
 }
 

@@ -80,6 +80,7 @@ struct Cache {
   uint8_t* vc;
   __half* vm;
   float* an;
+  float* sigmax;             // [heads_total] running max of sigma (non-negative: ordered as ints)
   // trailing FP16 partial blocks [heads_total][16][128]
   __half* trail_k;
   __half* trail_v;
@@ -101,6 +102,7 @@ struct Cache {
   // optional per-launch timing of the split kernel (pairs of events on the launch stream)
   hipEvent_t* prof_ev;
   int prof_cap, prof_n;
+  int debug;                 // timing probes (0 in production)
   int variant;               // 0 = matrix-core split kernel (default), 1 = vector-ALU split kernel
 };
 
@@ -110,6 +112,7 @@ struct DecodeArgs {
   const uint8_t* vc;
   const __half* vm;
   const float* an;
+  const float* sigmax; // [Bt * Hkv] of the layer: running max of sigma over sealed blocks and channels
   const __half* q;     // [Bt][Hq][128]
   float* partials;     // [Bt][Hq][nsplit][PART_FLOATS]
   float* blk_logmass;  // [Bt][Hq][nb] or null
@@ -118,6 +121,7 @@ struct DecodeArgs {
   int nsplit;
   int bps;             // blocks per split
   int n_q, n_kv;
+  int debug;           // 0 in production; 1 = every load of a wave hits its first block (timing probe)
 };
 
 

@@ -488,6 +488,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.vc = c->vc + layer_head0 * c->nb_cap * VC_BYTES;
     a.vm = c->vm + layer_head0 * c->nb_cap * (VM_BYTES / 2);
     a.an = c->an + layer_head0 * c->nb_cap * 2;
+    a.sigmax = c->sigmax + layer_head0;
     a.q = q;
     a.partials = c->partials;
     a.blk_logmass = blk_logmass;
@@ -497,6 +498,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;
+    a.debug = c->debug;
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
     if (prof) CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n], st));

@@ -2,17 +2,17 @@
 //
 // Same mathematics as the paper's Algorithm 1 with no promoted blocks and its
 // scaled-query identity  q . k_hat = sum_c (q_c sigma_c) code_c + sum_c q_c z_c;
-// the two contractions run as bf16 MFMAs with FP32 accumulation:
+// the two contractions run as 16x16x32 MFMAs with FP32 accumulation:
 //
-//  scores   S[token][(h, j)] = sum_c code[token][c] * q~[(h, j)][c]
+//  scores   S[(h, j)][token] = sum_c q~[(h, j)][c] * code[token][c]            (FP16 inputs)
 //           One wave takes four consecutive blocks (a "quad") per iteration.
-//           A = the 16 tokens of block i as exact bf16 integers (u = code + 128);
-//           B = 16 columns = 4 query heads x the 4 blocks of the quad, each column
-//           holding that block's scaled query q~ = q (.) sigma as THREE bf16 terms
-//           (hi + mid + lo = 24 significant bits, i.e. FP32-exact); only the
-//           columns of block i are kept from A_i's product.  Forming B once per
-//           quad keeps every lane busy: lane (n, kg) owns column n, channels of kg.
-//  values   O[(h, g')][c] = sum_t w[t][(h, g')] * (16 + code[t][c]),
+//           B = the 16 tokens of block i, codes as exact FP16 integers;
+//           A = 16 rows = 4 query heads x the 4 blocks of the quad, each row holding that
+//           block's scaled query q~ = q (.) sigma as TWO FP16 terms (hi + lo, 22 significant
+//           bits), q pre-scaled per head by a power of two so that q~ cannot overflow FP16;
+//           only the rows of block i are kept from B_i's product.  Forming A once per quad
+//           keeps every lane busy: lane (n, kg) owns row n, channels of slice kg.
+//  values   O[(h, g')][c] = sum_t w[t][(h, g')] * (16 + code[t][c])               (bf16 inputs)
 //           w = p_t * scale_{t,g} as TWO bf16 terms, K = 32 tokens (two blocks),
 //           one 16-channel value group per tile; the bias 16 (which makes the
 //           4-bit code an exact bf16 by bit insertion) and the group offsets are
@@ -35,10 +35,30 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
 union BF8 {
   bf16x8 v;
   uint32_t u[4];
 };
+union HF8 {
+  f16x8 v;
+  uint32_t u[4];
+};
+
+// two FP32 values -> packed FP16, round toward zero (never overflows to infinity); x0 in the low half
+__device__ __forceinline__ f16x2 pack_f16_rtz(float x0, float x1) {
+  return __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(x0, x1));
+}
+// bytes (b_lo, b_hi) of a dword -> FP16 pair (b_lo - 128, b_hi - 128): the byte is dropped into the
+// mantissa of 1024.0 (0x6400 | b = 1024 + b exactly) and 1152 is subtracted, both exact
+template <uint32_t SEL>
+__device__ __forceinline__ uint32_t bytes_to_f16_codes(uint32_t d) {
+  const uint32_t m = __builtin_amdgcn_perm(0x64646464u, d, SEL);
+  const f16x2 c = {(_Float16)-1152.0f, (_Float16)-1152.0f};
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, m) + c);
+}
 
 __device__ __forceinline__ void wave_sync_m() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -61,6 +81,12 @@ __device__ __forceinline__ uint32_t pack_rne(float x1, float x0) {
   } r;
   r.v = __builtin_convertvector(x, bf16x2_t);
   return r.u;
+}
+// (mask & a) | (~mask & b) in one VALU operation (v_bfi_b32)
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "s"(mask), "v"(a), "v"(b));
+  return r;
 }
 __device__ __forceinline__ float trunc_bf16(float x) {
   return __uint_as_float(__float_as_uint(x) & 0xffff0000u);
@@ -125,17 +151,39 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ __align__(16) float pbuf[4][4][P_HEAD];     // [wave][head][block of quad][token]
   __shared__ __align__(16) float cbuf[4][2][4][4];       // [wave][c_b | Delta_b][head][block]
   __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
-  __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query
+  __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
+  __shared__ float sbuf[4];                              // [head] 1 / S_h
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
-  // queries of the group as FP32 in LDS, rows of absent heads zero; lane (h, kg) reads the
-  // channels (u>>1)*64 + kg*16 + (u&1)*8 + e of head h when it forms slice u
+  // Queries of the group as FP32 in LDS, rows of absent heads zero, each head pre-scaled by a
+  // power of two S_h chosen so that |q S_h sigma| <= 2^14 for every sigma of this KV head (its
+  // running maximum is kept at seal time): the scaled query then fits FP16 without overflow, and
+  // elements too small for a normal FP16 low part are negligible against the largest ones.
+  // Lane (h, kg) reads channels (u>>1)*64 + kg*16 + (u&1)*8 + e of head h when it forms slice u.
   for (int idx = threadIdx.x; idx < 4 * D; idx += 256) {
     const int hh = idx / D, c = idx % D;
     qbuf[hh][c] = hh < G ? __half2float(a.q[((int64_t)b * a.n_q + kvh * G + hh) * D + c]) : 0.0f;
   }
   __syncthreads();
+  {
+    float2 qq = *reinterpret_cast<const float2*>(&qbuf[w][2 * l]);
+    float qmax = fmaxf(fabsf(qq.x), fabsf(qq.y));
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, m));
+    const float bound = qmax * a.sigmax[(int64_t)b * a.n_kv + kvh];
+    int e = 0;
+    (void)frexpf(bound, &e);                       // bound < 2^e
+    e = bound > 0.0f ? min(max(14 - e, -100), 100) : 0;
+    const float S = ldexpf(1.0f, e);
+    qq.x *= S;
+    qq.y *= S;
+    *reinterpret_cast<float2*>(&qbuf[w][2 * l]) = qq;
+    if (l == 0) sbuf[w] = ldexpf(1.0f, -e);
+  }
+  __syncthreads();
+  const float unscale_op = sbuf[h];                // 1 / S of my operand head
+  const float score_scale = sbuf[kg] * inv_sqrt_d; // raw MFMA sum -> logit, for my softmax head
 
   // softmax state of head kg (replicated over the 16 lanes of the row)
   float m_run = -INFINITY, l_run = 0.0f, ev = 0.0f, evmax = 0.0f, dmax = 0.0f, vmax = 0.0f;
@@ -154,16 +202,15 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
   //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
   //             2r + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
-  const int bl = max(b1 - 1, 0);   // last block of this wave's run
-#define CQA_LOAD_K(QB)                                                                   \
+  const int bl = a.debug == 1 ? b0 : max(b1 - 1, 0);   // last block of this wave's run
+#define CQA_LOAD_K(QB, CQ)                                                               \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const uint8_t* kcb = a.kc + (base_blk + min((QB) + i, bl)) * KC_BYTES;         \
-    kraw[i][0] = reinterpret_cast<const uint4*>(kcb)[l];                                 \
-    kraw[i][1] = reinterpret_cast<const uint4*>(kcb + 1024)[l];                          \
+    const uint8_t* kcb = a.kc + (base_blk + min((QB) + i, bl)) * KC_BYTES;               \
+    kraw[i][CQ] = reinterpret_cast<const uint4*>(kcb + (CQ) * 1024)[l];                  \
   }
-#define CQA_LOAD_V(QB)                                                                   \
-  _Pragma("unroll") for (int P = 0; P < 2; ++P) {                                        \
-    const int64_t gbp = base_blk + min((QB) + 2 * P + (kg >> 1), bl);              \
+#define CQA_LOAD_V(QB, P)                                                                \
+  {                                                                                      \
+    const int64_t gbp = base_blk + min((QB) + 2 * (P) + (kg >> 1), bl);                  \
     const uint8_t* vcb = a.vc + gbp * VC_BYTES + (kg & 1) * 512 + n * 16;                \
     vraw[P][0] = *reinterpret_cast<const uint4*>(vcb);                                   \
     vraw[P][1] = *reinterpret_cast<const uint4*>(vcb + 256);                             \
@@ -179,16 +226,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     vm_n[P] = reinterpret_cast<const u32x4*>(a.vm + gbm * (VM_BYTES / 2))[l & 31];       \
   }
 
-  // Software pipeline: the K codes of quad k+1 are requested after the score phase of quad k
-  // (into the registers it has just freed), the V codes of quad k at the top of its iteration
-  // (used after the score phase), the metadata of quad k+1 at the top of iteration k.
+  // Software pipeline without extra registers: every piece of raw data is re-requested for the
+  // NEXT quad right after its last use for the current one, into the registers it has just
+  // freed -- K codes per channel half (after slices u = 1 and u = 3), V codes per pair of
+  // blocks -- so each load has 70-85 % of an iteration to arrive and the requests are spread
+  // evenly over time.  The metadata of quad k+1 is requested at the top of iteration k.
   uint4 kraw[4][2], vraw[2][2];
   u32x4 km_n[4], vm_n[2];
   float2 an_n[4];
   int qb = b0;
   if (qb < b1) {
-    CQA_LOAD_META(qb)   // same issue order as in the loop: metadata, then K codes
-    CQA_LOAD_K(qb)
+    CQA_LOAD_META(qb)
+    CQA_LOAD_K(qb, 0)
+    CQA_LOAD_K(qb, 1)
+    CQA_LOAD_V(qb, 0)
+    CQA_LOAD_V(qb, 1)
   }
 
   for (; qb < b1; qb += 4) {
@@ -201,7 +253,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
     for (int P = 0; P < 2; ++P)
       reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
-    CQA_LOAD_V(qb)
     CQA_LOAD_META(qb + 4)
     wave_sync_m();
 
@@ -211,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     f32x4 C[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    float csum = 0.0f, qsum = 0.0f, dsum = 0.0f;
+    float csum = 0.0f, dsum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
@@ -224,54 +275,54 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
       const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
       const float qq[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-      float qt[8], r1[8], r2[8];
+      float qt[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float qv = qq[e];
         qt[e] = qv * sg[e];
         csum = fmaf(qv, zz[e], csum);
-        qsum += qt[e];
         dsum = fmaf(fabsf(qv), sg[e], dsum);
-        r1[e] = qt[e] - trunc_bf16(qt[e]);
-        r2[e] = r1[e] - trunc_bf16(r1[e]);
       }
-      BF8 qh3, qm3, ql3;
+      HF8 qh2, ql2;   // scaled query = hi + lo, two FP16 terms (22 significant bits)
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        qh3.u[p] = pack_hi16(qt[2 * p + 1], qt[2 * p]);
-        qm3.u[p] = pack_hi16(r1[2 * p + 1], r1[2 * p]);
-        ql3.u[p] = pack_rne(r2[2 * p + 1], r2[2 * p]);
+        const f16x2 hp = pack_f16_rtz(qt[2 * p], qt[2 * p + 1]);
+        const f16x2 lp = pack_f16_rtz(qt[2 * p] - (float)hp[0], qt[2 * p + 1] - (float)hp[1]);
+        qh2.u[p] = __builtin_bit_cast(uint32_t, hp);
+        ql2.u[p] = __builtin_bit_cast(uint32_t, lp);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint4 kx = kraw[i][u >> 1];
         const uint32_t d0 = (u & 1) ? kx.z : kx.x, d1 = (u & 1) ? kx.w : kx.y;
-        float kf[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          kf[e] = (float)((d0 >> (8 * e)) & 0xffu);
-          kf[4 + e] = (float)((d1 >> (8 * e)) & 0xffu);
-        }
-        BF8 kv;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) kv.u[p] = pack_hi16(kf[2 * p + 1], kf[2 * p]);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh3.v, kv.v, C[i], 0, 0, 0);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qm3.v, kv.v, C[i], 0, 0, 0);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql3.v, kv.v, C[i], 0, 0, 0);
+        HF8 kv;       // the 8 codes of my token and channel slice, exact in FP16
+        kv.u[0] = bytes_to_f16_codes<0x04010400u>(d0);
+        kv.u[1] = bytes_to_f16_codes<0x04030402u>(d0);
+        kv.u[2] = bytes_to_f16_codes<0x04010400u>(d1);
+        kv.u[3] = bytes_to_f16_codes<0x04030402u>(d1);
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, kv.v, C[i], 0, 0, 0);
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv.v, C[i], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
+      if (u == 1) {
+        CQA_LOAD_K(qb + 4, 0)
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (u == 3) {
+        CQA_LOAD_K(qb + 4, 1)
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    CQA_LOAD_K(qb + 4)
-    // per-block constant c_b = q.z - 128 sum(q~) (stored bytes are code + 128) and Delta_b:
-    // summed over the four channel slices, then handed to the rows that own head kg
-    float cb = fmaf(-128.0f, qsum, csum);
+    // per-block constant c_b = q.z and Delta_b (both still times S_h): summed over the four
+    // channel slices, then handed to the rows that own head kg
+    float cb = csum;
     cb += __shfl_xor(cb, 16);
     cb += __shfl_xor(cb, 32);
     dsum += __shfl_xor(dsum, 16);
     dsum += __shfl_xor(dsum, 32);
     if (kg == 0) {
       cbuf[w][0][h][j] = cb;
-      cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d);
+      cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d) * unscale_op;
     }
     wave_sync_m();
     const float4 cb4 = *reinterpret_cast<const float4*>(&cbuf[w][0][kg][0]);
@@ -284,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float mq = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float s = (C[i][i] + cbs[i]) * inv_sqrt_d;
+      const float s = (C[i][i] + cbs[i]) * score_scale;
       mbv[i] = row_max(s);
       ptv[i] = __expf(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
@@ -374,14 +425,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
         for (int t = 0; t < 4; ++t) {
           const uint32_t x = xs[t];
           BF8 bv;   // bf16(16 + code): exponent bits 0x4180, code in mantissa bits 6..3
-          bv.u[0] = ((x << 3) & 0x00780078u) | (0x41804180u & ~0x00780078u);
-          bv.u[1] = ((x >> 1) & 0x00780078u) | (0x41804180u & ~0x00780078u);
-          bv.u[2] = ((x >> 5) & 0x00780078u) | (0x41804180u & ~0x00780078u);
-          bv.u[3] = ((x >> 9) & 0x00780078u) | (0x41804180u & ~0x00780078u);
+          bv.u[0] = bfi(0x00780078u, x << 3, 0x41804180u);
+          bv.u[1] = bfi(0x00780078u, x >> 1, 0x41804180u);
+          bv.u[2] = bfi(0x00780078u, x >> 5, 0x41804180u);
+          bv.u[3] = bfi(0x00780078u, x >> 9, 0x41804180u);
           acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.v, bv.v, acc[4 * gs + t], 0, 0, 0);
           acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, bv.v, acc[4 * gs + t], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
+      if (P == 0) {
+        CQA_LOAD_V(qb + 4, 0)
+      } else {
+        CQA_LOAD_V(qb + 4, 1)
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     wave_sync_m();
   }

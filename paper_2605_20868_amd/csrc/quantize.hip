@@ -27,6 +27,7 @@ struct SealArgs {
   uint8_t* vc;
   __half* vm;
   float* an;
+  float* sigmax;        // [heads]: running max of sigma per (layer, batch, kv-head)
   int64_t nb_cap;
   int64_t nb_old;       // sealed blocks before this append
   int64_t n_new;
@@ -82,6 +83,14 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   float* km = a.km + (head * a.nb_cap + blk) * (KM_BYTES / 4);
   km[c] = sigma;
   km[D + c] = z;
+  {
+    // running maximum of sigma over the head's blocks (used by the decode pass to pick an
+    // overflow-free power-of-two scaling); sigma >= 0, so its bit pattern orders like an int
+    float smax = sigma;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) smax = fmaxf(smax, __shfl_xor(smax, m));
+    if ((c & 63) == 0) atomicMax(reinterpret_cast<int*>(a.sigmax + head), __float_as_int(smax));
+  }
 
   // ---- values: per-token, per-group asymmetric INT4
   const int g = c >> 4;
@@ -188,6 +197,7 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
     a.vc = c->vc;
     a.vm = c->vm;
     a.an = c->an;
+    a.sigmax = c->sigmax;
     a.nb_cap = c->nb_cap;
     a.nb_old = nb_old;
     a.n_new = n_new;
