@@ -13,7 +13,7 @@ import math
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcqa.so")
+LIB_PATH = os.environ.get("CQA_LIB") or os.path.join(_HERE, "libcqa.so")
 
 OK = 0
 ERR_INVALID_ARG = -1

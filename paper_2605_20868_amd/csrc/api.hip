@@ -70,6 +70,7 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->vm);
   (void)hipFree(c->an);
   (void)hipFree(c->sigmax);
+  (void)hipFree(c->tickets);
   (void)hipFree(c->trail_k);
   (void)hipFree(c->trail_v);
   (void)hipFree(c->partials);
@@ -195,6 +196,8 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   CQA_ALLOC_DEV(c->an, s.an);
   CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
   CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
+  CQA_ALLOC_DEV(c->tickets, s.heads * 4);
+  CQA_TRY(hipMemset(c->tickets, 0, (size_t)s.heads * 4));
   CQA_ALLOC_DEV(c->trail_k, s.trail);
   CQA_ALLOC_DEV(c->trail_v, s.trail);
   CQA_ALLOC_DEV(c->partials, s.partials);
@@ -249,7 +252,7 @@ int32_t cqa_set_splits(cqa_cache* h, int32_t n_splits) {
 }
 
 int32_t cqa_set_kernel_variant(cqa_cache* h, int32_t variant) {
-  if (h == nullptr || variant < 0 || variant > 0x101) return CQA_ERR_INVALID_ARG;
+  if (h == nullptr || variant < 0 || variant > 0x301) return CQA_ERR_INVALID_ARG;
   h->impl.variant = variant & 1;
   h->impl.debug = variant >> 8;
   return CQA_OK;
@@ -274,7 +277,10 @@ int32_t cqa_cache_append(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
   hipStream_t st = (hipStream_t)stream;
   const __half* k = (const __half*)k_fp16_dev;
   const __half* v = (const __half*)v_fp16_dev;
-  if (c->desc.tier2_mode == CQA_TIER2_PINNED) {
+  // short appends (the decode-time case) store their originals from the kernel that also fills
+  // the trailing block; long ones (prefill) use the copy engines
+  const bool t2_by_kernel = c->desc.tier2_mode == CQA_TIER2_PINNED && n_new <= BLK;
+  if (c->desc.tier2_mode == CQA_TIER2_PINNED && !t2_by_kernel) {
     // one strided copy per tensor: row = one (batch, kv-head) sequence
     const int64_t head0 = head_index(c, layer, 0, 0);
     const size_t rows = (size_t)c->desc.batch * c->desc.n_kv_heads;
@@ -285,7 +291,7 @@ int32_t cqa_cache_append(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
     CQA_HIP(hipMemcpy2DAsync(c->t2_v + (head0 * c->desc.max_tokens + len) * D, dpitch, v, width,
                              width, rows, hipMemcpyDeviceToHost, st));
   }
-  const int32_t rc = launch_seal(c, layer, k, v, n_new, len, st);
+  const int32_t rc = launch_seal(c, layer, k, v, n_new, len, t2_by_kernel, st);
   if (rc != CQA_OK) return rc;
   c->length[layer] = len + n_new;
   return CQA_OK;
@@ -344,7 +350,7 @@ int32_t cqa_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev
   if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
     return CQA_ERR_INVALID_ARG;
   return launch_certified(&h->impl, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
-                          flags_dev, blk_logmass_dev, (hipStream_t)stream);
+                          flags_dev, nullptr, blk_logmass_dev, (hipStream_t)stream);
 }
 
 int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
@@ -470,15 +476,22 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                         const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
                         uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
                         void* stream) {
-  int32_t rc = cqa_certified_decode(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev,
-                                    blk_logmass_dev, stream);
-  if (rc != CQA_OK) return rc;
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
+      tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
+    return CQA_ERR_INVALID_ARG;
   Cache* c = &h->impl;
   hipStream_t st = (hipStream_t)stream;
+  // the reduction also writes the flag words into mapped pinned host memory, so the ladder
+  // needs one stream synchronisation and no copy
+  int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
+                                flags_dev, c->flags_host, blk_logmass_dev, st);
+  if (rc != CQA_OK) return rc;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
   const int n = bt * hq;
-  CQA_HIP(hipMemcpyAsync(c->flags_host, flags_dev, (size_t)n * 4, hipMemcpyDeviceToHost, st));
   CQA_HIP(hipStreamSynchronize(st));
   // ladder policy: PRECOND anywhere, or enough flagged KV groups, escalates to the whole layer
   bool any = false, precond = false;

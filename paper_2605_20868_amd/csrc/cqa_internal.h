@@ -80,6 +80,7 @@ struct Cache {
   uint8_t* vc;
   __half* vm;
   float* an;
+  uint32_t* tickets;         // [heads_total] arrival counters of the fused reduction (zero between launches)
   float* sigmax;             // [heads_total] running max of sigma (non-negative: ordered as ints)
   // trailing FP16 partial blocks [heads_total][16][128]
   __half* trail_k;
@@ -141,12 +142,15 @@ extern thread_local int g_last_hip_error;
 
 // ---- launchers implemented in the kernel translation units ---------------------
 int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in, int64_t n_new,
-                    int64_t len_before, hipStream_t st);
+                    int64_t len_before, bool tier2_by_kernel, hipStream_t st);
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
-                         cqa_head_cert* cert, uint32_t* flags, float* blk_logmass, hipStream_t st);
+                         cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
+                         float* blk_logmass, hipStream_t st);
 int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
-int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipStream_t st);
+struct ReduceArgs;
+int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
+                          dim3 grid, hipStream_t st);
 
 int dense_splits(int64_t n_tokens);
 // Dense FP16 attention for the G query heads of ONE kv group: k, v point at [n_tokens][128];

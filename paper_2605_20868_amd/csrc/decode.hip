@@ -13,6 +13,7 @@
 //   evaluates  E_key = 2 V_max min(tanh Delta_h, min{1, e^{c Delta_h} alpha_hat}(e^{2 Delta_h} - 1)),
 //   E_val = sum_b rho_b eta_b  and the flag word.
 #include "cqa_internal.h"
+#include "reduce_inl.h"
 
 namespace cqa {
 
@@ -255,193 +256,12 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   }
 }
 
-struct ReduceArgs {
-  const float* partials;
-  const __half* q;
-  const __half* trail_k;  // layer base [Bt*Hkv][16][128]
-  const __half* trail_v;
-  float* O;
-  cqa_head_cert* cert;
-  uint32_t* flags;
-  cqa_tolerances tol;
-  int nsplit, nb, r, n_q, n_kv;
-};
-
-constexpr int RED_THREADS = 256;
-
-// block-wide sum / max over 256 threads; every thread gets the result
-__device__ __forceinline__ float block_sum(float v, float* scratch4) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch4[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
-}
-__device__ __forceinline__ float block_max(float v, float* scratch4) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch4[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return fmaxf(fmaxf(scratch4[0], scratch4[1]), fmaxf(scratch4[2], scratch4[3]));
-}
-
-__global__ __launch_bounds__(RED_THREADS) void certified_reduce_kernel(ReduceArgs a) {
-  const int t = threadIdx.x, w = t >> 6, l = t & 63;
-  const int c = t & (D - 1);            // channel owned by threads 0..127 in the epilogue
-  const bool own = t < D;
-  const int hq = blockIdx.x, b = blockIdx.y;
-  const int group = a.n_q / a.n_kv;
-  const int kvh = hq / group;
-  const float inv_sqrt_d = 0.08838834764831845f;
-  __shared__ float scratch4[4];
-  __shared__ float wsm[MAX_SPLITS];     // per-split max, then per-split weight e^{m_s - M}
-  __shared__ float t2s[4][3];
-  __shared__ __align__(8) float osum[4][D];
-
-  const float* part = a.partials + ((int64_t)b * a.n_q + hq) * a.nsplit * PART_FLOATS;
-  // ---- per-split scalars, spread over the threads
-  float m_loc = -INFINITY;
-  for (int s = t; s < a.nsplit; s += RED_THREADS) {
-    const float m = part[s * PART_FLOATS + P_M];
-    wsm[s] = m;
-    m_loc = fmaxf(m_loc, m);
-  }
-  float M = block_max(m_loc, scratch4);
-  float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f;
-  float T1 = -INFINITY, T2 = -INFINITY;
-  int I1 = -1;
-  for (int s = t; s < a.nsplit; s += RED_THREADS) {
-    const float* ps = part + s * PART_FLOATS;
-    const float f = __expf(wsm[s] - M);
-    wsm[s] = f;
-    L += f * ps[P_L];
-    EV += f * ps[P_EV];
-    EVM = fmaxf(EVM, f * ps[P_EVMAX]);
-    DM = fmaxf(DM, ps[P_DMAX]);
-    VM = fmaxf(VM, ps[P_VMAX]);
-    top2_merge(T1, I1, T2, ps[P_T1], __float_as_int(ps[P_I1]), ps[P_T2]);
-  }
-  L = block_sum(L, scratch4);
-  EV = block_sum(EV, scratch4);
-  EVM = block_max(EVM, scratch4);
-  DM = block_max(DM, scratch4);
-  VM = block_max(VM, scratch4);
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) {
-    const float u1 = __shfl_xor(T1, m), u2 = __shfl_xor(T2, m);
-    const int j1 = __shfl_xor(I1, m);
-    top2_merge(T1, I1, T2, u1, j1, u2);
-  }
-  if (l == 0) {
-    t2s[w][0] = T1;
-    t2s[w][1] = T2;
-    t2s[w][2] = __int_as_float(I1);
-  }
-  __syncthreads();   // also publishes wsm
-  T1 = t2s[0][0];
-  T2 = t2s[0][1];
-  I1 = __float_as_int(t2s[0][2]);
-#pragma unroll
-  for (int ww = 1; ww < 4; ++ww)
-    top2_merge(T1, I1, T2, t2s[ww][0], __float_as_int(t2s[ww][2]), t2s[ww][1]);
-
-  // ---- weighted sum of the partial outputs: wave w takes splits w, w+4, ...; lane l channels 2l, 2l+1
-  float2 o2 = make_float2(0.0f, 0.0f);
-#pragma unroll 4
-  for (int s = w; s < a.nsplit; s += 4) {
-    const float f = wsm[s];
-    const float2 x = reinterpret_cast<const float2*>(part + s * PART_FLOATS + P_O)[l];
-    o2.x = fmaf(f, x.x, o2.x);
-    o2.y = fmaf(f, x.y, o2.y);
-  }
-  reinterpret_cast<float2*>(&osum[w][0])[l] = o2;
-  __syncthreads();
-  float o = (osum[0][c] + osum[1][c]) + (osum[2][c] + osum[3][c]);
-  float L_sealed = L;
-
-  // ---- trailing FP16 tokens: exact keys and values, eta = 0
-  if (a.r > 0) {
-    const float qc = own ? __half2float(a.q[((int64_t)b * a.n_q + hq) * D + c]) : 0.0f;
-    const __half* tk = a.trail_k + ((int64_t)b * a.n_kv + kvh) * BLK * D;
-    const __half* tv = a.trail_v + ((int64_t)b * a.n_kv + kvh) * BLK * D;
-    float st[BLK - 1];
-    float vt[BLK - 1];
-    float mt = -INFINITY;
-    for (int tt = 0; tt < a.r; ++tt) {
-      vt[tt] = own ? __half2float(tv[tt * D + c]) : 0.0f;
-      st[tt] = block_sum(qc * __half2float(tk[tt * D + c]), scratch4) * inv_sqrt_d;
-      mt = fmaxf(mt, st[tt]);
-      const float n2 = block_sum(vt[tt] * vt[tt], scratch4);
-      VM = fmaxf(VM, sqrtf(n2));
-    }
-    const float M2 = fmaxf(M, mt);
-    const float fs = __expf(M - M2);
-    L *= fs;
-    o *= fs;
-    EV *= fs;
-    EVM *= fs;
-    L_sealed = L;
-    for (int tt = 0; tt < a.r; ++tt) {
-      const float pt = __expf(st[tt] - M2);
-      L += pt;
-      o = fmaf(pt, vt[tt], o);
-    }
-    M = M2;
-  }
-
-  const float out = o / L;
-  if (own) a.O[((int64_t)b * a.n_q + hq) * D + c] = out;
-  const int bad = __syncthreads_or(!isfinite(out));
-
-  if (t == 0) {
-    const double Ld = (double)L;
-    const double e_val = (double)EV / Ld;
-    const double maxc = (double)EVM / Ld;
-    const double lse = (double)M + log(Ld);
-    const double alpha_hat = (double)L_sealed / Ld;
-    const double delta = (double)DM;
-    const double vmax = (double)VM;
-    double t_tail = 0.0;
-    if (alpha_hat > 0.0 && delta != 0.0) {
-      const double grow = exp(fmin((double)a.tol.mass_exp * delta, 700.0));
-      const double widen = expm1(fmin(2.0 * delta, 700.0));
-      t_tail = fmin(1.0, grow * alpha_hat) * widen;
-    }
-    const double t_full = tanh(delta);
-    double tv = a.tol.key_bound_mode == 0 ? fmin(t_full, t_tail)
-                                          : (a.tol.key_bound_mode == 1 ? t_tail : t_full);
-    const double e_key = 2.0 * vmax * tv;
-    const double margin = a.nb >= 2 ? (double)T1 - (double)T2 : (double)INFINITY;
-    const double rho_top = a.nb >= 1 ? exp((double)T1 - lse) : 0.0;
-
-    uint32_t fl = 0;
-    if (e_key > (double)a.tol.eps_key) fl |= CQA_FLAG_KEY;
-    if (e_val > (double)a.tol.eps_val || maxc > (double)a.tol.v_tol) fl |= CQA_FLAG_VAL;
-    if (a.tol.rank_depth >= 1 && a.nb >= 2 && rho_top >= (double)a.tol.rank_min_mass &&
-        margin <= 2.0 * delta + (double)a.tol.eps_guard)
-      fl |= CQA_FLAG_RANK;
-    if (bad || !isfinite(e_key) || !isfinite(e_val) || !isfinite(delta) || !isfinite(vmax) ||
-        !isfinite(lse))
-      fl |= CQA_FLAG_PRECOND;
-    if (e_key + e_val > (double)a.tol.eps_total) fl |= CQA_FLAG_TOTAL;
-    fl |= a.tol.force_flags;
-
-    cqa_head_cert ct;
-    ct.E_key = (float)e_key;
-    ct.E_val = (float)e_val;
-    ct.delta_h = DM;
-    ct.v_max = VM;
-    ct.alpha_tail_hat = (float)alpha_hat;
-    ct.lse = (float)lse;
-    ct.max_block_contrib = (float)maxc;
-    ct.rank_margin = (float)margin;
-    ct.top_block = I1;
-    ct.served_rung = 0;
-    a.cert[(int64_t)b * a.n_q + hq] = ct;
-    a.flags[(int64_t)b * a.n_q + hq] = fl;
-  }
+// Stand-alone cross-split reduction: one wave per (batch, query head).
+__global__ __launch_bounds__(256) void certified_reduce_kernel(ReduceArgs a) {
+  __shared__ float wsm[4][64];
+  const int w = threadIdx.x >> 6;
+  const int hq = blockIdx.x * 4 + w, b = blockIdx.y;
+  if (hq < a.n_q) reduce_head_wave<false>(a, b, hq, wsm[w]);
 }
 
 // Workgroups ("splits") per (batch, kv-head) and, for the vector-ALU kernel, blocks per split.
@@ -473,7 +293,8 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
 }
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
-                         cqa_head_cert* cert, uint32_t* flags, float* blk_logmass, hipStream_t st) {
+                         cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
+                         float* blk_logmass, hipStream_t st) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
@@ -481,6 +302,22 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   int nsplit = 0, bps = 0;
   split_geometry(c, nb, &nsplit, &bps);
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
+  ReduceArgs ra;
+  ra.partials = c->partials;
+  ra.q = q;
+  ra.trail_k = c->trail_k + layer_head0 * BLK * D;
+  ra.trail_v = c->trail_v + layer_head0 * BLK * D;
+  ra.O = O;
+  ra.cert = cert;
+  ra.flags = flags;
+  ra.flags_mirror = flags_mirror;
+  ra.tol = tol;
+  ra.nsplit = nsplit;
+  ra.nb = (int)nb;
+  ra.r = r;
+  ra.n_q = hq;
+  ra.n_kv = hkv;
+  bool fused = false;
   if (nb > 0) {
     DecodeArgs a;
     a.kc = c->kc + layer_head0 * c->nb_cap * KC_BYTES;
@@ -503,7 +340,12 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
     if (prof) CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n], st));
     if (c->variant == 0) {
-      const int32_t rc = launch_split_mfma(a, hq / hkv, grid, st);
+      // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction
+      // (measured slower than the separate launch: the reduction is a chain of dependent
+      // device-scope round trips either way, and fused it also extends the big kernel)
+      fused = c->debug == 3;
+      const int32_t rc = launch_split_mfma(a, ra, fused ? c->tickets + layer_head0 : nullptr,
+                                           hq / hkv, grid, st);
       if (rc != CQA_OK) return rc;
     } else {
       switch (hq / hkv) {
@@ -519,22 +361,10 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
       ++c->prof_n;
     }
   }
-  ReduceArgs ra;
-  ra.partials = c->partials;
-  ra.q = q;
-  ra.trail_k = c->trail_k + layer_head0 * BLK * D;
-  ra.trail_v = c->trail_v + layer_head0 * BLK * D;
-  ra.O = O;
-  ra.cert = cert;
-  ra.flags = flags;
-  ra.tol = tol;
-  ra.nsplit = nsplit;
-  ra.nb = (int)nb;
-  ra.r = r;
-  ra.n_q = hq;
-  ra.n_kv = hkv;
-  hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(RED_THREADS), 0, st, ra);
-  CQA_HIP(hipGetLastError());
+  if (!fused) {
+    hipLaunchKernelGGL(certified_reduce_kernel, dim3((hq + 3) / 4, bt), dim3(256), 0, st, ra);
+    CQA_HIP(hipGetLastError());
+  }
   return CQA_OK;
 }
 

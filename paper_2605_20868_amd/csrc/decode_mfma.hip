@@ -28,6 +28,7 @@
 // metadata (sigma, z, scale, offset) is staged through wave-private LDS so that each byte is
 // fetched once although four heads consume it.
 #include "cqa_internal.h"
+#include "reduce_inl.h"
 
 namespace cqa {
 
@@ -104,34 +105,13 @@ __device__ __forceinline__ void top2_merge_m(float& t1, int& i1, float& t2, floa
   }
 }
 
-// DPP moves inside a row of 16 lanes (no LDS round trip)
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float x) {
-  return __uint_as_float(
-      (uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true));
-}
-// all-reduce over the 16 lanes of a row: quad xor 1, quad xor 2, half-row mirror, row mirror
-__device__ __forceinline__ float row_max(float x) {
-  x = fmaxf(x, dpp_mov<0xB1>(x));
-  x = fmaxf(x, dpp_mov<0x4E>(x));
-  x = fmaxf(x, dpp_mov<0x141>(x));
-  x = fmaxf(x, dpp_mov<0x140>(x));
-  return x;
-}
-__device__ __forceinline__ float row_sum(float x) {
-  x += dpp_mov<0xB1>(x);
-  x += dpp_mov<0x4E>(x);
-  x += dpp_mov<0x141>(x);
-  x += dpp_mov<0x140>(x);
-  return x;
-}
-
 constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: bank spread over blocks)
 constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
 constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
 
 template <int G>
-__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
+                                                                      uint32_t* tickets) {
   const int l = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
@@ -153,6 +133,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
   __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
   __shared__ float sbuf[4];                              // [head] 1 / S_h
+  __shared__ int lastflag;
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
@@ -263,8 +244,13 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
     for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     float csum = 0.0f, dsum = 0.0f;
+#ifdef CQA_EXP_SKIP_QK
+#define CQA_QK_U 0
+#else
+#define CQA_QK_U 4
+#endif
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < CQA_QK_U; ++u) {
       const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
       const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
       const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
@@ -291,18 +277,23 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
         qh2.u[p] = __builtin_bit_cast(uint32_t, hp);
         ql2.u[p] = __builtin_bit_cast(uint32_t, lp);
       }
+      HF8 kv[4];      // the 8 codes of my token and channel slice in each block, exact in FP16
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint4 kx = kraw[i][u >> 1];
         const uint32_t d0 = (u & 1) ? kx.z : kx.x, d1 = (u & 1) ? kx.w : kx.y;
-        HF8 kv;       // the 8 codes of my token and channel slice, exact in FP16
-        kv.u[0] = bytes_to_f16_codes<0x04010400u>(d0);
-        kv.u[1] = bytes_to_f16_codes<0x04030402u>(d0);
-        kv.u[2] = bytes_to_f16_codes<0x04010400u>(d1);
-        kv.u[3] = bytes_to_f16_codes<0x04030402u>(d1);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, kv.v, C[i], 0, 0, 0);
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv.v, C[i], 0, 0, 0);
+        kv[i].u[0] = bytes_to_f16_codes<0x04010400u>(d0);
+        kv[i].u[1] = bytes_to_f16_codes<0x04030402u>(d0);
+        kv[i].u[2] = bytes_to_f16_codes<0x04010400u>(d1);
+        kv[i].u[3] = bytes_to_f16_codes<0x04030402u>(d1);
       }
+      // consecutive MFMAs go to different accumulators, so none waits for its predecessor
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, kv[i].v, C[i], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv[i].v, C[i], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
       if (u == 1) {
         CQA_LOAD_K(qb + 4, 0)
@@ -315,6 +306,10 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     }
     // per-block constant c_b = q.z and Delta_b (both still times S_h): summed over the four
     // channel slices, then handed to the rows that own head kg
+#ifdef CQA_EXP_SKIP_CB
+    const float cbs[4] = {csum, csum, csum, csum};
+    const float dls[4] = {dsum, dsum, dsum, dsum};
+#else
     float cb = csum;
     cb += __shfl_xor(cb, 16);
     cb += __shfl_xor(cb, 32);
@@ -329,6 +324,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
     const float cbs[4] = {cb4.x, cb4.y, cb4.z, cb4.w};
     const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
+#endif
 
     // ---- block statistics and online softmax of head kg; this lane is token n of each block
     float mbv[4], ptv[4], sbv[4];
@@ -388,6 +384,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     offacc[1] *= alpha_op;
 
     // ---- values: two pairs of blocks, K = 32 tokens each; operand role (head h, group g' = j)
+#ifndef CQA_EXP_SKIP_PV
 #pragma unroll
     for (int P = 0; P < 2; ++P) {
       const int bi = 2 * P + (kg >> 1);
@@ -421,17 +418,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
           al.u[p] = pack_rne(wr[p + 4], wr[p]);
         }
         const uint32_t xs[4] = {vraw[P][gs].x, vraw[P][gs].y, vraw[P][gs].z, vraw[P][gs].w};
+        BF8 bv[4];   // bf16(16 + code): exponent bits 0x4180, code in mantissa bits 6..3
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const uint32_t x = xs[t];
-          BF8 bv;   // bf16(16 + code): exponent bits 0x4180, code in mantissa bits 6..3
-          bv.u[0] = bfi(0x00780078u, x << 3, 0x41804180u);
-          bv.u[1] = bfi(0x00780078u, x >> 1, 0x41804180u);
-          bv.u[2] = bfi(0x00780078u, x >> 5, 0x41804180u);
-          bv.u[3] = bfi(0x00780078u, x >> 9, 0x41804180u);
-          acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.v, bv.v, acc[4 * gs + t], 0, 0, 0);
-          acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, bv.v, acc[4 * gs + t], 0, 0, 0);
+          bv[t].u[0] = bfi(0x00780078u, x << 3, 0x41804180u);
+          bv[t].u[1] = bfi(0x00780078u, x >> 1, 0x41804180u);
+          bv[t].u[2] = bfi(0x00780078u, x >> 5, 0x41804180u);
+          bv[t].u[3] = bfi(0x00780078u, x >> 9, 0x41804180u);
         }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.v, bv[t].v, acc[4 * gs + t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, bv[t].v, acc[4 * gs + t], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (P == 0) {
@@ -441,6 +442,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+#endif
     wave_sync_m();
   }
 
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float o = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - M) * mo[ww][hh][c];
-    a.partials[(((int64_t)b * a.n_q + kvh * G + hh) * a.nsplit + split) * PART_FLOATS + P_O + c] = o;
+    st_agent(a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.nsplit + split) * PART_FLOATS + P_O + c, o);
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
@@ -496,27 +498,46 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       top2_merge_m(T1, I1, T2, ms[ww][hh][6], __float_as_int(ms[ww][hh][8]), ms[ww][hh][7]);
     }
     float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.nsplit + split) * PART_FLOATS;
-    pp[P_M] = M;
-    pp[P_L] = L;
-    pp[P_EV] = EV;
-    pp[P_EVMAX] = EVM;
-    pp[P_DMAX] = DM;
-    pp[P_VMAX] = VM;
-    pp[P_T1] = T1;
-    pp[P_T2] = T2;
-    pp[P_I1] = __int_as_float(I1);
+    st_agent(pp + P_M, M);
+    st_agent(pp + P_L, L);
+    st_agent(pp + P_EV, EV);
+    st_agent(pp + P_EVMAX, EVM);
+    st_agent(pp + P_DMAX, DM);
+    st_agent(pp + P_VMAX, VM);
+    st_agent(pp + P_T1, T1);
+    st_agent(pp + P_T2, T2);
+    st_agent(pp + P_I1, __int_as_float(I1));
   }
+
+  // ---- fused cross-split reduction: the workgroup that arrives last for this (batch, kv-head)
+  //      merges all partials.  The partials are written and read with device-coherent accesses;
+  //      every thread waits until its own stores have been acknowledged before the ticket is
+  //      taken, so whoever draws the last ticket finds every partial in place.
+  if (tickets == nullptr) return;   // the reduction runs as its own launch
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* tk = tickets + (int64_t)b * a.n_kv + kvh;
+    const uint32_t t = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = t == (uint32_t)a.nsplit - 1u;
+    if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    lastflag = last ? 1 : 0;
+  }
+  __syncthreads();
+  if (lastflag && w < G && a.debug != 2) reduce_head_wave<true>(ra, b, kvh * G + w, &kmbuf[w][0][0]);
 }
 
 #undef CQA_LOAD_K
 #undef CQA_LOAD_V
 #undef CQA_LOAD_META
 
-int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
+int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
+                          dim3 grid, hipStream_t st) {
+  static_assert(4 * KM_ROW >= MAX_SPLITS, "reduction scratch aliases one wave's K-meta staging");
   switch (group) {
-    case 1: hipLaunchKernelGGL(certified_split_mfma_kernel<1>, grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL(certified_split_mfma_kernel<2>, grid, dim3(256), 0, st, a); break;
-    case 4: hipLaunchKernelGGL(certified_split_mfma_kernel<4>, grid, dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL(certified_split_mfma_kernel<1>, grid, dim3(256), 0, st, a, ra, tickets); break;
+    case 2: hipLaunchKernelGGL(certified_split_mfma_kernel<2>, grid, dim3(256), 0, st, a, ra, tickets); break;
+    case 4: hipLaunchKernelGGL(certified_split_mfma_kernel<4>, grid, dim3(256), 0, st, a, ra, tickets); break;
     default: return CQA_ERR_UNSUPPORTED;
   }
   return CQA_OK;

@@ -161,14 +161,18 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   }
 }
 
-// Moves the tokens that stay unsealed into the trailing FP16 block.
-// src_first: index (within this append's input) of the first token to keep;
-// dst_first: slot of the trailing block it goes to; count tokens.
+// Moves the tokens that stay unsealed into the trailing FP16 block and, for short appends,
+// stores the FP16 originals of ALL new tokens straight into the pinned Tier-2 arrays (device
+// stores to mapped host memory: a decode-time append of one token per head is then a single
+// small launch instead of two strided copies).
+// src_first: index (within this append's input) of the first token to keep in the trailing
+// block; dst_first: its slot there; count tokens.  t2_k / t2_v: null = Tier-2 handled elsewhere.
 __global__ __launch_bounds__(128) void trail_kernel(const __half* k_in, const __half* v_in,
                                                     __half* trail_k, __half* trail_v,
                                                     int64_t n_new, int64_t src_first,
                                                     int dst_first, int count, int layer, int batch,
-                                                    int n_kv) {
+                                                    int n_kv, __half* t2_k, __half* t2_v,
+                                                    int64_t t2_cap, int64_t len_before) {
   const int c = threadIdx.x;
   const int kvh = blockIdx.x, b = blockIdx.y;
   const int64_t head = ((int64_t)layer * batch + b) * n_kv + kvh;
@@ -177,10 +181,16 @@ __global__ __launch_bounds__(128) void trail_kernel(const __half* k_in, const __
     trail_k[(head * BLK + dst_first + t) * D + c] = k_in[(in_head + src_first + t) * D + c];
     trail_v[(head * BLK + dst_first + t) * D + c] = v_in[(in_head + src_first + t) * D + c];
   }
+  if (t2_k != nullptr) {
+    for (int64_t t = 0; t < n_new; ++t) {
+      t2_k[(head * t2_cap + len_before + t) * D + c] = k_in[(in_head + t) * D + c];
+      t2_v[(head * t2_cap + len_before + t) * D + c] = v_in[(in_head + t) * D + c];
+    }
+  }
 }
 
 int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in, int64_t n_new,
-                    int64_t len_before, hipStream_t st) {
+                    int64_t len_before, bool tier2_by_kernel, hipStream_t st) {
   const int r = (int)(len_before % BLK);
   const int64_t nb_old = len_before / BLK;
   const int64_t n_seal = (r + n_new) / BLK;
@@ -220,9 +230,11 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
     dst_first = 0;
     count = r_new;
   }
-  if (count > 0) {
+  if (count > 0 || tier2_by_kernel) {
     hipLaunchKernelGGL(trail_kernel, dim3(hkv, bt), dim3(128), 0, st, k_in, v_in, c->trail_k,
-                       c->trail_v, n_new, src_first, dst_first, count, layer, bt, hkv);
+                       c->trail_v, n_new, src_first, dst_first, count, layer, bt, hkv,
+                       tier2_by_kernel ? c->t2_k : nullptr, tier2_by_kernel ? c->t2_v : nullptr,
+                       (int64_t)c->desc.max_tokens, len_before);
     CQA_HIP(hipGetLastError());
   }
   return CQA_OK;

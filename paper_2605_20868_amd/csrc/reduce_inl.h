@@ -1,0 +1,279 @@
+// Cross-split reduction of one (batch, query head), executed by ONE wave of 64 lanes.
+//
+// Merges the per-split partial states (m, l, o[128], value-term sums, maxima, two largest block
+// log-masses) with the usual log-sum-exp factors, attends the trailing FP16 tokens exactly
+// (their keys and values are not quantized: eta = 0, no contribution to Delta_h), and
+// evaluates the certificate of the paper's total error bound:
+//   E_val = sum_b rho_b eta_b,   E_key = 2 V_max min(tanh Delta_h, min{1, e^{c Delta_h} alpha_hat}(e^{2 Delta_h} - 1))
+// (key_bound_mode 1 / 2 select the second / first factor alone), the interval form of the
+// ranking test  l_(1) - l_(2) <= 2 Delta_h + eps_guard,  and the flag word.
+// Used by the stand-alone reduction kernel and by the last workgroup of the matrix-core pass.
+#pragma once
+
+#include "cqa_internal.h"
+
+namespace cqa {
+
+struct ReduceArgs {
+  const float* partials;  // [Bt][Hq][nsplit][PART_FLOATS]
+  const __half* q;        // [Bt][Hq][128]
+  const __half* trail_k;  // layer base [Bt*Hkv][16][128]
+  const __half* trail_v;
+  float* O;
+  cqa_head_cert* cert;
+  uint32_t* flags;
+  uint32_t* flags_mirror;  // optional second copy of the flag words (mapped pinned host memory)
+  cqa_tolerances tol;
+  int nsplit, nb, r, n_q, n_kv;
+};
+
+__device__ __forceinline__ void top2_merge_r(float& t1, int& i1, float& t2, float u1, int j1,
+                                             float u2) {
+  const bool keep = (t1 > u1) || (t1 == u1 && (unsigned)i1 <= (unsigned)j1);
+  if (keep) {
+    t2 = fmaxf(t2, u1);
+  } else {
+    t2 = fmaxf(u2, t1);
+    t1 = u1;
+    i1 = j1;
+  }
+}
+// Device-coherent accesses for data exchanged between workgroups of ONE launch: relaxed
+// agent-scope atomics go straight to the device's coherence point, so no cache-wide
+// write-back or invalidate is needed around them.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool COHERENT>
+__device__ __forceinline__ float ld_part(const float* p) {
+  if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return *p;
+}
+template <bool COHERENT>
+__device__ __forceinline__ float2 ld_part2(const float* p) {
+  if (COHERENT) {
+    const uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+  }
+  return *reinterpret_cast<const float2*>(p);
+}
+// DPP move inside a row of 16 lanes (no LDS round trip)
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __uint_as_float(
+      (uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_movi(int x) {
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+// all-reduce over the 16 lanes of a row: quad xor 1, quad xor 2, half-row mirror, row mirror
+__device__ __forceinline__ float row_max(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));
+  x = fmaxf(x, dpp_mov<0x4E>(x));
+  x = fmaxf(x, dpp_mov<0x141>(x));
+  x = fmaxf(x, dpp_mov<0x140>(x));
+  return x;
+}
+__device__ __forceinline__ float row_sum(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  x += dpp_mov<0x141>(x);
+  x += dpp_mov<0x140>(x);
+  return x;
+}
+// all-reduce over the 64 lanes of the wave: the row step on DPP, two cross-row exchanges
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row_sum(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  v = row_max(v);
+  v = fmaxf(v, __shfl_xor(v, 16));
+  v = fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+template <int CTRL>
+__device__ __forceinline__ void top2_step_dpp(float& t1, int& i1, float& t2) {
+  const float u1 = dpp_mov<CTRL>(t1), u2 = dpp_mov<CTRL>(t2);
+  const int j1 = dpp_movi<CTRL>(i1);
+  top2_merge_r(t1, i1, t2, u1, j1, u2);
+}
+__device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
+  top2_step_dpp<0xB1>(t1, i1, t2);
+  top2_step_dpp<0x4E>(t1, i1, t2);
+  top2_step_dpp<0x141>(t1, i1, t2);
+  top2_step_dpp<0x140>(t1, i1, t2);
+#pragma unroll
+  for (int m = 16; m < 64; m <<= 1) {
+    const float u1 = __shfl_xor(t1, m), u2 = __shfl_xor(t2, m);
+    const int j1 = __shfl_xor(i1, m);
+    top2_merge_r(t1, i1, t2, u1, j1, u2);
+  }
+}
+
+// wsm: wave-private LDS scratch of at least 64 floats.  All 64 lanes of the wave must call.
+// COHERENT: the partials were written by other workgroups of the same launch.
+// This code runs on the critical tail of the launch: it is written for few dependent memory
+// round trips (all loads of a chunk of 64 splits are issued before anything is consumed) and
+// short cross-lane chains, not for few instructions.
+template <bool COHERENT>
+__device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int hq, float* wsm) {
+  const int l = threadIdx.x & 63;
+  const int kvh = hq / (a.n_q / a.n_kv);
+  const float inv_sqrt_d = 0.08838834764831845f;
+  const float* part = a.partials + ((int64_t)b * a.n_q + hq) * a.nsplit * PART_FLOATS;
+
+  // trailing FP16 tokens (at most 15): request them first, they are used last
+  const __half* tk = a.trail_k + ((int64_t)b * a.n_kv + kvh) * BLK * D;
+  const __half* tv = a.trail_v + ((int64_t)b * a.n_kv + kvh) * BLK * D;
+  const __half2 qh = reinterpret_cast<const __half2*>(a.q + ((int64_t)b * a.n_q + hq) * D)[l];
+  __half2 kt[BLK - 1], vt[BLK - 1];
+#pragma unroll
+  for (int t = 0; t < BLK - 1; ++t) {
+    const int tt = min(t, max(a.r - 1, 0));
+    kt[t] = reinterpret_cast<const __half2*>(tk + tt * D)[l];
+    vt[t] = reinterpret_cast<const __half2*>(tv + tt * D)[l];
+  }
+
+  float M = -INFINITY, L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f;
+  float T1 = -INFINITY, T2 = -INFINITY;
+  int I1 = -1;
+  float2 o2 = make_float2(0.0f, 0.0f);
+  for (int s0 = 0; s0 < a.nsplit; s0 += 64) {
+    // scalars of split s0 + l (one split per lane) and, for my two channels, the partial
+    // outputs of all 64 splits of the chunk
+    const int s = s0 + l;
+    const bool on = s < a.nsplit;
+    const float* ps = part + (int64_t)(on ? s : a.nsplit - 1) * PART_FLOATS;
+    float sc[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) sc[i] = ld_part<COHERENT>(ps + i);
+    float2 x[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i)
+      x[i] = ld_part2<COHERENT>(part + (int64_t)min(s0 + i, a.nsplit - 1) * PART_FLOATS + P_O + 2 * l);
+
+    const float m = on ? sc[P_M] : -INFINITY;
+    const float Mn = fmaxf(M, wave_max(m));
+    const float fo = __expf(M - Mn);        // rescales what earlier chunks accumulated
+    const float f = on ? __expf(m - Mn) : 0.0f;
+    wsm[l] = f;
+    L = L * fo + wave_sum(f * sc[P_L]);
+    EV = EV * fo + wave_sum(f * sc[P_EV]);
+    EVM = fmaxf(EVM * fo, wave_max(f * sc[P_EVMAX]));
+    DM = fmaxf(DM, wave_max(on ? sc[P_DMAX] : 0.0f));
+    VM = fmaxf(VM, wave_max(on ? sc[P_VMAX] : 0.0f));
+    float u1 = on ? sc[P_T1] : -INFINITY, u2 = on ? sc[P_T2] : -INFINITY;
+    int j1 = on ? __float_as_int(sc[P_I1]) : -1;
+    wave_top2(u1, j1, u2);
+    top2_merge_r(T1, I1, T2, u1, j1, u2);
+    M = Mn;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    o2.x *= fo;
+    o2.y *= fo;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+      const float fi = wsm[i];            // zero for splits past the end
+      o2.x = fmaf(fi, x[i].x, o2.x);
+      o2.y = fmaf(fi, x[i].y, o2.y);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  float L_sealed = L;
+
+  // ---- trailing FP16 tokens: exact keys and values, eta = 0
+  if (a.r > 0) {
+    const float q0 = __low2float(qh), q1 = __high2float(qh);
+    float st[BLK - 1];
+    float mt = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < BLK - 1; ++t) {
+      st[t] = wave_sum(q0 * __low2float(kt[t]) + q1 * __high2float(kt[t])) * inv_sqrt_d;
+      if (t < a.r) mt = fmaxf(mt, st[t]);
+    }
+    const float M2 = fmaxf(M, mt);
+    const float fs = __expf(M - M2);
+    L *= fs;
+    o2.x *= fs;
+    o2.y *= fs;
+    EV *= fs;
+    EVM *= fs;
+    L_sealed = L;
+#pragma unroll
+    for (int t = 0; t < BLK - 1; ++t) {
+      const float v0 = __low2float(vt[t]), v1 = __high2float(vt[t]);
+      const float n2 = wave_sum(v0 * v0 + v1 * v1);
+      if (t < a.r) {
+        VM = fmaxf(VM, sqrtf(n2));
+        const float pt = __expf(st[t] - M2);
+        L += pt;
+        o2.x = fmaf(pt, v0, o2.x);
+        o2.y = fmaf(pt, v1, o2.y);
+      }
+    }
+    M = M2;
+  }
+
+  const float out0 = o2.x / L, out1 = o2.y / L;
+  reinterpret_cast<float2*>(a.O + ((int64_t)b * a.n_q + hq) * D)[l] = make_float2(out0, out1);
+  const bool bad = __any(!isfinite(out0) || !isfinite(out1));
+
+  if (l == 0) {
+    // certificate scalars in FP32 (a handful of operations; their rounding is ~1e-7 relative)
+    const float e_val = EV / L;
+    const float maxc = EVM / L;
+    const float lse = M + logf(L);
+    const float alpha_hat = L_sealed / L;
+    const float delta = DM;
+    const float vmax = VM;
+    float t_tail = 0.0f;
+    if (alpha_hat > 0.0f && delta != 0.0f) {
+      const float grow = expf(fminf((float)a.tol.mass_exp * delta, 80.0f));
+      const float widen = expm1f(fminf(2.0f * delta, 80.0f));
+      t_tail = fminf(1.0f, grow * alpha_hat) * widen;
+    }
+    const float t_full = tanhf(delta);
+    const float tv = a.tol.key_bound_mode == 0 ? fminf(t_full, t_tail)
+                                               : (a.tol.key_bound_mode == 1 ? t_tail : t_full);
+    const float e_key = 2.0f * vmax * tv;
+    const float margin = a.nb >= 2 ? T1 - T2 : INFINITY;
+    const float rho_top = a.nb >= 1 ? expf(T1 - lse) : 0.0f;
+
+    uint32_t fl = 0;
+    if (e_key > a.tol.eps_key) fl |= CQA_FLAG_KEY;
+    if (e_val > a.tol.eps_val || maxc > a.tol.v_tol) fl |= CQA_FLAG_VAL;
+    if (a.tol.rank_depth >= 1 && a.nb >= 2 && rho_top >= a.tol.rank_min_mass &&
+        margin <= 2.0f * delta + a.tol.eps_guard)
+      fl |= CQA_FLAG_RANK;
+    if (bad || !isfinite(e_key) || !isfinite(e_val) || !isfinite(delta) || !isfinite(vmax) ||
+        !isfinite(lse))
+      fl |= CQA_FLAG_PRECOND;
+    if (e_key + e_val > a.tol.eps_total) fl |= CQA_FLAG_TOTAL;
+    fl |= a.tol.force_flags;
+
+    cqa_head_cert ct;
+    ct.E_key = e_key;
+    ct.E_val = e_val;
+    ct.delta_h = DM;
+    ct.v_max = VM;
+    ct.alpha_tail_hat = alpha_hat;
+    ct.lse = lse;
+    ct.max_block_contrib = maxc;
+    ct.rank_margin = margin;
+    ct.top_block = I1;
+    ct.served_rung = 0;
+    a.cert[(int64_t)b * a.n_q + hq] = ct;
+    a.flags[(int64_t)b * a.n_q + hq] = fl;
+    if (a.flags_mirror != nullptr) a.flags_mirror[(int64_t)b * a.n_q + hq] = fl;
+  }
+}
+
+}  // namespace cqa

@@ -110,6 +110,24 @@ def test_gqa_group_sizes(group):
         compare_all(gc, oc.certified_decode(q, oracle.Tolerances()), O, cert, flags, ("gqa", group))
 
 
+def test_vector_alu_variant_and_standalone_reduction():
+    say("vector-ALU split kernel + stand-alone reduction")
+    rng = np.random.default_rng(17)
+    bt, hkv, hq, n = 2, 2, 8, 16 * 150 + 7
+    k = (rng.standard_normal((bt, hkv, n, 128)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    q = rng.standard_normal((bt, hq, 128)).astype(np.float16)
+    oc = oracle.OracleLayerCache(bt, hkv)
+    oc.append(k, v)
+    ref = oc.certified_decode(q, oracle.Tolerances(rank_depth=1))
+    with GpuLayerCache(bt, hq, hkv, 4096) as gc:
+        gc.append(k, v)
+        for variant in (1, 0):
+            gc.cqa.cqa_set_kernel_variant(gc.h, variant)
+            O, cert, flags = gc.certified_decode(q, gc.cqa.Tolerances(rank_depth=1))
+            compare_all(gc, ref, O, cert, flags, ("variant", variant))
+
+
 def test_split_invariance():
     say("split invariance")
     rng = np.random.default_rng(3)
