@@ -223,8 +223,9 @@ int32_t cqa_time_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp1
                                   void* stream);
 
 /* Per-launch timing of the split-K decode kernel (the dominant kernel), taken
- * with HIP event pairs recorded on the stream each cqa_certified_decode /
- * cqa_decode_step call launches it on.  begin arms up to max_launches pairs
+ * with HIP event pairs attached to its dispatch on the stream each
+ * cqa_certified_decode / cqa_decode_step call launches it on (the pair brackets
+ * the kernel's execution, not the launch overhead).  begin arms up to max_launches pairs
  * (<= 65536); end synchronises on them and returns the mean and minimum kernel
  * duration in milliseconds and the number of launches timed (host pointers,
  * any may be NULL).  For benchmarks. */

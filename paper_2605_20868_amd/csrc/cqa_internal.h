@@ -150,7 +150,7 @@ int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
-                          dim3 grid, hipStream_t st);
+                          dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st);
 
 int dense_splits(int64_t n_tokens);
 // Dense FP16 attention for the G query heads of ONE kv group: k, v point at [n_tokens][128];

@@ -338,14 +338,16 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.debug = c->debug;
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
-    if (prof) CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n], st));
+    hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;
+    hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
+    if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
     if (c->variant == 0) {
       // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction
       // (measured slower than the separate launch: the reduction is a chain of dependent
       // device-scope round trips either way, and fused it also extends the big kernel)
       fused = c->debug == 3;
       const int32_t rc = launch_split_mfma(a, ra, fused ? c->tickets + layer_head0 : nullptr,
-                                           hq / hkv, grid, st);
+                                           hq / hkv, grid, ev0, ev1, st);
       if (rc != CQA_OK) return rc;
     } else {
       switch (hq / hkv) {
@@ -357,7 +359,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     }
     CQA_HIP(hipGetLastError());
     if (prof) {
-      CQA_HIP(hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st));
+      if (c->variant != 0) CQA_HIP(hipEventRecord(ev1, st));
       ++c->prof_n;
     }
   }

@@ -27,6 +27,8 @@
 // The raw data of the next quad is loaded while the current one is processed; the per-block
 // metadata (sigma, z, scale, offset) is staged through wave-private LDS so that each byte is
 // fetched once although four heads consume it.
+#include <hip/hip_ext.h>
+
 #include "cqa_internal.h"
 #include "reduce_inl.h"
 
@@ -531,13 +533,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #undef CQA_LOAD_V
 #undef CQA_LOAD_META
 
+// ev0 / ev1 (both or neither): HIP events attached to the dispatch itself, so their elapsed time
+// is the kernel's own execution time (what a kernel trace reports), not launch overhead.
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
-                          dim3 grid, hipStream_t st) {
-  static_assert(4 * KM_ROW >= MAX_SPLITS, "reduction scratch aliases one wave's K-meta staging");
+                          dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
+  static_assert(4 * KM_ROW >= 64, "reduction scratch aliases one wave's K-meta staging");
   switch (group) {
-    case 1: hipLaunchKernelGGL(certified_split_mfma_kernel<1>, grid, dim3(256), 0, st, a, ra, tickets); break;
-    case 2: hipLaunchKernelGGL(certified_split_mfma_kernel<2>, grid, dim3(256), 0, st, a, ra, tickets); break;
-    case 4: hipLaunchKernelGGL(certified_split_mfma_kernel<4>, grid, dim3(256), 0, st, a, ra, tickets); break;
+    case 1:
+      hipExtLaunchKernelGGL(certified_split_mfma_kernel<1>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
+      break;
+    case 2:
+      hipExtLaunchKernelGGL(certified_split_mfma_kernel<2>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
+      break;
+    case 4:
+      hipExtLaunchKernelGGL(certified_split_mfma_kernel<4>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
+      break;
     default: return CQA_ERR_UNSUPPORTED;
   }
   return CQA_OK;

@@ -127,17 +127,23 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
   const float inv_sqrt_d = 0.08838834764831845f;
   const float* part = a.partials + ((int64_t)b * a.n_q + hq) * a.nsplit * PART_FLOATS;
 
-  // trailing FP16 tokens (at most 15): request them first, they are used last
+  // trailing FP16 tokens (at most 15): request them first, they are used last.
+  //   scores / norms: lane (t = l >> 2, cpart = l & 3) covers channels 32 cpart .. 32 cpart + 31 of
+  //   token t; values for the output: lane l covers channels 2l, 2l+1 of every token.
   const __half* tk = a.trail_k + ((int64_t)b * a.n_kv + kvh) * BLK * D;
   const __half* tv = a.trail_v + ((int64_t)b * a.n_kv + kvh) * BLK * D;
-  const __half2 qh = reinterpret_cast<const __half2*>(a.q + ((int64_t)b * a.n_q + hq) * D)[l];
-  __half2 kt[BLK - 1], vt[BLK - 1];
+  const int tt = min(l >> 2, max(a.r - 1, 0)), cpart = l & 3;
+  uint4 kq[4], vq[4], qq[4];
 #pragma unroll
-  for (int t = 0; t < BLK - 1; ++t) {
-    const int tt = min(t, max(a.r - 1, 0));
-    kt[t] = reinterpret_cast<const __half2*>(tk + tt * D)[l];
-    vt[t] = reinterpret_cast<const __half2*>(tv + tt * D)[l];
+  for (int i = 0; i < 4; ++i) {
+    kq[i] = reinterpret_cast<const uint4*>(tk + tt * D + cpart * 32)[i];
+    vq[i] = reinterpret_cast<const uint4*>(tv + tt * D + cpart * 32)[i];
+    qq[i] = reinterpret_cast<const uint4*>(a.q + ((int64_t)b * a.n_q + hq) * D + cpart * 32)[i];
   }
+  __half2 vt[BLK - 1];
+#pragma unroll
+  for (int t = 0; t < BLK - 1; ++t)
+    vt[t] = reinterpret_cast<const __half2*>(tv + min(t, max(a.r - 1, 0)) * D)[l];
 
   float M = -INFINITY, L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f;
   float T1 = -INFINITY, T2 = -INFINITY;
@@ -191,33 +197,46 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
 
   // ---- trailing FP16 tokens: exact keys and values, eta = 0
   if (a.r > 0) {
-    const float q0 = __low2float(qh), q1 = __high2float(qh);
-    float st[BLK - 1];
-    float mt = -INFINITY;
+    float dot = 0.0f, n2 = 0.0f;
 #pragma unroll
-    for (int t = 0; t < BLK - 1; ++t) {
-      st[t] = wave_sum(q0 * __low2float(kt[t]) + q1 * __high2float(kt[t])) * inv_sqrt_d;
-      if (t < a.r) mt = fmaxf(mt, st[t]);
+    for (int i = 0; i < 4; ++i) {
+      const __half2* kh = reinterpret_cast<const __half2*>(&kq[i]);
+      const __half2* vh = reinterpret_cast<const __half2*>(&vq[i]);
+      const __half2* qh = reinterpret_cast<const __half2*>(&qq[i]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dot = fmaf(__low2float(qh[e]), __low2float(kh[e]), dot);
+        dot = fmaf(__high2float(qh[e]), __high2float(kh[e]), dot);
+        n2 = fmaf(__low2float(vh[e]), __low2float(vh[e]), n2);
+        n2 = fmaf(__high2float(vh[e]), __high2float(vh[e]), n2);
+      }
     }
-    const float M2 = fmaxf(M, mt);
+    dot += dpp_mov<0xB1>(dot);      // the four parts of a token are one quad of lanes
+    dot += dpp_mov<0x4E>(dot);
+    n2 += dpp_mov<0xB1>(n2);
+    n2 += dpp_mov<0x4E>(n2);
+    const bool live = (l >> 2) < a.r;
+    const float st = live ? dot * inv_sqrt_d : -INFINITY;
+    const float M2 = fmaxf(M, wave_max(st));
+    VM = fmaxf(VM, wave_max(live ? sqrtf(n2) : 0.0f));
     const float fs = __expf(M - M2);
+    const float pt = live ? __expf(st - M2) : 0.0f;
     L *= fs;
     o2.x *= fs;
     o2.y *= fs;
     EV *= fs;
     EVM *= fs;
     L_sealed = L;
+    L += wave_sum(pt) * 0.25f;      // every token is held by four lanes
+    if (cpart == 0) wsm[l >> 2] = pt;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
     for (int t = 0; t < BLK - 1; ++t) {
-      const float v0 = __low2float(vt[t]), v1 = __high2float(vt[t]);
-      const float n2 = wave_sum(v0 * v0 + v1 * v1);
-      if (t < a.r) {
-        VM = fmaxf(VM, sqrtf(n2));
-        const float pt = __expf(st[t] - M2);
-        L += pt;
-        o2.x = fmaf(pt, v0, o2.x);
-        o2.y = fmaf(pt, v1, o2.y);
-      }
+      const float p = wsm[t];       // zero for t >= r
+      o2.x = fmaf(p, __low2float(vt[t]), o2.x);
+      o2.y = fmaf(p, __high2float(vt[t]), o2.y);
     }
     M = M2;
   }
