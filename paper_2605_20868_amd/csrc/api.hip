@@ -31,7 +31,7 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 }
 
 struct Sizes {
-  int64_t nb_cap, heads, kc, km, vc, vm, an, trail, t2, partials, dense_ws, stage, select;
+  int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select;
   int max_splits;
 };
 
@@ -39,11 +39,8 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   Sizes s;
   s.nb_cap = (d->max_tokens + BLK - 1) / BLK;
   s.heads = (int64_t)d->n_layers * d->batch * d->n_kv_heads;
-  s.kc = s.heads * s.nb_cap * KC_BYTES;
-  s.km = s.heads * s.nb_cap * KM_BYTES;
-  s.vc = s.heads * s.nb_cap * VC_BYTES;
-  s.vm = s.heads * s.nb_cap * VM_BYTES;
-  s.an = s.heads * s.nb_cap * AN_BYTES;
+  s.nq_cap = (s.nb_cap + 3) / 4;
+  s.t1 = s.heads * s.nq_cap * QUAD_BYTES;
   s.trail = s.heads * BLK * D * 2;
   s.t2 = d->tier2_mode == CQA_TIER2_PINNED ? s.heads * d->max_tokens * D * 2 : 0;
   int64_t ms = (4 * (int64_t)n_cu) / ((int64_t)d->batch * d->n_kv_heads);
@@ -64,11 +61,7 @@ static void release(cqa_cache* h) {
   Cache* c = &h->impl;
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
-  (void)hipFree(c->kc);
-  (void)hipFree(c->km);
-  (void)hipFree(c->vc);
-  (void)hipFree(c->vm);
-  (void)hipFree(c->an);
+  (void)hipFree(c->t1);
   (void)hipFree(c->sigmax);
   (void)hipFree(c->tickets);
   (void)hipFree(c->trail_k);
@@ -160,7 +153,7 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   if (st != CQA_OK) return st;
   const Sizes s = compute_sizes(desc, 256);
   if (device_bytes)
-    *device_bytes = s.kc + s.km + s.vc + s.vm + s.an + 2 * s.trail + s.partials +
+    *device_bytes = s.t1 + 2 * s.trail + s.partials +
                     2 * s.dense_ws + 4 * s.stage + s.select;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
@@ -187,13 +180,10 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   if (c->n_cu < 1) c->n_cu = 256;
   const Sizes s = compute_sizes(desc, c->n_cu);
   c->nb_cap = s.nb_cap;
+  c->nq_cap = s.nq_cap;
   c->heads_total = s.heads;
   c->max_splits = s.max_splits;
-  CQA_ALLOC_DEV(c->kc, s.kc);
-  CQA_ALLOC_DEV(c->km, s.km);
-  CQA_ALLOC_DEV(c->vc, s.vc);
-  CQA_ALLOC_DEV(c->vm, s.vm);
-  CQA_ALLOC_DEV(c->an, s.an);
+  CQA_ALLOC_DEV(c->t1, s.t1);
   CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
   CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
   CQA_ALLOC_DEV(c->tickets, s.heads * 4);
@@ -308,17 +298,17 @@ int32_t cqa_cache_export_block(const cqa_cache* h, int32_t layer, int32_t batch,
       block >= c->length[layer] / BLK)
     return CQA_ERR_INVALID_ARG;
   CQA_HIP(hipDeviceSynchronize());
-  const int64_t gb = head_index(c, layer, batch, kv_head) * c->nb_cap + block;
+  const int64_t head_rec = head_index(c, layer, batch, kv_head) * c->nq_cap;
   uint8_t kc[KC_BYTES];
   float km[KM_BYTES / 4];
   uint32_t vc[VC_BYTES / 4];
   uint16_t vm[VM_BYTES / 2];
   float an[2];
-  CQA_HIP(hipMemcpy(kc, c->kc + gb * KC_BYTES, KC_BYTES, hipMemcpyDeviceToHost));
-  CQA_HIP(hipMemcpy(km, c->km + gb * (KM_BYTES / 4), KM_BYTES, hipMemcpyDeviceToHost));
-  CQA_HIP(hipMemcpy(vc, c->vc + gb * VC_BYTES, VC_BYTES, hipMemcpyDeviceToHost));
-  CQA_HIP(hipMemcpy(vm, c->vm + gb * (VM_BYTES / 2), VM_BYTES, hipMemcpyDeviceToHost));
-  CQA_HIP(hipMemcpy(an, c->an + gb * 2, AN_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(kc, c->t1 + t1_offset(head_rec, block, Q_KC, KC_BYTES), KC_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(km, c->t1 + t1_offset(head_rec, block, Q_KM, KM_BYTES), KM_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(vc, c->t1 + t1_offset(head_rec, block, Q_VC, VC_BYTES), VC_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(vm, c->t1 + t1_offset(head_rec, block, Q_VM, VM_BYTES), VM_BYTES, hipMemcpyDeviceToHost));
+  CQA_HIP(hipMemcpy(an, c->t1 + t1_offset(head_rec, block, Q_AN, AN_BYTES), AN_BYTES, hipMemcpyDeviceToHost));
   for (int t = 0; t < BLK; ++t)
     for (int ch = 0; ch < D; ++ch) {
       if (kcodes) kcodes[t * D + ch] = (int8_t)((int)kc[kc_offset(t, ch)] - 128);

@@ -36,6 +36,24 @@ constexpr int VC_BYTES = BLK * D / 2;        // 1024
 constexpr int VM_BYTES = 2 * BLK * NG * 2;   // 512
 constexpr int AN_BYTES = 8;
 
+// The five per-block pieces of four consecutive blocks (a "quad") are stored together as one
+// contiguous record, piece-major inside the record:
+//   [K codes 4 x 2048][K meta 4 x 1024][V codes 4 x 1024][V meta 4 x 512][annotations 4 x 8]
+// so that a wave, which works on one quad at a time, streams a single 18464-byte run instead of
+// five separate arrays (measured: 7.1 TB/s against 6.5 TB/s for the same bytes in five arrays).
+constexpr int Q_KC = 0;
+constexpr int Q_KM = Q_KC + 4 * KC_BYTES;   //  8192
+constexpr int Q_VC = Q_KM + 4 * KM_BYTES;   // 12288
+constexpr int Q_VM = Q_VC + 4 * VC_BYTES;   // 16384
+constexpr int Q_AN = Q_VM + 4 * VM_BYTES;   // 18432
+constexpr int QUAD_BYTES = Q_AN + 4 * AN_BYTES;  // 18464 = 64 tokens x 288.5 B
+
+// address of one piece of block `blk` of head-local numbering; `head_rec` = first record of the head
+__host__ __device__ inline int64_t t1_offset(int64_t head_rec, int64_t blk, int piece_off,
+                                             int piece_bytes) {
+  return (head_rec + (blk >> 2)) * QUAD_BYTES + piece_off + (blk & 3) * piece_bytes;
+}
+
 __host__ __device__ inline int kc_offset(int token, int channel) {
   const int cq = channel >> 6, kg = (channel >> 4) & 3, j = channel & 15;
   return cq * 1024 + kg * 256 + token * 16 + j;
@@ -74,12 +92,9 @@ struct Cache {
   int64_t* length;           // host, per layer
   int forced_splits;
   int max_splits;
-  // Tier-1 streams
-  uint8_t* kc;
-  float* km;
-  uint8_t* vc;
-  __half* vm;
-  float* an;
+  // Tier-1: quad records, [heads_total][nq_cap][QUAD_BYTES]
+  uint8_t* t1;
+  int64_t nq_cap;            // quad records of capacity per head
   uint32_t* tickets;         // [heads_total] arrival counters of the fused reduction (zero between launches)
   float* sigmax;             // [heads_total] running max of sigma (non-negative: ordered as ints)
   // trailing FP16 partial blocks [heads_total][16][128]
@@ -108,16 +123,12 @@ struct Cache {
 };
 
 struct DecodeArgs {
-  const uint8_t* kc;   // layer base of each Tier-1 stream
-  const float* km;
-  const uint8_t* vc;
-  const __half* vm;
-  const float* an;
+  const uint8_t* t1;   // layer base of the Tier-1 quad records
   const float* sigmax; // [Bt * Hkv] of the layer: running max of sigma over sealed blocks and channels
   const __half* q;     // [Bt][Hq][128]
   float* partials;     // [Bt][Hq][nsplit][PART_FLOATS]
   float* blk_logmass;  // [Bt][Hq][nb] or null
-  int64_t nb_cap;
+  int64_t nq_cap;      // quad records per head
   int nb;              // sealed blocks
   int nsplit;
   int bps;             // blocks per split

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   const int tok = l & 15, kg = l >> 4;              // roles in the score phase
   const int vn = l & 15, vgh = (l >> 4) & 1, vo = l >> 5;  // roles in the value phase
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int64_t base_blk = ((int64_t)b * a.n_kv + kvh) * a.nb_cap;
+  const int64_t head_rec = ((int64_t)b * a.n_kv + kvh) * a.nq_cap;
   // blocks are dealt evenly over the splits (every split gets at least one: nsplit <= nb)
   const int b0 = (int)(((int64_t)split * a.nb) / a.nsplit);
   const int b1 = (int)(((int64_t)(split + 1) * a.nb) / a.nsplit);
@@ -82,12 +82,11 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   }
 
   for (int blk = b0 + w; blk < b1; blk += 4) {
-    const int64_t gb = base_blk + blk;
     // ---- scaled query, per-block constant, per-block score-error bound
-    const float* kmb = a.km + gb * (KM_BYTES / 4);
+    const float* kmb = reinterpret_cast<const float*>(a.t1 + t1_offset(head_rec, blk, Q_KM, KM_BYTES));
     const float2 sg = reinterpret_cast<const float2*>(kmb)[l];
     const float2 zz = reinterpret_cast<const float2*>(kmb + D)[l];
-    const float2 an = *reinterpret_cast<const float2*>(a.an + gb * 2);
+    const float2 an = *reinterpret_cast<const float2*>(a.t1 + t1_offset(head_rec, blk, Q_AN, AN_BYTES));
     float csum[G], dsum[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -108,7 +107,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     wave_sync();
 
     // ---- scores: lane (tok, kg) covers channels cq*64 + kg*16 + 0..15, cq = 0, 1
-    const uint8_t* kcb = a.kc + gb * KC_BYTES;
+    const uint8_t* kcb = a.t1 + t1_offset(head_rec, blk, Q_KC, KC_BYTES);
     float dot[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
@@ -164,9 +163,9 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     wave_sync();
 
     // ---- values: lane (vo, vgh, vn) covers tokens vo*8..+7 of channels (vgh*4+gq)*16 + vn
-    const uint4 vx = reinterpret_cast<const uint4*>(a.vc + gb * VC_BYTES)[l];
+    const uint4 vx = reinterpret_cast<const uint4*>(a.t1 + t1_offset(head_rec, blk, Q_VC, VC_BYTES))[l];
     const uint32_t vw[4] = {vx.x, vx.y, vx.z, vx.w};
-    const __half* vmb = a.vm + gb * (VM_BYTES / 2);
+    const __half* vmb = reinterpret_cast<const __half*>(a.t1 + t1_offset(head_rec, blk, Q_VM, VM_BYTES));
     float pi[8][G];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -320,16 +319,12 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   bool fused = false;
   if (nb > 0) {
     DecodeArgs a;
-    a.kc = c->kc + layer_head0 * c->nb_cap * KC_BYTES;
-    a.km = c->km + layer_head0 * c->nb_cap * (KM_BYTES / 4);
-    a.vc = c->vc + layer_head0 * c->nb_cap * VC_BYTES;
-    a.vm = c->vm + layer_head0 * c->nb_cap * (VM_BYTES / 2);
-    a.an = c->an + layer_head0 * c->nb_cap * 2;
+    a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
     a.sigmax = c->sigmax + layer_head0;
     a.q = q;
     a.partials = c->partials;
     a.blk_logmass = blk_logmass;
-    a.nb_cap = c->nb_cap;
+    a.nq_cap = c->nq_cap;
     a.nb = (int)nb;
     a.nsplit = nsplit;
     a.bps = bps;

@@ -111,7 +111,7 @@ constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: b
 constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
 constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
 
-template <int G>
+template <int G, bool LM>
 __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
                                                                       uint32_t* tickets) {
   const int l = threadIdx.x & 63;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int n = l & 15, kg = l >> 4;
   const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int64_t base_blk = ((int64_t)b * a.n_kv + kvh) * a.nb_cap;
+  const int64_t head_rec = ((int64_t)b * a.n_kv + kvh) * a.nq_cap;
   // This wave's contiguous run of quads: the head's quads are dealt out evenly (sizes differ by
   // at most one) over all 4 * nsplit waves that work on the head.
   const int nquads = (a.nb + 3) >> 2;
@@ -188,25 +188,28 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int bl = a.debug == 1 ? b0 : max(b1 - 1, 0);   // last block of this wave's run
 #define CQA_LOAD_K(QB, CQ)                                                               \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const uint8_t* kcb = a.kc + (base_blk + min((QB) + i, bl)) * KC_BYTES;               \
+    const uint8_t* kcb = a.t1 + t1_offset(head_rec, min((QB) + i, bl), Q_KC, KC_BYTES);   \
     kraw[i][CQ] = reinterpret_cast<const uint4*>(kcb + (CQ) * 1024)[l];                  \
   }
 #define CQA_LOAD_V(QB, P)                                                                \
   {                                                                                      \
-    const int64_t gbp = base_blk + min((QB) + 2 * (P) + (kg >> 1), bl);                  \
-    const uint8_t* vcb = a.vc + gbp * VC_BYTES + (kg & 1) * 512 + n * 16;                \
+    const uint8_t* vcb = a.t1 + t1_offset(head_rec, min((QB) + 2 * (P) + (kg >> 1), bl), \
+                                          Q_VC, VC_BYTES) + (kg & 1) * 512 + n * 16;     \
     vraw[P][0] = *reinterpret_cast<const uint4*>(vcb);                                   \
     vraw[P][1] = *reinterpret_cast<const uint4*>(vcb + 256);                             \
   }
 #define CQA_LOAD_META(QB)                                                                \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const int64_t gb = base_blk + min((QB) + i, bl);                               \
-    km_n[i] = reinterpret_cast<const u32x4*>(a.km + gb * (KM_BYTES / 4))[l];             \
-    an_n[i] = *reinterpret_cast<const float2*>(a.an + gb * 2);                           \
+    const int gb = min((QB) + i, bl);                                                    \
+    km_n[i] = reinterpret_cast<const u32x4*>(                                            \
+        a.t1 + t1_offset(head_rec, gb, Q_KM, KM_BYTES))[l];                              \
+    an_n[i] = *reinterpret_cast<const float2*>(                                          \
+        a.t1 + t1_offset(head_rec, gb, Q_AN, AN_BYTES));                                 \
   }                                                                                      \
   _Pragma("unroll") for (int P = 0; P < 2; ++P) {                                        \
-    const int64_t gbm = base_blk + min((QB) + 2 * P + (l >> 5), bl);               \
-    vm_n[P] = reinterpret_cast<const u32x4*>(a.vm + gbm * (VM_BYTES / 2))[l & 31];       \
+    const int gbm = min((QB) + 2 * P + (l >> 5), bl);                                    \
+    vm_n[P] = reinterpret_cast<const u32x4*>(                                            \
+        a.t1 + t1_offset(head_rec, gbm, Q_VM, VM_BYTES))[l & 31];                        \
   }
 
   // Software pipeline without extra registers: every piece of raw data is re-requested for the
@@ -317,10 +320,9 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     cb += __shfl_xor(cb, 32);
     dsum += __shfl_xor(dsum, 16);
     dsum += __shfl_xor(dsum, 32);
-    if (kg == 0) {
-      cbuf[w][0][h][j] = cb;
-      cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d) * unscale_op;
-    }
+    // (all four kg lanes of a column hold the same sums and store the same words: no branch)
+    cbuf[w][0][h][j] = cb;
+    cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d) * unscale_op;
     wave_sync_m();
     const float4 cb4 = *reinterpret_cast<const float4*>(&cbuf[w][0][kg][0]);
     const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
@@ -328,7 +330,9 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
 #endif
 
-    // ---- block statistics and online softmax of head kg; this lane is token n of each block
+    // ---- block statistics and online softmax of head kg; this lane is token n of each block.
+    //      Branch-free: blocks past the wave's run (only in its last quad) are computed on the
+    //      clamped data and masked by wave-uniform selects.
     float mbv[4], ptv[4], sbv[4];
     float mq = -INFINITY;
 #pragma unroll
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       mbv[i] = row_max(s);
       ptv[i] = __expf(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
-      if (qb + i < b1) mq = fmaxf(mq, mbv[i]);
+      mq = (qb + i < b1) ? fmaxf(mq, mbv[i]) : mq;
     }
     const float m_new = fmaxf(m_run, mq);
     const float alpha = __expf(m_run - m_new);
@@ -345,33 +349,35 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     ev *= alpha;
     evmax *= alpha;
     m_run = m_new;
+    float lbv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float p = 0.0f;
-      if (qb + i < b1) {
-        const float f = __expf(mbv[i] - m_new);
-        p = ptv[i] * f;
-        const float sf = sbv[i] * f;
-        const float ce = sf * an[i].x;
-        const float lb = mbv[i] + __logf(sbv[i]);
-        l_run += sf;
-        ev += ce;
-        evmax = fmaxf(evmax, ce);
-        dmax = fmaxf(dmax, dls[i]);
-        vmax = fmaxf(vmax, an[i].y);
-        if (lb > t1) {
-          t2 = t1;
-          t1 = lb;
-          i1 = qb + i;
-        } else if (lb > t2) {
-          t2 = lb;
-        }
-        if (a.blk_logmass != nullptr && n == 0 && kg < G)
-          a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lb;
-      }
-      pbuf[w][kg][i * BLK + n] = p;
+      const bool vi = qb + i < b1;
+      const float f = vi ? __expf(mbv[i] - m_new) : 0.0f;
+      const float sf = sbv[i] * f;
+      const float ce = sf * an[i].x;
+      const float lb = vi ? mbv[i] + __logf(sbv[i]) : -INFINITY;
+      lbv[i] = lb;
+      l_run += sf;
+      ev += ce;
+      evmax = fmaxf(evmax, ce);
+      dmax = fmaxf(dmax, vi ? dls[i] : 0.0f);
+      vmax = fmaxf(vmax, vi ? an[i].y : 0.0f);
+      const bool g1 = lb > t1, g2 = lb > t2;   // blocks arrive in increasing order: ties keep the lower index
+      t2 = g1 ? t1 : (g2 ? lb : t2);
+      i1 = g1 ? qb + i : i1;
+      t1 = g1 ? lb : t1;
+      pbuf[w][kg][i * BLK + n] = ptv[i] * f;
     }
-    if (n == 0) abuf[w][kg] = alpha;
+    if (LM) {
+      if (n == 0 && kg < G) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (qb + i < b1)
+            a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lbv[i];
+      }
+    }
+    abuf[w][kg] = alpha;   // every lane of the row stores the same word
     wave_sync_m();
 
     // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
@@ -538,18 +544,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
                           dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
   static_assert(4 * KM_ROW >= 64, "reduction scratch aliases one wave's K-meta staging");
+  const bool lm = a.blk_logmass != nullptr;
+#define CQA_LAUNCH(GG)                                                                           \
+  if (lm)                                                                                        \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true>), grid, dim3(256), 0, st, ev0,   \
+                          ev1, 0, a, ra, tickets);                                               \
+  else                                                                                           \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false>), grid, dim3(256), 0, st, ev0,  \
+                          ev1, 0, a, ra, tickets);
   switch (group) {
-    case 1:
-      hipExtLaunchKernelGGL(certified_split_mfma_kernel<1>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
-      break;
-    case 2:
-      hipExtLaunchKernelGGL(certified_split_mfma_kernel<2>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
-      break;
-    case 4:
-      hipExtLaunchKernelGGL(certified_split_mfma_kernel<4>, grid, dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
-      break;
+    case 1: CQA_LAUNCH(1) break;
+    case 2: CQA_LAUNCH(2) break;
+    case 4: CQA_LAUNCH(4) break;
     default: return CQA_ERR_UNSUPPORTED;
   }
+#undef CQA_LAUNCH
   return CQA_OK;
 }
 

@@ -22,13 +22,9 @@ struct SealArgs {
   const __half* v_in;
   const __half* trail_k;  // [heads][16][128]
   const __half* trail_v;
-  uint8_t* kc;
-  float* km;
-  uint8_t* vc;
-  __half* vm;
-  float* an;
+  uint8_t* t1;          // Tier-1 quad records
   float* sigmax;        // [heads]: running max of sigma per (layer, batch, kv-head)
-  int64_t nb_cap;
+  int64_t nq_cap;
   int64_t nb_old;       // sealed blocks before this append
   int64_t n_new;
   int r;                // tokens in the trailing block before this append
@@ -80,7 +76,7 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
     }
     kbuf[kc_offset(t, c)] = (uint8_t)(code + 128);
   }
-  float* km = a.km + (head * a.nb_cap + blk) * (KM_BYTES / 4);
+  float* km = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_KM, KM_BYTES));
   km[c] = sigma;
   km[D + c] = z;
   {
@@ -132,10 +128,10 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   __syncthreads();
 
   // ---- write out, 16 bytes per thread where possible
-  uint8_t* kc = a.kc + (head * a.nb_cap + blk) * KC_BYTES;
+  uint8_t* kc = a.t1 + t1_offset(head * a.nq_cap, blk, Q_KC, KC_BYTES);
   reinterpret_cast<uint4*>(kc)[c] = reinterpret_cast<const uint4*>(kbuf)[c];
 
-  uint32_t* vc = reinterpret_cast<uint32_t*>(a.vc + (head * a.nb_cap + blk) * VC_BYTES);
+  uint32_t* vc = reinterpret_cast<uint32_t*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_VC, VC_BYTES));
 #pragma unroll
   for (int rep = 0; rep < 2; ++rep) {
     const int dw = c + rep * 128;
@@ -146,7 +142,7 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
     for (int i = 0; i < 8; ++i) x |= (uint32_t)vnib[o * 8 + i][ch] << (4 * i);
     vc[dw] = x;
   }
-  __half* vm = a.vm + (head * a.nb_cap + blk) * (VM_BYTES / 2);
+  __half* vm = reinterpret_cast<__half*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_VM, VM_BYTES));
   reinterpret_cast<uint32_t*>(vm)[c] = reinterpret_cast<const uint32_t*>(vmeta)[c];
 
   if (c == 0) {
@@ -155,7 +151,7 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
       eta2 = fmax(eta2, red[0][t][0] + red[1][t][0]);
       nu2 = fmax(nu2, red[0][t][1] + red[1][t][1]);
     }
-    float* an = a.an + (head * a.nb_cap + blk) * 2;
+    float* an = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_AN, AN_BYTES));
     an[0] = (float)sqrt(eta2);
     an[1] = (float)sqrt(nu2);
   }
@@ -202,13 +198,9 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
     a.v_in = v_in;
     a.trail_k = c->trail_k;
     a.trail_v = c->trail_v;
-    a.kc = c->kc;
-    a.km = c->km;
-    a.vc = c->vc;
-    a.vm = c->vm;
-    a.an = c->an;
+    a.t1 = c->t1;
     a.sigmax = c->sigmax;
-    a.nb_cap = c->nb_cap;
+    a.nq_cap = c->nq_cap;
     a.nb_old = nb_old;
     a.n_new = n_new;
     a.r = r;
