@@ -5,6 +5,8 @@
 #include <new>
 #include <vector>
 
+#include <chrono>
+
 #include "cqa_internal.h"
 
 struct cqa_cache {
@@ -74,6 +76,7 @@ static void release(cqa_cache* h) {
   if (c->t2_k) (void)hipHostFree(c->t2_k);
   if (c->t2_v) (void)hipHostFree(c->t2_v);
   if (c->flags_host) (void)hipHostFree(c->flags_host);
+  delete[] c->need;
   if (c->side) (void)hipStreamDestroy(c->side);
   for (int i = 0; i < 2; ++i) {
     if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
@@ -194,6 +197,12 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   CQA_ALLOC_DEV(c->dense_ws, 2 * s.dense_ws);
   CQA_ALLOC_DEV(c->select_dev, s.select);
   CQA_ALLOC_PIN(c->flags_host, s.select);
+  memset(c->flags_host, 0, s.select);
+  c->need = new (std::nothrow) uint32_t[(size_t)desc->batch * desc->n_q_heads];
+  if (c->need == nullptr) {
+    release(h);
+    return CQA_ERR_INVALID_ARG;
+  }
   if (desc->tier2_mode == CQA_TIER2_PINNED) {
     for (int i = 0; i < 2; ++i)
       for (int j = 0; j < 2; ++j) CQA_ALLOC_DEV(c->stage[i][j], s.stage);
@@ -340,7 +349,7 @@ int32_t cqa_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev
   if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
     return CQA_ERR_INVALID_ARG;
   return launch_certified(&h->impl, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
-                          flags_dev, nullptr, blk_logmass_dev, (hipStream_t)stream);
+                          flags_dev, nullptr, 0u, blk_logmass_dev, (hipStream_t)stream);
 }
 
 int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
@@ -474,25 +483,51 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
     return CQA_ERR_INVALID_ARG;
   Cache* c = &h->impl;
   hipStream_t st = (hipStream_t)stream;
-  // the reduction also writes the flag words into mapped pinned host memory, so the ladder
-  // needs one stream synchronisation and no copy
+  // The reduction also writes each head's flag word, tagged with this step's sequence number,
+  // into mapped pinned host memory as its last store.  The host polls those words instead of
+  // waiting for the stream: the ladder decision needs nothing else on the host, and everything
+  // enqueued afterwards is ordered behind the reduction by the stream itself.  The poll is
+  // bounded; when the tags do not all show up in time it falls back to a stream synchronisation.
+  c->step_seq = (c->step_seq % 0xFFFFu) + 1u;            // 1 .. 65535, never 0
+  const uint32_t tag = c->step_seq << 16;
   int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
-                                flags_dev, c->flags_host, blk_logmass_dev, st);
+                                flags_dev, c->flags_host, tag, blk_logmass_dev, st);
   if (rc != CQA_OK) return rc;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
   const int n = bt * hq;
-  CQA_HIP(hipStreamSynchronize(st));
+  {
+    volatile const uint32_t* mirror = c->flags_host;
+    const auto t_start = std::chrono::steady_clock::now();
+    bool seen = false;
+    for (uint32_t spin = 0; !seen; ++spin) {
+      seen = true;
+      for (int i = 0; i < n; ++i)
+        if ((mirror[i] & 0xFFFF0000u) != tag) {
+          seen = false;
+          break;
+        }
+      if (!seen && (spin & 1023u) == 1023u &&
+          std::chrono::steady_clock::now() - t_start > std::chrono::milliseconds(20))
+        break;
+    }
+    if (!seen) {
+      CQA_HIP(hipStreamSynchronize(st));
+      for (int i = 0; i < n; ++i)
+        if ((mirror[i] & 0xFFFF0000u) != tag) return CQA_ERR_HIP;
+    }
+  }
   // ladder policy: PRECOND anywhere, or enough flagged KV groups, escalates to the whole layer
   bool any = false, precond = false;
   int flagged_groups = 0;
-  std::vector<uint32_t> need(n, 0u);
+  uint32_t* need = c->need;
+  memset(need, 0, sizeof(uint32_t) * n);
   for (int b = 0; b < bt; ++b)
     for (int kh = 0; kh < hkv; ++kh) {
       bool grp = false;
       for (int i = 0; i < g; ++i) {
         const int idx = b * hq + kh * g + i;
-        const uint32_t f = c->flags_host[idx];
+        const uint32_t f = c->flags_host[idx] & 0xFFFFu;
         if (f & CQA_FLAG_ANY) {
           need[idx] = 1u;
           grp = true;
@@ -511,7 +546,7 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
   }
   if (rung_served) *rung_served = rung;
   if (rung == 0) return CQA_OK;
-  return cqa_dense_fallback(h, layer, q_fp16_dev, need.data(), rung == 4, rung, O_dev, cert_dev,
+  return cqa_dense_fallback(h, layer, q_fp16_dev, need, rung == 4, rung, O_dev, cert_dev,
                             flags_dev, stream);
 }
 

@@ -109,6 +109,8 @@ struct Cache {
   __half* stage[2][2];       // [buffer][K|V] : max_tokens * 128 halves each
   uint32_t* select_dev;      // [batch][Hq]
   uint32_t* flags_host;      // pinned [batch][Hq]
+  uint32_t step_seq;         // 16-bit tag of the decode step whose flags the mirror must carry
+  uint32_t* need;            // host [batch][Hq]: ladder scratch, heads to recompute
   hipStream_t side;
   hipEvent_t ev_ready[2];    // staging buffer filled (recorded on side)
   hipEvent_t ev_free[2];     // staging buffer consumed (recorded on main)
@@ -156,7 +158,7 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
                     int64_t len_before, bool tier2_by_kernel, hipStream_t st);
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         float* blk_logmass, hipStream_t st);
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st);
 int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;

@@ -293,7 +293,7 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         float* blk_logmass, hipStream_t st) {
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
@@ -310,6 +310,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   ra.cert = cert;
   ra.flags = flags;
   ra.flags_mirror = flags_mirror;
+  ra.mirror_tag = mirror_tag;
   ra.tol = tol;
   ra.nsplit = nsplit;
   ra.nb = (int)nb;

@@ -23,6 +23,7 @@ struct ReduceArgs {
   cqa_head_cert* cert;
   uint32_t* flags;
   uint32_t* flags_mirror;  // optional second copy of the flag words (mapped pinned host memory)
+  uint32_t mirror_tag;     // OR-ed into each mirrored word (bits 16-31): the host polls for it
   cqa_tolerances tol;
   int nsplit, nb, r, n_q, n_kv;
 };
@@ -291,7 +292,12 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     ct.served_rung = 0;
     a.cert[(int64_t)b * a.n_q + hq] = ct;
     a.flags[(int64_t)b * a.n_q + hq] = fl;
-    if (a.flags_mirror != nullptr) a.flags_mirror[(int64_t)b * a.n_q + hq] = fl;
+    // last store of this head: a host thread polling the mirror may take the tagged word as
+    // "this head's row, certificate and flags have been issued" (device consumers rely on
+    // stream order, not on this word)
+    if (a.flags_mirror != nullptr)
+      __hip_atomic_store(a.flags_mirror + (int64_t)b * a.n_q + hq, fl | a.mirror_tag,
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 
