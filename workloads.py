@@ -174,19 +174,28 @@ def make_peaked_q(k: np.ndarray, n_q_heads: int, gap: float = 10.0, seed: int = 
 
 
 def plant_near_tie(k: np.ndarray, v: np.ndarray, q: np.ndarray, b: int, hq: int,
-                   n_q_heads: int, seed: int = 0, gap: float = 10.0, nudge: float = 0.01):
+                   n_q_heads: int, seed: int = 0, gap: float = 10.0, nudge: float = 0.01,
+                   longest_key: bool = False):
     """Adversarial head: two keys in different blocks whose logits nearly tie.
 
     Position p2 receives a copy of key p1 with one channel nudged so the two
     FP16 logits differ by about `nudge`, both exceeding every other logit by
     about `gap`; the value at p2 is the negation of the value at p1.  Edits k, v
     and q in place and returns (p1, p2).
+
+    p1 is a seeded position in the first half of the context, or, with
+    `longest_key`, the longest key of the first half: on heavy-tailed keys a
+    typical key is out-scored along its own direction by some far longer key,
+    and only the longest one can be given a positive logit gap by scaling.
     """
     bt, hkv, n, d = k.shape
     g = n_q_heads // hkv
     kh = hq // g
     r = _rng(seed, "near_tie", b, hq)
     p1 = int(r.integers(0, n // 2))
+    if longest_key:
+        kk = k[b, kh, : n // 2].astype(np.float32)
+        p1 = int(np.argmax(np.einsum("td,td->t", kk, kk)))
     p2 = int(n // 2 + r.integers(0, n // 2))
     p2 = min(p2, n - 1)
     if p1 // BLOCK == p2 // BLOCK:
@@ -197,6 +206,7 @@ def plant_near_tie(k: np.ndarray, v: np.ndarray, q: np.ndarray, b: int, hq: int,
     a = dots[p1]
     dots[p1] = -np.inf
     dots[p2] = -np.inf
+    assert a > dots.max(), "the planted key does not lead along its own direction"
     c = gap / (a - dots.max())
     q[b, hq] = (c * base).astype(np.float16)
     qf = q[b, hq].astype(np.float64)
