@@ -74,6 +74,82 @@ def cpu_baseline(k, v, steps_budget_s=12.0):
                       f"of the same workload; numpy float64, host has {len(os.sched_getaffinity(0))} cores"}
 
 
+def bench_stack(args) -> int:
+    """The 32-layer stack (batch 2, 128K per sequence): all layers resident, one pass = every layer's
+    append + decode step.  Not the headline line; prints its own JSON line."""
+    import torch
+    from paper_2605_20868_amd import binding as cqa
+
+    sh = workloads.SHAPES["stack"]
+    ctx = args.context or sh.context
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = min(args.steps, 20), min(args.warmup, 3)
+    L = sh.n_layers
+    h = cqa.cqa_cache_create(L, sh.batch, sh.n_q_heads, sh.n_kv_heads, ctx + K + W + 16)
+    try:
+        for layer in range(L):
+            kd, vd = workloads.torch_device_kv("stack", layer, dev, context=ctx)
+            cqa.cqa_cache_append(h, layer, kd, vd, ctx)
+            torch.cuda.synchronize()
+            del kd, vd
+        rng = np.random.Generator(np.random.Philox(11))
+        n_in = K + W
+        ks = torch.from_numpy(workloads.student_t3_f16(rng, (n_in, L, sh.batch, sh.n_kv_heads, 1, 128))).to(dev)
+        vs = torch.from_numpy(workloads.normal_f16(rng, (n_in, L, sh.batch, sh.n_kv_heads, 1, 128))).to(dev)
+        qs = torch.from_numpy(workloads.normal_f16(rng, (n_in, L, sh.batch, sh.n_q_heads, 128))).to(dev)
+        O = torch.empty((sh.batch, sh.n_q_heads, 128), dtype=torch.float32, device=dev)
+        cert = torch.zeros((sh.batch * sh.n_q_heads, cqa.CERT_BYTES), dtype=torch.uint8, device=dev)
+        flags = torch.zeros((sh.batch * sh.n_q_heads,), dtype=torch.int32, device=dev)
+        tol = cqa.Tolerances()
+        stream = torch.cuda.current_stream().cuda_stream
+        kp, vp, qp = ks.data_ptr(), vs.data_ptr(), qs.data_ptr()
+        kv_stride, q_stride = ks[0, 0].numel() * 2, qs[0, 0].numel() * 2
+        Op, certp, flagsp = O.data_ptr(), cert.data_ptr(), flags.data_ptr()
+
+        def step(i):
+            for layer in range(L):
+                j = i * L + layer
+                cqa.cqa_cache_append(h, layer, kp + j * kv_stride, vp + j * kv_stride, 1, stream)
+                cqa.cqa_decode_step(h, layer, qp + j * q_stride, tol, Op, certp, flagsp, None, stream)
+
+        for i in range(W):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(W, W + K):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        cqa.cqa_profile_begin(h, K * L)
+        for i in range(W, W + K):
+            for layer in range(L):
+                cqa.cqa_decode_step(h, layer, qp + (i * L + layer) * q_stride, tol, Op, certp, flagsp, None, stream)
+        torch.cuda.synchronize()
+        mean_ms, min_ms, n_timed = cqa.cqa_profile_end(h)
+        splits = cqa.cqa_decode_splits(h, 0)
+    finally:
+        cqa.cqa_cache_destroy(h)
+    nb_mid = (ctx + W + K // 2) // 16
+    alg_bytes = sh.batch * sh.n_kv_heads * nb_mid * 16 * BYTES_PER_TOKEN
+    achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "certified decode attention layer-steps/s, 32-layer stack at 128K ctx, batch 2",
+        "value": K * L / (t1 - t0), "unit": "layer-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": (t1 - t0) * 1e3 / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"stack: {L} layers, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
+                               f"context {ctx}+steps, K ~ Student-t(3), V ~ N(0,1), tolerances +inf",
+                   "step": "for each of the 32 layers: append 1 token + decode step", "splits": splits},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "certified_split_mfma_kernel<4>", "kernel_mean_ms": mean_ms,
+                     "kernel_min_ms": min_ms, "algorithmic_bytes_per_launch": alg_bytes},
+        "cpu_baseline": None,
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +157,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--context", type=int, default=None, help="override the context length (debug)")
+    ap.add_argument("--workload", default=WORKLOAD, choices=[WORKLOAD, "stack"],
+                    help="t128k (default, the headline line) or stack: 32 layers x batch 2 x 128K, a step "
+                         "= append + decode step on every layer (reported as layer-steps/s)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
@@ -91,6 +170,8 @@ def main() -> int:
     if int(os.environ.get("RANK", "0")) != 0:
         return 0
 
+    if args.workload == "stack":
+        return bench_stack(args)
     sh = workloads.SHAPES[WORKLOAD]
     ctx = args.context or sh.context
     k, v = workloads.make_kv(WORKLOAD, seed=0, context=ctx)

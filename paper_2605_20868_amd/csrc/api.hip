@@ -187,6 +187,9 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   c->heads_total = s.heads;
   c->max_splits = s.max_splits;
   CQA_ALLOC_DEV(c->t1, s.t1);
+  // blocks that are not sealed yet must read as finite numbers: the decode pass may load (and
+  // mask) the unsealed blocks of a head's last record
+  CQA_TRY(hipMemset(c->t1, 0, (size_t)s.t1));
   CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
   CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
   CQA_ALLOC_DEV(c->tickets, s.heads * 4);

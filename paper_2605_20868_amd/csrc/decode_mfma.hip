@@ -127,6 +127,15 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int b0 = 4 * (int)(((int64_t)gw * nquads) / nw);
   const int b1 = min(4 * (int)(((int64_t)(gw + 1) * nquads) / nw), a.nb);
   const float inv_sqrt_d = 0.08838834764831845f;
+#ifdef CQA_PROBE_TIMESTAMPS
+  // Build-time probe (off in the library): with -DCQA_PROBE_TIMESTAMPS every wave stamps the
+  // 100 MHz wall clock at start, loop entry, loop exit and end into the buffer passed as
+  // blk_logmass ([waves][4] uint64), which shows launch skew, per-XCD speed and the tail.
+  uint64_t* ts = reinterpret_cast<uint64_t*>(a.blk_logmass) +
+                 ((((int64_t)b * a.n_kv + kvh) * a.nsplit + split) * 4 + w) * 4;
+  const bool ts_on = a.blk_logmass != nullptr && l == 0;   // no buffer given: no stamps
+  if (ts_on) ts[0] = wall_clock64();
+#endif
 
   __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
   __shared__ __align__(16) __half vmbuf[4][4][VM_ROW];   // [wave][block of quad][scale | offset]
@@ -139,22 +148,91 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
+  // Wave priorities.  A SIMD holds one wave of each of the two workgroups resident on its CU and,
+  // at equal priority, always issues the older wave first: left alone, the older workgroup runs
+  // ~25 % faster and the younger one finishes the launch alone on a half-empty CU.  So the short
+  // set-up runs at the highest priority (ahead of other waves' main loops), and in the main loop a
+  // wave is high while it forms operands for the score product and low during the value product,
+  // the presumably younger workgroup (second half of the launch order) one level above the older
+  // one in the high phase: of the four phase combinations each wave then wins two.
+  __builtin_amdgcn_s_setprio(3);
+  // This wave's query row (head w of the group), requested before the bulk loads: loads return in
+  // order, so the row arrives first and the set-up below does not wait for a whole quad.
+  __half2 q_in = __floats2half2_rn(0.0f, 0.0f);
+  if (w < G)
+    q_in = *reinterpret_cast<const __half2*>(a.q + ((int64_t)b * a.n_q + kvh * G + w) * D + 2 * l);
+  const float sigmax_head = a.sigmax[(int64_t)b * a.n_kv + kvh];
+
+  // Loads of one quad = one Tier-1 record.  Every address is the record's wave-uniform base plus
+  // a constant plus a per-lane 32-bit offset that never changes, so the loop carries no vector
+  // address arithmetic.  The prefetch issued by a wave's last iteration is aimed at its own last
+  // record again (cached, never used); a ragged last quad of the head reads the not yet sealed
+  // blocks of its record, which hold zeros or an earlier run's finite data and are masked out.
+  // The prefetch is unconditional on purpose: guarding it with a branch makes every prefetched
+  // register a phi and costs dozens of spilled VGPRs.
+  //   K codes : block i, channel half cq; lane (token n, kg) takes bytes [16 l, +16) of each KB
+  //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
+  //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
+  //             2P + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
+  const int ql = a.debug == 1 ? b0 : max((b1 - 1) & ~3, b0);   // first block of the wave's last quad
+  const uint8_t* const head_base = a.t1 + head_rec * QUAD_BYTES;
+  const uint32_t lo16 = (uint32_t)l * 16u;
+  const uint32_t vo16 = (uint32_t)kg * 512u + (uint32_t)n * 16u;
+#define CQA_REC(QB) (head_base + (int64_t)(min((QB), ql) >> 2) * QUAD_BYTES)
+#define CQA_LOAD_K(QB, CQ)                                                               \
+  {                                                                                      \
+    const uint8_t* rec = CQA_REC(QB) + (Q_KC + (CQ) * 1024);                             \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
+      kraw[i][CQ] = *reinterpret_cast<const uint4*>(rec + i * KC_BYTES + lo16);          \
+  }
+#define CQA_LOAD_V(QB, P)                                                                \
+  {                                                                                      \
+    const uint8_t* rec = CQA_REC(QB) + (Q_VC + (P) * 2 * VC_BYTES);                      \
+    vraw[P][0] = *reinterpret_cast<const uint4*>(rec + vo16);                            \
+    vraw[P][1] = *reinterpret_cast<const uint4*>(rec + 256 + vo16);                      \
+  }
+#define CQA_LOAD_META(QB)                                                                \
+  {                                                                                      \
+    const uint8_t* rec = CQA_REC(QB);                                                    \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
+      km_n[i] = *reinterpret_cast<const u32x4*>(rec + (Q_KM + i * KM_BYTES) + lo16);     \
+      an_n[i] = *reinterpret_cast<const float2*>(rec + (Q_AN + i * AN_BYTES));           \
+    }                                                                                    \
+    _Pragma("unroll") for (int P = 0; P < 2; ++P)                                        \
+      vm_n[P] = *reinterpret_cast<const u32x4*>(rec + (Q_VM + P * 2 * VM_BYTES) + lo16); \
+  }
+
+  // The first quad is requested before anything else, so the query set-up below runs under the
+  // latency of these loads.
+  // Software pipeline without extra registers: every piece of raw data is re-requested for the
+  // NEXT quad right after its last use for the current one, into the registers it has just
+  // freed -- K codes per channel half (after slices u = 1 and u = 3), V codes per pair of
+  // blocks -- so each load has 70-85 % of an iteration to arrive and the requests are spread
+  // evenly over time.  The metadata of quad k+1 is requested at the top of iteration k.
+  uint4 kraw[4][2], vraw[2][2];
+  u32x4 km_n[4], vm_n[2];
+  float2 an_n[4];
+  int qb = b0;
+  if (qb < b1) {
+    CQA_LOAD_META(qb)
+    CQA_LOAD_K(qb, 0)
+    CQA_LOAD_K(qb, 1)
+    CQA_LOAD_V(qb, 0)
+    CQA_LOAD_V(qb, 1)
+  }
+
   // Queries of the group as FP32 in LDS, rows of absent heads zero, each head pre-scaled by a
   // power of two S_h chosen so that |q S_h sigma| <= 2^14 for every sigma of this KV head (its
   // running maximum is kept at seal time): the scaled query then fits FP16 without overflow, and
   // elements too small for a normal FP16 low part are negligible against the largest ones.
+  // Wave w prepares the row of head w.
   // Lane (h, kg) reads channels (u>>1)*64 + kg*16 + (u&1)*8 + e of head h when it forms slice u.
-  for (int idx = threadIdx.x; idx < 4 * D; idx += 256) {
-    const int hh = idx / D, c = idx % D;
-    qbuf[hh][c] = hh < G ? __half2float(a.q[((int64_t)b * a.n_q + kvh * G + hh) * D + c]) : 0.0f;
-  }
-  __syncthreads();
   {
-    float2 qq = *reinterpret_cast<const float2*>(&qbuf[w][2 * l]);
+    float2 qq = __half22float2(q_in);
     float qmax = fmaxf(fabsf(qq.x), fabsf(qq.y));
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, m));
-    const float bound = qmax * a.sigmax[(int64_t)b * a.n_kv + kvh];
+    const float bound = qmax * sigmax_head;
     int e = 0;
     (void)frexpf(bound, &e);                       // bound < 2^e
     e = bound > 0.0f ? min(max(14 - e, -100), 100) : 0;
@@ -177,59 +255,13 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
   for (int g = 0; g < 8; ++g) acc[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // Loads of one quad.  Block indices are clamped to the split's last block, so a ragged tail
-  // and the prefetch issued by the last iteration re-read valid (cached) memory; what they
-  // bring in is masked or never used.  The prefetch is unconditional on purpose: guarding it
-  // with a branch makes every prefetched register a phi and costs dozens of spilled VGPRs.
-  //   K codes : block i, channel half cq; lane (token n, kg) takes bytes [16 l, +16) of each KB
-  //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
-  //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
-  //             2r + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
-  const int bl = a.debug == 1 ? b0 : max(b1 - 1, 0);   // last block of this wave's run
-#define CQA_LOAD_K(QB, CQ)                                                               \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const uint8_t* kcb = a.t1 + t1_offset(head_rec, min((QB) + i, bl), Q_KC, KC_BYTES);   \
-    kraw[i][CQ] = reinterpret_cast<const uint4*>(kcb + (CQ) * 1024)[l];                  \
-  }
-#define CQA_LOAD_V(QB, P)                                                                \
-  {                                                                                      \
-    const uint8_t* vcb = a.t1 + t1_offset(head_rec, min((QB) + 2 * (P) + (kg >> 1), bl), \
-                                          Q_VC, VC_BYTES) + (kg & 1) * 512 + n * 16;     \
-    vraw[P][0] = *reinterpret_cast<const uint4*>(vcb);                                   \
-    vraw[P][1] = *reinterpret_cast<const uint4*>(vcb + 256);                             \
-  }
-#define CQA_LOAD_META(QB)                                                                \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const int gb = min((QB) + i, bl);                                                    \
-    km_n[i] = reinterpret_cast<const u32x4*>(                                            \
-        a.t1 + t1_offset(head_rec, gb, Q_KM, KM_BYTES))[l];                              \
-    an_n[i] = *reinterpret_cast<const float2*>(                                          \
-        a.t1 + t1_offset(head_rec, gb, Q_AN, AN_BYTES));                                 \
-  }                                                                                      \
-  _Pragma("unroll") for (int P = 0; P < 2; ++P) {                                        \
-    const int gbm = min((QB) + 2 * P + (l >> 5), bl);                                    \
-    vm_n[P] = reinterpret_cast<const u32x4*>(                                            \
-        a.t1 + t1_offset(head_rec, gbm, Q_VM, VM_BYTES))[l & 31];                        \
-  }
-
-  // Software pipeline without extra registers: every piece of raw data is re-requested for the
-  // NEXT quad right after its last use for the current one, into the registers it has just
-  // freed -- K codes per channel half (after slices u = 1 and u = 3), V codes per pair of
-  // blocks -- so each load has 70-85 % of an iteration to arrive and the requests are spread
-  // evenly over time.  The metadata of quad k+1 is requested at the top of iteration k.
-  uint4 kraw[4][2], vraw[2][2];
-  u32x4 km_n[4], vm_n[2];
-  float2 an_n[4];
-  int qb = b0;
-  if (qb < b1) {
-    CQA_LOAD_META(qb)
-    CQA_LOAD_K(qb, 0)
-    CQA_LOAD_K(qb, 1)
-    CQA_LOAD_V(qb, 0)
-    CQA_LOAD_V(qb, 1)
-  }
-
+#ifdef CQA_PROBE_TIMESTAMPS
+  if (ts_on) ts[1] = wall_clock64();
+#endif
+  const int wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const bool younger = 2 * wg_lin >= (int)(gridDim.x * gridDim.y * gridDim.z);
   for (; qb < b1; qb += 4) {
+    if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
     float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -249,13 +281,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
     for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     float csum = 0.0f, dsum = 0.0f;
-#ifdef CQA_EXP_SKIP_QK
-#define CQA_QK_U 0
-#else
-#define CQA_QK_U 4
-#endif
 #pragma unroll
-    for (int u = 0; u < CQA_QK_U; ++u) {
+    for (int u = 0; u < 4; ++u) {
       const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
       const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
       const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
@@ -311,10 +338,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     }
     // per-block constant c_b = q.z and Delta_b (both still times S_h): summed over the four
     // channel slices, then handed to the rows that own head kg
-#ifdef CQA_EXP_SKIP_CB
-    const float cbs[4] = {csum, csum, csum, csum};
-    const float dls[4] = {dsum, dsum, dsum, dsum};
-#else
     float cb = csum;
     cb += __shfl_xor(cb, 16);
     cb += __shfl_xor(cb, 32);
@@ -328,7 +351,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
     const float cbs[4] = {cb4.x, cb4.y, cb4.z, cb4.w};
     const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
-#endif
 
     // ---- block statistics and online softmax of head kg; this lane is token n of each block.
     //      Branch-free: blocks past the wave's run (only in its last quad) are computed on the
@@ -380,6 +402,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     abuf[w][kg] = alpha;   // every lane of the row stores the same word
     wave_sync_m();
 
+    __builtin_amdgcn_s_setprio(0);
     // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
     if (__any(alpha != 1.0f)) {
 #pragma unroll
@@ -392,7 +415,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     offacc[1] *= alpha_op;
 
     // ---- values: two pairs of blocks, K = 32 tokens each; operand role (head h, group g' = j)
-#ifndef CQA_EXP_SKIP_PV
 #pragma unroll
     for (int P = 0; P < 2; ++P) {
       const int bi = 2 * P + (kg >> 1);
@@ -450,10 +472,12 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-#endif
     wave_sync_m();
   }
 
+#ifdef CQA_PROBE_TIMESTAMPS
+  if (ts_on) ts[2] = wall_clock64();
+#endif
   // ---- per-wave epilogue: fold the offset sums in; the softmax state of head kg is already
   //      complete in every lane of row kg
 #pragma unroll
@@ -521,6 +545,9 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   //      merges all partials.  The partials are written and read with device-coherent accesses;
   //      every thread waits until its own stores have been acknowledged before the ticket is
   //      taken, so whoever draws the last ticket finds every partial in place.
+#ifdef CQA_PROBE_TIMESTAMPS
+  if (ts_on) ts[3] = wall_clock64();
+#endif
   if (tickets == nullptr) return;   // the reduction runs as its own launch
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -535,6 +562,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   if (lastflag && w < G && a.debug != 2) reduce_head_wave<true>(ra, b, kvh * G + w, &kmbuf[w][0][0]);
 }
 
+#undef CQA_REC
 #undef CQA_LOAD_K
 #undef CQA_LOAD_V
 #undef CQA_LOAD_META
@@ -544,7 +572,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
                           dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
   static_assert(4 * KM_ROW >= 64, "reduction scratch aliases one wave's K-meta staging");
+#ifdef CQA_PROBE_TIMESTAMPS
+  const bool lm = false;
+#else
   const bool lm = a.blk_logmass != nullptr;
+#endif
 #define CQA_LAUNCH(GG)                                                                           \
   if (lm)                                                                                        \
     hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true>), grid, dim3(256), 0, st, ev0,   \
