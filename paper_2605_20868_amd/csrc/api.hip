@@ -187,8 +187,8 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   c->heads_total = s.heads;
   c->max_splits = s.max_splits;
   CQA_ALLOC_DEV(c->t1, s.t1);
-  // blocks that are not sealed yet must read as finite numbers: the decode pass may load (and
-  // mask) the unsealed blocks of a head's last record
+  // blocks that are not sealed yet must read as zeros: the decode pass loads whole records and
+  // only masks the scores of the unsealed blocks of a head's last record
   CQA_TRY(hipMemset(c->t1, 0, (size_t)s.t1));
   CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
   CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
@@ -243,6 +243,9 @@ int32_t cqa_cache_reset(cqa_cache* h, int32_t layer) {
   CQA_HIP(hipDeviceSynchronize());
   CQA_HIP(hipMemset(c->sigmax + head_index(c, layer, 0, 0), 0,
                     (size_t)c->desc.batch * c->desc.n_kv_heads * 4));
+  // unsealed blocks must read as zeros (the decode pass loads whole records and relies on it)
+  CQA_HIP(hipMemset(c->t1 + head_index(c, layer, 0, 0) * c->nq_cap * QUAD_BYTES, 0,
+                    (size_t)c->desc.batch * c->desc.n_kv_heads * c->nq_cap * QUAD_BYTES));
   c->length[layer] = 0;
   return CQA_OK;
 }

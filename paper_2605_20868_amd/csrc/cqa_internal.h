@@ -41,12 +41,16 @@ constexpr int AN_BYTES = 8;
 //   [K codes 4 x 2048][K meta 4 x 1024][V codes 4 x 1024][V meta 4 x 512][annotations 4 x 8]
 // so that a wave, which works on one quad at a time, streams a single 18464-byte run instead of
 // five separate arrays (measured: 7.1 TB/s against 6.5 TB/s for the same bytes in five arrays).
+// Blocks that are not sealed (yet) always read as zeros: the memory is cleared at creation and at reset.
 constexpr int Q_KC = 0;
 constexpr int Q_KM = Q_KC + 4 * KC_BYTES;   //  8192
 constexpr int Q_VC = Q_KM + 4 * KM_BYTES;   // 12288
 constexpr int Q_VM = Q_VC + 4 * VC_BYTES;   // 16384
 constexpr int Q_AN = Q_VM + 4 * VM_BYTES;   // 18432
-constexpr int QUAD_BYTES = Q_AN + 4 * AN_BYTES;  // 18464 = 64 tokens x 288.5 B
+constexpr int QUAD_DATA_BYTES = Q_AN + 4 * AN_BYTES;            // 18464 = 64 tokens x 288.5 B
+// records start on 128-byte lines (96 bytes of padding, 0.5 %): every 1 KB wave load then covers
+// exactly 8 lines and no line is shared between two records
+constexpr int QUAD_BYTES = (QUAD_DATA_BYTES + 127) / 128 * 128;    // 18560
 
 // address of one piece of block `blk` of head-local numbering; `head_rec` = first record of the head
 __host__ __device__ inline int64_t t1_offset(int64_t head_rec, int64_t blk, int piece_off,

@@ -156,6 +156,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   // the presumably younger workgroup (second half of the launch order) one level above the older
   // one in the high phase: of the four phase combinations each wave then wins two.
   __builtin_amdgcn_s_setprio(3);
+  const int wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const bool younger = 2 * wg_lin >= (int)(gridDim.x * gridDim.y * gridDim.z);
   // This wave's query row (head w of the group), requested before the bulk loads: loads return in
   // order, so the row arrives first and the set-up below does not wait for a whole quad.
   __half2 q_in = __floats2half2_rn(0.0f, 0.0f);
@@ -258,8 +260,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #ifdef CQA_PROBE_TIMESTAMPS
   if (ts_on) ts[1] = wall_clock64();
 #endif
-  const int wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  const bool younger = 2 * wg_lin >= (int)(gridDim.x * gridDim.y * gridDim.z);
   for (; qb < b1; qb += 4) {
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
     float2 an[4];
@@ -353,17 +353,18 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
 
     // ---- block statistics and online softmax of head kg; this lane is token n of each block.
-    //      Branch-free: blocks past the wave's run (only in its last quad) are computed on the
-    //      clamped data and masked by wave-uniform selects.
+    //      Branch-free.  Blocks past the end of the head (only in its last quad) hold zeros --
+    //      unsealed memory is cleared -- so their eta, nu and Delta_b are already zero; giving
+    //      their scores a huge negative value makes every weight and mass they produce vanish.
     float mbv[4], ptv[4], sbv[4];
     float mq = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float s = (C[i][i] + cbs[i]) * score_scale;
+      const float s = (qb + i < b1) ? (C[i][i] + cbs[i]) * score_scale : -1.0e30f;
       mbv[i] = row_max(s);
       ptv[i] = __expf(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
-      mq = (qb + i < b1) ? fmaxf(mq, mbv[i]) : mq;
+      mq = fmaxf(mq, mbv[i]);
     }
     const float m_new = fmaxf(m_run, mq);
     const float alpha = __expf(m_run - m_new);
@@ -374,17 +375,16 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float lbv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const bool vi = qb + i < b1;
-      const float f = vi ? __expf(mbv[i] - m_new) : 0.0f;
+      const float f = __expf(mbv[i] - m_new);
       const float sf = sbv[i] * f;
       const float ce = sf * an[i].x;
-      const float lb = vi ? mbv[i] + __logf(sbv[i]) : -INFINITY;
+      const float lb = mbv[i] + __logf(sbv[i]);
       lbv[i] = lb;
       l_run += sf;
       ev += ce;
       evmax = fmaxf(evmax, ce);
-      dmax = fmaxf(dmax, vi ? dls[i] : 0.0f);
-      vmax = fmaxf(vmax, vi ? an[i].y : 0.0f);
+      dmax = fmaxf(dmax, dls[i]);
+      vmax = fmaxf(vmax, an[i].y);
       const bool g1 = lb > t1, g2 = lb > t2;   // blocks arrive in increasing order: ties keep the lower index
       t2 = g1 ? t1 : (g2 ? lb : t2);
       i1 = g1 ? qb + i : i1;
