@@ -167,9 +167,10 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 
   // Loads of one quad = one Tier-1 record.  Every address is the record's wave-uniform base plus
   // a constant plus a per-lane 32-bit offset that never changes, so the loop carries no vector
-  // address arithmetic.  The prefetch issued by a wave's last iteration is aimed at its own last
-  // record again (cached, never used); a ragged last quad of the head reads the not yet sealed
-  // blocks of its record, which hold zeros or an earlier run's finite data and are masked out.
+  // address arithmetic.  The prefetch issued by a wave's last iteration is never used: it is
+  // aimed at one record per head that every wave shares (the head's first), which stays in L2, so
+  // it costs no HBM traffic.  A ragged last quad of the head reads the not yet sealed blocks of
+  // its record, which hold zeros and are masked out.
   // The prefetch is unconditional on purpose: guarding it with a branch makes every prefetched
   // register a phi and costs dozens of spilled VGPRs.
   //   K codes : block i, channel half cq; lane (token n, kg) takes bytes [16 l, +16) of each KB
@@ -177,10 +178,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
   //             2P + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
   const int ql = a.debug == 1 ? b0 : max((b1 - 1) & ~3, b0);   // first block of the wave's last quad
+  const int park = a.debug == 1 ? (b0 >> 2) : 0;   // record that absorbs the unused last prefetch
   const uint8_t* const head_base = a.t1 + head_rec * QUAD_BYTES;
   const uint32_t lo16 = (uint32_t)l * 16u;
   const uint32_t vo16 = (uint32_t)kg * 512u + (uint32_t)n * 16u;
-#define CQA_REC(QB) (head_base + (int64_t)(min((QB), ql) >> 2) * QUAD_BYTES)
+#define CQA_REC(QB) (head_base + (int64_t)((QB) <= ql ? (QB) >> 2 : park) * QUAD_BYTES)
 #define CQA_LOAD_K(QB, CQ)                                                               \
   {                                                                                      \
     const uint8_t* rec = CQA_REC(QB) + (Q_KC + (CQ) * 1024);                             \
