@@ -8,7 +8,9 @@ from .attention import (FLAG_ANY, FLAG_KEY, FLAG_PRECOND, FLAG_RANK, FLAG_TOTAL,
                         RUNG_SHIFT, Tolerances, certified_head, key_term, softmax_attention)
 from .cache import OracleLayerCache, ladder_decision
 from . import quantizer
+from . import adaptive
+from .adaptive import SelectorParams
 
 __all__ = ["FLAG_ANY", "FLAG_KEY", "FLAG_PRECOND", "FLAG_RANK", "FLAG_TOTAL", "FLAG_VAL",
            "RUNG_SHIFT", "Tolerances", "certified_head", "key_term", "softmax_attention",
-           "OracleLayerCache", "ladder_decision", "quantizer"]
+           "OracleLayerCache", "ladder_decision", "quantizer", "adaptive", "SelectorParams"]

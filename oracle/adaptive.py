@@ -1,0 +1,232 @@
+"""CPU oracle, part 4: adaptive key precision (test infrastructure only).
+
+Follows the paper's "Adaptive Precision Selection" steps, the first rung of its
+"Fallback Ladder", the tail-restricted key bound with the achieved INT8-estimated
+tail mass (total error bound), the "INT8 Mass Estimation" theorem's normalised
+tail implication, and the "Ranking-Consistency Check" with its boundary
+verification.  All real-number arithmetic is float64.
+
+Readings where the paper is silent or offers a choice (the HIP path follows the same):
+
+* Mass fractions are taken over EVERYTHING the head attends to, i.e. the sealed
+  blocks and the trailing FP16 tokens.  The trailing tokens are exact, so their
+  mass counts as covered: C_k = rho_trail + sum of the k largest block masses,
+  and the estimated tail mass is alpha_hat_T = 1 - C_K = sum over unpromoted
+  blocks of p_b^int8.  With nothing promoted this is the alpha_hat of the one-pass
+  certificate.
+* Blocks are ranked by INT8 log-mass, ties by lower block index.
+* K* = min{k : C_k >= tau_cov}, then clamped to [K_min, K_max] and to the number
+  of sealed blocks.
+* Rung 1: while the key term computed from the achieved alpha_hat_T exceeds
+  eps_key and K can still grow, K doubles (capped at k_limit >= K_max, the
+  scratch capacity, and at the number of blocks).
+* Key precision is chosen per KV group: the promoted set of a group is the union
+  of its query heads' selections (the paper's per-KV-group selection variant).
+  A head's tail is then the complement of the union, which only shrinks
+  alpha_hat_T; the bound stays valid.
+* Delta in the bound is Delta_h of the scoring pass (maximum over all sealed
+  blocks): the global-max-shift factor of the mass theorem ranges over all blocks.
+* Ranking check at depth r = 1 over the promoted set F of the head's group:
+  (i) the block with the largest FP16 log-mass in F must be the block with the
+  largest INT8 log-mass in F; (ii) boundary: no unpromoted block may have
+  l_b^int8 + Delta_h (+ eps_guard) > the largest FP16 log-mass in F.  Either
+  failure sets RANK.  The optional rank_min_mass gate of the one-pass path
+  applies here too (0 = the paper's unconditional check).
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+
+from . import attention as att
+
+
+@dataclasses.dataclass
+class SelectorParams:
+    tau_cov: float = 0.995
+    k_min: int = 2
+    k_max: int = 128
+    k_limit: int = 128          # cap for Rung-1 doubling (>= k_max)
+
+
+def rank_blocks(logmass: np.ndarray) -> np.ndarray:
+    """Block indices by descending INT8 log-mass; equal masses keep the lower index first."""
+    return np.argsort(-np.asarray(logmass, dtype=np.float64), kind="stable")
+
+
+def select_blocks(logmass: np.ndarray, lse: float, par: SelectorParams) -> dict:
+    """Steps 1-4 of the adaptive selection for one head.
+
+    logmass [NB]: INT8 block log-masses of the scoring pass; lse: log of the total
+    estimated mass (sealed + trailing tokens).  Returns the ranking, K* before any
+    Rung-1 growth, and the estimated tail mass left after promoting the K* best.
+    """
+    l = np.asarray(logmass, dtype=np.float64)
+    nb = l.shape[0]
+    order = rank_blocks(l)
+    p = np.exp(l[order] - lse)                 # estimated normalised block masses, descending
+    total_blocks = float(p.sum())
+    rho_trail = 1.0 - total_blocks             # exact FP16 tokens: always covered
+    covered = rho_trail + np.concatenate([[0.0], np.cumsum(p)])   # C_0 .. C_NB
+    hit = np.nonzero(covered >= par.tau_cov)[0]
+    k = int(hit[0]) if hit.size else nb
+    k = max(par.k_min, min(k, par.k_max))
+    k = min(k, nb)
+    return dict(order=order, k_star=k, p_sorted=p, rho_trail=rho_trail)
+
+
+def tail_mass(sel: dict, k: int) -> float:
+    """alpha_hat_T after promoting the k best-ranked blocks: sum of the other blocks' masses."""
+    return float(sel["p_sorted"][k:].sum())
+
+
+def rung1_expand(sel: dict, delta_h: float, v_max: float, tol: att.Tolerances,
+                 par: SelectorParams) -> int:
+    """Rung 1: double K while the key term of the achieved tail exceeds eps_key."""
+    nb = sel["order"].shape[0]
+    cap = min(max(par.k_limit, par.k_max), nb)
+    k = sel["k_star"]
+    while k < cap and att.key_term(delta_h, tail_mass(sel, k), v_max, tol.mass_exp,
+                                   tol.key_bound_mode) > tol.eps_key:
+        k = min(max(2 * k, 1), cap)
+    return k
+
+
+def group_union(selections, nb: int) -> np.ndarray:
+    """Boolean mask [NB]: union of the heads' promoted sets (each an index array)."""
+    mask = np.zeros(nb, dtype=bool)
+    for idx in selections:
+        mask[np.asarray(idx, dtype=np.int64)] = True
+    return mask
+
+
+def ranking_check(l_int8: np.ndarray, l_fp16: np.ndarray, promoted: np.ndarray, delta_h: float,
+                  eps_guard: float) -> dict:
+    """Depth-1 ranking consistency plus boundary verification for one head.
+
+    l_fp16 holds FP16 log-masses on promoted blocks (its values elsewhere are ignored).
+    """
+    promoted = np.asarray(promoted, dtype=bool)
+    if not promoted.any():
+        return dict(disagree=False, boundary=False, top_fp16=-1, top_int8=-1)
+    idx = np.nonzero(promoted)[0]
+    top_fp16 = int(idx[np.argmax(l_fp16[idx])])          # first maximum = lowest index
+    top_int8 = int(idx[np.argmax(l_int8[idx])])
+    best = float(l_fp16[top_fp16])
+    tail = ~promoted
+    boundary = bool(tail.any() and float(l_int8[tail].max()) + delta_h + eps_guard > best)
+    return dict(disagree=top_fp16 != top_int8, boundary=boundary, top_fp16=top_fp16,
+                top_int8=top_int8)
+
+
+def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat: np.ndarray,
+               eta: np.ndarray, nu: np.ndarray, k_trail16: np.ndarray, v_trail16: np.ndarray,
+               promoted: np.ndarray, l_int8: np.ndarray, lse_int8: float, delta_h: float,
+               tol: att.Tolerances) -> dict:
+    """The attend pass with mask-gated key precision, one head, one step.
+
+    k_hat float64 [NB*B, d] INT8 reconstructions; k16_sealed float16 [NB*B, d] the FP16
+    originals of the same tokens; promoted bool [NB]; l_int8, lse_int8, delta_h: the scoring
+    pass's block log-masses, total log-mass and Delta_h for this head.
+    Values are INT4 reconstructions for every sealed block.
+    """
+    q = q16.astype(np.float64)
+    d = q.shape[0]
+    nb = promoted.shape[0]
+    blk = k_hat.shape[0] // nb if nb else 16
+    inv = 1.0 / math.sqrt(d)
+    tok_prom = np.repeat(np.asarray(promoted, dtype=bool), blk)
+    k_mix = np.where(tok_prom[:, None], k16_sealed.astype(np.float64), k_hat)
+    s_seal = (k_mix @ q) * inv if nb else np.zeros(0)
+    r = k_trail16.shape[0]
+    kt = k_trail16.astype(np.float64)
+    vt = v_trail16.astype(np.float64)
+    s_trail = (kt @ q) * inv if r else np.zeros(0)
+    s_all = np.concatenate([s_seal, s_trail])
+    m = s_all.max()
+    e = np.exp(s_all - m)
+    z_sum = e.sum()
+    a = e / z_sum
+    lse = m + math.log(z_sum)
+    v_all = np.concatenate([v_hat, vt]) if r else v_hat
+    o = a @ v_all
+
+    sb = s_seal.reshape(nb, blk)
+    m_b = sb.max(axis=1)
+    l_b = m_b + np.log(np.exp(sb - m_b[:, None]).sum(axis=1))
+    rho = np.exp(l_b - lse)
+    contrib = rho * eta.astype(np.float64)
+    e_val = float(contrib.sum())
+    max_contrib = float(contrib.max())
+    v_max = float(nu.max())
+    if r:
+        v_max = max(v_max, float(np.sqrt((vt ** 2).sum(axis=1)).max()))
+    alpha_hat = float(np.exp(np.asarray(l_int8, dtype=np.float64)[~promoted] - lse_int8).sum())
+    e_key = att.key_term(delta_h, alpha_hat, v_max, tol.mass_exp, tol.key_bound_mode)
+
+    rk = ranking_check(np.asarray(l_int8, dtype=np.float64), l_b, promoted, delta_h, tol.eps_guard)
+    flags = 0
+    if e_key > tol.eps_key:
+        flags |= att.FLAG_KEY
+    if e_val > tol.eps_val or max_contrib > tol.v_tol:
+        flags |= att.FLAG_VAL
+    if tol.rank_depth >= 1 and promoted.any():
+        rho_top = float(rho[rk["top_fp16"]])
+        if rho_top >= tol.rank_min_mass and (rk["disagree"] or rk["boundary"]):
+            flags |= att.FLAG_RANK
+    if not all(math.isfinite(x) for x in (e_key, e_val, delta_h, v_max, lse)) \
+            or not np.isfinite(o).all():
+        flags |= att.FLAG_PRECOND
+    if e_key + e_val > tol.eps_total:
+        flags |= att.FLAG_TOTAL
+    flags |= tol.force_flags
+    return dict(O=o, E_key=e_key, E_val=e_val, delta_h=delta_h, v_max=v_max,
+                alpha_tail_hat=alpha_hat, lse=lse, max_block_contrib=max_contrib,
+                flags=flags, blk_logmass=l_b, weights=a, ranking=rk)
+
+
+def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorParams,
+                    groups=None) -> dict:
+    """Scoring pass, selection (+ Rung 1), per-group union, attend pass with gated key precision.
+
+    cache: an OracleLayerCache.  q16 float16 [Bt, Hq, d].  `groups` optionally restricts the
+    work to an iterable of (b, kv_head) pairs.  Returns {(b, h): result dict}; each result is
+    mixed_head's, plus 'k_star' (the head's own K after Rung 1), 'selected' (its own block
+    indices, best first), 'promoted' (the group's union mask) and 'scoring' (the one-pass result).
+    The scoring pass runs with every threshold disabled: its flags are not part of the result.
+    """
+    from . import quantizer as qz
+
+    bt, hq, d = q16.shape
+    g = hq // cache.hkv
+    nb = cache.n_blocks
+    todo = [(b, kh) for b in range(bt) for kh in range(cache.hkv)] if groups is None else list(groups)
+    out = {}
+    for b, kh in todo:
+        k_hat = qz.dequantize_keys(cache.k_codes[b, kh], cache.sigma[b, kh],
+                                   cache.z[b, kh]).reshape(nb * qz.B, d)
+        v_hat = qz.dequantize_values(cache.v_codes[b, kh], cache.v_scale[b, kh],
+                                     cache.v_offset[b, kh]).reshape(nb * qz.B, d)
+        k_tr, v_tr = cache.k16[b, kh, nb * qz.B:], cache.v16[b, kh, nb * qz.B:]
+        scoring, picks, ks = [], [], []
+        for i in range(g):
+            h = kh * g + i
+            sc = att.certified_head(q16[b, h], k_hat, v_hat, cache.sigma[b, kh], cache.eta[b, kh],
+                                    cache.nu[b, kh], k_tr, v_tr, att.Tolerances())
+            sel = select_blocks(sc["blk_logmass"], sc["lse"], par)
+            k = rung1_expand(sel, sc["delta_h"], sc["v_max"], tol, par)
+            scoring.append(sc)
+            picks.append(sel["order"][:k])
+            ks.append(k)
+        union = group_union(picks, nb)
+        for i in range(g):
+            h = kh * g + i
+            sc = scoring[i]
+            res = mixed_head(q16[b, h], k_hat, cache.k16[b, kh, :nb * qz.B], v_hat, cache.eta[b, kh],
+                             cache.nu[b, kh], k_tr, v_tr, union, sc["blk_logmass"], sc["lse"],
+                             sc["delta_h"], tol)
+            res.update(k_star=ks[i], selected=picks[i], promoted=union, scoring=sc)
+            out[(b, h)] = res
+    return out

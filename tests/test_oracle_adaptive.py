@@ -1,0 +1,218 @@
+"""Pins for the adaptive-precision part of the oracle: each test checks it against something
+other than itself (brute force, the paper's theorem and worked numbers, textbook special cases)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from oracle import adaptive as ad
+from oracle import attention as att
+from oracle import quantizer as qz
+
+
+def small_cache(seed, n_tokens=300, scale=1.0, outlier=False):
+    """One KV head with 4 query heads, a few hundred tokens (18 sealed blocks + 12 trailing)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    k = (rng.standard_normal((1, 1, n_tokens, 128)) * scale).astype(np.float32)
+    if outlier:
+        k[..., 5] *= 20.0
+    v = rng.standard_normal((1, 1, n_tokens, 128)).astype(np.float32)
+    q = (rng.standard_normal((1, 4, 128)) * 1.5).astype(np.float16)
+    oc = oracle.OracleLayerCache(1, 1)
+    oc.append(k.astype(np.float16), v.astype(np.float16))
+    return oc, q
+
+
+# ---------------------------------------------------------------- selector (steps 1-4)
+
+def brute_force_k(masses, rho_trail, tau):
+    """Smallest number of blocks whose masses, taken largest first, cover tau with the trailing mass."""
+    best = sorted(masses, reverse=True)
+    c = rho_trail
+    for k in range(len(best) + 1):
+        if c >= tau:
+            return k
+        if k < len(best):
+            c += best[k]
+    return len(best)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_selector_is_the_minimal_cover(seed):
+    rng = np.random.Generator(np.random.Philox(100 + seed))
+    nb = 40
+    logits = rng.standard_normal(nb) * 3.0
+    rho_trail = 0.07
+    masses = np.exp(logits) / np.exp(logits).sum() * (1.0 - rho_trail)
+    lse = 1.234
+    logmass = np.log(masses) + lse
+    for tau in (0.5, 0.9, 0.995):
+        sel = ad.select_blocks(logmass, lse, ad.SelectorParams(tau_cov=tau, k_min=0, k_max=nb))
+        assert sel["k_star"] == brute_force_k(list(masses), rho_trail, tau)
+        k = sel["k_star"]
+        # the chosen blocks are the k heaviest, the tail mass is what the others hold
+        chosen = set(sel["order"][:k].tolist())
+        assert chosen == set(np.argsort(-masses, kind="stable")[:k].tolist())
+        others = [masses[i] for i in range(nb) if i not in chosen]
+        assert ad.tail_mass(sel, k) == pytest.approx(sum(others), rel=1e-12, abs=1e-15)
+        assert abs(sel["rho_trail"] - rho_trail) < 1e-12
+        if k < nb:
+            assert ad.tail_mass(sel, k) <= 1.0 - tau + 1e-12       # target met when not clamped
+
+
+def test_selector_clamps_and_ties():
+    logmass = np.array([0.0, 2.0, 2.0, -1.0, 2.0, 0.5])
+    lse = math.log(np.exp(logmass).sum())
+    sel = ad.select_blocks(logmass, lse, ad.SelectorParams(tau_cov=0.0, k_min=2, k_max=4))
+    assert sel["k_star"] == 2                                     # K_min
+    assert sel["order"].tolist() == [1, 2, 4, 5, 0, 3]            # equal masses: lower index first
+    sel = ad.select_blocks(logmass, lse, ad.SelectorParams(tau_cov=1.1, k_min=2, k_max=4))
+    assert sel["k_star"] == 4                                     # K_max
+    sel = ad.select_blocks(logmass, lse, ad.SelectorParams(tau_cov=1.1, k_min=2, k_max=100))
+    assert sel["k_star"] == 6                                     # never more than the blocks there are
+
+
+def test_rung1_doubles_until_the_key_term_fits():
+    nb = 64
+    logmass = -0.05 * np.arange(nb)
+    lse = math.log(np.exp(logmass).sum())
+    par = ad.SelectorParams(tau_cov=0.2, k_min=1, k_max=4, k_limit=64)
+    sel = ad.select_blocks(logmass, lse, par)
+    k0 = sel["k_star"]
+    delta, vmax = 0.18, 10.0
+    loose = att.Tolerances(eps_key=math.inf, key_bound_mode=1)
+    assert ad.rung1_expand(sel, delta, vmax, loose, par) == k0
+    target = att.key_term(delta, ad.tail_mass(sel, 4 * k0), vmax, 2, 1)
+    tol = att.Tolerances(eps_key=target * 1.0001, key_bound_mode=1)
+    assert ad.rung1_expand(sel, delta, vmax, tol, par) == 4 * k0  # two doublings, not three
+    never = att.Tolerances(eps_key=0.0, key_bound_mode=1)
+    assert ad.rung1_expand(sel, delta, vmax, never, par) == 64    # stops at the cap
+
+
+def test_worked_operating_point():
+    """tau_cov = 0.995, Delta = 0.18: tail mass 0.005 gives 0.006211 V_max (0.007436 with e^{3 Delta}),
+    the numbers of the paper's tail-restricted key bound."""
+    masses = np.array([0.9, 0.095, 0.003, 0.002])
+    logmass = np.log(masses)
+    sel = ad.select_blocks(logmass, 0.0, ad.SelectorParams(tau_cov=0.995, k_min=0, k_max=4))
+    assert sel["k_star"] == 2
+    alpha = ad.tail_mass(sel, 2)
+    assert alpha == pytest.approx(0.005, rel=1e-12)
+    assert att.key_term(0.18, alpha, 1.0, 2, 1) == pytest.approx(0.006211, abs=5e-7)
+    assert att.key_term(0.18, alpha, 1.0, 3, 1) == pytest.approx(0.007436, abs=5e-7)
+
+
+# ---------------------------------------------------------------- attend pass with gated key precision
+
+@pytest.mark.parametrize("seed", range(4))
+def test_special_cases_reduce_to_known_attention(seed):
+    oc, q = small_cache(seed)
+    nb = oc.n_blocks
+    k_hat = qz.dequantize_keys(oc.k_codes[0, 0], oc.sigma[0, 0], oc.z[0, 0]).reshape(nb * 16, 128)
+    v_hat = qz.dequantize_values(oc.v_codes[0, 0], oc.v_scale[0, 0], oc.v_offset[0, 0]).reshape(nb * 16, 128)
+    k_tr, v_tr = oc.k16[0, 0, nb * 16:], oc.v16[0, 0, nb * 16:]
+    tol = att.Tolerances()
+    one_pass = att.certified_head(q[0, 1], k_hat, v_hat, oc.sigma[0, 0], oc.eta[0, 0], oc.nu[0, 0],
+                                  k_tr, v_tr, tol)
+    args = (q[0, 1], k_hat, oc.k16[0, 0, :nb * 16], v_hat, oc.eta[0, 0], oc.nu[0, 0], k_tr, v_tr)
+    tail = (one_pass["blk_logmass"], one_pass["lse"], one_pass["delta_h"], tol)
+    # nothing promoted: the one-pass result
+    none = ad.mixed_head(*args, np.zeros(nb, bool), *tail)
+    assert np.allclose(none["O"], one_pass["O"], rtol=0, atol=1e-14)
+    for f in ("E_key", "E_val", "alpha_tail_hat", "lse", "max_block_contrib"):
+        assert none[f] == pytest.approx(one_pass[f], rel=1e-12)
+    # everything promoted: textbook attention over the FP16 keys and the INT4-reconstructed values
+    full = ad.mixed_head(*args, np.ones(nb, bool), *tail)
+    ref = att.softmax_attention(q[0, 1], oc.k16[0, 0].astype(np.float64),
+                                np.concatenate([v_hat, v_tr.astype(np.float64)]))
+    assert np.allclose(full["O"], ref, rtol=0, atol=1e-13)
+    assert full["alpha_tail_hat"] == 0.0 and full["E_key"] == 0.0
+
+
+@pytest.mark.parametrize("seed,scale,outlier", [(0, 1.0, False), (1, 1.0, True), (2, 3.0, False),
+                                                (3, 0.3, True), (4, 2.0, True)])
+def test_tail_theorem_and_bounds_hold(seed, scale, outlier):
+    """The true (FP16-key) mass of the unpromoted blocks is at most e^{2 Delta_h} alpha_hat_T, the key
+    term bounds the output change caused by the INT8 keys that remain, and key + value terms bound
+    the distance to the FP16 reference."""
+    oc, q = small_cache(10 + seed, scale=scale, outlier=outlier)
+    nb = oc.n_blocks
+    v_hat = qz.dequantize_values(oc.v_codes[0, 0], oc.v_scale[0, 0], oc.v_offset[0, 0]).reshape(nb * 16, 128)
+    v_mixed_all = np.concatenate([v_hat, oc.v16[0, 0, nb * 16:].astype(np.float64)])
+    for tau, kmax in ((0.5, 3), (0.9, 8), (0.995, nb)):
+        par = ad.SelectorParams(tau_cov=tau, k_min=1, k_max=kmax, k_limit=kmax)
+        res = ad.adaptive_decode(oc, q, att.Tolerances(key_bound_mode=1), par)
+        for h in range(4):
+            r = res[(0, h)]
+            qf = q[0, h].astype(np.float64)
+            s_true = oc.k16[0, 0].astype(np.float64) @ qf / math.sqrt(128.0)
+            a_true = np.exp(s_true - s_true.max())
+            a_true /= a_true.sum()
+            tail_tok = np.concatenate([np.repeat(~r["promoted"], 16), np.zeros(oc.length - nb * 16, bool)])
+            true_tail = a_true[tail_tok].sum()
+            assert true_tail <= min(1.0, math.exp(2 * r["delta_h"]) * r["alpha_tail_hat"]) * (1 + 1e-9)
+            # the head's own selection is inside the union, the union holds at most 4 K_max blocks
+            assert r["promoted"][r["selected"]].all() and r["promoted"].sum() <= 4 * kmax
+            o_exact_keys = a_true @ v_mixed_all
+            assert np.linalg.norm(r["O"] - o_exact_keys) <= r["E_key"] * (1 + 1e-9) + 1e-12
+            o_ref = att.softmax_attention(q[0, h], oc.k16[0, 0], oc.v16[0, 0])
+            assert np.linalg.norm(r["O"] - o_ref) <= (r["E_key"] + r["E_val"]) * (1 + 1e-9) + 1e-12
+            # promotion can only lower the estimated tail
+            assert r["alpha_tail_hat"] <= r["scoring"]["alpha_tail_hat"] + 1e-15
+
+
+def test_promotion_shrinks_the_key_term_by_orders_of_magnitude():
+    """A peaked head: a handful of promoted blocks hold almost all the mass, so the key term with the
+    achieved tail is far below the one-pass key term (the reason for the second pass)."""
+    oc, q = small_cache(77, n_tokens=1024 + 5)
+    q = q.copy()
+    q[0, 2] = (oc.k16[0, 0, 321].astype(np.float32) * 0.9).astype(np.float16)   # aligned with one key
+    res = ad.adaptive_decode(oc, q, att.Tolerances(key_bound_mode=1),
+                             ad.SelectorParams(tau_cov=0.995, k_min=2, k_max=16, k_limit=16))
+    r = res[(0, 2)]
+    assert r["promoted"][321 // 16]
+    assert r["E_key"] < 0.05 * r["scoring"]["E_key"]
+
+
+# ---------------------------------------------------------------- ranking consistency
+
+def test_ranking_check_hand_cases():
+    l8 = np.array([5.0, 4.0, 1.0, 0.5, 0.2])
+    prom = np.array([True, True, False, False, False])
+    ok = ad.ranking_check(l8, np.array([5.1, 3.9, 0, 0, 0]), prom, 0.2, 1e-6)
+    assert not ok["disagree"] and not ok["boundary"] and ok["top_fp16"] == 0
+    swap = ad.ranking_check(l8, np.array([4.4, 4.6, 0, 0, 0]), prom, 0.2, 1e-6)
+    assert swap["disagree"] and swap["top_fp16"] == 1 and swap["top_int8"] == 0
+    # a tail block whose upper-bounded log-mass reaches the best promoted FP16 log-mass
+    near = ad.ranking_check(np.array([5.0, 4.0, 4.95, 0.5, 0.2]), np.array([5.1, 3.9, 0, 0, 0]), prom, 0.2, 1e-6)
+    assert near["boundary"] and not near["disagree"]
+    # exactly at the boundary counts as not certified once the guard is added, strictly below passes
+    edge = ad.ranking_check(np.array([5.0, 4.0, 4.75, 0.5, 0.25]), np.array([5.0, 3.5, 0, 0, 0]), prom, 0.25, 0.0)
+    assert not edge["boundary"]                                  # 4.75 + 0.25 = 5.0 is not > 5.0
+    over = ad.ranking_check(np.array([5.0, 4.0, 4.75, 0.5, 0.25]), np.array([5.0, 3.5, 0, 0, 0]), prom, 0.25, 2.0 ** -20)
+    assert over["boundary"]
+    empty = ad.ranking_check(l8, l8, np.zeros(5, bool), 0.2, 1e-6)
+    assert not empty["disagree"] and not empty["boundary"]
+
+
+def test_boundary_check_is_sound():
+    """When no flag is raised, the block with the largest true (FP16-key) log-mass is the promoted
+    block the check names: an unpromoted block cannot outrank it."""
+    hits = 0
+    for seed in range(12):
+        oc, q = small_cache(200 + seed, outlier=bool(seed & 1))
+        nb = oc.n_blocks
+        res = ad.adaptive_decode(oc, q, att.Tolerances(rank_depth=1),
+                                 ad.SelectorParams(tau_cov=0.9, k_min=1, k_max=6, k_limit=6))
+        for h in range(4):
+            r = res[(0, h)]
+            if r["flags"] & att.FLAG_RANK:
+                continue
+            hits += 1
+            s_true = (oc.k16[0, 0, :nb * 16].astype(np.float64) @ q[0, h].astype(np.float64)) / math.sqrt(128.0)
+            sb = s_true.reshape(nb, 16)
+            l_true = sb.max(axis=1) + np.log(np.exp(sb - sb.max(axis=1, keepdims=True)).sum(axis=1))
+            assert int(np.argmax(l_true)) == r["ranking"]["top_fp16"]
+    assert hits > 0
