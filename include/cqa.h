@@ -198,6 +198,64 @@ int32_t cqa_decode_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
                         uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
                         void* stream);
 
+/* ---- adaptive key precision: the paper's "Adaptive Precision Selection",
+ *      first rung of its "Fallback Ladder", the total error bound with the
+ *      achieved tail mass, and its "Ranking-Consistency Check" ---------------- */
+
+/* Parameters of the selector (the paper's policy table: tau_cov, K_min, K_max). */
+typedef struct cqa_selector {
+  float tau_cov;   /* coverage threshold on INT8-estimated mass (paper: 0.995)       */
+  int32_t k_min;   /* K* is clamped to [k_min, k_max] and to the sealed blocks       */
+  int32_t k_max;   /* 0 <= k_min <= k_max <= k_limit <= 512                          */
+  int32_t k_limit; /* cap of the Rung-1 doubling (scratch capacity per head)         */
+} cqa_selector;
+
+/* One decode step of `layer` with mask-gated key precision, all on `stream`:
+ *  1. scoring pass = cqa_certified_decode, which also yields the INT8 block
+ *     log-masses l_b, Delta_h and V_max of every head;
+ *  2. selection per head: blocks ranked by l_b (ties: lower index), K* = the
+ *     smallest k whose blocks, with the exact trailing tokens, hold >= tau_cov
+ *     of the estimated mass, clamped; Rung 1: K doubles (up to k_limit) while
+ *     the key term of the achieved tail exceeds tol->eps_key;
+ *  3. the promoted set of a (batch, kv-head) group is the union of its heads'
+ *     selections; the FP16 keys of those blocks are gathered from the pinned
+ *     Tier-2 originals into a device scratch by a kernel (no host step);
+ *  4. attend pass: as the scoring pass, but promoted blocks are scored with
+ *     their FP16 keys (values stay INT4); E_val uses the masses of this pass;
+ *     E_key uses alpha_hat_T = the scoring pass's estimated mass of the blocks
+ *     the group left in INT8, and the scoring pass's Delta_h;
+ *  5. ranking check at depth 1 (if tol->rank_depth >= 1): RANK is set when the
+ *     promoted block with the largest FP16 log-mass is not the one with the
+ *     largest INT8 log-mass, or when an unpromoted block has
+ *     l_b + Delta_h + eps_guard > that largest FP16 log-mass (gated by
+ *     tol->rank_min_mass on the top block's mass).
+ * Outputs as cqa_certified_decode; cert.alpha_tail_hat is the achieved tail,
+ * cert.top_block the promoted block with the largest FP16 log-mass,
+ * cert.rank_margin = that log-mass - (largest unpromoted l_b + Delta_h).
+ * Flags only REQUEST a fallback (Rung 3 / 4), as in cqa_certified_decode.
+ * Needs the Tier-2 originals.  Asynchronous; shares the handle's workspaces.
+ * Errors: INVALID_ARG (incl. selector out of range), NO_TIER2, HIP. */
+int32_t cqa_adaptive_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                            const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                            cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream);
+
+/* cqa_adaptive_decode, then the ladder exactly as in cqa_decode_step. */
+int32_t cqa_adaptive_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                          const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                          cqa_head_cert* cert_dev, uint32_t* flags_dev, int32_t* rung_served,
+                          void* stream);
+
+/* Test hook: what the last adaptive decode decided, copied to the host after a
+ * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
+ * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*
+ * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (1 = the
+ * group scored this block with FP16 keys); logmass_int8_host / logmass_mixed_host
+ * float [batch][n_q_heads][n_blocks] (block log-masses of the two passes).
+ * Any pointer may be NULL.  n_blocks = sealed blocks of `layer`. */
+int32_t cqa_adaptive_state(cqa_cache* c, int32_t layer, int32_t* k_star_host,
+                           int32_t* selected_host, uint8_t* promoted_host,
+                           float* logmass_int8_host, float* logmass_mixed_host);
+
 /* Dense FP16 decode attention on device-resident K, V (the same kernel the
  * fallback runs after paging): softmax(q K^T / sqrt(128)) V with FP32
  * accumulation.  q [batch][n_q_heads][128] FP16; k, v [batch][n_kv_heads]

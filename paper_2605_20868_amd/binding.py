@@ -55,6 +55,18 @@ class Tolerances(C.Structure):
                          mass_exp, key_bound_mode, rung4_min_groups, force_flags)
 
 
+class Selector(C.Structure):
+    """Parameters of the adaptive key-precision selector (cqa_selector)."""
+    _fields_ = [("tau_cov", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32),
+                ("k_limit", C.c_int32)]
+
+    def __init__(self, tau_cov=0.995, k_min=2, k_max=128, k_limit=None):
+        super().__init__(tau_cov, k_min, k_max, k_max if k_limit is None else k_limit)
+
+
+MAX_K_LIMIT = 512
+
+
 class HeadCert(C.Structure):
     _fields_ = [("E_key", C.c_float), ("E_val", C.c_float), ("delta_h", C.c_float),
                 ("v_max", C.c_float), ("alpha_tail_hat", C.c_float), ("lse", C.c_float),
@@ -101,6 +113,11 @@ def _load():
         "cqa_dense_fallback": (i32, [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp]),
         "cqa_decode_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
                                   C.POINTER(i32), vp]),
+        "cqa_adaptive_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
+                                      vp, vp]),
+        "cqa_adaptive_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
+                                    vp, C.POINTER(i32), vp]),
+        "cqa_adaptive_state": (i32, [vp, i32, vp, vp, vp, vp, vp]),
         "cqa_dense_attention": (i32, [vp, vp, vp, i32, i32, i32, i64, vp, vp, vp]),
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
         "cqa_time_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
@@ -230,6 +247,37 @@ def cqa_decode_step(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev
                                 _ptr(flags_dev), _ptr(blk_logmass_dev), C.byref(rung),
                                 _ptr(stream)), "cqa_decode_step")
     return rung.value
+
+
+def cqa_adaptive_decode(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, cert_dev, flags_dev,
+                        stream=None) -> None:
+    _check(_lib.cqa_adaptive_decode(h, layer, _ptr(q_dev), C.byref(tol), C.byref(sel), _ptr(O_dev),
+                                    _ptr(cert_dev), _ptr(flags_dev), _ptr(stream)),
+           "cqa_adaptive_decode")
+
+
+def cqa_adaptive_step(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, cert_dev, flags_dev,
+                      stream=None) -> int:
+    rung = C.c_int32(0)
+    _check(_lib.cqa_adaptive_step(h, layer, _ptr(q_dev), C.byref(tol), C.byref(sel), _ptr(O_dev),
+                                  _ptr(cert_dev), _ptr(flags_dev), C.byref(rung), _ptr(stream)),
+           "cqa_adaptive_step")
+    return rung.value
+
+
+def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):
+    """Returns (k_star i32[Bt,Hq], selected i32[Bt,Hq,512], promoted u8[Bt,Hkv,NB],
+    logmass_int8 f32[Bt,Hq,NB], logmass_mixed f32[Bt,Hq,NB]) of the last adaptive decode."""
+    import numpy as np
+    nb = cqa_cache_length(h, layer) // 16
+    ks = np.zeros((batch, n_q_heads), np.int32)
+    sel = np.zeros((batch, n_q_heads, MAX_K_LIMIT), np.int32)
+    prom = np.zeros((batch, n_kv_heads, nb), np.uint8)
+    l8 = np.zeros((batch, n_q_heads, nb), np.float32)
+    lx = np.zeros((batch, n_q_heads, nb), np.float32)
+    _check(_lib.cqa_adaptive_state(h, layer, _ptr(ks), _ptr(sel), _ptr(prom), _ptr(l8), _ptr(lx)),
+           "cqa_adaptive_state")
+    return ks, sel, prom, l8, lx
 
 
 def cqa_dense_workspace_bytes(batch, n_q_heads, n_tokens) -> int:

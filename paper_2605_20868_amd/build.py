@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libcqa.so")
 BUILD = os.path.join(HERE, "_build")
 
-SOURCES = ["quantize.hip", "decode.hip", "decode_mfma.hip", "dense.hip", "api.hip"]
+SOURCES = ["quantize.hip", "decode.hip", "decode_mfma.hip", "adaptive.hip", "dense.hip", "api.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}

@@ -1,0 +1,550 @@
+// Adaptive key precision: selector, promoted-set bookkeeping, FP16-key gather, and the
+// reduction of the attend pass with its ranking check.
+//
+// Follows the paper's "Adaptive Precision Selection" (rank blocks by INT8-estimated mass, K* =
+// smallest prefix that covers tau_cov, clamp to [K_min, K_max]), the first rung of its "Fallback
+// Ladder" (grow K while the key term is over its threshold), its total error bound with the
+// achieved INT8-estimated tail mass, and its "Ranking-Consistency Check" with the boundary
+// verification, at depth 1.  Key precision is chosen per KV group (the union of the group's
+// query heads' selections): the paper's per-KV-group selection variant.
+//
+// Sequence on one stream (launch_adaptive): scoring pass (the ordinary certified decode, which
+// also emits the INT8 block log-masses) -> select_kernel (per head) -> compact_kernel (per group:
+// union bit mask -> slot map and ordered list) -> gather_kernel (FP16 keys of the listed blocks
+// from the pinned Tier-2 originals, read by the device over the host link, into the scratch) ->
+// attend pass = matrix-core split pass that leaves promoted blocks out + promoted-block pass on
+// the FP16 keys -> adaptive_reduce_kernel.
+#include <algorithm>
+
+#include "cqa_internal.h"
+#include "reduce_inl.h"
+
+namespace cqa {
+
+// defined in decode.hip
+int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStream_t st);
+
+namespace {
+
+// order-preserving map float -> uint32 (larger float <=> larger integer)
+__device__ __forceinline__ uint32_t ord32(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+struct SelectArgs {
+  const float* lm8;            // [Bt][Hq][nb]
+  const cqa_head_cert* cert;   // scoring pass: lse, delta_h, v_max
+  int32_t* sel;                // [Bt][Hq][MAX_K_LIMIT]
+  int32_t* kstar;              // [Bt][Hq]
+  uint32_t* umask;             // [Bt][Hkv][mask_words]
+  int64_t mask_words;
+  int nb, n_q, n_kv;
+  float tau_cov;
+  int k_min, k_max, k_limit;
+  float eps_key;
+  int mass_exp, key_bound_mode;
+};
+
+// E_key / (1) from Delta_h, the estimated tail mass and V_max, in double (decision only)
+__device__ double key_term_d(double delta, double alpha, double vmax, int mass_exp, int mode) {
+  double t_tail = 0.0;
+  if (alpha > 0.0 && delta != 0.0) {
+    const double grow = exp(fmin((double)mass_exp * delta, 700.0));
+    const double widen = expm1(fmin(2.0 * delta, 700.0));
+    t_tail = fmin(1.0, grow * alpha) * widen;
+  }
+  const double t_full = tanh(delta);
+  const double tv = mode == 0 ? fmin(t_full, t_tail) : (mode == 1 ? t_tail : t_full);
+  return 2.0 * vmax * tv;
+}
+
+// One workgroup per (batch, query head).  Finds the KL = min(k_limit, nb) best blocks under the
+// total order (larger log-mass first, equal log-masses: lower index first) by radix selection
+// over the row, sorts them, and takes the covering prefix.
+__global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
+  const int tid = threadIdx.x;
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const int64_t row = (int64_t)b * a.n_q + hq;
+  const float* lm = a.lm8 + row * a.nb;
+  const int nb = a.nb;
+  const int KL = min(max(a.k_limit, a.k_max), min(nb, MAX_K_LIMIT));
+
+  __shared__ uint32_t hist[256];
+  __shared__ unsigned long long cand[MAX_K_LIMIT];
+  __shared__ double dsum[256];
+  __shared__ uint32_t s_prefix, s_want, s_cnt;
+  __shared__ uint32_t s_idx_prefix, s_idx_want;
+  __shared__ int s_k;
+
+  const double lse = (double)a.cert[row].lse;
+
+  // ---- total estimated mass of the sealed blocks (the rest of 1 is the exact trailing tokens)
+  double part = 0.0;
+  for (int i = tid; i < nb; i += 256) part += exp((double)lm[i] - lse);
+  dsum[tid] = part;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) dsum[tid] += dsum[tid + s];
+    __syncthreads();
+  }
+  const double total_blocks = dsum[0];
+  __syncthreads();
+  if (KL == 0) {
+    if (tid == 0) a.kstar[row] = 0;
+    return;
+  }
+
+  // ---- radix selection of the KL-th largest key, 8 bits at a time from the top
+  if (tid == 0) {
+    s_prefix = 0u;
+    s_want = (uint32_t)KL;
+  }
+  __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    hist[tid] = 0u;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    for (int i = tid; i < nb; i += 256) {
+      const uint32_t k = ord32(lm[i]);
+      if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t want = s_want, cum = 0u;
+      int bin = 255;
+      for (; bin > 0; --bin) {
+        if (cum + hist[bin] >= want) break;
+        cum += hist[bin];
+      }
+      s_want = want - cum;                       // still to take inside the chosen bin
+      s_prefix = prefix | ((uint32_t)bin << shift);
+    }
+    __syncthreads();
+  }
+  const uint32_t T = s_prefix;                   // key of the KL-th best block
+  // blocks with key == T: s_want of them are needed, the ones with the lowest indices.
+  // Select the s_want-th smallest index among them the same way (indices < 2^24 * 256).
+  if (tid == 0) {
+    s_idx_prefix = 0u;
+    s_idx_want = s_want;
+  }
+  __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    hist[tid] = 0u;
+    __syncthreads();
+    const uint32_t prefix = s_idx_prefix;
+    for (int i = tid; i < nb; i += 256) {
+      if (ord32(lm[i]) == T && (((uint32_t)i) & himask) == prefix)
+        atomicAdd(&hist[(((uint32_t)i) >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t want = s_idx_want, cum = 0u;
+      int bin = 0;
+      for (; bin < 255; ++bin) {
+        if (cum + hist[bin] >= want) break;
+        cum += hist[bin];
+      }
+      s_idx_want = want - cum;
+      s_idx_prefix = prefix | ((uint32_t)bin << shift);
+    }
+    __syncthreads();
+  }
+  const uint32_t Tidx = s_idx_prefix;            // largest index taken among the ties
+
+  // ---- collect the KL winners as composite keys (log-mass order, then lower index first)
+  if (tid == 0) s_cnt = 0u;
+  for (int i = tid; i < MAX_K_LIMIT; i += 256) cand[i] = 0ull;
+  __syncthreads();
+  for (int i = tid; i < nb; i += 256) {
+    const uint32_t k = ord32(lm[i]);
+    if (k > T || (k == T && (uint32_t)i <= Tidx)) {
+      const uint32_t pos = atomicAdd(&s_cnt, 1u);
+      if (pos < (uint32_t)MAX_K_LIMIT)
+        cand[pos] = ((unsigned long long)k << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
+    }
+  }
+  __syncthreads();
+  // ---- bitonic sort, descending, of the MAX_K_LIMIT slots (empty slots are zero = smallest)
+  for (int size = 2; size <= MAX_K_LIMIT; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < MAX_K_LIMIT / 2; t += 256) {
+        const int lo = 2 * t - (t & (stride - 1));
+        const int hi = lo + stride;
+        const bool desc = (lo & size) == 0;
+        const unsigned long long x = cand[lo], y = cand[hi];
+        if ((x < y) == desc) {
+          cand[lo] = y;
+          cand[hi] = x;
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- covering prefix, clamps, Rung-1 growth (a few hundred scalar operations)
+  if (tid == 0) {
+    const int n = (int)min(s_cnt, (uint32_t)KL);
+    const double rho_trail = 1.0 - total_blocks;
+    double cum = 0.0;
+    int k = -1;
+    // C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so stop looking there
+    const int look = min(n, a.k_max);
+    for (int i = 0; i <= look; ++i) {
+      if (rho_trail + cum >= (double)a.tau_cov) {
+        k = i;
+        break;
+      }
+      if (i < look) {
+        const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
+        cum += exp((double)lm[idx] - lse);
+      }
+    }
+    if (k < 0) k = nb;                                  // no prefix up to k_max covers tau_cov
+    k = max(a.k_min, min(k, a.k_max));
+    k = min(k, nb);
+    k = min(k, n);
+    // Rung 1
+    const double delta = (double)a.cert[row].delta_h, vmax = (double)a.cert[row].v_max;
+    const int cap = min(max(a.k_limit, a.k_max), n);
+    while (k < cap) {
+      double covered = 0.0;
+      for (int i = 0; i < k; ++i) {
+        const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
+        covered += exp((double)lm[idx] - lse);
+      }
+      const double tail = total_blocks - covered;
+      if (!(key_term_d(delta, tail, vmax, a.mass_exp, a.key_bound_mode) > (double)a.eps_key)) break;
+      k = min(max(2 * k, 1), cap);
+    }
+    s_k = k;
+    a.kstar[row] = k;
+  }
+  __syncthreads();
+  const int k = s_k;
+  uint32_t* um = a.umask + ((int64_t)b * a.n_kv + hq / (a.n_q / a.n_kv)) * a.mask_words;
+  for (int i = tid; i < k; i += 256) {
+    const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
+    a.sel[row * MAX_K_LIMIT + i] = idx;
+    if (idx >= 0 && idx < nb) atomicOr(&um[idx >> 5], 1u << (idx & 31));
+  }
+}
+
+struct CompactArgs {
+  uint32_t* umask;     // [Bt][Hkv][mask_words]; cleared on the way out
+  int64_t mask_words;
+  int32_t* slot;       // [Bt][Hkv][slot_stride]
+  int64_t slot_stride;
+  int32_t* ulist;      // [Bt][Hkv][MAX_UNION]
+  int32_t* ucount;     // [Bt][Hkv]
+  int nb;
+};
+
+// One workgroup per KV group: bit mask -> slot of every block (position among the promoted
+// blocks in ascending order, -1 for the others) and the ordered list.  Clears the mask.
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
+  const int tid = threadIdx.x;
+  const int64_t grp = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+  uint32_t* um = a.umask + grp * a.mask_words;
+  int32_t* slot = a.slot + grp * a.slot_stride;
+  int32_t* ulist = a.ulist + grp * MAX_UNION;
+  const int words = (a.nb + 31) >> 5;
+  __shared__ int scan[256];
+  __shared__ int s_base;
+  if (tid == 0) s_base = 0;
+  __syncthreads();
+  for (int w0 = 0; w0 < words; w0 += 256) {
+    const int w = w0 + tid;
+    uint32_t bits = 0u;
+    if (w < words) {
+      bits = um[w];
+      um[w] = 0u;
+      if (w == words - 1 && (a.nb & 31)) bits &= (1u << (a.nb & 31)) - 1u;   // nothing past nb
+    }
+    const int cnt = __popc(bits);
+    scan[tid] = cnt;
+    __syncthreads();
+    for (int s = 1; s < 256; s <<= 1) {
+      const int v = tid >= s ? scan[tid - s] : 0;
+      __syncthreads();
+      scan[tid] += v;
+      __syncthreads();
+    }
+    int pos = s_base + scan[tid] - cnt;          // slot of my word's first promoted block
+    if (w < words) {
+      for (int j = 0; j < 32; ++j) {
+        const int blk = w * 32 + j;
+        if (blk >= a.nb) break;
+        if ((bits >> j) & 1u) {
+          const int sidx = pos < MAX_UNION ? pos : -1;   // cannot overflow: 4 heads x MAX_K_LIMIT
+          slot[blk] = sidx;
+          if (sidx >= 0) ulist[sidx] = blk;
+          ++pos;
+        } else {
+          slot[blk] = -1;
+        }
+      }
+    }
+    __syncthreads();
+    if (tid == 255) s_base += scan[255];
+    __syncthreads();
+  }
+  if (tid == 0) a.ucount[grp] = min(s_base, MAX_UNION);
+}
+
+struct GatherArgs {
+  const __half* t2_k;     // pinned host originals of the layer: [Bt * Hkv][max_tokens][128]
+  int64_t max_tokens;
+  const int32_t* ulist;
+  const int32_t* ucount;
+  __half* kscratch;
+  int nb;
+};
+
+// One workgroup per (list position, KV group): 4 KB of FP16 keys from the host-resident originals
+// into the scratch, 16 bytes per thread.  Positions past the group's count exit at once.
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  const int pos = blockIdx.x;
+  const int64_t grp = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  if (pos >= a.ucount[grp]) return;
+  const int blk = a.ulist[grp * MAX_UNION + pos];
+  if (blk < 0 || blk >= a.nb) return;
+  const uint4* src = reinterpret_cast<const uint4*>(a.t2_k + (grp * a.max_tokens + (int64_t)blk * BLK) * D);
+  uint4* dst = reinterpret_cast<uint4*>(a.kscratch + (grp * MAX_UNION + pos) * BLK * D);
+  dst[threadIdx.x] = src[threadIdx.x];
+}
+
+struct AdaptiveReduceArgs {
+  ReduceArgs ra;
+  const float* lm8;      // [Bt][Hq][nb]
+  const float* lmx;      // [Bt][Hq][nb]
+  const int32_t* slot;   // [Bt][Hkv][slot_stride]
+  int64_t slot_stride;
+  float* alpha_out;      // [Bt][Hq]
+};
+
+// One workgroup per (batch, query head): all threads scan the block log-masses of both passes
+// (estimated mass left in INT8, best promoted block under either ranking, best unpromoted
+// block), then the first wave merges the partial sets of the attend pass and finalises the
+// certificate with these substituted.
+__global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs a) {
+  const int tid = threadIdx.x;
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const ReduceArgs& ra = a.ra;
+  const int64_t row = (int64_t)b * ra.n_q + hq;
+  const int64_t grp = (int64_t)b * ra.n_kv + hq / (ra.n_q / ra.n_kv);
+  const float* l8 = a.lm8 + row * ra.nb;
+  const float* lx = a.lmx + row * ra.nb;
+  const int32_t* slot = a.slot + grp * a.slot_stride;
+  // the scoring pass left its certificate in the caller's array; read what is needed before
+  // the first wave overwrites it
+  const float lse8 = ra.cert[row].lse;
+  const float delta = ra.cert[row].delta_h;
+
+  float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY;
+  int ix = -1, i8 = -1;
+  double tail_mass = 0.0;
+  for (int i = tid; i < ra.nb; i += 256) {
+    const float v8 = l8[i];
+    if (slot[i] >= 0) {
+      const float vx = lx[i];
+      if (vx > best_x) {        // ascending scan per thread: strict > keeps the lowest index
+        best_x = vx;
+        ix = i;
+      }
+      if (v8 > best_8) {
+        best_8 = v8;
+        i8 = i;
+      }
+    } else {
+      tail_max = fmaxf(tail_max, v8);
+      tail_mass += (double)expf(v8 - lse8);
+    }
+  }
+  __shared__ float s_bx[256], s_b8[256], s_tm[256];
+  __shared__ int s_ix[256], s_i8[256];
+  __shared__ double s_mass[256];
+  __shared__ float wsm[64];
+  __shared__ AdaptiveIn s_ad;
+  s_bx[tid] = best_x;
+  s_ix[tid] = ix;
+  s_b8[tid] = best_8;
+  s_i8[tid] = i8;
+  s_tm[tid] = tail_max;
+  s_mass[tid] = tail_mass;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      // larger value wins; equal values: the lower block index (-1 = nothing seen loses)
+      const float ox = s_bx[tid + s];
+      const int oix = s_ix[tid + s];
+      if (oix >= 0 && (s_ix[tid] < 0 || ox > s_bx[tid] || (ox == s_bx[tid] && oix < s_ix[tid]))) {
+        s_bx[tid] = ox;
+        s_ix[tid] = oix;
+      }
+      const float o8 = s_b8[tid + s];
+      const int oi8 = s_i8[tid + s];
+      if (oi8 >= 0 && (s_i8[tid] < 0 || o8 > s_b8[tid] || (o8 == s_b8[tid] && oi8 < s_i8[tid]))) {
+        s_b8[tid] = o8;
+        s_i8[tid] = oi8;
+      }
+      s_tm[tid] = fmaxf(s_tm[tid], s_tm[tid + s]);
+      s_mass[tid] += s_mass[tid + s];
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    AdaptiveIn ad;
+    ad.alpha = (float)s_mass[0];
+    ad.delta = delta;
+    ad.top_block = s_ix[0];
+    ad.top_fp16 = s_ix[0] >= 0 ? s_bx[0] : -INFINITY;
+    const bool has_tail = s_tm[0] > -INFINITY;
+    ad.tail_ub = has_tail ? s_tm[0] + delta : -INFINITY;
+    const bool disagree = s_ix[0] >= 0 && s_ix[0] != s_i8[0];
+    const bool boundary = s_ix[0] >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > s_bx[0];
+    ad.rank_fail = (disagree || boundary) ? 1 : 0;
+    s_ad = ad;
+    a.alpha_out[row] = ad.alpha;
+  }
+  __syncthreads();
+  if (tid < 64) reduce_head_wave<false>(ra, b, hq, wsm, &s_ad);
+}
+
+}  // namespace
+
+int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
+                        const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
+                        uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st) {
+  const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
+  const int g = hq / hkv;
+  const int64_t len = c->length[layer];
+  const int64_t nb = len / BLK;
+  const int r = (int)(len % BLK);
+  AdaptiveWs& w = c->ad;
+
+  // ---- 1. scoring pass: every threshold off (its flags are overwritten below), log-masses out
+  cqa_tolerances loose = tol;
+  loose.eps_total = loose.eps_key = loose.eps_val = loose.v_tol = INFINITY;
+  loose.rank_depth = 0;
+  loose.force_flags = 0;
+  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st);
+  if (rc != CQA_OK) return rc;
+  if (nb == 0) {
+    // nothing sealed: the scoring pass (exact trailing tokens only) is the answer; rerun it
+    // with the caller's thresholds so the flag words and the mirror are the caller's
+    return launch_certified(c, layer, q, tol, O, cert, flags, flags_mirror, mirror_tag, nullptr, st);
+  }
+
+  // ---- 2. selection per head (+ Rung 1), union bit mask per group
+  SelectArgs sa;
+  sa.lm8 = w.lm8;
+  sa.cert = cert;
+  sa.sel = w.sel;
+  sa.kstar = w.kstar;
+  sa.umask = w.umask;
+  sa.mask_words = w.mask_words;
+  sa.nb = (int)nb;
+  sa.n_q = hq;
+  sa.n_kv = hkv;
+  sa.tau_cov = sel.tau_cov;
+  sa.k_min = sel.k_min;
+  sa.k_max = sel.k_max;
+  sa.k_limit = sel.k_limit;
+  sa.eps_key = tol.eps_key;
+  sa.mass_exp = tol.mass_exp;
+  sa.key_bound_mode = tol.key_bound_mode;
+  hipLaunchKernelGGL(select_kernel, dim3(hq, bt), dim3(256), 0, st, sa);
+  CQA_HIP(hipGetLastError());
+
+  // ---- 3. slot map and ordered list per group; FP16 keys of the listed blocks into the scratch
+  CompactArgs ca;
+  ca.umask = w.umask;
+  ca.mask_words = w.mask_words;
+  ca.slot = w.slot;
+  ca.slot_stride = c->nq_cap * 4;
+  ca.ulist = w.ulist;
+  ca.ucount = w.ucount;
+  ca.nb = (int)nb;
+  hipLaunchKernelGGL(compact_kernel, dim3(hkv, bt), dim3(256), 0, st, ca);
+  CQA_HIP(hipGetLastError());
+
+  const int64_t layer_head0 = head_index(c, layer, 0, 0);
+  GatherArgs ga;
+  ga.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
+  ga.max_tokens = c->desc.max_tokens;
+  ga.ulist = w.ulist;
+  ga.ucount = w.ucount;
+  ga.kscratch = w.kscratch;
+  ga.nb = (int)nb;
+  const int max_union = (int)std::min<int64_t>(std::min<int64_t>(MAX_UNION, nb),
+                                               (int64_t)g * std::max(sel.k_limit, sel.k_max));
+  if (max_union > 0) {
+    hipLaunchKernelGGL(gather_kernel, dim3(max_union, hkv, bt), dim3(256), 0, st, ga);
+    CQA_HIP(hipGetLastError());
+  }
+
+  // ---- 4. attend pass: matrix-core pass without the promoted blocks + promoted-block pass
+  int nsplit = 0, bps = 0;
+  split_geometry(c, nb, &nsplit, &bps);
+  const int total = nsplit + PROM_SPLITS;
+  ReduceArgs ra;
+  ra.partials = c->partials;
+  ra.q = q;
+  ra.trail_k = c->trail_k + layer_head0 * BLK * D;
+  ra.trail_v = c->trail_v + layer_head0 * BLK * D;
+  ra.O = O;
+  ra.cert = cert;
+  ra.flags = flags;
+  ra.flags_mirror = flags_mirror;
+  ra.mirror_tag = mirror_tag;
+  ra.tol = tol;
+  ra.nsplit = total;
+  ra.nb = (int)nb;
+  ra.r = r;
+  ra.n_q = hq;
+  ra.n_kv = hkv;
+  DecodeArgs a;
+  a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
+  a.sigmax = c->sigmax + layer_head0;
+  a.q = q;
+  a.partials = c->partials;
+  a.blk_logmass = w.lmx;
+  a.nq_cap = c->nq_cap;
+  a.nb = (int)nb;
+  a.nsplit = nsplit;
+  a.pstride = total;
+  a.bps = bps;
+  a.n_q = hq;
+  a.n_kv = hkv;
+  a.debug = 0;
+  a.slot = w.slot;
+  a.ulist = w.ulist;
+  a.ucount = w.ucount;
+  a.kscratch = w.kscratch;
+  a.split0 = nsplit;
+  rc = launch_split_mfma(a, ra, nullptr, g, dim3(nsplit, hkv, bt), nullptr, nullptr, st);
+  if (rc != CQA_OK) return rc;
+  CQA_HIP(hipGetLastError());
+  rc = launch_promoted_pass(a, g, dim3(PROM_SPLITS, hkv, bt), st);
+  if (rc != CQA_OK) return rc;
+
+  // ---- 5. merge, certificate with the achieved tail, ranking check
+  AdaptiveReduceArgs ar;
+  ar.ra = ra;
+  ar.lm8 = w.lm8;
+  ar.lmx = w.lmx;
+  ar.slot = w.slot;
+  ar.slot_stride = c->nq_cap * 4;
+  ar.alpha_out = w.alpha;
+  hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(256), 0, st, ar);
+  CQA_HIP(hipGetLastError());
+  return CQA_OK;
+}
+
+}  // namespace cqa

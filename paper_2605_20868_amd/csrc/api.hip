@@ -34,6 +34,7 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 
 struct Sizes {
   int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select;
+  int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist, ad_scratch;
   int max_splits;
 };
 
@@ -51,10 +52,23 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   if (ms > s.nb_cap) ms = s.nb_cap;
   if (ms < 1) ms = 1;
   s.max_splits = (int)ms;
-  s.partials = (int64_t)d->batch * d->n_q_heads * s.max_splits * PART_FLOATS * 4;
+  s.partials = (int64_t)d->batch * d->n_q_heads * (s.max_splits + PROM_SPLITS) * PART_FLOATS * 4;
   s.dense_ws = dense_ws_floats(d->n_q_heads / d->n_kv_heads, d->max_tokens) * 4;
   s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
   s.select = (int64_t)d->batch * d->n_q_heads * 4;
+  // adaptive key precision (needs the originals): log-masses of two passes, selections, masks,
+  // slot maps, lists and the FP16-key scratch, for one layer-step at a time
+  const bool ad = d->tier2_mode == CQA_TIER2_PINNED;
+  const int64_t rows = (int64_t)d->batch * d->n_q_heads, groups = (int64_t)d->batch * d->n_kv_heads;
+  s.ad_lm = ad ? rows * s.nb_cap * 4 : 0;
+  s.ad_sel = ad ? rows * MAX_K_LIMIT * 4 : 0;
+  s.ad_head = ad ? rows * 4 : 0;
+  s.ad_mask_words = (s.nb_cap + 31) / 32;
+  s.ad_mask = ad ? groups * s.ad_mask_words * 4 : 0;
+  s.ad_slot = ad ? groups * s.nq_cap * 4 * 4 : 0;
+  s.ad_group = ad ? groups * 4 : 0;
+  s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
+  s.ad_scratch = ad ? groups * MAX_UNION * BLK * D * 2 : 0;
   return s;
 }
 
@@ -71,6 +85,16 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->partials);
   (void)hipFree(c->dense_ws);
   (void)hipFree(c->select_dev);
+  (void)hipFree(c->ad.lm8);
+  (void)hipFree(c->ad.lmx);
+  (void)hipFree(c->ad.sel);
+  (void)hipFree(c->ad.kstar);
+  (void)hipFree(c->ad.alpha);
+  (void)hipFree(c->ad.umask);
+  (void)hipFree(c->ad.slot);
+  (void)hipFree(c->ad.ucount);
+  (void)hipFree(c->ad.ulist);
+  (void)hipFree(c->ad.kscratch);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
   if (c->t2_k) (void)hipHostFree(c->t2_k);
@@ -156,8 +180,9 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   if (st != CQA_OK) return st;
   const Sizes s = compute_sizes(desc, 256);
   if (device_bytes)
-    *device_bytes = s.t1 + 2 * s.trail + s.partials +
-                    2 * s.dense_ws + 4 * s.stage + s.select;
+    *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
+                    2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
+                    s.ad_ulist + s.ad_scratch;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
 }
@@ -199,6 +224,23 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   CQA_ALLOC_DEV(c->partials, s.partials);
   CQA_ALLOC_DEV(c->dense_ws, 2 * s.dense_ws);
   CQA_ALLOC_DEV(c->select_dev, s.select);
+  if (desc->tier2_mode == CQA_TIER2_PINNED) {
+    CQA_ALLOC_DEV(c->ad.lm8, s.ad_lm);
+    CQA_ALLOC_DEV(c->ad.lmx, s.ad_lm);
+    CQA_ALLOC_DEV(c->ad.sel, s.ad_sel);
+    CQA_ALLOC_DEV(c->ad.kstar, s.ad_head);
+    CQA_ALLOC_DEV(c->ad.alpha, s.ad_head);
+    CQA_ALLOC_DEV(c->ad.umask, s.ad_mask);
+    CQA_ALLOC_DEV(c->ad.slot, s.ad_slot);
+    CQA_ALLOC_DEV(c->ad.ucount, s.ad_group);
+    CQA_ALLOC_DEV(c->ad.ulist, s.ad_ulist);
+    CQA_ALLOC_DEV(c->ad.kscratch, s.ad_scratch);
+    c->ad.mask_words = s.ad_mask_words;
+    CQA_TRY(hipMemset(c->ad.umask, 0, (size_t)s.ad_mask));       // the selector ORs into it
+    CQA_TRY(hipMemset(c->ad.slot, 0xFF, (size_t)s.ad_slot));     // -1: no block is promoted
+    CQA_TRY(hipMemset(c->ad.ucount, 0, (size_t)s.ad_group));
+    CQA_TRY(hipMemset(c->ad.kstar, 0, (size_t)s.ad_head));
+  }
   CQA_ALLOC_PIN(c->flags_host, s.select);
   memset(c->flags_host, 0, s.select);
   c->need = new (std::nothrow) uint32_t[(size_t)desc->batch * desc->n_q_heads];
@@ -477,16 +519,11 @@ int32_t cqa_dense_fallback(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
   return CQA_OK;
 }
 
-int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
-                        const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
-                        uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
-                        void* stream) {
-  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
-      tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr)
-    return CQA_ERR_INVALID_ARG;
-  if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
-    return CQA_ERR_INVALID_ARG;
+// Flag read-back and ladder shared by the one-call steps.  `adaptive` selects which decode runs.
+static int32_t step_with_ladder(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                                const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                                cqa_head_cert* cert_dev, uint32_t* flags_dev,
+                                float* blk_logmass_dev, int32_t* rung_served, void* stream) {
   Cache* c = &h->impl;
   hipStream_t st = (hipStream_t)stream;
   // The reduction also writes each head's flag word, tagged with this step's sequence number,
@@ -496,8 +533,13 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
   // bounded; when the tags do not all show up in time it falls back to a stream synchronisation.
   c->step_seq = (c->step_seq % 0xFFFFu) + 1u;            // 1 .. 65535, never 0
   const uint32_t tag = c->step_seq << 16;
-  int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
-                                flags_dev, c->flags_host, tag, blk_logmass_dev, st);
+  int32_t rc;
+  if (sel != nullptr)
+    rc = launch_adaptive(c, layer, (const __half*)q_fp16_dev, *tol, *sel, O_dev, cert_dev, flags_dev,
+                         c->flags_host, tag, st);
+  else
+    rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
+                          c->flags_host, tag, blk_logmass_dev, st);
   if (rc != CQA_OK) return rc;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
@@ -554,6 +596,87 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
   if (rung == 0) return CQA_OK;
   return cqa_dense_fallback(h, layer, q_fp16_dev, need, rung == 4, rung, O_dev, cert_dev,
                             flags_dev, stream);
+}
+
+static int32_t check_decode_args(cqa_cache* h, int32_t layer, const void* q, const cqa_tolerances* tol,
+                                 float* O, cqa_head_cert* cert, uint32_t* flags) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q == nullptr ||
+      tol == nullptr || O == nullptr || cert == nullptr || flags == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
+    return CQA_ERR_INVALID_ARG;
+  return CQA_OK;
+}
+
+static int32_t check_selector(const cqa_cache* h, const cqa_selector* sel) {
+  if (sel == nullptr || !(sel->tau_cov == sel->tau_cov) || sel->k_min < 0 || sel->k_max < sel->k_min ||
+      sel->k_limit < sel->k_max || sel->k_limit > MAX_K_LIMIT)
+    return CQA_ERR_INVALID_ARG;
+  if (h->impl.desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  return CQA_OK;
+}
+
+int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                        const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                        uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
+                        void* stream) {
+  const int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  if (rc != CQA_OK) return rc;
+  return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev,
+                          blk_logmass_dev, rung_served, stream);
+}
+
+int32_t cqa_adaptive_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                            const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                            cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream) {
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  if (rc != CQA_OK) return rc;
+  rc = check_selector(h, sel);
+  if (rc != CQA_OK) return rc;
+  return launch_adaptive(&h->impl, layer, (const __half*)q_fp16_dev, *tol, *sel, O_dev, cert_dev,
+                         flags_dev, nullptr, 0u, (hipStream_t)stream);
+}
+
+int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                          const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                          cqa_head_cert* cert_dev, uint32_t* flags_dev, int32_t* rung_served,
+                          void* stream) {
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  if (rc != CQA_OK) return rc;
+  rc = check_selector(h, sel);
+  if (rc != CQA_OK) return rc;
+  return step_with_ladder(h, layer, q_fp16_dev, tol, sel, O_dev, cert_dev, flags_dev, nullptr,
+                          rung_served, stream);
+}
+
+int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
+                           int32_t* selected_host, uint8_t* promoted_host,
+                           float* logmass_int8_host, float* logmass_mixed_host) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  CQA_HIP(hipDeviceSynchronize());
+  const int64_t rows = (int64_t)c->desc.batch * c->desc.n_q_heads;
+  const int64_t groups = (int64_t)c->desc.batch * c->desc.n_kv_heads;
+  const int64_t nb = c->length[layer] / BLK;
+  if (k_star_host)
+    CQA_HIP(hipMemcpy(k_star_host, c->ad.kstar, (size_t)rows * 4, hipMemcpyDeviceToHost));
+  if (selected_host)
+    CQA_HIP(hipMemcpy(selected_host, c->ad.sel, (size_t)rows * MAX_K_LIMIT * 4, hipMemcpyDeviceToHost));
+  if (logmass_int8_host && nb > 0)
+    CQA_HIP(hipMemcpy(logmass_int8_host, c->ad.lm8, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+  if (logmass_mixed_host && nb > 0)
+    CQA_HIP(hipMemcpy(logmass_mixed_host, c->ad.lmx, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+  if (promoted_host && nb > 0) {
+    std::vector<int32_t> slot((size_t)nb);
+    for (int64_t gidx = 0; gidx < groups; ++gidx) {
+      CQA_HIP(hipMemcpy(slot.data(), c->ad.slot + gidx * c->nq_cap * 4, (size_t)nb * 4,
+                        hipMemcpyDeviceToHost));
+      for (int64_t i = 0; i < nb; ++i) promoted_host[gidx * nb + i] = slot[(size_t)i] >= 0 ? 1 : 0;
+    }
+  }
+  return CQA_OK;
 }
 
 int64_t cqa_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int64_t n_tokens) {

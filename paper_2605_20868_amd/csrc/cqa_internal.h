@@ -87,6 +87,26 @@ constexpr int P_O = 16;     // o[128]
 constexpr int PART_FLOATS = 16 + D;  // 144
 constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-head)
 
+// ---- adaptive key precision ------------------------------------------------------
+constexpr int MAX_K_LIMIT = 512;            // blocks one head may promote (Rung-1 growth included)
+constexpr int MAX_UNION = 4 * MAX_K_LIMIT;  // blocks one KV group may promote (union of <= 4 heads)
+constexpr int PROM_SPLITS = 8;              // workgroups (= partial sets) of the promoted-block pass per KV group
+
+// Workspace of the adaptive path, shared by all layers (one decode step at a time).
+struct AdaptiveWs {
+  float* lm8;        // [Bt][Hq][nb_cap]      INT8 block log-masses of the scoring pass
+  float* lmx;        // [Bt][Hq][nb_cap]      block log-masses of the attend pass (FP16 keys where promoted)
+  int32_t* sel;      // [Bt][Hq][MAX_K_LIMIT] the head's own selection, best first
+  int32_t* kstar;    // [Bt][Hq]              its size after Rung-1 growth
+  float* alpha;      // [Bt][Hq]              estimated mass of the blocks its group left in INT8
+  uint32_t* umask;   // [Bt][Hkv][mask_words] union of the group's selections, one bit per block
+  int32_t* slot;     // [Bt][Hkv][4 nq_cap]   scratch slot of a promoted block, -1 otherwise
+  int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
+  int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
+  __half* kscratch;  // [Bt][Hkv][MAX_UNION][16][128]  FP16 keys of the promoted blocks
+  int64_t mask_words;
+};
+
 struct Cache {
   cqa_cache_desc desc;
   int device;
@@ -126,6 +146,7 @@ struct Cache {
   int prof_cap, prof_n;
   int debug;                 // timing probes (0 in production)
   int variant;               // 0 = matrix-core split kernel (default), 1 = vector-ALU split kernel
+  AdaptiveWs ad;             // allocated with the cache when Tier-2 is retained
 };
 
 struct DecodeArgs {
@@ -140,6 +161,13 @@ struct DecodeArgs {
   int bps;             // blocks per split
   int n_q, n_kv;
   int debug;           // 0 in production; 1 = every load of a wave hits its first block (timing probe)
+  int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
+  // attend pass with gated key precision (null slot = every block uses its INT8 keys)
+  const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: scratch slot of a promoted block, -1 otherwise
+  const int32_t* ulist;     // [Bt][Hkv][MAX_UNION]: promoted blocks of the group, ascending
+  const int32_t* ucount;    // [Bt][Hkv]
+  const __half* kscratch;   // [Bt][Hkv][MAX_UNION][16][128]
+  int split0;               // promoted-block pass: index of its first partial set
 };
 
 
@@ -166,6 +194,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
 int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;
+int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
+                        const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
+                        uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st);
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
                           dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st);
 

@@ -38,7 +38,12 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
   }
 }
 
-template <int G>
+// PROM = false: the vector-ALU split pass over a contiguous range of sealed blocks (INT8 keys).
+// PROM = true : the promoted-block pass of the attend pass with gated key precision: the
+//               workgroups of a KV group walk the group's list of promoted blocks, score them
+//               from the FP16 keys gathered into the scratch (sigma = 1, z = 0, no score error),
+//               attend their INT4 values as usual, and write partial sets split0 + blockIdx.x.
+template <int G, bool PROM>
 __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = l & 15, kg = l >> 4;              // roles in the score phase
@@ -46,8 +51,12 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int64_t head_rec = ((int64_t)b * a.n_kv + kvh) * a.nq_cap;
   // blocks are dealt evenly over the splits (every split gets at least one: nsplit <= nb)
-  const int b0 = (int)(((int64_t)split * a.nb) / a.nsplit);
-  const int b1 = (int)(((int64_t)(split + 1) * a.nb) / a.nsplit);
+  const int64_t grp = (int64_t)b * a.n_kv + kvh;
+  // PROM: positions split * 4 + w, + 4 * gridDim.x, ... of the group's list; else a block range
+  const int b0 = PROM ? split * 4 : (int)(((int64_t)split * a.nb) / a.nsplit);
+  const int b1 = PROM ? min(a.ucount[grp], MAX_UNION) : (int)(((int64_t)(split + 1) * a.nb) / a.nsplit);
+  const int bstep = PROM ? 4 * (int)gridDim.x : 4;
+  const int out_split = PROM ? a.split0 + split : split;
   const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
 
   __shared__ __align__(16) float qs[4][G][D];     // scaled query of the block in flight, per wave
@@ -81,11 +90,14 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     for (int gq = 0; gq < 4; ++gq) acc[gq][h] = 0.0f;
   }
 
-  for (int blk = b0 + w; blk < b1; blk += 4) {
+  for (int pos = b0 + w; pos < b1; pos += bstep) {
+    // every index is bounded on the way in: a list entry outside [0, nb) is skipped
+    const int blk = PROM ? a.ulist[grp * MAX_UNION + pos] : pos;
+    if (PROM && (blk < 0 || blk >= a.nb)) continue;
     // ---- scaled query, per-block constant, per-block score-error bound
     const float* kmb = reinterpret_cast<const float*>(a.t1 + t1_offset(head_rec, blk, Q_KM, KM_BYTES));
-    const float2 sg = reinterpret_cast<const float2*>(kmb)[l];
-    const float2 zz = reinterpret_cast<const float2*>(kmb + D)[l];
+    const float2 sg = PROM ? make_float2(1.0f, 1.0f) : reinterpret_cast<const float2*>(kmb)[l];
+    const float2 zz = PROM ? make_float2(0.0f, 0.0f) : reinterpret_cast<const float2*>(kmb + D)[l];
     const float2 an = *reinterpret_cast<const float2*>(a.t1 + t1_offset(head_rec, blk, Q_AN, AN_BYTES));
     float csum[G], dsum[G];
 #pragma unroll
@@ -93,8 +105,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       const float q0 = qv[h][0] * sg.x, q1 = qv[h][1] * sg.y;
       reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
       // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
-      csum[h] = qv[h][0] * zz.x + qv[h][1] * zz.y - 128.0f * (q0 + q1);
-      dsum[h] = fabsf(qv[h][0]) * sg.x + fabsf(qv[h][1]) * sg.y;
+      csum[h] = PROM ? 0.0f : qv[h][0] * zz.x + qv[h][1] * zz.y - 128.0f * (q0 + q1);
+      dsum[h] = PROM ? 0.0f : fabsf(qv[h][0]) * sg.x + fabsf(qv[h][1]) * sg.y;
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) {
@@ -111,16 +123,36 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     float dot[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
+    if (PROM) {
+      // FP16 keys of the block: scratch slot = position in the list, [16 tokens][128 channels]
+      const __half* kf16 = a.kscratch + ((grp * MAX_UNION + pos) * BLK + tok) * D;
 #pragma unroll
-    for (int cq = 0; cq < 2; ++cq) {
-      const uint4 x = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
-      const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
-      const int c0 = cq * 64 + kg * 16;
+      for (int cq = 0; cq < 2; ++cq) {
+        const int c0 = cq * 64 + kg * 16;
+        const uint4 x0 = *reinterpret_cast<const uint4*>(kf16 + c0);
+        const uint4 x1 = *reinterpret_cast<const uint4*>(kf16 + c0 + 8);
+        const __half2* h0 = reinterpret_cast<const __half2*>(&x0);
+        const __half2* h1 = reinterpret_cast<const __half2*>(&x1);
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const float kf = (float)((wd[j >> 2] >> (8 * (j & 3))) & 0xffu);
+        for (int j = 0; j < 16; ++j) {
+          const __half2 pr = (j < 8) ? h0[j >> 1] : h1[(j - 8) >> 1];
+          const float kf = (j & 1) ? __high2float(pr) : __low2float(pr);
 #pragma unroll
-        for (int h = 0; h < G; ++h) dot[h] = fmaf(qs[w][h][c0 + j], kf, dot[h]);
+          for (int h = 0; h < G; ++h) dot[h] = fmaf(qs[w][h][c0 + j], kf, dot[h]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int cq = 0; cq < 2; ++cq) {
+        const uint4 x = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
+        const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
+        const int c0 = cq * 64 + kg * 16;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float kf = (float)((wd[j >> 2] >> (8 * (j & 3))) & 0xffu);
+#pragma unroll
+          for (int h = 0; h < G; ++h) dot[h] = fmaf(qs[w][h][c0 + j], kf, dot[h]);
+        }
       }
     }
     float p[G], alpha[G];
@@ -222,19 +254,21 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     float M = -INFINITY;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][h][0]);
+    const float Mr = (M == -INFINITY) ? 0.0f : M;   // a workgroup without blocks writes zeros
     float o = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][h][0] - M) * mo[(ww * G + h) * D + c];
-    a.partials[(((int64_t)b * a.n_q + kvh * G + h) * a.nsplit + split) * PART_FLOATS + P_O + c] = o;
+    for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][h][0] - Mr) * mo[(ww * G + h) * D + c];
+    a.partials[(((int64_t)b * a.n_q + kvh * G + h) * a.pstride + out_split) * PART_FLOATS + P_O + c] = o;
   }
   if (threadIdx.x < G) {
     const int h = threadIdx.x;
     float M = -INFINITY;
     for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][h][0]);
+    const float Mr = (M == -INFINITY) ? 0.0f : M;
     float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f, T1 = -INFINITY, T2 = -INFINITY;
     int I1 = -1;
     for (int ww = 0; ww < 4; ++ww) {
-      const float f = __expf(ms[ww][h][0] - M);
+      const float f = __expf(ms[ww][h][0] - Mr);
       L += f * ms[ww][h][1];
       EV += f * ms[ww][h][2];
       EVM = fmaxf(EVM, f * ms[ww][h][3]);
@@ -242,7 +276,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       VM = fmaxf(VM, ms[ww][h][5]);
       top2_merge(T1, I1, T2, ms[ww][h][6], __float_as_int(ms[ww][h][8]), ms[ww][h][7]);
     }
-    float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + h) * a.nsplit + split) * PART_FLOATS;
+    float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + h) * a.pstride + out_split) * PART_FLOATS;
     pp[P_M] = M;
     pp[P_L] = L;
     pp[P_EV] = EV;
@@ -291,6 +325,19 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
   return nsplit;
 }
 
+// Promoted-block pass of the attend pass with gated key precision (see certified_split_kernel).
+int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
+  if (a.ulist == nullptr || a.ucount == nullptr || a.kscratch == nullptr) return CQA_ERR_INVALID_ARG;
+  switch (group) {
+    case 1: hipLaunchKernelGGL((certified_split_kernel<1, true>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((certified_split_kernel<2, true>), grid, dim3(256), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((certified_split_kernel<4, true>), grid, dim3(256), 0, st, a); break;
+    default: return CQA_ERR_UNSUPPORTED;
+  }
+  CQA_HIP(hipGetLastError());
+  return CQA_OK;
+}
+
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st) {
@@ -328,6 +375,12 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.nq_cap = c->nq_cap;
     a.nb = (int)nb;
     a.nsplit = nsplit;
+    a.pstride = nsplit;
+    a.slot = nullptr;
+    a.ulist = nullptr;
+    a.ucount = nullptr;
+    a.kscratch = nullptr;
+    a.split0 = 0;
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;
@@ -347,9 +400,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
       if (rc != CQA_OK) return rc;
     } else {
       switch (hq / hkv) {
-        case 1: hipLaunchKernelGGL(certified_split_kernel<1>, grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(certified_split_kernel<2>, grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL(certified_split_kernel<4>, grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((certified_split_kernel<1, false>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((certified_split_kernel<2, false>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((certified_split_kernel<4, false>), grid, dim3(256), 0, st, a); break;
         default: return CQA_ERR_UNSUPPORTED;
       }
     }

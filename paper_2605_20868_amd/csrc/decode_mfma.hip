@@ -111,7 +111,11 @@ constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: b
 constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
 constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
 
-template <int G, bool LM>
+// MIX: attend pass with gated key precision.  Blocks whose group promoted them to FP16 keys are
+// left out here (their scores get the same huge negative value as blocks past the end, so every
+// weight and mass they produce vanishes, and their log-mass is not written); a second, small
+// kernel attends them from the FP16 keys and adds its own partial sets.
+template <int G, bool LM, bool MIX>
 __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
                                                                       uint32_t* tickets) {
   const int l = threadIdx.x & 63;
@@ -273,8 +277,12 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #ifdef CQA_PROBE_TIMESTAMPS
   if (ts_on) ts[1] = wall_clock64();
 #endif
+  const int32_t* slotrow = MIX ? a.slot + ((int64_t)b * a.n_kv + kvh) * (a.nq_cap * 4) : nullptr;
   for (; qb < b1; qb += 4) {
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
+    bool live[4];   // block is inside this wave's run and scored from its INT8 keys in this pass
+#pragma unroll
+    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1 && (!MIX || slotrow[qb + i] < 0);
     float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -373,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float mq = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float s = (qb + i < b1) ? (C[i][i] + cbs[i]) * score_scale : -1.0e30f;
+      const float s = live[i] ? (C[i][i] + cbs[i]) * score_scale : -1.0e30f;
       mbv[i] = row_max(s);
       ptv[i] = __expf(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
@@ -408,7 +416,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       if (n == 0 && kg < G) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (qb + i < b1)
+          if (live[i])
             a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lbv[i];
       }
     }
@@ -525,7 +533,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float o = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - M) * mo[ww][hh][c];
-    st_agent(a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.nsplit + split) * PART_FLOATS + P_O + c, o);
+    st_agent(a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c, o);
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
@@ -542,7 +550,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       VM = fmaxf(VM, ms[ww][hh][5]);
       top2_merge_m(T1, I1, T2, ms[ww][hh][6], __float_as_int(ms[ww][hh][8]), ms[ww][hh][7]);
     }
-    float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.nsplit + split) * PART_FLOATS;
+    float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS;
     st_agent(pp + P_M, M);
     st_agent(pp + P_L, L);
     st_agent(pp + P_EV, EV);
@@ -590,13 +598,18 @@ int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* t
 #else
   const bool lm = a.blk_logmass != nullptr;
 #endif
+  const bool mix = a.slot != nullptr;
+  if (mix && !lm) return CQA_ERR_INVALID_ARG;   // the gated pass always reports block log-masses
 #define CQA_LAUNCH(GG)                                                                           \
-  if (lm)                                                                                        \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true>), grid, dim3(256), 0, st, ev0,   \
-                          ev1, 0, a, ra, tickets);                                               \
+  if (mix)                                                                                       \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, true>), grid, dim3(256), 0, st,  \
+                          ev0, ev1, 0, a, ra, tickets);                                          \
+  else if (lm)                                                                                   \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false>), grid, dim3(256), 0, st, \
+                          ev0, ev1, 0, a, ra, tickets);                                          \
   else                                                                                           \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false>), grid, dim3(256), 0, st, ev0,  \
-                          ev1, 0, a, ra, tickets);
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, false>), grid, dim3(256), 0,    \
+                          st, ev0, ev1, 0, a, ra, tickets);
   switch (group) {
     case 1: CQA_LAUNCH(1) break;
     case 2: CQA_LAUNCH(2) break;

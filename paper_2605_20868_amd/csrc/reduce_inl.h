@@ -116,13 +116,27 @@ __device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
   }
 }
 
+// What the attend pass with gated key precision substitutes in the certificate (the paper's total
+// error bound with the achieved tail mass, and its ranking-consistency check): the estimated mass
+// of the blocks left in INT8 and Delta_h come from the scoring pass, the ranking verdict from a scan
+// over the block log-masses of both passes.
+struct AdaptiveIn {
+  float alpha;       // sum over unpromoted blocks of the scoring pass's normalised masses
+  float delta;       // Delta_h of the scoring pass
+  float top_fp16;    // largest FP16 log-mass among promoted blocks (-inf if none)
+  float tail_ub;     // largest unpromoted INT8 log-mass + Delta_h (-inf if none)
+  int top_block;     // the promoted block with the largest FP16 log-mass (-1 if none)
+  int rank_fail;     // the two rankings disagree on the top block, or the boundary test failed
+};
+
 // wsm: wave-private LDS scratch of at least 64 floats.  All 64 lanes of the wave must call.
 // COHERENT: the partials were written by other workgroups of the same launch.
 // This code runs on the critical tail of the launch: it is written for few dependent memory
 // round trips (all loads of a chunk of 64 splits are issued before anything is consumed) and
 // short cross-lane chains, not for few instructions.
 template <bool COHERENT>
-__device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int hq, float* wsm) {
+__device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int hq, float* wsm,
+                                                 const AdaptiveIn* ad = nullptr) {
   const int l = threadIdx.x & 63;
   const int kvh = hq / (a.n_q / a.n_kv);
   const float inv_sqrt_d = 0.08838834764831845f;
@@ -251,8 +265,8 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     const float e_val = EV / L;
     const float maxc = EVM / L;
     const float lse = M + logf(L);
-    const float alpha_hat = L_sealed / L;
-    const float delta = DM;
+    const float alpha_hat = ad != nullptr ? ad->alpha : L_sealed / L;
+    const float delta = ad != nullptr ? ad->delta : DM;
     const float vmax = VM;
     float t_tail = 0.0f;
     if (alpha_hat > 0.0f && delta != 0.0f) {
@@ -264,15 +278,22 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     const float tv = a.tol.key_bound_mode == 0 ? fminf(t_full, t_tail)
                                                : (a.tol.key_bound_mode == 1 ? t_tail : t_full);
     const float e_key = 2.0f * vmax * tv;
-    const float margin = a.nb >= 2 ? T1 - T2 : INFINITY;
-    const float rho_top = a.nb >= 1 ? expf(T1 - lse) : 0.0f;
+    float margin = a.nb >= 2 ? T1 - T2 : INFINITY;
+    float rho_top = a.nb >= 1 ? expf(T1 - lse) : 0.0f;
+    bool rank_flag = a.tol.rank_depth >= 1 && a.nb >= 2 && rho_top >= a.tol.rank_min_mass &&
+                     margin <= 2.0f * delta + a.tol.eps_guard;
+    if (ad != nullptr) {
+      const bool any = ad->top_block >= 0;
+      margin = any ? ad->top_fp16 - ad->tail_ub : INFINITY;
+      rho_top = any ? expf(ad->top_fp16 - lse) : 0.0f;
+      rank_flag = a.tol.rank_depth >= 1 && any && rho_top >= a.tol.rank_min_mass && ad->rank_fail != 0;
+      I1 = ad->top_block;
+    }
 
     uint32_t fl = 0;
     if (e_key > a.tol.eps_key) fl |= CQA_FLAG_KEY;
     if (e_val > a.tol.eps_val || maxc > a.tol.v_tol) fl |= CQA_FLAG_VAL;
-    if (a.tol.rank_depth >= 1 && a.nb >= 2 && rho_top >= a.tol.rank_min_mass &&
-        margin <= 2.0f * delta + a.tol.eps_guard)
-      fl |= CQA_FLAG_RANK;
+    if (rank_flag) fl |= CQA_FLAG_RANK;
     if (bad || !isfinite(e_key) || !isfinite(e_val) || !isfinite(delta) || !isfinite(vmax) ||
         !isfinite(lse))
       fl |= CQA_FLAG_PRECOND;
@@ -282,7 +303,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     cqa_head_cert ct;
     ct.E_key = e_key;
     ct.E_val = e_val;
-    ct.delta_h = DM;
+    ct.delta_h = delta;
     ct.v_max = VM;
     ct.alpha_tail_hat = alpha_hat;
     ct.lse = lse;

@@ -1,0 +1,244 @@
+"""GPU parity of the adaptive key-precision path (selector, Rung-1 growth, per-group union, FP16-key
+gather, attend pass with gated key precision, achieved-tail certificate, ranking check) against
+the oracle, through the C ABI.
+
+Integer decisions (K*, the selected blocks, the promoted mask) are compared exactly: the oracle's
+selector is run on the very log-masses the scoring pass produced on the GPU, so both sides decide
+on identical numbers.  The attend pass is then compared against the oracle's, given that mask,
+to the usual floating-point bars (O 1e-3, certificate terms 1e-4, log-masses 1e-4 absolute).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from oracle import adaptive as ad
+from oracle import attention as att
+from oracle import quantizer as qz
+from helpers import GpuLayerCache, load_binding, to_gpu_tol
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def make_case(seed, bt, hq, hkv, n_tokens, student=False, peaked=()):
+    rng = np.random.Generator(np.random.Philox(seed))
+    shape = (bt, hkv, n_tokens, 128)
+    k = workloads.student_t3_f16(rng, shape) if student else workloads.normal_f16(rng, shape)
+    v = workloads.normal_f16(rng, shape)
+    q = workloads.normal_f16(rng, (bt, hq, 128))
+    g = hq // hkv
+    for (b, h, pos, c) in peaked:                    # heads aligned with one key
+        q[b, h] = (k[b, h // g, pos].astype(np.float32) * c).astype(np.float16)
+    return k, v, q
+
+
+def gpu_adaptive(gc, q, tol, sel, step=False):
+    cqa = gc.cqa
+    qd = gc.to_dev(q)
+    gtol = to_gpu_tol(cqa, tol)
+    gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit)
+    # the scoring pass on its own first: its certificate (lse, Delta_h, V_max) is what the selector
+    # reads inside the adaptive call, bit for bit (same kernel, same inputs)
+    gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
+    _, cert0, _ = gc.results()
+    rung = None
+    if step:
+        rung = cqa.cqa_adaptive_step(gc.h, 0, qd, gtol, gsel, gc.O, gc.cert, gc.flags)
+    else:
+        cqa.cqa_adaptive_decode(gc.h, 0, qd, gtol, gsel, gc.O, gc.cert, gc.flags)
+    O, cert, flags = gc.results()
+    state = cqa.cqa_adaptive_state(gc.h, 0, gc.bt, gc.hq, gc.hkv)
+    return dict(O=O, cert=cert, flags=flags, cert0=cert0, rung=rung, k_star=state[0], selected=state[1],
+                promoted=state[2].astype(bool), l8=state[3], lx=state[4])
+
+
+def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
+    """Exact selector decisions on the GPU's log-masses; attend pass vs the oracle given the mask."""
+    bt, hq, _ = q.shape
+    g = hq // oc.hkv
+    nb = oc.n_blocks
+    heads = heads or [(b, h) for b in range(bt) for h in range(hq)]
+    groups = sorted({(b, h // g) for (b, h) in heads})
+    for (b, kh) in groups:
+        k_hat = qz.dequantize_keys(oc.k_codes[b, kh], oc.sigma[b, kh], oc.z[b, kh]).reshape(nb * 16, 128)
+        v_hat = qz.dequantize_values(oc.v_codes[b, kh], oc.v_scale[b, kh], oc.v_offset[b, kh]).reshape(nb * 16, 128)
+        k_tr, v_tr = oc.k16[b, kh, nb * 16:], oc.v16[b, kh, nb * 16:]
+        picks = []
+        for i in range(g):
+            h = kh * g + i
+            # ---- selector, on the GPU's own numbers
+            c0 = out["cert0"][b, h]
+            s = ad.select_blocks(out["l8"][b, h].astype(np.float64), float(c0["lse"]), sel)
+            k = ad.rung1_expand(s, float(c0["delta_h"]), float(c0["v_max"]), tol, sel)
+            assert int(out["k_star"][b, h]) == k, ("K*", b, h, int(out["k_star"][b, h]), k)
+            assert out["selected"][b, h, :k].tolist() == s["order"][:k].tolist(), ("selection", b, h)
+            picks.append(s["order"][:k])
+        union = ad.group_union(picks, nb)
+        assert (out["promoted"][b, kh] == union).all(), ("promoted mask", b, kh)
+        for i in range(g):
+            h = kh * g + i
+            if (b, h) not in heads:
+                continue
+            sc = att.certified_head(q[b, h], k_hat, v_hat, oc.sigma[b, kh], oc.eta[b, kh], oc.nu[b, kh],
+                                    k_tr, v_tr, att.Tolerances())
+            assert np.abs(out["l8"][b, h] - sc["blk_logmass"]).max() <= 1e-4, ("scoring log-masses", b, h)
+            ref = ad.mixed_head(q[b, h], k_hat, oc.k16[b, kh, :nb * 16], v_hat, oc.eta[b, kh], oc.nu[b, kh],
+                                k_tr, v_tr, union, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol)
+            w = ("adaptive", b, h)
+            ct = out["cert"][b, h]
+            if served and served.get((b, h)):
+                dense = oc.dense_head(q, b, h, hq)
+                assert np.linalg.norm(out["O"][b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6, w
+                assert int(ct["served_rung"]) == served[(b, h)] and ct["E_key"] == 0 and ct["E_val"] == 0, w
+                assert int(out["flags"][b, h]) == (ref["flags"] | (served[(b, h)] << att.RUNG_SHIFT)), w
+                continue
+            # O is a convex combination of value rows of norm <= V_max, accumulated in FP32: the
+            # absolute floor scales with V_max (it matters for the planted head, whose two
+            # dominant values cancel and leave ||O|| ~ 4e-4 V_max)
+            err = np.linalg.norm(out["O"][b, h] - ref["O"])
+            assert err <= 1e-3 * np.linalg.norm(ref["O"]) + 2e-6 * ref["v_max"], (w, "O", err)
+            for name in ("E_key", "E_val", "delta_h", "v_max", "alpha_tail_hat", "max_block_contrib"):
+                x, y = float(ct[name]), ref[name]
+                assert abs(x - y) <= 1e-4 * abs(y) + 1e-9, (w, name, x, y)
+            assert abs(float(ct["lse"]) - ref["lse"]) <= 1e-4 * max(1.0, abs(ref["lse"])), (w, "lse")
+            assert np.abs(out["lx"][b, h] - ref["blk_logmass"]).max() <= 1e-4, (w, "attend log-masses")
+            if union.any():
+                rk = ref["ranking"]
+                top2 = np.sort(ref["blk_logmass"][union])[::-1]
+                if len(top2) < 2 or top2[0] - top2[1] > 1e-3:
+                    assert int(ct["top_block"]) == rk["top_fp16"], (w, "top block")
+            assert int(out["flags"][b, h]) == ref["flags"], (w, "flags", int(out["flags"][b, h]), ref["flags"])
+
+
+def test_adaptive_small_all_heads():
+    say("adaptive: 2 sequences x 2 KV heads x 8 query heads, 2000 tokens, every head against the oracle")
+    k, v, q = make_case(1, 2, 8, 2, 2000, peaked=[(0, 1, 333, 0.8), (1, 6, 1500, 1.2), (1, 7, 1501, 0.5)])
+    oc = oracle.OracleLayerCache(2, 2)
+    oc.append(k, v)
+    with GpuLayerCache(2, 8, 2, 2048) as gc:
+        gc.append(k, v)
+        for tau, kmin, kmax in ((0.995, 2, 16), (0.5, 0, 4), (0.9, 1, 64)):
+            sel = ad.SelectorParams(tau, kmin, kmax, kmax)
+            tol = att.Tolerances(rank_depth=1)
+            out = gpu_adaptive(gc, q, tol, sel)
+            check_against_oracle(oc, q, tol, sel, out)
+            say(f"  tau {tau} K in [{kmin},{kmax}]: K* = {out['k_star'].ravel().tolist()}, "
+                f"promoted per group {out['promoted'].sum(axis=2).ravel().tolist()}")
+            # promotion lowers the key term of a peaked head by orders of magnitude
+            if kmax >= 16:
+                assert out["cert"]["E_key"][1, 6] < 0.05 * out["cert0"]["E_key"][1, 6]
+
+
+def test_adaptive_rung1_growth_and_clamps():
+    say("adaptive: Rung-1 doubling against a key-term threshold, K_min / K_max / block-count clamps")
+    k, v, q = make_case(2, 1, 4, 1, 1024 + 7, peaked=[(0, 2, 100, 0.7)])
+    oc = oracle.OracleLayerCache(1, 1)
+    oc.append(k, v)
+    with GpuLayerCache(1, 4, 1, 1100) as gc:
+        gc.append(k, v)
+        base = gpu_adaptive(gc, q, att.Tolerances(key_bound_mode=1), ad.SelectorParams(0.3, 1, 2, 64))
+        # a threshold between the key terms at K and at 4K of the most diffuse head forces growth
+        ek = np.sort(base["cert"]["E_key"].ravel())
+        eps = float(0.25 * ek[-1])
+        tol = att.Tolerances(key_bound_mode=1, eps_key=eps)
+        sel = ad.SelectorParams(0.3, 1, 2, 64)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert (out["k_star"] > base["k_star"]).any() and out["k_star"].max() <= 64
+        say(f"  K* {base['k_star'].ravel().tolist()} -> {out['k_star'].ravel().tolist()} at eps_key {eps:.3g}")
+        # K_max above the number of blocks: everything is promoted, the key term vanishes and the
+        # output is plain attention over the FP16 keys and the INT4-reconstructed values
+        sel = ad.SelectorParams(2.0, 0, 512, 512)
+        out = gpu_adaptive(gc, q, att.Tolerances(), sel)
+        check_against_oracle(oc, q, att.Tolerances(), sel, out)
+        assert out["promoted"].all() and (out["k_star"] == oc.n_blocks).all()
+        assert (out["cert"]["E_key"] == 0).all() and (out["cert"]["alpha_tail_hat"] == 0).all()
+        # nothing promoted: the one-pass result
+        sel = ad.SelectorParams(0.995, 0, 0, 0)
+        out = gpu_adaptive(gc, q, att.Tolerances(), sel)
+        assert not out["promoted"].any() and (out["k_star"] == 0).all()
+        O1, cert1, _ = gc.certified_decode(q)
+        assert np.allclose(out["O"], O1, rtol=0, atol=1e-6)
+        for name in ("E_key", "E_val", "alpha_tail_hat", "lse"):
+            assert np.allclose(out["cert"][name], cert1[name], rtol=1e-6, atol=0)
+
+
+def test_adaptive_ranking_check_and_ladder():
+    say("adaptive: ranking disagreement / boundary failure set RANK, the ladder serves the head by Rung 3")
+    # two planted keys in different blocks, FP16 logits 0.002 apart, both far above the rest; with this
+    # seed the INT8 scores order the two blocks the other way round (found with the oracle)
+    k, v, q = make_case(10, 1, 8, 2, 4096 + 3)
+    workloads.plant_near_tie(k, v, q, 0, 5, 8, seed=10, gap=12.0, nudge=0.002)
+    oc = oracle.OracleLayerCache(1, 2)
+    oc.append(k, v)
+    with GpuLayerCache(1, 8, 2, 4200) as gc:
+        gc.append(k, v)
+        tol = att.Tolerances(rank_depth=1, rank_min_mass=0.25)
+        # (i) both tied blocks promoted: the two rankings disagree on the top block
+        sel = ad.SelectorParams(0.995, 2, 32, 32)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert out["flags"][0, 5] & att.FLAG_RANK
+        # (ii) room for one block only: the other tied block stays in INT8 and its upper-bounded
+        # log-mass reaches the promoted one's, so the boundary test cannot certify the ranking
+        sel1 = ad.SelectorParams(0.0, 1, 1, 1)
+        out1 = gpu_adaptive(gc, q, tol, sel1)
+        check_against_oracle(oc, q, tol, sel1, out1)
+        assert out1["flags"][0, 5] & att.FLAG_RANK and out1["cert"]["rank_margin"][0, 5] < 0
+        # the ladder
+        flagged = {(0, h): 3 for h in range(8) if out["flags"][0, h] & att.FLAG_ANY}
+        stepped = gpu_adaptive(gc, q, tol, sel, step=True)
+        assert stepped["rung"] == 3 and (0, 5) in flagged
+        check_against_oracle(oc, q, tol, sel, stepped, served=flagged)
+        say(f"  heads served by Rung 3: {sorted(h for (_, h) in flagged)}")
+
+
+def test_adaptive_error_paths():
+    cqa = load_binding()
+    k, v, q = make_case(4, 1, 4, 1, 64)
+    with GpuLayerCache(1, 4, 1, 128, tier2=False) as gc:
+        gc.append(k, v)
+        with pytest.raises(cqa.CqaError) as e:
+            cqa.cqa_adaptive_decode(gc.h, 0, gc.to_dev(q), cqa.Tolerances(), cqa.Selector(), gc.O, gc.cert, gc.flags)
+        assert e.value.status == cqa.ERR_NO_TIER2
+    with GpuLayerCache(1, 4, 1, 128) as gc:
+        gc.append(k, v)
+        for bad in (cqa.Selector(0.9, 4, 2, 2), cqa.Selector(0.9, 0, 600, 600), cqa.Selector(0.9, -1, 2, 2),
+                    cqa.Selector(0.9, 0, 8, 4)):
+            with pytest.raises(cqa.CqaError) as e:
+                cqa.cqa_adaptive_decode(gc.h, 0, gc.to_dev(q), cqa.Tolerances(), bad, gc.O, gc.cert, gc.flags)
+            assert e.value.status == cqa.ERR_INVALID_ARG
+
+
+def test_adaptive_128k_sampled_heads():
+    say("adaptive: N=131072, Student-t(3) keys; selector exact on every head, oracle attend pass on 3 heads")
+    sh = workloads.SHAPES["t128k"]
+    k, v = workloads.make_kv("t128k", seed=0)
+    q = workloads.make_q("t128k", 3, seed=0)
+    oc = oracle.OracleLayerCache(sh.batch, sh.n_kv_heads)
+    oc.append(k, v)
+    ks, vs = workloads.make_step_kv("t128k", 0, seed=0)
+    oc.append(ks, vs)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 64) as gc:
+        gc.append(k, v)
+        gc.append(ks, vs)
+        sel = ad.SelectorParams(0.995, 2, 128, 128)
+        tol = att.Tolerances(rank_depth=1, rank_min_mass=0.25)
+        out = gpu_adaptive(gc, q, tol, sel)
+        # selector decisions on every head (cheap), attend pass on the heads of one KV group
+        bt, hq = sh.batch, sh.n_q_heads
+        nb = oc.n_blocks
+        for h in range(hq):
+            c0 = out["cert0"][0, h]
+            s = ad.select_blocks(out["l8"][0, h].astype(np.float64), float(c0["lse"]), sel)
+            kk = ad.rung1_expand(s, float(c0["delta_h"]), float(c0["v_max"]), tol, sel)
+            assert int(out["k_star"][0, h]) == kk and out["selected"][0, h, :kk].tolist() == s["order"][:kk].tolist()
+        check_against_oracle(oc, q, tol, sel, out, heads=[(0, 8), (0, 9), (0, 11)])
+        say(f"  K* min/median/max {out['k_star'].min()}/{int(np.median(out['k_star']))}/{out['k_star'].max()}, "
+            f"promoted per group {out['promoted'].sum(axis=2).ravel().tolist()} of {nb}")

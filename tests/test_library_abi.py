@@ -29,6 +29,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(cqa.HeadCert) == 40
     assert ctypes.sizeof(cqa.Tolerances) == 44
     assert ctypes.sizeof(cqa.CacheDesc) == 40
+    assert ctypes.sizeof(cqa.Selector) == 16
     assert cqa.CERT_BYTES == 40
 
 
@@ -38,7 +39,8 @@ def test_host_side_argument_checks_need_no_gpu():
     dev, pin = cqa.cqa_workspace_bytes(d)
     # Tier-1 is 288.5 bytes per token per kv head; Tier-2 is 512
     assert dev >= 131072 * 8 * 288.5 and pin >= 131072 * 8 * 512
-    assert dev < 131072 * 8 * 288.5 * 1.6
+    # + fallback staging for one KV group (2 buffers x K, V) and the adaptive-precision scratch
+    assert dev < 131072 * 8 * 288.5 * 1.8
     for bad in (cqa.CacheDesc(1, 1, 32, 8, 64, 16, 16, 0, 1024),      # head_dim
                 cqa.CacheDesc(1, 1, 32, 8, 128, 32, 16, 0, 1024),     # block
                 cqa.CacheDesc(1, 1, 32, 8, 128, 16, 32, 0, 1024),     # group
