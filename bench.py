@@ -372,6 +372,27 @@ def main() -> int:
         torch.cuda.synchronize()
         fb_ms = (time.perf_counter() - tf0) * 1e3 / n_fb
 
+        # adaptive key precision, reported apart from `value`: scoring pass, selection (tau_cov 0.995,
+        # K in [2, 128]), FP16-key gather from pinned host RAM, attend pass, ranking check, ladder
+        sel = cqa.Selector(0.995, 2, 128, 128)
+        atol = cqa.Tolerances(rank_depth=1, rank_min_mass=0.25)
+        n_ad = 20
+        for i in range(3):
+            cqa.cqa_adaptive_step(h, 0, qp + i * q_stride, atol, sel, Op, certp, flagsp, stream)
+        torch.cuda.synchronize()
+        ta0 = time.perf_counter()
+        rungs = []
+        for i in range(n_ad):
+            rungs.append(cqa.cqa_adaptive_step(h, 0, qp + (W + i) * q_stride, atol, sel, Op, certp, flagsp, stream))
+        torch.cuda.synchronize()
+        ad_ms = (time.perf_counter() - ta0) * 1e3 / n_ad
+        kst, _, prom, _, _ = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
+        ad_info = {"ms_per_step": ad_ms, "steps_with_fallback": int(sum(1 for r in rungs if r)),
+                   "k_star_median": float(np.median(kst)), "k_star_max": int(kst.max()),
+                   "promoted_blocks_per_group_max": int(prom.sum(axis=2).max()),
+                   "what": f"cqa_adaptive_step, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
+                           "check on, rank_min_mass 0.25; steps that fall back include the dense recompute)"}
+
         # kernel-only rate: split pass + reduction back to back, no host synchronisation in between
         ko_ms = cqa.cqa_time_certified_decode(h, 0, qs[0], tol, O, cert, flags, None, 50, stream)
         splits = cqa.cqa_decode_splits(h, 0)
@@ -422,6 +443,7 @@ def main() -> int:
             "steps_per_s": 1e3 / ko_ms,
             "what": "split pass + reduction, 50 back-to-back launches between two HIP events",
         },
+        "adaptive_step": ad_info,
         "fallback_step": {
             "ms_per_step": fb_ms,
             "what": "certified decode + Rung 3 for 1 of 32 heads (one KV group paged from pinned host RAM: "

@@ -46,6 +46,40 @@ struct SelectArgs {
   int mass_exp, key_bound_mode;
 };
 
+// Strided pass over a row in batches: all loads of a batch are issued before anything is consumed
+// (a plain strided loop has one load in flight per thread and is bound by its latency).
+constexpr int BATCH = 16;
+#define CQA_ROW_PASS(ROW, N, TID, BODY)                                           \
+  for (int base__ = 0; base__ < (N); base__ += 256 * BATCH) {                      \
+    float val__[BATCH];                                                            \
+    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
+      const int i__ = base__ + j__ * 256 + (TID);                                  \
+      val__[j__] = i__ < (N) ? (ROW)[i__] : 0.0f;                                  \
+    }                                                                              \
+    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
+      const int i = base__ + j__ * 256 + (TID);                                    \
+      const float x = val__[j__];                                                  \
+      if (i < (N)) { BODY }                                                        \
+    }                                                                              \
+  }
+
+// The selector walks its row of log-masses several times.  Rows of up to LDS_KEYS blocks are read
+// from memory once, as order-preserving integer keys kept in LDS; longer rows are re-read.
+constexpr int LDS_KEYS = 10240;   // 40 KB: contexts up to 160K tokens
+#define CQA_KEY_PASS(ROW, N, TID, CACHED, KEYS, BODY)                             \
+  for (int base__ = 0; base__ < (N); base__ += 256 * BATCH) {                      \
+    uint32_t key__[BATCH];                                                         \
+    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
+      const int i__ = base__ + j__ * 256 + (TID);                                  \
+      key__[j__] = i__ < (N) ? ((CACHED) ? (KEYS)[i__] : ord32((ROW)[i__])) : 0u;  \
+    }                                                                              \
+    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
+      const int i = base__ + j__ * 256 + (TID);                                    \
+      const uint32_t k = key__[j__];                                               \
+      if (i < (N)) { BODY }                                                        \
+    }                                                                              \
+  }
+
 // E_key / (1) from Delta_h, the estimated tail mass and V_max, in double (decision only)
 __device__ double key_term_d(double delta, double alpha, double vmax, int mass_exp, int mode) {
   double t_tail = 0.0;
@@ -71,6 +105,9 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
   const int KL = min(max(a.k_limit, a.k_max), min(nb, MAX_K_LIMIT));
 
   __shared__ uint32_t hist[256];
+  __shared__ uint32_t scan[256];
+  __shared__ uint32_t keys[LDS_KEYS];
+  const bool cached = nb <= LDS_KEYS;
   __shared__ unsigned long long cand[MAX_K_LIMIT];
   __shared__ double dsum[256];
   __shared__ uint32_t s_prefix, s_want, s_cnt;
@@ -79,21 +116,14 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
 
   const double lse = (double)a.cert[row].lse;
 
-  // ---- total estimated mass of the sealed blocks (the rest of 1 is the exact trailing tokens)
-  double part = 0.0;
-  for (int i = tid; i < nb; i += 256) part += exp((double)lm[i] - lse);
-  dsum[tid] = part;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) dsum[tid] += dsum[tid + s];
-    __syncthreads();
-  }
-  const double total_blocks = dsum[0];
-  __syncthreads();
   if (KL == 0) {
     if (tid == 0) a.kstar[row] = 0;
     return;
   }
+  // total estimated mass of the sealed blocks (the rest of 1 is the exact trailing tokens):
+  // single-precision exponentials summed in double, gathered during the first selection pass
+  double part = 0.0;
+  const float lse_f = a.cert[row].lse;
 
   // ---- radix selection of the KL-th largest key, 8 bits at a time from the top
   if (tid == 0) {
@@ -107,51 +137,86 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     hist[tid] = 0u;
     __syncthreads();
     const uint32_t prefix = s_prefix;
-    for (int i = tid; i < nb; i += 256) {
-      const uint32_t k = ord32(lm[i]);
-      if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    if (pass == 0) {
+      CQA_ROW_PASS(lm, nb, tid, {
+        part += (double)__expf(x - lse_f);
+        const uint32_t k = ord32(x);
+        if (cached) keys[i] = k;
+        atomicAdd(&hist[k >> 24], 1u);
+      })
+    } else {
+      CQA_KEY_PASS(lm, nb, tid, cached, keys, {
+        if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      })
     }
     __syncthreads();
-    if (tid == 0) {
-      uint32_t want = s_want, cum = 0u;
-      int bin = 255;
-      for (; bin > 0; --bin) {
-        if (cum + hist[bin] >= want) break;
-        cum += hist[bin];
+    {
+      // suffix sums over the 256 bins in parallel: scan[t] = blocks in bins >= t.  The bin to
+      // descend into is the one where the count from the top first reaches `want`.
+      scan[tid] = hist[tid];
+      __syncthreads();
+      for (int s = 1; s < 256; s <<= 1) {
+        const uint32_t v = tid + s < 256 ? scan[tid + s] : 0u;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
       }
-      s_want = want - cum;                       // still to take inside the chosen bin
-      s_prefix = prefix | ((uint32_t)bin << shift);
+      const uint32_t want = s_want;
+      const uint32_t above = tid < 255 ? scan[tid + 1] : 0u;
+      __syncthreads();
+      if (scan[tid] >= want && above < want) {
+        s_want = want - above;                     // still to take inside the chosen bin
+        s_prefix = prefix | ((uint32_t)tid << shift);
+      }
     }
     __syncthreads();
   }
+  dsum[tid] = part;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) dsum[tid] += dsum[tid + s];
+    __syncthreads();
+  }
+  const double total_blocks = dsum[0];
   const uint32_t T = s_prefix;                   // key of the KL-th best block
   // blocks with key == T: s_want of them are needed, the ones with the lowest indices.
   // Select the s_want-th smallest index among them the same way (indices < 2^24 * 256).
+  // (the last histogram still holds the number of blocks with key == T: when all of them are
+  // wanted, which is the rule unless log-masses tie exactly, no index needs to be selected)
+  const bool all_ties = hist[T & 255u] == s_want;
   if (tid == 0) {
-    s_idx_prefix = 0u;
+    s_idx_prefix = all_ties ? 0xFFFFFFFFu : 0u;
     s_idx_want = s_want;
   }
   __syncthreads();
-  for (int pass = 0; pass < 4; ++pass) {
+  for (int pass = 0; pass < (all_ties ? 0 : 4); ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
     hist[tid] = 0u;
     __syncthreads();
     const uint32_t prefix = s_idx_prefix;
-    for (int i = tid; i < nb; i += 256) {
-      if (ord32(lm[i]) == T && (((uint32_t)i) & himask) == prefix)
+    CQA_KEY_PASS(lm, nb, tid, cached, keys, {
+      if (k == T && (((uint32_t)i) & himask) == prefix)
         atomicAdd(&hist[(((uint32_t)i) >> shift) & 255u], 1u);
-    }
+    })
     __syncthreads();
-    if (tid == 0) {
-      uint32_t want = s_idx_want, cum = 0u;
-      int bin = 0;
-      for (; bin < 255; ++bin) {
-        if (cum + hist[bin] >= want) break;
-        cum += hist[bin];
+    {
+      // prefix sums: scan[t] = ties with this digit <= t; descend where the count first reaches `want`
+      scan[tid] = hist[tid];
+      __syncthreads();
+      for (int s = 1; s < 256; s <<= 1) {
+        const uint32_t v = tid >= s ? scan[tid - s] : 0u;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
       }
-      s_idx_want = want - cum;
-      s_idx_prefix = prefix | ((uint32_t)bin << shift);
+      const uint32_t want = s_idx_want;
+      const uint32_t below = tid > 0 ? scan[tid - 1] : 0u;
+      __syncthreads();
+      if (scan[tid] >= want && below < want) {
+        s_idx_want = want - below;
+        s_idx_prefix = prefix | ((uint32_t)tid << shift);
+      }
     }
     __syncthreads();
   }
@@ -161,19 +226,21 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
   if (tid == 0) s_cnt = 0u;
   for (int i = tid; i < MAX_K_LIMIT; i += 256) cand[i] = 0ull;
   __syncthreads();
-  for (int i = tid; i < nb; i += 256) {
-    const uint32_t k = ord32(lm[i]);
+  CQA_KEY_PASS(lm, nb, tid, cached, keys, {
     if (k > T || (k == T && (uint32_t)i <= Tidx)) {
       const uint32_t pos = atomicAdd(&s_cnt, 1u);
       if (pos < (uint32_t)MAX_K_LIMIT)
         cand[pos] = ((unsigned long long)k << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
     }
-  }
+  })
   __syncthreads();
-  // ---- bitonic sort, descending, of the MAX_K_LIMIT slots (empty slots are zero = smallest)
-  for (int size = 2; size <= MAX_K_LIMIT; size <<= 1) {
+  // ---- bitonic sort, descending, of the first NS slots, NS = the power of two that holds the
+  //      KL winners (empty slots are zero = smallest)
+  int NS = 2;
+  while (NS < KL) NS <<= 1;
+  for (int size = 2; size <= NS; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < MAX_K_LIMIT / 2; t += 256) {
+      for (int t = tid; t < NS / 2; t += 256) {
         const int lo = 2 * t - (t & (stride - 1));
         const int hi = lo + stride;
         const bool desc = (lo & size) == 0;
@@ -187,25 +254,35 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     }
   }
 
-  // ---- covering prefix, clamps, Rung-1 growth (a few hundred scalar operations)
+  // ---- masses of the winners, best first, and their inclusive prefix sums (parallel)
+  __shared__ double pm[MAX_K_LIMIT];
+  __shared__ int s_first;
+  const int n = (int)min(s_cnt, (uint32_t)KL);
+  for (int i = tid; i < MAX_K_LIMIT; i += 256) {
+    const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
+    pm[i] = (i < n && idx >= 0 && idx < nb) ? exp((double)lm[idx] - lse) : 0.0;
+  }
+  if (tid == 0) s_first = MAX_K_LIMIT + 1;
+  __syncthreads();
+  for (int s = 1; s < MAX_K_LIMIT; s <<= 1) {
+    const double a0 = tid >= s ? pm[tid - s] : 0.0;
+    const double a1 = tid + 256 >= s ? pm[tid + 256 - s] : 0.0;
+    __syncthreads();
+    pm[tid] += a0;
+    pm[tid + 256] += a1;
+    __syncthreads();
+  }
+  // ---- covering prefix: C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so the
+  //      search stops there; then clamps and Rung-1 growth
+  const double rho_trail = 1.0 - total_blocks;
+  const int look = min(n, a.k_max);
+  for (int kk = tid; kk <= look; kk += 256) {
+    const double covered = rho_trail + (kk > 0 ? pm[kk - 1] : 0.0);
+    if (covered >= (double)a.tau_cov) atomicMin(&s_first, kk);
+  }
+  __syncthreads();
   if (tid == 0) {
-    const int n = (int)min(s_cnt, (uint32_t)KL);
-    const double rho_trail = 1.0 - total_blocks;
-    double cum = 0.0;
-    int k = -1;
-    // C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so stop looking there
-    const int look = min(n, a.k_max);
-    for (int i = 0; i <= look; ++i) {
-      if (rho_trail + cum >= (double)a.tau_cov) {
-        k = i;
-        break;
-      }
-      if (i < look) {
-        const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
-        cum += exp((double)lm[idx] - lse);
-      }
-    }
-    if (k < 0) k = nb;                                  // no prefix up to k_max covers tau_cov
+    int k = s_first <= look ? s_first : nb;             // no prefix up to k_max covers tau_cov
     k = max(a.k_min, min(k, a.k_max));
     k = min(k, nb);
     k = min(k, n);
@@ -213,12 +290,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const double delta = (double)a.cert[row].delta_h, vmax = (double)a.cert[row].v_max;
     const int cap = min(max(a.k_limit, a.k_max), n);
     while (k < cap) {
-      double covered = 0.0;
-      for (int i = 0; i < k; ++i) {
-        const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
-        covered += exp((double)lm[idx] - lse);
-      }
-      const double tail = total_blocks - covered;
+      const double tail = total_blocks - (k > 0 ? pm[k - 1] : 0.0);
       if (!(key_term_d(delta, tail, vmax, a.mass_exp, a.key_bound_mode) > (double)a.eps_key)) break;
       k = min(max(2 * k, 1), cap);
     }
@@ -349,21 +421,36 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY;
   int ix = -1, i8 = -1;
   double tail_mass = 0.0;
-  for (int i = tid; i < ra.nb; i += 256) {
-    const float v8 = l8[i];
-    if (slot[i] >= 0) {
-      const float vx = lx[i];
-      if (vx > best_x) {        // ascending scan per thread: strict > keeps the lowest index
-        best_x = vx;
-        ix = i;
+  for (int base = 0; base < ra.nb; base += 256 * BATCH) {
+    float b8[BATCH], bx[BATCH];
+    int bs[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {       // all loads of the batch first
+      const int i = base + j * 256 + tid;
+      const bool in = i < ra.nb;
+      b8[j] = in ? l8[i] : 0.0f;
+      bs[j] = in ? slot[i] : -1;
+      bx[j] = in ? lx[i] : 0.0f;            // unpromoted blocks: the matrix-core pass's value, unused
+    }
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const int i = base + j * 256 + tid;
+      if (i >= ra.nb) continue;
+      const float v8 = b8[j];
+      if (bs[j] >= 0) {
+        const float vx = bx[j];
+        if (vx > best_x) {      // ascending scan per thread: strict > keeps the lowest index
+          best_x = vx;
+          ix = i;
+        }
+        if (v8 > best_8) {
+          best_8 = v8;
+          i8 = i;
+        }
+      } else {
+        tail_max = fmaxf(tail_max, v8);
+        tail_mass += (double)expf(v8 - lse8);
       }
-      if (v8 > best_8) {
-        best_8 = v8;
-        i8 = i;
-      }
-    } else {
-      tail_max = fmaxf(tail_max, v8);
-      tail_mass += (double)expf(v8 - lse8);
     }
   }
   __shared__ float s_bx[256], s_b8[256], s_tm[256];
