@@ -49,17 +49,20 @@ struct SelectArgs {
 // Strided pass over a row in batches: all loads of a batch are issued before anything is consumed
 // (a plain strided loop has one load in flight per thread and is bound by its latency).
 constexpr int BATCH = 16;
+constexpr int ST = 1024;          // threads of the selector workgroup
+constexpr int SBATCH = 8;
 #define CQA_ROW_PASS(ROW, N, TID, BODY)                                           \
-  for (int base__ = 0; base__ < (N); base__ += 256 * BATCH) {                      \
-    float val__[BATCH];                                                            \
-    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
-      const int i__ = base__ + j__ * 256 + (TID);                                  \
+  for (int base__ = 0; base__ < (N); base__ += ST * SBATCH) {                      \
+    float val__[SBATCH];                                                            \
+    _Pragma("unroll") for (int j__ = 0; j__ < SBATCH; ++j__) {                      \
+      const int i__ = base__ + j__ * ST + (TID);                                  \
       val__[j__] = i__ < (N) ? (ROW)[i__] : 0.0f;                                  \
     }                                                                              \
-    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
-      const int i = base__ + j__ * 256 + (TID);                                    \
+    _Pragma("unroll") for (int j__ = 0; j__ < SBATCH; ++j__) {                      \
+      const int i = base__ + j__ * ST + (TID);                                    \
       const float x = val__[j__];                                                  \
-      if (i < (N)) { BODY }                                                        \
+      const bool in = i < (N);                                                     \
+      BODY                                                                         \
     }                                                                              \
   }
 
@@ -67,16 +70,17 @@ constexpr int BATCH = 16;
 // from memory once, as order-preserving integer keys kept in LDS; longer rows are re-read.
 constexpr int LDS_KEYS = 10240;   // 40 KB: contexts up to 160K tokens
 #define CQA_KEY_PASS(ROW, N, TID, CACHED, KEYS, BODY)                             \
-  for (int base__ = 0; base__ < (N); base__ += 256 * BATCH) {                      \
-    uint32_t key__[BATCH];                                                         \
-    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
-      const int i__ = base__ + j__ * 256 + (TID);                                  \
+  for (int base__ = 0; base__ < (N); base__ += ST * SBATCH) {                      \
+    uint32_t key__[SBATCH];                                                         \
+    _Pragma("unroll") for (int j__ = 0; j__ < SBATCH; ++j__) {                      \
+      const int i__ = base__ + j__ * ST + (TID);                                  \
       key__[j__] = i__ < (N) ? ((CACHED) ? (KEYS)[i__] : ord32((ROW)[i__])) : 0u;  \
     }                                                                              \
-    _Pragma("unroll") for (int j__ = 0; j__ < BATCH; ++j__) {                      \
-      const int i = base__ + j__ * 256 + (TID);                                    \
+    _Pragma("unroll") for (int j__ = 0; j__ < SBATCH; ++j__) {                      \
+      const int i = base__ + j__ * ST + (TID);                                    \
       const uint32_t k = key__[j__];                                               \
-      if (i < (N)) { BODY }                                                        \
+      const bool in = i < (N);                                                     \
+      BODY                                                                         \
     }                                                                              \
   }
 
@@ -93,10 +97,47 @@ __device__ double key_term_d(double delta, double alpha, double vmax, int mass_e
   return 2.0 * vmax * tv;
 }
 
+// Histogram increment for a whole wave.  Log-masses of one head share their leading bits, so in
+// the first passes most lanes hit the same bin and plain LDS atomics would serialise 64 ways: up
+// to two bins are first counted by ballot (one atomic each), the rest go one by one.
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool pred) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const unsigned long long active = __ballot(pred);
+    if (active == 0ull) return;
+    const int leader = __ffsll((long long)active) - 1;
+    const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
+    const bool same = pred && bin == lb;
+    const unsigned long long votes = __ballot(same);
+    if (lane == leader) atomicAdd(&hist[lb], (uint32_t)__popcll(votes));
+    if (same) pred = false;
+  }
+  if (pred) atomicAdd(&hist[bin], 1u);
+}
+
+// Inclusive scan over the threads of a workgroup with two barriers: shuffles inside each wave,
+// then the preceding waves' totals.  `tot` = one word of LDS scratch per wave.
+template <typename T>
+__device__ __forceinline__ T block_scan_incl(T v, T* tot, int tid) {
+  const int l = tid & 63, w = tid >> 6;
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    const T u = __shfl_up(v, s);
+    if (l >= s) v += u;
+  }
+  __syncthreads();            // protects `tot` against the previous use
+  if (l == 63) tot[w] = v;
+  __syncthreads();
+  T off = 0;
+  for (int j = 0; j < w; ++j) off += tot[j];
+  return v + off;
+}
+
 // One workgroup per (batch, query head).  Finds the KL = min(k_limit, nb) best blocks under the
 // total order (larger log-mass first, equal log-masses: lower index first) by radix selection
-// over the row, sorts them, and takes the covering prefix.
-__global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
+// over the row, ranks them, and takes the covering prefix.
+__global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   const int tid = threadIdx.x;
   const int hq = blockIdx.x, b = blockIdx.y;
   const int64_t row = (int64_t)b * a.n_q + hq;
@@ -105,178 +146,141 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
   const int KL = min(max(a.k_limit, a.k_max), min(nb, MAX_K_LIMIT));
 
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t scan[256];
   __shared__ uint32_t keys[LDS_KEYS];
   const bool cached = nb <= LDS_KEYS;
-  __shared__ unsigned long long cand[MAX_K_LIMIT];
-  __shared__ double dsum[256];
+  __shared__ unsigned long long cand[MAX_K_LIMIT];     // winners, unordered
+  __shared__ int sorted_idx[MAX_K_LIMIT];              // their block indices, best first
+  __shared__ double pm[MAX_K_LIMIT];                   // prefix sums of their masses
+  __shared__ double dtot[ST / 64];
+  __shared__ uint32_t utot[ST / 64];
   __shared__ uint32_t s_prefix, s_want, s_cnt;
   __shared__ uint32_t s_idx_prefix, s_idx_want;
-  __shared__ int s_k;
-
-  const double lse = (double)a.cert[row].lse;
+  __shared__ int s_k, s_first;
 
   if (KL == 0) {
     if (tid == 0) a.kstar[row] = 0;
     return;
   }
-  // total estimated mass of the sealed blocks (the rest of 1 is the exact trailing tokens):
-  // single-precision exponentials summed in double, gathered during the first selection pass
-  double part = 0.0;
+#ifdef CQA_PROBE_SELECT
+  const uint64_t ts0 = wall_clock64();
+#define CQA_STAMP(N) if (tid == 0) a.sel[row * MAX_K_LIMIT + 500 + (N)] = (int)(wall_clock64() - ts0);
+#else
+#define CQA_STAMP(N)
+#endif
+  const double lse = (double)a.cert[row].lse;
   const float lse_f = a.cert[row].lse;
 
-  // ---- radix selection of the KL-th largest key, 8 bits at a time from the top
+  // ---- radix selection of the KL-th largest key, 8 bits at a time from the top.  The first pass
+  //      also keeps the keys in LDS and sums the estimated mass of the sealed blocks (single-
+  //      precision exponentials, accumulated in double; the rest of 1 is the exact trailing tokens).
+  double part = 0.0;
   if (tid == 0) {
     s_prefix = 0u;
     s_want = (uint32_t)KL;
   }
-  __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    hist[tid] = 0u;
+    if (tid < 256) hist[tid] = 0u;
     __syncthreads();
     const uint32_t prefix = s_prefix;
+    const uint32_t want = s_want;
     if (pass == 0) {
       CQA_ROW_PASS(lm, nb, tid, {
-        part += (double)__expf(x - lse_f);
         const uint32_t k = ord32(x);
-        if (cached) keys[i] = k;
-        atomicAdd(&hist[k >> 24], 1u);
+        if (in) {
+          part += (double)__expf(x - lse_f);
+          if (cached) keys[i] = k;
+        }
+        hist_add(hist, k >> 24, in);
       })
     } else {
       CQA_KEY_PASS(lm, nb, tid, cached, keys, {
-        if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        hist_add(hist, (k >> shift) & 255u, in && (k & himask) == prefix);
       })
     }
     __syncthreads();
-    {
-      // suffix sums over the 256 bins in parallel: scan[t] = blocks in bins >= t.  The bin to
-      // descend into is the one where the count from the top first reaches `want`.
-      scan[tid] = hist[tid];
-      __syncthreads();
-      for (int s = 1; s < 256; s <<= 1) {
-        const uint32_t v = tid + s < 256 ? scan[tid + s] : 0u;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-      }
-      const uint32_t want = s_want;
-      const uint32_t above = tid < 255 ? scan[tid + 1] : 0u;
-      __syncthreads();
-      if (scan[tid] >= want && above < want) {
-        s_want = want - above;                     // still to take inside the chosen bin
-        s_prefix = prefix | ((uint32_t)tid << shift);
-      }
+    // thread t looks at bin 255 - t, so an inclusive scan over threads counts from the top bin down;
+    // the bin to descend into is the one where that count first reaches `want`
+    const uint32_t mine = tid < 256 ? hist[255 - tid] : 0u;
+    const uint32_t upto = block_scan_incl<uint32_t>(mine, utot, tid);
+    if (upto >= want && upto - mine < want) {
+      s_want = want - (upto - mine);               // still to take inside the chosen bin
+      s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
     }
     __syncthreads();
   }
-  dsum[tid] = part;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) dsum[tid] += dsum[tid + s];
-    __syncthreads();
-  }
-  const double total_blocks = dsum[0];
+  CQA_STAMP(0)
+  const double total_blocks = block_scan_incl<double>(part, dtot, tid);   // last thread: the total
+  __shared__ double s_total;
+  if (tid == ST - 1) s_total = total_blocks;
   const uint32_t T = s_prefix;                   // key of the KL-th best block
-  // blocks with key == T: s_want of them are needed, the ones with the lowest indices.
-  // Select the s_want-th smallest index among them the same way (indices < 2^24 * 256).
-  // (the last histogram still holds the number of blocks with key == T: when all of them are
-  // wanted, which is the rule unless log-masses tie exactly, no index needs to be selected)
+  // blocks with key == T: s_want of them are needed, the ones with the lowest indices.  The last
+  // histogram still holds how many there are: when all of them are wanted, which is the rule
+  // unless log-masses tie exactly, no index needs to be selected.
   const bool all_ties = hist[T & 255u] == s_want;
+  __syncthreads();
   if (tid == 0) {
     s_idx_prefix = all_ties ? 0xFFFFFFFFu : 0u;
     s_idx_want = s_want;
+    s_cnt = 0u;
+    s_first = MAX_K_LIMIT + 1;
   }
-  __syncthreads();
   for (int pass = 0; pass < (all_ties ? 0 : 4); ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    hist[tid] = 0u;
+    if (tid < 256) hist[tid] = 0u;
     __syncthreads();
     const uint32_t prefix = s_idx_prefix;
+    const uint32_t want = s_idx_want;
     CQA_KEY_PASS(lm, nb, tid, cached, keys, {
-      if (k == T && (((uint32_t)i) & himask) == prefix)
-        atomicAdd(&hist[(((uint32_t)i) >> shift) & 255u], 1u);
+      hist_add(hist, (((uint32_t)i) >> shift) & 255u, in && k == T && (((uint32_t)i) & himask) == prefix);
     })
     __syncthreads();
-    {
-      // prefix sums: scan[t] = ties with this digit <= t; descend where the count first reaches `want`
-      scan[tid] = hist[tid];
-      __syncthreads();
-      for (int s = 1; s < 256; s <<= 1) {
-        const uint32_t v = tid >= s ? scan[tid - s] : 0u;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-      }
-      const uint32_t want = s_idx_want;
-      const uint32_t below = tid > 0 ? scan[tid - 1] : 0u;
-      __syncthreads();
-      if (scan[tid] >= want && below < want) {
-        s_idx_want = want - below;
-        s_idx_prefix = prefix | ((uint32_t)tid << shift);
-      }
+    const uint32_t mine = tid < 256 ? hist[tid] : 0u;   // ascending: the lowest indices are taken first
+    const uint32_t upto = block_scan_incl<uint32_t>(mine, utot, tid);
+    if (upto >= want && upto - mine < want) {
+      s_idx_want = want - (upto - mine);
+      s_idx_prefix = prefix | ((uint32_t)tid << shift);
     }
     __syncthreads();
   }
+  __syncthreads();
+  CQA_STAMP(1)
   const uint32_t Tidx = s_idx_prefix;            // largest index taken among the ties
+  const double total = s_total;
 
   // ---- collect the KL winners as composite keys (log-mass order, then lower index first)
-  if (tid == 0) s_cnt = 0u;
-  for (int i = tid; i < MAX_K_LIMIT; i += 256) cand[i] = 0ull;
-  __syncthreads();
   CQA_KEY_PASS(lm, nb, tid, cached, keys, {
-    if (k > T || (k == T && (uint32_t)i <= Tidx)) {
+    if (in && (k > T || (k == T && (uint32_t)i <= Tidx))) {
       const uint32_t pos = atomicAdd(&s_cnt, 1u);
       if (pos < (uint32_t)MAX_K_LIMIT)
         cand[pos] = ((unsigned long long)k << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
     }
   })
   __syncthreads();
-  // ---- bitonic sort, descending, of the first NS slots, NS = the power of two that holds the
-  //      KL winners (empty slots are zero = smallest)
-  int NS = 2;
-  while (NS < KL) NS <<= 1;
-  for (int size = 2; size <= NS; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < NS / 2; t += 256) {
-        const int lo = 2 * t - (t & (stride - 1));
-        const int hi = lo + stride;
-        const bool desc = (lo & size) == 0;
-        const unsigned long long x = cand[lo], y = cand[hi];
-        if ((x < y) == desc) {
-          cand[lo] = y;
-          cand[hi] = x;
-        }
-      }
-      __syncthreads();
-    }
-  }
-
-  // ---- masses of the winners, best first, and their inclusive prefix sums (parallel)
-  __shared__ double pm[MAX_K_LIMIT];
-  __shared__ int s_first;
+  CQA_STAMP(2)
   const int n = (int)min(s_cnt, (uint32_t)KL);
-  for (int i = tid; i < MAX_K_LIMIT; i += 256) {
-    const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
-    pm[i] = (i < n && idx >= 0 && idx < nb) ? exp((double)lm[idx] - lse) : 0.0;
+  // ---- rank sort: a winner's place is the number of winners that precede it (keys are distinct)
+  for (int i = tid; i < n; i += ST) {
+    const unsigned long long mine = cand[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) rank += cand[j] > mine ? 1 : 0;
+    sorted_idx[rank] = (int)(0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull));
   }
-  if (tid == 0) s_first = MAX_K_LIMIT + 1;
   __syncthreads();
-  for (int s = 1; s < MAX_K_LIMIT; s <<= 1) {
-    const double a0 = tid >= s ? pm[tid - s] : 0.0;
-    const double a1 = tid + 256 >= s ? pm[tid + 256 - s] : 0.0;
-    __syncthreads();
-    pm[tid] += a0;
-    pm[tid + 256] += a1;
-    __syncthreads();
-  }
+  CQA_STAMP(3)
+  // ---- masses of the winners, best first, and their inclusive prefix sums: thread t owns place t
+  const double m0 = tid < n ? exp((double)lm[sorted_idx[tid]] - lse) : 0.0;
+  const double upto1 = block_scan_incl<double>(m0, dtot, tid);
+  if (tid < MAX_K_LIMIT) pm[tid] = upto1;
+  __syncthreads();
+  CQA_STAMP(4)
   // ---- covering prefix: C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so the
   //      search stops there; then clamps and Rung-1 growth
-  const double rho_trail = 1.0 - total_blocks;
+  const double rho_trail = 1.0 - total;
   const int look = min(n, a.k_max);
-  for (int kk = tid; kk <= look; kk += 256) {
+  for (int kk = tid; kk <= look; kk += ST) {
     const double covered = rho_trail + (kk > 0 ? pm[kk - 1] : 0.0);
     if (covered >= (double)a.tau_cov) atomicMin(&s_first, kk);
   }
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const double delta = (double)a.cert[row].delta_h, vmax = (double)a.cert[row].v_max;
     const int cap = min(max(a.k_limit, a.k_max), n);
     while (k < cap) {
-      const double tail = total_blocks - (k > 0 ? pm[k - 1] : 0.0);
+      const double tail = total - (k > 0 ? pm[k - 1] : 0.0);
       if (!(key_term_d(delta, tail, vmax, a.mass_exp, a.key_bound_mode) > (double)a.eps_key)) break;
       k = min(max(2 * k, 1), cap);
     }
@@ -298,10 +302,11 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     a.kstar[row] = k;
   }
   __syncthreads();
+  CQA_STAMP(5)
   const int k = s_k;
   uint32_t* um = a.umask + ((int64_t)b * a.n_kv + hq / (a.n_q / a.n_kv)) * a.mask_words;
-  for (int i = tid; i < k; i += 256) {
-    const int idx = (int)(0xFFFFFFFFu - (uint32_t)(cand[i] & 0xFFFFFFFFull));
+  for (int i = tid; i < k; i += ST) {
+    const int idx = sorted_idx[i];
     a.sel[row * MAX_K_LIMIT + i] = idx;
     if (idx >= 0 && idx < nb) atomicOr(&um[idx >> 5], 1u << (idx & 31));
   }
@@ -546,7 +551,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   sa.eps_key = tol.eps_key;
   sa.mass_exp = tol.mass_exp;
   sa.key_bound_mode = tol.key_bound_mode;
-  hipLaunchKernelGGL(select_kernel, dim3(hq, bt), dim3(256), 0, st, sa);
+  hipLaunchKernelGGL(select_kernel, dim3(hq, bt), dim3(ST), 0, st, sa);
   CQA_HIP(hipGetLastError());
 
   // ---- 3. slot map and ordered list per group; FP16 keys of the listed blocks into the scratch
