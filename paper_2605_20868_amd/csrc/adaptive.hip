@@ -525,7 +525,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   loose.eps_total = loose.eps_key = loose.eps_val = loose.v_tol = INFINITY;
   loose.rank_depth = 0;
   loose.force_flags = 0;
-  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st);
+  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st,
+                                /*score_only=*/nb > 0);
   if (rc != CQA_OK) return rc;
   if (nb == 0) {
     // nothing sealed: the scoring pass (exact trailing tokens only) is the answer; rerun it
@@ -620,6 +621,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.ucount = w.ucount;
   a.kscratch = w.kscratch;
   a.split0 = nsplit;
+  a.score_only = 0;
   rc = launch_split_mfma(a, ra, nullptr, g, dim3(nsplit, hkv, bt), nullptr, nullptr, st);
   if (rc != CQA_OK) return rc;
   CQA_HIP(hipGetLastError());

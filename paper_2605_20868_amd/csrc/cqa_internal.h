@@ -168,6 +168,7 @@ struct DecodeArgs {
   const int32_t* ucount;    // [Bt][Hkv]
   const __half* kscratch;   // [Bt][Hkv][MAX_UNION][16][128]
   int split0;               // promoted-block pass: index of its first partial set
+  int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
 };
 
 
@@ -190,7 +191,8 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
                     int64_t len_before, bool tier2_by_kernel, hipStream_t st);
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st);
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
+                         bool score_only = false);
 int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;

@@ -340,7 +340,7 @@ int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStrea
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st) {
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st, bool score_only) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
@@ -381,6 +381,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.ucount = nullptr;
     a.kscratch = nullptr;
     a.split0 = 0;
+    a.score_only = (score_only && c->variant == 0 && blk_logmass != nullptr) ? 1 : 0;
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;

@@ -115,7 +115,10 @@ constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability bu
 // left out here (their scores get the same huge negative value as blocks past the end, so every
 // weight and mass they produce vanishes, and their log-mass is not written); a second, small
 // kernel attends them from the FP16 keys and adds its own partial sets.
-template <int G, bool LM, bool MIX>
+// SCORE: scoring pass only (the first phase of the two-phase path): no value codes or value
+// metadata are read and no output is accumulated; block log-masses, the softmax mass, Delta_b,
+// nu_b and eta_b statistics are produced as usual and the partial outputs are written as zeros.
+template <int G, bool LM, bool MIX, bool SCORE>
 __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
                                                                       uint32_t* tickets) {
   const int l = threadIdx.x & 63;
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       kraw[i][CQ] = *reinterpret_cast<const uint4*>(rec + i * KC_BYTES + lo16);          \
   }
 #define CQA_LOAD_V(QB, P)                                                                \
-  {                                                                                      \
+  if (!SCORE) {                                                                          \
     const uint8_t* rec = CQA_REC(QB) + (Q_VC + (P) * 2 * VC_BYTES);                      \
     vraw[P][0] = *reinterpret_cast<const uint4*>(rec + vo16);                            \
     vraw[P][1] = *reinterpret_cast<const uint4*>(rec + 256 + vo16);                      \
@@ -217,8 +220,10 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       km_n[i] = *reinterpret_cast<const u32x4*>(rec + (Q_KM + i * KM_BYTES) + lo16);     \
       an_n[i] = *reinterpret_cast<const float2*>(rec + (Q_AN + i * AN_BYTES));           \
     }                                                                                    \
-    _Pragma("unroll") for (int P = 0; P < 2; ++P)                                        \
-      vm_n[P] = *reinterpret_cast<const u32x4*>(rec + (Q_VM + P * 2 * VM_BYTES) + lo16); \
+    if (!SCORE) {                                                                        \
+      _Pragma("unroll") for (int P = 0; P < 2; ++P)                                      \
+        vm_n[P] = *reinterpret_cast<const u32x4*>(rec + (Q_VM + P * 2 * VM_BYTES) + lo16); \
+    }                                                                                    \
   }
 
   // The first quad is requested before anything else, so the query set-up below runs under the
@@ -289,9 +294,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       an[i] = an_n[i];
       reinterpret_cast<u32x4*>(&kmbuf[w][i][0])[l] = km_n[i];
     }
+    if (!SCORE) {
 #pragma unroll
-    for (int P = 0; P < 2; ++P)
-      reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
+      for (int P = 0; P < 2; ++P)
+        reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
+    }
     CQA_LOAD_META(qb + 4)
     wave_sync_m();
 
@@ -410,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       t2 = g1 ? t1 : (g2 ? lb : t2);
       i1 = g1 ? qb + i : i1;
       t1 = g1 ? lb : t1;
-      pbuf[w][kg][i * BLK + n] = ptv[i] * f;
+      if (!SCORE) pbuf[w][kg][i * BLK + n] = ptv[i] * f;
     }
     if (LM) {
       if (n == 0 && kg < G) {
@@ -424,6 +431,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     wave_sync_m();
 
     __builtin_amdgcn_s_setprio(0);
+    if (SCORE) continue;   // scoring pass: nothing below applies (the K prefetch sits above)
     // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
     if (__any(alpha != 1.0f)) {
 #pragma unroll
@@ -599,17 +607,22 @@ int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* t
   const bool lm = a.blk_logmass != nullptr;
 #endif
   const bool mix = a.slot != nullptr;
-  if (mix && !lm) return CQA_ERR_INVALID_ARG;   // the gated pass always reports block log-masses
+  const bool score = a.score_only != 0;
+  if ((mix || score) && !lm) return CQA_ERR_INVALID_ARG;   // both always report block log-masses
+  if (mix && score) return CQA_ERR_INVALID_ARG;
 #define CQA_LAUNCH(GG)                                                                           \
-  if (mix)                                                                                       \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, true>), grid, dim3(256), 0, st,  \
-                          ev0, ev1, 0, a, ra, tickets);                                          \
+  if (score)                                                                                     \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false, true>), grid, dim3(256),  \
+                          0, st, ev0, ev1, 0, a, ra, tickets);                                   \
+  else if (mix)                                                                                  \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, true, false>), grid, dim3(256),  \
+                          0, st, ev0, ev1, 0, a, ra, tickets);                                   \
   else if (lm)                                                                                   \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false>), grid, dim3(256), 0, st, \
-                          ev0, ev1, 0, a, ra, tickets);                                          \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false, false>), grid, dim3(256), \
+                          0, st, ev0, ev1, 0, a, ra, tickets);                                   \
   else                                                                                           \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, false>), grid, dim3(256), 0,    \
-                          st, ev0, ev1, 0, a, ra, tickets);
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, false, false>), grid,           \
+                          dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
   switch (group) {
     case 1: CQA_LAUNCH(1) break;
     case 2: CQA_LAUNCH(2) break;
