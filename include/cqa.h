@@ -211,17 +211,18 @@ typedef struct cqa_selector {
 } cqa_selector;
 
 /* One decode step of `layer` with mask-gated key precision, all on `stream`:
- *  1. scoring pass = cqa_certified_decode, which also yields the INT8 block
- *     log-masses l_b, Delta_h and V_max of every head;
+ *  1. scoring pass over the INT8 keys only (no value reads): the INT8 block
+ *     log-masses l_b, the total log-mass, Delta_h and V_max of every head;
  *  2. selection per head: blocks ranked by l_b (ties: lower index), K* = the
  *     smallest k whose blocks, with the exact trailing tokens, hold >= tau_cov
  *     of the estimated mass, clamped; Rung 1: K doubles (up to k_limit) while
  *     the key term of the achieved tail exceeds tol->eps_key;
  *  3. the promoted set of a (batch, kv-head) group is the union of its heads'
- *     selections; the FP16 keys of those blocks are gathered from the pinned
- *     Tier-2 originals into a device scratch by a kernel (no host step);
- *  4. attend pass: as the scoring pass, but promoted blocks are scored with
- *     their FP16 keys (values stay INT4); E_val uses the masses of this pass;
+ *     selections;
+ *  4. attend pass: as cqa_certified_decode, but promoted blocks are scored
+ *     with their FP16 keys, which the device reads straight from the pinned
+ *     Tier-2 originals (no host step, no staging); values stay INT4; E_val
+ *     uses the masses of this pass;
  *     E_key uses alpha_hat_T = the scoring pass's estimated mass of the blocks
  *     the group left in INT8, and the scoring pass's Delta_h;
  *  5. ranking check at depth 1 (if tol->rank_depth >= 1): RANK is set when the

@@ -1,5 +1,5 @@
-// Adaptive key precision: selector, promoted-set bookkeeping, FP16-key gather, and the
-// reduction of the attend pass with its ranking check.
+// Adaptive key precision: selector, promoted-set bookkeeping, and the reduction of the attend
+// pass with its ranking check.
 //
 // Follows the paper's "Adaptive Precision Selection" (rank blocks by INT8-estimated mass, K* =
 // smallest prefix that covers tau_cov, clamp to [K_min, K_max]), the first rung of its "Fallback
@@ -8,12 +8,12 @@
 // verification, at depth 1.  Key precision is chosen per KV group (the union of the group's
 // query heads' selections): the paper's per-KV-group selection variant.
 //
-// Sequence on one stream (launch_adaptive): scoring pass (the ordinary certified decode, which
-// also emits the INT8 block log-masses) -> select_kernel (per head) -> compact_kernel (per group:
-// union bit mask -> slot map and ordered list) -> gather_kernel (FP16 keys of the listed blocks
-// from the pinned Tier-2 originals, read by the device over the host link, into the scratch) ->
-// attend pass = matrix-core split pass that leaves promoted blocks out + promoted-block pass on
-// the FP16 keys -> adaptive_reduce_kernel.
+// Sequence on one stream (launch_adaptive): scoring pass (the certified decode kernel in a form that
+// only reads keys and emits the INT8 block log-masses) -> select_kernel (per head) ->
+// compact_kernel (per group: union bit mask -> slot map and ordered list) -> attend pass =
+// matrix-core split pass that leaves promoted blocks out + promoted-block pass, which reads the
+// FP16 keys of the listed blocks straight from the pinned Tier-2 originals over the host link ->
+// adaptive_reduce_kernel.
 #include <algorithm>
 
 #include "cqa_internal.h"
@@ -374,28 +374,6 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   if (tid == 0) a.ucount[grp] = min(s_base, MAX_UNION);
 }
 
-struct GatherArgs {
-  const __half* t2_k;     // pinned host originals of the layer: [Bt * Hkv][max_tokens][128]
-  int64_t max_tokens;
-  const int32_t* ulist;
-  const int32_t* ucount;
-  __half* kscratch;
-  int nb;
-};
-
-// One workgroup per (list position, KV group): 4 KB of FP16 keys from the host-resident originals
-// into the scratch, 16 bytes per thread.  Positions past the group's count exit at once.
-__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
-  const int pos = blockIdx.x;
-  const int64_t grp = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
-  if (pos >= a.ucount[grp]) return;
-  const int blk = a.ulist[grp * MAX_UNION + pos];
-  if (blk < 0 || blk >= a.nb) return;
-  const uint4* src = reinterpret_cast<const uint4*>(a.t2_k + (grp * a.max_tokens + (int64_t)blk * BLK) * D);
-  uint4* dst = reinterpret_cast<uint4*>(a.kscratch + (grp * MAX_UNION + pos) * BLK * D);
-  dst[threadIdx.x] = src[threadIdx.x];
-}
-
 struct AdaptiveReduceArgs {
   ReduceArgs ra;
   const float* lm8;      // [Bt][Hq][nb]
@@ -555,7 +533,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   hipLaunchKernelGGL(select_kernel, dim3(hq, bt), dim3(ST), 0, st, sa);
   CQA_HIP(hipGetLastError());
 
-  // ---- 3. slot map and ordered list per group; FP16 keys of the listed blocks into the scratch
+  // ---- 3. slot map and ordered list per group
   CompactArgs ca;
   ca.umask = w.umask;
   ca.mask_words = w.mask_words;
@@ -568,19 +546,6 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   CQA_HIP(hipGetLastError());
 
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
-  GatherArgs ga;
-  ga.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
-  ga.max_tokens = c->desc.max_tokens;
-  ga.ulist = w.ulist;
-  ga.ucount = w.ucount;
-  ga.kscratch = w.kscratch;
-  ga.nb = (int)nb;
-  const int max_union = (int)std::min<int64_t>(std::min<int64_t>(MAX_UNION, nb),
-                                               (int64_t)g * std::max(sel.k_limit, sel.k_max));
-  if (max_union > 0) {
-    hipLaunchKernelGGL(gather_kernel, dim3(max_union, hkv, bt), dim3(256), 0, st, ga);
-    CQA_HIP(hipGetLastError());
-  }
 
   // ---- 4. attend pass: matrix-core pass without the promoted blocks + promoted-block pass
   int nsplit = 0, bps = 0;
@@ -619,7 +584,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.slot = w.slot;
   a.ulist = w.ulist;
   a.ucount = w.ucount;
-  a.kscratch = w.kscratch;
+  a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
+  a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
   a.score_only = 0;
   rc = launch_split_mfma(a, ra, nullptr, g, dim3(nsplit, hkv, bt), nullptr, nullptr, st);

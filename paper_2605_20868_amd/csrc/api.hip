@@ -34,7 +34,7 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 
 struct Sizes {
   int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select;
-  int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist, ad_scratch;
+  int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist;
   int max_splits;
 };
 
@@ -57,7 +57,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
   s.select = (int64_t)d->batch * d->n_q_heads * 4;
   // adaptive key precision (needs the originals): log-masses of two passes, selections, masks,
-  // slot maps, lists and the FP16-key scratch, for one layer-step at a time
+  // slot maps and lists, for one layer-step at a time
   const bool ad = d->tier2_mode == CQA_TIER2_PINNED;
   const int64_t rows = (int64_t)d->batch * d->n_q_heads, groups = (int64_t)d->batch * d->n_kv_heads;
   s.ad_lm = ad ? rows * s.nb_cap * 4 : 0;
@@ -68,7 +68,6 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.ad_slot = ad ? groups * s.nq_cap * 4 * 4 : 0;
   s.ad_group = ad ? groups * 4 : 0;
   s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
-  s.ad_scratch = ad ? groups * MAX_UNION * BLK * D * 2 : 0;
   return s;
 }
 
@@ -94,7 +93,6 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.slot);
   (void)hipFree(c->ad.ucount);
   (void)hipFree(c->ad.ulist);
-  (void)hipFree(c->ad.kscratch);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
   if (c->t2_k) (void)hipHostFree(c->t2_k);
@@ -182,7 +180,7 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   if (device_bytes)
     *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
                     2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
-                    s.ad_ulist + s.ad_scratch;
+                    s.ad_ulist;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
 }
@@ -234,7 +232,6 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_ALLOC_DEV(c->ad.slot, s.ad_slot);
     CQA_ALLOC_DEV(c->ad.ucount, s.ad_group);
     CQA_ALLOC_DEV(c->ad.ulist, s.ad_ulist);
-    CQA_ALLOC_DEV(c->ad.kscratch, s.ad_scratch);
     c->ad.mask_words = s.ad_mask_words;
     CQA_TRY(hipMemset(c->ad.umask, 0, (size_t)s.ad_mask));       // the selector ORs into it
     CQA_TRY(hipMemset(c->ad.slot, 0xFF, (size_t)s.ad_slot));     // -1: no block is promoted

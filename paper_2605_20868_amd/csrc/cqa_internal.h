@@ -103,7 +103,6 @@ struct AdaptiveWs {
   int32_t* slot;     // [Bt][Hkv][4 nq_cap]   scratch slot of a promoted block, -1 otherwise
   int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
   int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
-  __half* kscratch;  // [Bt][Hkv][MAX_UNION][16][128]  FP16 keys of the promoted blocks
   int64_t mask_words;
 };
 
@@ -166,7 +165,8 @@ struct DecodeArgs {
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: scratch slot of a promoted block, -1 otherwise
   const int32_t* ulist;     // [Bt][Hkv][MAX_UNION]: promoted blocks of the group, ascending
   const int32_t* ucount;    // [Bt][Hkv]
-  const __half* kscratch;   // [Bt][Hkv][MAX_UNION][16][128]
+  const __half* t2_k;       // pinned FP16 key originals of the layer: [Bt * Hkv][max_tokens][128]
+  int64_t max_tokens;
   int split0;               // promoted-block pass: index of its first partial set
   int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
 };

@@ -41,7 +41,8 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
 // PROM = false: the vector-ALU split pass over a contiguous range of sealed blocks (INT8 keys).
 // PROM = true : the promoted-block pass of the attend pass with gated key precision: the
 //               workgroups of a KV group walk the group's list of promoted blocks, score them
-//               from the FP16 keys gathered into the scratch (sigma = 1, z = 0, no score error),
+//               from their FP16 keys, which the device reads straight from the pinned Tier-2
+//               originals over the host link (sigma = 1, z = 0, no score error),
 //               attend their INT4 values as usual, and write partial sets split0 + blockIdx.x.
 template <int G, bool PROM>
 __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
@@ -124,8 +125,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
     if (PROM) {
-      // FP16 keys of the block: scratch slot = position in the list, [16 tokens][128 channels]
-      const __half* kf16 = a.kscratch + ((grp * MAX_UNION + pos) * BLK + tok) * D;
+      // FP16 keys of the block in the host-resident originals: [token][128 channels]
+      const __half* kf16 = a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
         const int c0 = cq * 64 + kg * 16;
@@ -327,7 +328,7 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
 
 // Promoted-block pass of the attend pass with gated key precision (see certified_split_kernel).
 int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
-  if (a.ulist == nullptr || a.ucount == nullptr || a.kscratch == nullptr) return CQA_ERR_INVALID_ARG;
+  if (a.ulist == nullptr || a.ucount == nullptr || a.t2_k == nullptr) return CQA_ERR_INVALID_ARG;
   switch (group) {
     case 1: hipLaunchKernelGGL((certified_split_kernel<1, true>), grid, dim3(256), 0, st, a); break;
     case 2: hipLaunchKernelGGL((certified_split_kernel<2, true>), grid, dim3(256), 0, st, a); break;
@@ -379,7 +380,8 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.slot = nullptr;
     a.ulist = nullptr;
     a.ucount = nullptr;
-    a.kscratch = nullptr;
+    a.t2_k = nullptr;
+    a.max_tokens = 0;
     a.split0 = 0;
     a.score_only = (score_only && c->variant == 0 && blk_logmass != nullptr) ? 1 : 0;
     a.bps = bps;
