@@ -26,6 +26,16 @@ Readings where the paper is silent or offers a choice (the HIP path follows the 
   alpha_hat_T; the bound stays valid.
 * Delta in the bound is Delta_h of the scoring pass (maximum over all sealed
   blocks): the global-max-shift factor of the mass theorem ranges over all blocks.
+* Value promotion (the ladder's second rung) is decided from the scoring pass too: a block's
+  estimated contribution is c_b = p_b^int8 * eta_b.  Default policy: promote every block with
+  c_b > v_tol.  Hard-budget variant (v_greedy): additionally promote blocks in descending c_b
+  (ties: lower index) until the estimated value term left, sum of the unpromoted c_b, is at
+  most eps_val.  Both are prefixes of the same ordering, so the head's selection is the longer
+  of the two, capped at v_limit.  Like keys, values are promoted per KV group (union of the
+  group's heads' selections).  A promoted block is attended with its FP16 values and enters
+  E_val and max_b rho_b eta_b with eta_b = 0; E_val is the achieved one (attend-pass masses).
+  Using the estimated masses for the greedy stop is this build's reading: the paper states the
+  stop on the achieved term, which is only known after the pass.
 * Ranking check at depth r = 1 over the promoted set F of the head's group:
   (i) the block with the largest FP16 log-mass in F must be the block with the
   largest INT8 log-mass in F; (ii) boundary: no unpromoted block may have
@@ -49,6 +59,8 @@ class SelectorParams:
     k_min: int = 2
     k_max: int = 128
     k_limit: int = 128          # cap for Rung-1 doubling (>= k_max)
+    v_limit: int = 0            # blocks one head may promote to FP16 values (0 = off)
+    v_greedy: bool = False      # hard-budget variant: also promote until the estimate fits eps_val
 
 
 def rank_blocks(logmass: np.ndarray) -> np.ndarray:
@@ -94,6 +106,33 @@ def rung1_expand(sel: dict, delta_h: float, v_max: float, tol: att.Tolerances,
     return k
 
 
+def value_contributions(logmass: np.ndarray, lse: float, eta: np.ndarray) -> np.ndarray:
+    """Estimated contribution of each block to the value term: c_b = p_b^int8 * eta_b."""
+    return np.exp(np.asarray(logmass, dtype=np.float64) - lse) * np.asarray(eta, dtype=np.float64)
+
+
+def select_value_blocks_from(contrib: np.ndarray, tol: att.Tolerances, par: SelectorParams) -> np.ndarray:
+    """The head's blocks to promote to FP16 values, in descending estimated contribution."""
+    c = np.asarray(contrib, dtype=np.float64)
+    nb = c.shape[0]
+    if par.v_limit <= 0 or nb == 0:
+        return np.zeros(0, dtype=np.int64)
+    order = np.argsort(-c, kind="stable")
+    cs = c[order]
+    k = int((cs > tol.v_tol).sum())                                 # local policy: a prefix
+    if par.v_greedy:
+        left = cs.sum() - np.concatenate([[0.0], np.cumsum(cs)])    # estimate left after k blocks
+        hit = np.nonzero(left <= tol.eps_val)[0]
+        k = max(k, int(hit[0]) if hit.size else nb)
+    k = min(k, par.v_limit, nb)
+    return order[:k]
+
+
+def select_value_blocks(logmass: np.ndarray, lse: float, eta: np.ndarray, tol: att.Tolerances,
+                        par: SelectorParams) -> np.ndarray:
+    return select_value_blocks_from(value_contributions(logmass, lse, eta), tol, par)
+
+
 def group_union(selections, nb: int) -> np.ndarray:
     """Boolean mask [NB]: union of the heads' promoted sets (each an index array)."""
     mask = np.zeros(nb, dtype=bool)
@@ -124,13 +163,15 @@ def ranking_check(l_int8: np.ndarray, l_fp16: np.ndarray, promoted: np.ndarray, 
 def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat: np.ndarray,
                eta: np.ndarray, nu: np.ndarray, k_trail16: np.ndarray, v_trail16: np.ndarray,
                promoted: np.ndarray, l_int8: np.ndarray, lse_int8: float, delta_h: float,
-               tol: att.Tolerances) -> dict:
+               tol: att.Tolerances, v_promoted: np.ndarray | None = None,
+               v16_sealed: np.ndarray | None = None) -> dict:
     """The attend pass with mask-gated key precision, one head, one step.
 
     k_hat float64 [NB*B, d] INT8 reconstructions; k16_sealed float16 [NB*B, d] the FP16
     originals of the same tokens; promoted bool [NB]; l_int8, lse_int8, delta_h: the scoring
     pass's block log-masses, total log-mass and Delta_h for this head.
-    Values are INT4 reconstructions for every sealed block.
+    Values are INT4 reconstructions, except in the blocks of v_promoted (bool [NB], optional),
+    which use the FP16 originals v16_sealed [NB*B, d] and count with eta_b = 0.
     """
     q = q16.astype(np.float64)
     d = q.shape[0]
@@ -150,14 +191,20 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     z_sum = e.sum()
     a = e / z_sum
     lse = m + math.log(z_sum)
-    v_all = np.concatenate([v_hat, vt]) if r else v_hat
+    eta_eff = eta.astype(np.float64)
+    v_seal = v_hat
+    if v_promoted is not None and np.asarray(v_promoted, dtype=bool).any():
+        vp = np.asarray(v_promoted, dtype=bool)
+        v_seal = np.where(np.repeat(vp, blk)[:, None], v16_sealed.astype(np.float64), v_hat)
+        eta_eff = np.where(vp, 0.0, eta_eff)
+    v_all = np.concatenate([v_seal, vt]) if r else v_seal
     o = a @ v_all
 
     sb = s_seal.reshape(nb, blk)
     m_b = sb.max(axis=1)
     l_b = m_b + np.log(np.exp(sb - m_b[:, None]).sum(axis=1))
     rho = np.exp(l_b - lse)
-    contrib = rho * eta.astype(np.float64)
+    contrib = rho * eta_eff
     e_val = float(contrib.sum())
     max_contrib = float(contrib.max())
     v_max = float(nu.max())
@@ -210,7 +257,7 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
         v_hat = qz.dequantize_values(cache.v_codes[b, kh], cache.v_scale[b, kh],
                                      cache.v_offset[b, kh]).reshape(nb * qz.B, d)
         k_tr, v_tr = cache.k16[b, kh, nb * qz.B:], cache.v16[b, kh, nb * qz.B:]
-        scoring, picks, ks = [], [], []
+        scoring, picks, ks, vpicks = [], [], [], []
         for i in range(g):
             h = kh * g + i
             sc = att.certified_head(q16[b, h], k_hat, v_hat, cache.sigma[b, kh], cache.eta[b, kh],
@@ -220,13 +267,17 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
             scoring.append(sc)
             picks.append(sel["order"][:k])
             ks.append(k)
+            vpicks.append(select_value_blocks(sc["blk_logmass"], sc["lse"], cache.eta[b, kh], tol, par))
         union = group_union(picks, nb)
+        vunion = group_union(vpicks, nb)
         for i in range(g):
             h = kh * g + i
             sc = scoring[i]
             res = mixed_head(q16[b, h], k_hat, cache.k16[b, kh, :nb * qz.B], v_hat, cache.eta[b, kh],
                              cache.nu[b, kh], k_tr, v_tr, union, sc["blk_logmass"], sc["lse"],
-                             sc["delta_h"], tol)
-            res.update(k_star=ks[i], selected=picks[i], promoted=union, scoring=sc)
+                             sc["delta_h"], tol, v_promoted=vunion,
+                             v16_sealed=cache.v16[b, kh, :nb * qz.B])
+            res.update(k_star=ks[i], selected=picks[i], promoted=union, scoring=sc,
+                       v_selected=vpicks[i], v_promoted=vunion)
             out[(b, h)] = res
     return out

@@ -216,3 +216,84 @@ def test_boundary_check_is_sound():
             l_true = sb.max(axis=1) + np.log(np.exp(sb - sb.max(axis=1, keepdims=True)).sum(axis=1))
             assert int(np.argmax(l_true)) == r["ranking"]["top_fp16"]
     assert hits > 0
+
+
+# ---------------------------------------------------------------- value promotion (second rung)
+
+def test_value_selection_policies():
+    """Threshold policy = every block whose estimated contribution exceeds v_tol; greedy policy = the
+    smallest prefix (largest contributions first) that brings the estimated value term under the
+    budget: checked against brute force over all prefixes."""
+    rng = np.random.Generator(np.random.Philox(300))
+    nb = 30
+    logits = rng.standard_normal(nb) * 2.0
+    p = np.exp(logits) / np.exp(logits).sum() * 0.9
+    lse = 0.7
+    l = np.log(p) + lse
+    eta = rng.uniform(0.1, 1.0, nb).astype(np.float32)
+    c = p * eta.astype(np.float64)
+    order = sorted(range(nb), key=lambda i: (-c[i], i))
+    for v_tol in (0.01, 0.03, math.inf):
+        got = ad.select_value_blocks(l, lse, eta, att.Tolerances(v_tol=v_tol),
+                                     ad.SelectorParams(v_limit=nb))
+        want = [i for i in order if c[i] > v_tol]
+        assert got.tolist() == want
+    for budget in (0.05, 0.2, c.sum() * 1.01):
+        got = ad.select_value_blocks(l, lse, eta, att.Tolerances(eps_val=budget),
+                                     ad.SelectorParams(v_limit=nb, v_greedy=True))
+        k = next(k for k in range(nb + 1) if sum(c[i] for i in order[k:]) <= budget)
+        assert got.tolist() == order[:k]
+        assert c.sum() - c[got].sum() <= budget + 1e-15
+    capped = ad.select_value_blocks(l, lse, eta, att.Tolerances(eps_val=0.0),
+                                    ad.SelectorParams(v_limit=5, v_greedy=True))
+    assert capped.tolist() == order[:5]
+    assert ad.select_value_blocks(l, lse, eta, att.Tolerances(v_tol=0.0), ad.SelectorParams()).size == 0
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_value_promotion_special_cases_and_bound(seed):
+    oc, q = small_cache(400 + seed)
+    nb = oc.n_blocks
+    k_hat = qz.dequantize_keys(oc.k_codes[0, 0], oc.sigma[0, 0], oc.z[0, 0]).reshape(nb * 16, 128)
+    v_hat = qz.dequantize_values(oc.v_codes[0, 0], oc.v_scale[0, 0], oc.v_offset[0, 0]).reshape(nb * 16, 128)
+    k_tr, v_tr = oc.k16[0, 0, nb * 16:], oc.v16[0, 0, nb * 16:]
+    tol = att.Tolerances()
+    sc = att.certified_head(q[0, 0], k_hat, v_hat, oc.sigma[0, 0], oc.eta[0, 0], oc.nu[0, 0], k_tr, v_tr, tol)
+    args = (q[0, 0], k_hat, oc.k16[0, 0, :nb * 16], v_hat, oc.eta[0, 0], oc.nu[0, 0], k_tr, v_tr)
+    tail = (sc["blk_logmass"], sc["lse"], sc["delta_h"], tol)
+    v16 = oc.v16[0, 0, :nb * 16]
+    # every value promoted, no key promoted: attention over the INT8-reconstructed keys and the FP16
+    # values; the value term vanishes
+    allv = ad.mixed_head(*args, np.zeros(nb, bool), *tail, v_promoted=np.ones(nb, bool), v16_sealed=v16)
+    ref = att.softmax_attention(q[0, 0], np.concatenate([k_hat, k_tr.astype(np.float64)]), oc.v16[0, 0])
+    assert np.allclose(allv["O"], ref, rtol=0, atol=1e-13)
+    assert allv["E_val"] == 0.0 and allv["max_block_contrib"] == 0.0
+    # keys and values all promoted: the dense FP16 reference itself
+    both = ad.mixed_head(*args, np.ones(nb, bool), *tail, v_promoted=np.ones(nb, bool), v16_sealed=v16)
+    dense = att.softmax_attention(q[0, 0], oc.k16[0, 0], oc.v16[0, 0])
+    assert np.allclose(both["O"], dense, rtol=0, atol=1e-13) and both["E_key"] == 0.0 and both["E_val"] == 0.0
+    # a partial promotion: E_val drops by exactly the promoted blocks' share, and still bounds the
+    # value-side error against the same attention weights applied to the FP16 values
+    vp = np.zeros(nb, bool)
+    vp[np.argsort(-sc["blk_logmass"])[:4]] = True
+    part = ad.mixed_head(*args, np.zeros(nb, bool), *tail, v_promoted=vp, v16_sealed=v16)
+    rho = np.exp(part["blk_logmass"] - part["lse"])
+    assert part["E_val"] == pytest.approx(float((rho * oc.eta[0, 0])[~vp].sum()), rel=1e-12)
+    assert part["E_val"] < sc["E_val"]
+    o_fp16v = part["weights"] @ oc.v16[0, 0].astype(np.float64)
+    assert np.linalg.norm(part["O"] - o_fp16v) <= part["E_val"] * (1 + 1e-9) + 1e-12
+
+
+def test_greedy_budget_is_met_in_the_attend_pass_when_nothing_is_capped():
+    """With FP16 keys nowhere (masses unchanged between the passes) the achieved value term equals
+    the estimate the greedy rule stopped on, so it is under the budget."""
+    oc, q = small_cache(500, n_tokens=1024 + 3)
+    tol = att.Tolerances(eps_val=0.3)
+    par = ad.SelectorParams(tau_cov=0.0, k_min=0, k_max=0, k_limit=0, v_limit=512, v_greedy=True)
+    res = ad.adaptive_decode(oc, q, tol, par)
+    for h in range(4):
+        r = res[(0, h)]
+        assert not r["promoted"].any()
+        assert r["E_val"] <= 0.3 * (1 + 1e-9)
+        assert not (r["flags"] & att.FLAG_VAL)
+        assert r["E_val"] < r["scoring"]["E_val"]
