@@ -386,7 +386,8 @@ def main() -> int:
             rungs.append(cqa.cqa_adaptive_step(h, 0, qp + (W + i) * q_stride, atol, sel, Op, certp, flagsp, stream))
         torch.cuda.synchronize()
         ad_ms = (time.perf_counter() - ta0) * 1e3 / n_ad
-        kst, _, prom, _, _ = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
+        kst, _, prom, *_ = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
+        prom = prom & 1
         ad_info = {"ms_per_step": ad_ms, "steps_with_fallback": int(sum(1 for r in rungs if r)),
                    "k_star_median": float(np.median(kst)), "k_star_max": int(kst.max()),
                    "promoted_blocks_per_group_max": int(prom.sum(axis=2).max()),

@@ -207,7 +207,12 @@ typedef struct cqa_selector {
   float tau_cov;   /* coverage threshold on INT8-estimated mass (paper: 0.995)       */
   int32_t k_min;   /* K* is clamped to [k_min, k_max] and to the sealed blocks       */
   int32_t k_max;   /* 0 <= k_min <= k_max <= k_limit <= 512                          */
-  int32_t k_limit; /* cap of the Rung-1 doubling (scratch capacity per head)         */
+  int32_t k_limit; /* cap of the Rung-1 doubling                                     */
+  int32_t v_limit; /* blocks one head may promote to FP16 VALUES (Rung 2); 0 = off,  */
+                   /* at most 512                                                    */
+  int32_t v_greedy;/* 0: promote blocks whose estimated contribution p_b eta_b       */
+                   /* exceeds tol->v_tol; 1: also keep promoting, largest first,     */
+                   /* until the estimated value term left is <= tol->eps_val         */
 } cqa_selector;
 
 /* One decode step of `layer` with mask-gated key precision, all on `stream`:
@@ -218,11 +223,14 @@ typedef struct cqa_selector {
  *     of the estimated mass, clamped; Rung 1: K doubles (up to k_limit) while
  *     the key term of the achieved tail exceeds tol->eps_key;
  *  3. the promoted set of a (batch, kv-head) group is the union of its heads'
- *     selections;
+ *     selections; value promotion (the ladder's second rung, sel->v_limit > 0)
+ *     is decided the same way from the estimated contributions p_b eta_b and
+ *     is likewise per group;
  *  4. attend pass: as cqa_certified_decode, but promoted blocks are scored
  *     with their FP16 keys, which the device reads straight from the pinned
- *     Tier-2 originals (no host step, no staging); values stay INT4; E_val
- *     uses the masses of this pass;
+ *     Tier-2 originals (no host step, no staging); values are INT4 except
+ *     in value-promoted blocks, which are attended from their FP16 originals
+ *     and count with eta_b = 0; E_val uses the masses of this pass;
  *     E_key uses alpha_hat_T = the scoring pass's estimated mass of the blocks
  *     the group left in INT8, and the scoring pass's Delta_h;
  *  5. ranking check at depth 1 (if tol->rank_depth >= 1): RANK is set when the
@@ -249,13 +257,18 @@ int32_t cqa_adaptive_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
 /* Test hook: what the last adaptive decode decided, copied to the host after a
  * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
  * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*
- * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (1 = the
- * group scored this block with FP16 keys); logmass_int8_host / logmass_mixed_host
- * float [batch][n_q_heads][n_blocks] (block log-masses of the two passes).
+ * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (bit 0 = the
+ * group scored this block with FP16 keys, bit 1 = it attended its FP16 values);
+ * logmass_int8_host / logmass_mixed_host float [batch][n_q_heads][n_blocks] (block
+ * log-masses of the two passes); v_count_host int32 [batch][n_q_heads] and
+ * v_selected_host int32 [batch][n_q_heads][512] (the head's value selection, largest
+ * contribution first); contrib_host float [batch][n_q_heads][n_blocks] (the estimated
+ * contributions p_b eta_b the value selection ranked; valid when v_limit > 0).
  * Any pointer may be NULL.  n_blocks = sealed blocks of `layer`. */
 int32_t cqa_adaptive_state(cqa_cache* c, int32_t layer, int32_t* k_star_host,
                            int32_t* selected_host, uint8_t* promoted_host,
-                           float* logmass_int8_host, float* logmass_mixed_host);
+                           float* logmass_int8_host, float* logmass_mixed_host,
+                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host);
 
 /* Dense FP16 decode attention on device-resident K, V (the same kernel the
  * fallback runs after paging): softmax(q K^T / sqrt(128)) V with FP32

@@ -33,11 +33,13 @@ __device__ __forceinline__ uint32_t ord32(float f) {
 }
 
 struct SelectArgs {
-  const float* lm8;            // [Bt][Hq][nb]
+  const float* lm8;            // [Bt][Hq][nb]: the row that is ranked (log-masses, or contributions)
   const cqa_head_cert* cert;   // scoring pass: lse, delta_h, v_max
   int32_t* sel;                // [Bt][Hq][MAX_K_LIMIT]
   int32_t* kstar;              // [Bt][Hq]
   uint32_t* umask;             // [Bt][Hkv][mask_words]
+  float v_tol, eps_val;        // value selection: local threshold and budget
+  int v_greedy;
   int64_t mask_words;
   int nb, n_q, n_kv;
   float tau_cov;
@@ -135,8 +137,14 @@ __device__ __forceinline__ T block_scan_incl(T v, T* tot, int tid) {
 }
 
 // One workgroup per (batch, query head).  Finds the KL = min(k_limit, nb) best blocks under the
-// total order (larger log-mass first, equal log-masses: lower index first) by radix selection
-// over the row, ranks them, and takes the covering prefix.
+// total order (larger value first, equal values: lower index first) by radix selection over the
+// row, ranks them, and takes a prefix.
+//   VALUES = false: the row holds INT8 block log-masses; the prefix is the smallest one whose
+//                   estimated masses cover tau_cov, clamped, then grown by Rung 1.
+//   VALUES = true : the row holds estimated contributions c_b = p_b eta_b (second rung of the
+//                   ladder); the prefix is every block with c_b > v_tol and, in the hard-budget
+//                   variant, as many more as bring the estimate left under eps_val; cap k_limit.
+template <bool VALUES>
 __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   const int tid = threadIdx.x;
   const int hq = blockIdx.x, b = blockIdx.y;
@@ -189,7 +197,7 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
       CQA_ROW_PASS(lm, nb, tid, {
         const uint32_t k = ord32(x);
         if (in) {
-          part += (double)__expf(x - lse_f);
+          part += VALUES ? (double)x : (double)__expf(x - lse_f);
           if (cached) keys[i] = k;
         }
         hist_add(hist, k >> 24, in);
@@ -271,35 +279,60 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   __syncthreads();
   CQA_STAMP(3)
   // ---- masses of the winners, best first, and their inclusive prefix sums: thread t owns place t
-  const double m0 = tid < n ? exp((double)lm[sorted_idx[tid]] - lse) : 0.0;
+  const double m0 = tid < n ? (VALUES ? (double)lm[sorted_idx[tid]] : exp((double)lm[sorted_idx[tid]] - lse)) : 0.0;
   const double upto1 = block_scan_incl<double>(m0, dtot, tid);
   if (tid < MAX_K_LIMIT) pm[tid] = upto1;
   __syncthreads();
   CQA_STAMP(4)
-  // ---- covering prefix: C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so the
-  //      search stops there; then clamps and Rung-1 growth
-  const double rho_trail = 1.0 - total;
-  const int look = min(n, a.k_max);
-  for (int kk = tid; kk <= look; kk += ST) {
-    const double covered = rho_trail + (kk > 0 ? pm[kk - 1] : 0.0);
-    if (covered >= (double)a.tau_cov) atomicMin(&s_first, kk);
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int k = s_first <= look ? s_first : nb;             // no prefix up to k_max covers tau_cov
-    k = max(a.k_min, min(k, a.k_max));
-    k = min(k, nb);
-    k = min(k, n);
-    // Rung 1
-    const double delta = (double)a.cert[row].delta_h, vmax = (double)a.cert[row].v_max;
-    const int cap = min(max(a.k_limit, a.k_max), n);
-    while (k < cap) {
-      const double tail = total - (k > 0 ? pm[k - 1] : 0.0);
-      if (!(key_term_d(delta, tail, vmax, a.mass_exp, a.key_bound_mode) > (double)a.eps_key)) break;
-      k = min(max(2 * k, 1), cap);
+  if (!VALUES) {
+    // ---- covering prefix: C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so
+    //      the search stops there; then clamps and Rung-1 growth
+    const double rho_trail = 1.0 - total;
+    const int look = min(n, a.k_max);
+    for (int kk = tid; kk <= look; kk += ST) {
+      const double covered = rho_trail + (kk > 0 ? pm[kk - 1] : 0.0);
+      if (covered >= (double)a.tau_cov) atomicMin(&s_first, kk);
     }
-    s_k = k;
-    a.kstar[row] = k;
+    __syncthreads();
+    if (tid == 0) {
+      int k = s_first <= look ? s_first : nb;             // no prefix up to k_max covers tau_cov
+      k = max(a.k_min, min(k, a.k_max));
+      k = min(k, nb);
+      k = min(k, n);
+      // Rung 1
+      const double delta = (double)a.cert[row].delta_h, vmax = (double)a.cert[row].v_max;
+      const int cap = min(max(a.k_limit, a.k_max), n);
+      while (k < cap) {
+        const double tail = total - (k > 0 ? pm[k - 1] : 0.0);
+        if (!(key_term_d(delta, tail, vmax, a.mass_exp, a.key_bound_mode) > (double)a.eps_key)) break;
+        k = min(max(2 * k, 1), cap);
+      }
+      s_k = k;
+      a.kstar[row] = k;
+    }
+  } else {
+    // ---- value selection: the blocks over the local threshold form a prefix of the ranking
+    //      (count them), the hard-budget rule asks for the smallest prefix that leaves at most
+    //      eps_val of the estimate; the longer of the two, capped
+    __shared__ int s_over;
+    if (tid == 0) s_over = 0;
+    __syncthreads();
+    for (int kk = tid; kk < n; kk += ST)
+      if (lm[sorted_idx[kk]] > a.v_tol) atomicAdd(&s_over, 1);
+    if (a.v_greedy) {
+      for (int kk = tid; kk <= n; kk += ST) {
+        const double left = total - (kk > 0 ? pm[kk - 1] : 0.0);
+        if (left <= (double)a.eps_val) atomicMin(&s_first, kk);
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int k = s_over;
+      if (a.v_greedy) k = max(k, s_first <= n ? s_first : nb);
+      k = min(k, min(n, nb));
+      s_k = k;
+      a.kstar[row] = k;
+    }
   }
   __syncthreads();
   CQA_STAMP(5)
@@ -312,7 +345,21 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   }
 }
 
+// Estimated contribution of every block to a head's value term: c_b = exp(l_b - lse) eta_b
+// (the paper's rho_hat_b eta_b of its value-promotion rule), one thread per (head, block).
+__global__ __launch_bounds__(256) void contrib_kernel(const float* lm8, const float* eta_blk,
+                                                      const cqa_head_cert* cert, float* contrib,
+                                                      int nb, int n_q, int n_kv) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int hq = blockIdx.y, b = blockIdx.z;
+  if (i >= nb) return;
+  const int64_t row = (int64_t)b * n_q + hq;
+  const int64_t grp = (int64_t)b * n_kv + hq / (n_q / n_kv);
+  contrib[row * nb + i] = __expf(lm8[row * nb + i] - cert[row].lse) * eta_blk[grp * nb + i];
+}
+
 struct CompactArgs {
+  uint32_t* vmask;     // [Bt][Hkv][mask_words] value selections (null = none); cleared likewise
   uint32_t* umask;     // [Bt][Hkv][mask_words]; cleared on the way out
   int64_t mask_words;
   int32_t* slot;       // [Bt][Hkv][slot_stride]
@@ -322,12 +369,14 @@ struct CompactArgs {
   int nb;
 };
 
-// One workgroup per KV group: bit mask -> slot of every block (position among the promoted
-// blocks in ascending order, -1 for the others) and the ordered list.  Clears the mask.
+// One workgroup per KV group: the two bit masks (FP16 keys, FP16 values) -> per-block flags
+// (bit 0 keys, bit 1 values, 0 = neither) and the ascending list of blocks with any flag.
+// Clears the masks.
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   const int tid = threadIdx.x;
   const int64_t grp = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
   uint32_t* um = a.umask + grp * a.mask_words;
+  uint32_t* vm = a.vmask != nullptr ? a.vmask + grp * a.mask_words : nullptr;
   int32_t* slot = a.slot + grp * a.slot_stride;
   int32_t* ulist = a.ulist + grp * MAX_UNION;
   const int words = (a.nb + 31) >> 5;
@@ -337,12 +386,20 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   __syncthreads();
   for (int w0 = 0; w0 < words; w0 += 256) {
     const int w = w0 + tid;
-    uint32_t bits = 0u;
+    uint32_t kbits = 0u, vbits = 0u;
     if (w < words) {
-      bits = um[w];
+      kbits = um[w];
       um[w] = 0u;
-      if (w == words - 1 && (a.nb & 31)) bits &= (1u << (a.nb & 31)) - 1u;   // nothing past nb
+      if (vm != nullptr) {
+        vbits = vm[w];
+        vm[w] = 0u;
+      }
+      if (w == words - 1 && (a.nb & 31)) {      // nothing past nb
+        kbits &= (1u << (a.nb & 31)) - 1u;
+        vbits &= (1u << (a.nb & 31)) - 1u;
+      }
     }
+    const uint32_t bits = kbits | vbits;
     const int cnt = __popc(bits);
     scan[tid] = cnt;
     __syncthreads();
@@ -358,12 +415,14 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
         const int blk = w * 32 + j;
         if (blk >= a.nb) break;
         if ((bits >> j) & 1u) {
-          const int sidx = pos < MAX_UNION ? pos : -1;   // cannot overflow: 4 heads x MAX_K_LIMIT
-          slot[blk] = sidx;
-          if (sidx >= 0) ulist[sidx] = blk;
+          // the list cannot overflow (4 heads x MAX_K_LIMIT for keys and as many for values);
+          // a block that did not fit would simply stay unpromoted
+          const bool fits = pos < MAX_UNION;
+          slot[blk] = fits ? (int)(((kbits >> j) & 1u) | (((vbits >> j) & 1u) << 1)) : 0;
+          if (fits) ulist[pos] = blk;
           ++pos;
         } else {
-          slot[blk] = -1;
+          slot[blk] = 0;
         }
       }
     }
@@ -412,7 +471,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
       const int i = base + j * 256 + tid;
       const bool in = i < ra.nb;
       b8[j] = in ? l8[i] : 0.0f;
-      bs[j] = in ? slot[i] : -1;
+      bs[j] = in ? slot[i] : 0;
       bx[j] = in ? lx[i] : 0.0f;            // unpromoted blocks: the matrix-core pass's value, unused
     }
 #pragma unroll
@@ -420,7 +479,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
       const int i = base + j * 256 + tid;
       if (i >= ra.nb) continue;
       const float v8 = b8[j];
-      if (bs[j] >= 0) {
+      if (bs[j] & 1) {
         const float vx = bx[j];
         if (vx > best_x) {      // ascending scan per thread: strict > keeps the lowest index
           best_x = vx;
@@ -530,11 +589,32 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   sa.eps_key = tol.eps_key;
   sa.mass_exp = tol.mass_exp;
   sa.key_bound_mode = tol.key_bound_mode;
-  hipLaunchKernelGGL(select_kernel, dim3(hq, bt), dim3(ST), 0, st, sa);
+  sa.v_tol = tol.v_tol;
+  sa.eps_val = tol.eps_val;
+  sa.v_greedy = sel.v_greedy;
+  hipLaunchKernelGGL(select_kernel<false>, dim3(hq, bt), dim3(ST), 0, st, sa);
   CQA_HIP(hipGetLastError());
+  const bool values = sel.v_limit > 0;
+  if (values) {
+    // value promotion: rank the estimated contributions p_b eta_b
+    hipLaunchKernelGGL(contrib_kernel, dim3((unsigned)((nb + 255) / 256), hq, bt), dim3(256), 0, st,
+                       w.lm8, w.eta_blk, cert, w.contrib, (int)nb, hq, hkv);
+    CQA_HIP(hipGetLastError());
+    SelectArgs va = sa;
+    va.lm8 = w.contrib;
+    va.sel = w.vsel;
+    va.kstar = w.vcount;
+    va.umask = w.vmask;
+    va.k_min = 0;
+    va.k_max = sel.v_limit;
+    va.k_limit = sel.v_limit;
+    hipLaunchKernelGGL(select_kernel<true>, dim3(hq, bt), dim3(ST), 0, st, va);
+    CQA_HIP(hipGetLastError());
+  }
 
   // ---- 3. slot map and ordered list per group
   CompactArgs ca;
+  ca.vmask = values ? w.vmask : nullptr;
   ca.umask = w.umask;
   ca.mask_words = w.mask_words;
   ca.slot = w.slot;
@@ -585,6 +665,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.ulist = w.ulist;
   a.ucount = w.ucount;
   a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
+  a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
+  a.eta_out = nullptr;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
   a.score_only = 0;

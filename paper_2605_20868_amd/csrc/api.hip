@@ -34,7 +34,7 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 
 struct Sizes {
   int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select;
-  int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist;
+  int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist, ad_eta;
   int max_splits;
 };
 
@@ -68,6 +68,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.ad_slot = ad ? groups * s.nq_cap * 4 * 4 : 0;
   s.ad_group = ad ? groups * 4 : 0;
   s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
+  s.ad_eta = ad ? groups * s.nb_cap * 4 : 0;
   return s;
 }
 
@@ -93,6 +94,11 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.slot);
   (void)hipFree(c->ad.ucount);
   (void)hipFree(c->ad.ulist);
+  (void)hipFree(c->ad.vmask);
+  (void)hipFree(c->ad.eta_blk);
+  (void)hipFree(c->ad.contrib);
+  (void)hipFree(c->ad.vsel);
+  (void)hipFree(c->ad.vcount);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
   if (c->t2_k) (void)hipHostFree(c->t2_k);
@@ -180,7 +186,7 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   if (device_bytes)
     *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
                     2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
-                    s.ad_ulist;
+                    s.ad_ulist + s.ad_mask + s.ad_eta + s.ad_lm + s.ad_sel + s.ad_head;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
 }
@@ -232,9 +238,16 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_ALLOC_DEV(c->ad.slot, s.ad_slot);
     CQA_ALLOC_DEV(c->ad.ucount, s.ad_group);
     CQA_ALLOC_DEV(c->ad.ulist, s.ad_ulist);
+    CQA_ALLOC_DEV(c->ad.vmask, s.ad_mask);
+    CQA_ALLOC_DEV(c->ad.eta_blk, s.ad_eta);
+    CQA_ALLOC_DEV(c->ad.contrib, s.ad_lm);
+    CQA_ALLOC_DEV(c->ad.vsel, s.ad_sel);
+    CQA_ALLOC_DEV(c->ad.vcount, s.ad_head);
     c->ad.mask_words = s.ad_mask_words;
     CQA_TRY(hipMemset(c->ad.umask, 0, (size_t)s.ad_mask));       // the selector ORs into it
-    CQA_TRY(hipMemset(c->ad.slot, 0xFF, (size_t)s.ad_slot));     // -1: no block is promoted
+    CQA_TRY(hipMemset(c->ad.vmask, 0, (size_t)s.ad_mask));
+    CQA_TRY(hipMemset(c->ad.slot, 0, (size_t)s.ad_slot));        // 0: no block is promoted
+    CQA_TRY(hipMemset(c->ad.vcount, 0, (size_t)s.ad_head));
     CQA_TRY(hipMemset(c->ad.ucount, 0, (size_t)s.ad_group));
     CQA_TRY(hipMemset(c->ad.kstar, 0, (size_t)s.ad_head));
   }
@@ -608,7 +621,8 @@ static int32_t check_decode_args(cqa_cache* h, int32_t layer, const void* q, con
 
 static int32_t check_selector(const cqa_cache* h, const cqa_selector* sel) {
   if (sel == nullptr || !(sel->tau_cov == sel->tau_cov) || sel->k_min < 0 || sel->k_max < sel->k_min ||
-      sel->k_limit < sel->k_max || sel->k_limit > MAX_K_LIMIT)
+      sel->k_limit < sel->k_max || sel->k_limit > MAX_K_LIMIT || sel->v_limit < 0 ||
+      sel->v_limit > MAX_K_LIMIT || (sel->v_greedy != 0 && sel->v_greedy != 1))
     return CQA_ERR_INVALID_ARG;
   if (h->impl.desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
   return CQA_OK;
@@ -649,7 +663,8 @@ int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
 
 int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
                            int32_t* selected_host, uint8_t* promoted_host,
-                           float* logmass_int8_host, float* logmass_mixed_host) {
+                           float* logmass_int8_host, float* logmass_mixed_host,
+                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host) {
   if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers) return CQA_ERR_INVALID_ARG;
   Cache* c = &h->impl;
   if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
@@ -665,12 +680,18 @@ int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
     CQA_HIP(hipMemcpy(logmass_int8_host, c->ad.lm8, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
   if (logmass_mixed_host && nb > 0)
     CQA_HIP(hipMemcpy(logmass_mixed_host, c->ad.lmx, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+  if (v_count_host)
+    CQA_HIP(hipMemcpy(v_count_host, c->ad.vcount, (size_t)rows * 4, hipMemcpyDeviceToHost));
+  if (v_selected_host)
+    CQA_HIP(hipMemcpy(v_selected_host, c->ad.vsel, (size_t)rows * MAX_K_LIMIT * 4, hipMemcpyDeviceToHost));
+  if (contrib_host && nb > 0)
+    CQA_HIP(hipMemcpy(contrib_host, c->ad.contrib, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
   if (promoted_host && nb > 0) {
     std::vector<int32_t> slot((size_t)nb);
     for (int64_t gidx = 0; gidx < groups; ++gidx) {
       CQA_HIP(hipMemcpy(slot.data(), c->ad.slot + gidx * c->nq_cap * 4, (size_t)nb * 4,
                         hipMemcpyDeviceToHost));
-      for (int64_t i = 0; i < nb; ++i) promoted_host[gidx * nb + i] = slot[(size_t)i] >= 0 ? 1 : 0;
+      for (int64_t i = 0; i < nb; ++i) promoted_host[gidx * nb + i] = (uint8_t)(slot[(size_t)i] & 3);
     }
   }
   return CQA_OK;

@@ -89,7 +89,7 @@ constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-hea
 
 // ---- adaptive key precision ------------------------------------------------------
 constexpr int MAX_K_LIMIT = 512;            // blocks one head may promote (Rung-1 growth included)
-constexpr int MAX_UNION = 4 * MAX_K_LIMIT;  // blocks one KV group may promote (union of <= 4 heads)
+constexpr int MAX_UNION = 8 * MAX_K_LIMIT;  // blocks one KV group may promote (keys and values, <= 4 heads each)
 constexpr int PROM_SPLITS = 8;              // workgroups (= partial sets) of the promoted-block pass per KV group
 
 // Workspace of the adaptive path, shared by all layers (one decode step at a time).
@@ -99,8 +99,13 @@ struct AdaptiveWs {
   int32_t* sel;      // [Bt][Hq][MAX_K_LIMIT] the head's own selection, best first
   int32_t* kstar;    // [Bt][Hq]              its size after Rung-1 growth
   float* alpha;      // [Bt][Hq]              estimated mass of the blocks its group left in INT8
-  uint32_t* umask;   // [Bt][Hkv][mask_words] union of the group's selections, one bit per block
-  int32_t* slot;     // [Bt][Hkv][4 nq_cap]   scratch slot of a promoted block, -1 otherwise
+  uint32_t* umask;   // [Bt][Hkv][mask_words] union of the group's key selections, one bit per block
+  uint32_t* vmask;   // [Bt][Hkv][mask_words] union of its value selections
+  int32_t* slot;     // [Bt][Hkv][4 nq_cap]   per block: bit 0 = FP16 keys, bit 1 = FP16 values (0 = neither)
+  float* eta_blk;    // [Bt][Hkv][nb_cap]     eta_b as read by the scoring pass
+  float* contrib;    // [Bt][Hq][nb_cap]      estimated contributions p_b eta_b
+  int32_t* vsel;     // [Bt][Hq][MAX_K_LIMIT] the head's value selection
+  int32_t* vcount;   // [Bt][Hq]
   int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
   int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
   int64_t mask_words;
@@ -162,13 +167,15 @@ struct DecodeArgs {
   int debug;           // 0 in production; 1 = every load of a wave hits its first block (timing probe)
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
   // attend pass with gated key precision (null slot = every block uses its INT8 keys)
-  const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: scratch slot of a promoted block, -1 otherwise
+  const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
   const int32_t* ulist;     // [Bt][Hkv][MAX_UNION]: promoted blocks of the group, ascending
   const int32_t* ucount;    // [Bt][Hkv]
   const __half* t2_k;       // pinned FP16 key originals of the layer: [Bt * Hkv][max_tokens][128]
+  const __half* t2_v;       // value originals, same layout
   int64_t max_tokens;
   int split0;               // promoted-block pass: index of its first partial set
   int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
+  float* eta_out;           // scoring pass: eta_b per (batch, kv-head, block), or null
 };
 
 

@@ -39,11 +39,12 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
 }
 
 // PROM = false: the vector-ALU split pass over a contiguous range of sealed blocks (INT8 keys).
-// PROM = true : the promoted-block pass of the attend pass with gated key precision: the
-//               workgroups of a KV group walk the group's list of promoted blocks, score them
-//               from their FP16 keys, which the device reads straight from the pinned Tier-2
-//               originals over the host link (sigma = 1, z = 0, no score error),
-//               attend their INT4 values as usual, and write partial sets split0 + blockIdx.x.
+// PROM = true : the promoted-block pass of the attend pass with gated precision: the workgroups
+//               of a KV group walk the group's list of promoted blocks.  A key-promoted block is
+//               scored from its FP16 keys (sigma = 1, z = 0, no score error), a value-promoted
+//               block is attended from its FP16 values and counts with eta_b = 0; both kinds of
+//               originals are read by the device straight from the pinned Tier-2 arrays over the
+//               host link.  Writes partial sets split0 + blockIdx.x.
 template <int G, bool PROM>
 __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -63,6 +64,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   __shared__ __align__(16) float qs[4][G][D];     // scaled query of the block in flight, per wave
   __shared__ __align__(16) float ps[4][BLK][G];   // its probabilities
   __shared__ float ms[4][G][12];                  // per-wave scalars for the merge
+  // FP16 values of a value-promoted block, one buffer per wave (rows padded against bank conflicts)
+  __shared__ __align__(16) __half vst[PROM ? 4 : 1][PROM ? BLK : 1][PROM ? D + 8 : 8];
 
   float qv[G][2];
 #pragma unroll
@@ -95,19 +98,33 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     // every index is bounded on the way in: a list entry outside [0, nb) is skipped
     const int blk = PROM ? a.ulist[grp * MAX_UNION + pos] : pos;
     if (PROM && (blk < 0 || blk >= a.nb)) continue;
+    const int pf = PROM ? a.slot[grp * (a.nq_cap * 4) + blk] : 0;   // bit 0: FP16 keys, bit 1: FP16 values
+    const bool kfp = PROM && (pf & 1), vfp = PROM && (pf & 2);
     // ---- scaled query, per-block constant, per-block score-error bound
     const float* kmb = reinterpret_cast<const float*>(a.t1 + t1_offset(head_rec, blk, Q_KM, KM_BYTES));
-    const float2 sg = PROM ? make_float2(1.0f, 1.0f) : reinterpret_cast<const float2*>(kmb)[l];
-    const float2 zz = PROM ? make_float2(0.0f, 0.0f) : reinterpret_cast<const float2*>(kmb + D)[l];
-    const float2 an = *reinterpret_cast<const float2*>(a.t1 + t1_offset(head_rec, blk, Q_AN, AN_BYTES));
+    float2 sg = make_float2(1.0f, 1.0f), zz = make_float2(0.0f, 0.0f);
+    if (!kfp) {
+      sg = reinterpret_cast<const float2*>(kmb)[l];
+      zz = reinterpret_cast<const float2*>(kmb + D)[l];
+    }
+    float2 an = *reinterpret_cast<const float2*>(a.t1 + t1_offset(head_rec, blk, Q_AN, AN_BYTES));
+    if (vfp) {
+      an.x = 0.0f;     // exact values: the block adds nothing to the value term
+      // its FP16 values, row-major [token][128], coalesced into this wave's LDS buffer
+      const __half* v16 = a.t2_v + (grp * a.max_tokens + (int64_t)blk * BLK + (l >> 2)) * D + (l & 3) * 32;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) =
+            *reinterpret_cast<const uint4*>(v16 + j * 8);
+    }
     float csum[G], dsum[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       const float q0 = qv[h][0] * sg.x, q1 = qv[h][1] * sg.y;
       reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
       // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
-      csum[h] = PROM ? 0.0f : qv[h][0] * zz.x + qv[h][1] * zz.y - 128.0f * (q0 + q1);
-      dsum[h] = PROM ? 0.0f : fabsf(qv[h][0]) * sg.x + fabsf(qv[h][1]) * sg.y;
+      csum[h] = kfp ? 0.0f : qv[h][0] * zz.x + qv[h][1] * zz.y - 128.0f * (q0 + q1);
+      dsum[h] = kfp ? 0.0f : fabsf(qv[h][0]) * sg.x + fabsf(qv[h][1]) * sg.y;
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) {
@@ -124,7 +141,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     float dot[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
-    if (PROM) {
+    if (kfp) {
       // FP16 keys of the block in the host-resident originals: [token][128 channels]
       const __half* kf16 = a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
 #pragma unroll
@@ -217,7 +234,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       for (int i = 0; i < 8; ++i) {
         const float sc = (i & 1) ? __high2float(sh[i >> 1]) : __low2float(sh[i >> 1]);
         const float of = (i & 1) ? __high2float(oh[i >> 1]) : __low2float(oh[i >> 1]);
-        const float vh = fmaf((float)((vw[gq] >> (4 * i)) & 15u), sc, of);
+        const float vh = vfp ? __half2float(vst[w][vo * 8 + i][g * 16 + vn])
+                             : fmaf((float)((vw[gq] >> (4 * i)) & 15u), sc, of);
 #pragma unroll
         for (int h = 0; h < G; ++h) acc[gq][h] = fmaf(pi[i][h], vh, acc[gq][h]);
       }
@@ -328,7 +346,9 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
 
 // Promoted-block pass of the attend pass with gated key precision (see certified_split_kernel).
 int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
-  if (a.ulist == nullptr || a.ucount == nullptr || a.t2_k == nullptr) return CQA_ERR_INVALID_ARG;
+  if (a.ulist == nullptr || a.ucount == nullptr || a.slot == nullptr || a.t2_k == nullptr ||
+      a.t2_v == nullptr)
+    return CQA_ERR_INVALID_ARG;
   switch (group) {
     case 1: hipLaunchKernelGGL((certified_split_kernel<1, true>), grid, dim3(256), 0, st, a); break;
     case 2: hipLaunchKernelGGL((certified_split_kernel<2, true>), grid, dim3(256), 0, st, a); break;
@@ -381,9 +401,12 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.ulist = nullptr;
     a.ucount = nullptr;
     a.t2_k = nullptr;
+    a.t2_v = nullptr;
+    a.eta_out = nullptr;
     a.max_tokens = 0;
     a.split0 = 0;
-    a.score_only = (score_only && c->variant == 0 && blk_logmass != nullptr) ? 1 : 0;
+    a.score_only = (score_only && blk_logmass != nullptr) ? 1 : 0;   // always the matrix-core kernel
+    a.eta_out = a.score_only ? c->ad.eta_blk : nullptr;
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;
@@ -393,7 +416,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
-    if (c->variant == 0) {
+    if (c->variant == 0 || a.score_only) {
       // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction
       // (measured slower than the separate launch: the reduction is a chain of dependent
       // device-scope round trips either way, and fused it also extends the big kernel)

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
     bool live[4];   // block is inside this wave's run and scored from its INT8 keys in this pass
 #pragma unroll
-    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1 && (!MIX || slotrow[qb + i] < 0);
+    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1 && (!MIX || slotrow[qb + i] == 0);
     float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -425,6 +425,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
         for (int i = 0; i < 4; ++i)
           if (live[i])
             a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lbv[i];
+      }
+      if (SCORE && a.eta_out != nullptr && l == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (qb + i < b1) a.eta_out[((int64_t)b * a.n_kv + kvh) * a.nb + qb + i] = an[i].x;
       }
     }
     abuf[w][kg] = alpha;   // every lane of the row stores the same word

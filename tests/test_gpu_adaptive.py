@@ -42,7 +42,7 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     cqa = gc.cqa
     qd = gc.to_dev(q)
     gtol = to_gpu_tol(cqa, tol)
-    gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit)
+    gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit, sel.v_limit, sel.v_greedy)
     # the scoring pass on its own first: its certificate (lse, Delta_h, V_max) is what the selector
     # reads inside the adaptive call, bit for bit (same kernel, same inputs)
     gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
@@ -55,7 +55,8 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     O, cert, flags = gc.results()
     state = cqa.cqa_adaptive_state(gc.h, 0, gc.bt, gc.hq, gc.hkv)
     return dict(O=O, cert=cert, flags=flags, cert0=cert0, rung=rung, k_star=state[0], selected=state[1],
-                promoted=state[2].astype(bool), l8=state[3], lx=state[4])
+                promoted=(state[2] & 1).astype(bool), v_promoted=(state[2] & 2).astype(bool), l8=state[3],
+                lx=state[4], v_count=state[5], v_selected=state[6], contrib=state[7])
 
 
 def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
@@ -89,6 +90,22 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
             picks.append(s["order"][:k])
         union = ad.group_union(picks, nb)
         assert (out["promoted"][b, kh] == union).all(), ("promoted mask", b, kh)
+        # ---- value promotion: decisions on the GPU's own contributions, thresholds as the GPU holds them
+        vunion = np.zeros(nb, bool)
+        if sel.v_limit > 0:
+            tol32 = att.Tolerances(v_tol=float(np.float32(tol.v_tol)), eps_val=float(np.float32(tol.eps_val)))
+            vpicks = []
+            for i in range(g):
+                h = kh * g + i
+                c0 = out["cert0"][b, h]
+                want_c = ad.value_contributions(out["l8"][b, h].astype(np.float64), float(c0["lse"]), oc.eta[b, kh])
+                assert np.allclose(out["contrib"][b, h], want_c, rtol=1e-5, atol=1e-12), ("contributions", b, h)
+                vs = ad.select_value_blocks_from(out["contrib"][b, h].astype(np.float64), tol32, sel)
+                assert int(out["v_count"][b, h]) == len(vs), ("value count", b, h, int(out["v_count"][b, h]), len(vs))
+                assert out["v_selected"][b, h, :len(vs)].tolist() == vs.tolist(), ("value selection", b, h)
+                vpicks.append(vs)
+            vunion = ad.group_union(vpicks, nb)
+        assert (out["v_promoted"][b, kh] == vunion).all(), ("value-promoted mask", b, kh)
         for i in range(g):
             h = kh * g + i
             if (b, h) not in heads:
@@ -97,7 +114,8 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
                                     k_tr, v_tr, att.Tolerances())
             assert np.abs(out["l8"][b, h] - sc["blk_logmass"]).max() <= 1e-4, ("scoring log-masses", b, h)
             ref = ad.mixed_head(q[b, h], k_hat, oc.k16[b, kh, :nb * 16], v_hat, oc.eta[b, kh], oc.nu[b, kh],
-                                k_tr, v_tr, union, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol)
+                                k_tr, v_tr, union, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol,
+                                v_promoted=vunion, v16_sealed=oc.v16[b, kh, :nb * 16])
             w = ("adaptive", b, h)
             ct = out["cert"][b, h]
             if served and served.get((b, h)):
@@ -207,6 +225,49 @@ def test_adaptive_ranking_check_and_ladder():
         say(f"  heads served by Rung 3: {sorted(h for (_, h) in flagged)}")
 
 
+def test_adaptive_value_promotion():
+    say("adaptive: value promotion (threshold and hard-budget policies), alone and together with key promotion")
+    k, v, q = make_case(5, 2, 8, 2, 3000, peaked=[(0, 2, 700, 0.9), (1, 5, 2100, 1.1)])
+    oc = oracle.OracleLayerCache(2, 2)
+    oc.append(k, v)
+    with GpuLayerCache(2, 8, 2, 3100) as gc:
+        gc.append(k, v)
+        base = gpu_adaptive(gc, q, att.Tolerances(), ad.SelectorParams(0.995, 0, 0, 0))
+        ev = base["cert"]["E_val"]
+        # (i) threshold policy only, no key promotion
+        sel = ad.SelectorParams(0.995, 0, 0, 0, v_limit=64)
+        tol = att.Tolerances(v_tol=0.02)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert out["v_promoted"].any() and (out["cert"]["E_val"] <= ev + 1e-6).all()
+        assert (out["cert"]["max_block_contrib"] <= 0.02 * (1 + 1e-3)).all()
+        # (ii) hard budget: half of the one-pass value term of the most demanding head
+        sel = ad.SelectorParams(0.995, 0, 0, 0, v_limit=512, v_greedy=True)
+        tol = att.Tolerances(eps_val=float(0.5 * ev.max()))
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert (out["cert"]["E_val"] <= tol.eps_val * (1 + 1e-4)).all() and not (out["flags"] & att.FLAG_VAL).any()
+        say(f"  budget {tol.eps_val:.3f}: value blocks per head {out['v_count'].ravel().tolist()}")
+        # (iii) both rungs together
+        sel = ad.SelectorParams(0.995, 2, 32, 32, v_limit=128, v_greedy=True)
+        tol = att.Tolerances(eps_val=float(0.7 * ev.max()), v_tol=0.05, rank_depth=1)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        both = (out["promoted"] & out["v_promoted"]).sum()
+        say(f"  keys and values: {out['promoted'].sum()} key blocks, {out['v_promoted'].sum()} value blocks, {both} both")
+        # (iv) every value promoted and every key promoted: the dense result
+        sel = ad.SelectorParams(2.0, 0, 512, 512, v_limit=512, v_greedy=True)
+        tol = att.Tolerances(eps_val=0.0)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert out["promoted"].all() and out["v_promoted"].all()
+        assert (out["cert"]["E_key"] == 0).all() and (out["cert"]["E_val"] == 0).all()
+        for b in range(2):
+            for h in range(8):
+                dense = oc.dense_head(q, b, h, 8)
+                assert np.linalg.norm(out["O"][b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+
+
 def test_adaptive_error_paths():
     cqa = load_binding()
     k, v, q = make_case(4, 1, 4, 1, 64)
@@ -218,7 +279,8 @@ def test_adaptive_error_paths():
     with GpuLayerCache(1, 4, 1, 128) as gc:
         gc.append(k, v)
         for bad in (cqa.Selector(0.9, 4, 2, 2), cqa.Selector(0.9, 0, 600, 600), cqa.Selector(0.9, -1, 2, 2),
-                    cqa.Selector(0.9, 0, 8, 4)):
+                    cqa.Selector(0.9, 0, 8, 4), cqa.Selector(0.9, 0, 8, 8, v_limit=513),
+                    cqa.Selector(0.9, 0, 8, 8, v_limit=-1)):
             with pytest.raises(cqa.CqaError) as e:
                 cqa.cqa_adaptive_decode(gc.h, 0, gc.to_dev(q), cqa.Tolerances(), bad, gc.O, gc.cert, gc.flags)
             assert e.value.status == cqa.ERR_INVALID_ARG
