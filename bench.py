@@ -388,7 +388,21 @@ def main() -> int:
         ad_ms = (time.perf_counter() - ta0) * 1e3 / n_ad
         kst, _, prom, *_ = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
         prom = prom & 1
-        ad_info = {"ms_per_step": ad_ms, "steps_with_fallback": int(sum(1 for r in rungs if r)),
+        # the same with value promotion (second rung) on: blocks whose estimated contribution exceeds
+        # the paper's v_tol = 0.05 are attended from their FP16 values
+        vsel = cqa.Selector(0.995, 2, 128, 128, v_limit=128)
+        vtol = cqa.Tolerances(rank_depth=1, rank_min_mass=0.25, v_tol=0.05)
+        for i in range(3):
+            cqa.cqa_adaptive_step(h, 0, qp + i * q_stride, vtol, vsel, Op, certp, flagsp, stream)
+        torch.cuda.synchronize()
+        tv0 = time.perf_counter()
+        for i in range(n_ad):
+            cqa.cqa_adaptive_step(h, 0, qp + (W + i) * q_stride, vtol, vsel, Op, certp, flagsp, stream)
+        torch.cuda.synchronize()
+        adv_ms = (time.perf_counter() - tv0) * 1e3 / n_ad
+        vstate = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
+        ad_info = {"ms_per_step": ad_ms, "ms_per_step_with_value_promotion": adv_ms,
+                   "value_blocks_per_head_median": float(np.median(vstate[5])), "steps_with_fallback": int(sum(1 for r in rungs if r)),
                    "k_star_median": float(np.median(kst)), "k_star_max": int(kst.max()),
                    "promoted_blocks_per_group_max": int(prom.sum(axis=2).max()),
                    "what": f"cqa_adaptive_step, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
