@@ -36,6 +36,16 @@ Readings where the paper is silent or offers a choice (the HIP path follows the 
   E_val and max_b rho_b eta_b with eta_b = 0; E_val is the achieved one (attend-pass masses).
   Using the estimated masses for the greedy stop is this build's reading: the paper states the
   stop on the achieved term, which is only known after the pass.
+* Monitors (the paper's "Instability Detection").  Score-consistency check (canary): on every
+  key-promoted block the FP16 score of each token is compared with its INT8 score; a head with
+  |s_fp16 - s_int8| > Delta_h + eps_guard anywhere gets PRECOND (the quantization error left the
+  declared bound: metadata corruption or a hardware fault), which the ladder serves by Rung 4.
+  Exploration budget: a fraction of the blocks, drawn per (seed, KV group, block) by a counter-
+  based hash so both sides draw the same ones, is key-promoted on top of the selection, which
+  puts blocks the selector would never pick under the same check.  The hash is the 32-bit
+  multiply-xorshift mixer with constants 0x7FEB352D / 0x846CA68B applied to
+  block * 0x9E3779B1 ^ group * 0x85EBCA77 ^ seed * 0xC2B2AE3D; a block is explored when the
+  result is below explore_frac * 2^32.
 * Ranking check at depth r = 1 over the promoted set F of the head's group:
   (i) the block with the largest FP16 log-mass in F must be the block with the
   largest INT8 log-mass in F; (ii) boundary: no unpromoted block may have
@@ -61,6 +71,9 @@ class SelectorParams:
     k_limit: int = 128          # cap for Rung-1 doubling (>= k_max)
     v_limit: int = 0            # blocks one head may promote to FP16 values (0 = off)
     v_greedy: bool = False      # hard-budget variant: also promote until the estimate fits eps_val
+    canary: bool = False        # score-consistency check on key-promoted blocks
+    explore_frac: float = 0.0   # exploration budget: fraction of blocks key-promoted at random
+    explore_seed: int = 0       # counter of the draw (e.g. the decode step)
 
 
 def rank_blocks(logmass: np.ndarray) -> np.ndarray:
@@ -133,6 +146,24 @@ def select_value_blocks(logmass: np.ndarray, lse: float, eta: np.ndarray, tol: a
     return select_value_blocks_from(value_contributions(logmass, lse, eta), tol, par)
 
 
+def explored_blocks(nb: int, group: int, par: SelectorParams) -> np.ndarray:
+    """Boolean mask [NB] of the blocks the exploration budget key-promotes for KV group `group`
+    (= batch * n_kv_heads + kv_head)."""
+    if par.explore_frac <= 0.0 or nb == 0:
+        return np.zeros(nb, dtype=bool)
+    m = np.uint64(0xFFFFFFFF)
+    x = (np.arange(nb, dtype=np.uint64) * np.uint64(0x9E3779B1)) & m
+    x ^= np.uint64((group * 0x85EBCA77) & 0xFFFFFFFF)
+    x ^= np.uint64(((par.explore_seed & 0xFFFFFFFF) * 0xC2B2AE3D) & 0xFFFFFFFF)
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x7FEB352D)) & m
+    x ^= x >> np.uint64(15)
+    x = (x * np.uint64(0x846CA68B)) & m
+    x ^= x >> np.uint64(16)
+    threshold = min(int(par.explore_frac * 4294967296.0), 0xFFFFFFFF)
+    return x < np.uint64(threshold)
+
+
 def group_union(selections, nb: int) -> np.ndarray:
     """Boolean mask [NB]: union of the heads' promoted sets (each an index array)."""
     mask = np.zeros(nb, dtype=bool)
@@ -164,7 +195,7 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
                eta: np.ndarray, nu: np.ndarray, k_trail16: np.ndarray, v_trail16: np.ndarray,
                promoted: np.ndarray, l_int8: np.ndarray, lse_int8: float, delta_h: float,
                tol: att.Tolerances, v_promoted: np.ndarray | None = None,
-               v16_sealed: np.ndarray | None = None) -> dict:
+               v16_sealed: np.ndarray | None = None, canary: bool = False) -> dict:
     """The attend pass with mask-gated key precision, one head, one step.
 
     k_hat float64 [NB*B, d] INT8 reconstructions; k16_sealed float16 [NB*B, d] the FP16
@@ -214,7 +245,14 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     e_key = att.key_term(delta_h, alpha_hat, v_max, tol.mass_exp, tol.key_bound_mode)
 
     rk = ranking_check(np.asarray(l_int8, dtype=np.float64), l_b, promoted, delta_h, tol.eps_guard)
+    # score-consistency check: FP16 against INT8 scores on the key-promoted tokens
+    score_dev = 0.0
+    if nb and tok_prom.any():
+        s_int8 = (k_hat[tok_prom] @ q) * inv
+        score_dev = float(np.abs(s_seal[tok_prom] - s_int8).max())
     flags = 0
+    if canary and score_dev > delta_h + tol.eps_guard:
+        flags |= att.FLAG_PRECOND
     if e_key > tol.eps_key:
         flags |= att.FLAG_KEY
     if e_val > tol.eps_val or max_contrib > tol.v_tol:
@@ -231,7 +269,7 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     flags |= tol.force_flags
     return dict(O=o, E_key=e_key, E_val=e_val, delta_h=delta_h, v_max=v_max,
                 alpha_tail_hat=alpha_hat, lse=lse, max_block_contrib=max_contrib,
-                flags=flags, blk_logmass=l_b, weights=a, ranking=rk)
+                flags=flags, blk_logmass=l_b, weights=a, ranking=rk, score_dev=score_dev)
 
 
 def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorParams,
@@ -268,7 +306,7 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
             picks.append(sel["order"][:k])
             ks.append(k)
             vpicks.append(select_value_blocks(sc["blk_logmass"], sc["lse"], cache.eta[b, kh], tol, par))
-        union = group_union(picks, nb)
+        union = group_union(picks, nb) | explored_blocks(nb, b * cache.hkv + kh, par)
         vunion = group_union(vpicks, nb)
         for i in range(g):
             h = kh * g + i
@@ -276,7 +314,7 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
             res = mixed_head(q16[b, h], k_hat, cache.k16[b, kh, :nb * qz.B], v_hat, cache.eta[b, kh],
                              cache.nu[b, kh], k_tr, v_tr, union, sc["blk_logmass"], sc["lse"],
                              sc["delta_h"], tol, v_promoted=vunion,
-                             v16_sealed=cache.v16[b, kh, :nb * qz.B])
+                             v16_sealed=cache.v16[b, kh, :nb * qz.B], canary=par.canary)
             res.update(k_star=ks[i], selected=picks[i], promoted=union, scoring=sc,
                        v_selected=vpicks[i], v_promoted=vunion)
             out[(b, h)] = res

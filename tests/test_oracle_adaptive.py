@@ -297,3 +297,52 @@ def test_greedy_budget_is_met_in_the_attend_pass_when_nothing_is_capped():
         assert r["E_val"] <= 0.3 * (1 + 1e-9)
         assert not (r["flags"] & att.FLAG_VAL)
         assert r["E_val"] < r["scoring"]["E_val"]
+
+
+# ---------------------------------------------------------------- monitors
+
+def scalar_mix(block, group, seed):
+    """The exploration hash written out for one block with Python integers."""
+    x = (block * 0x9E3779B1) & 0xFFFFFFFF
+    x ^= (group * 0x85EBCA77) & 0xFFFFFFFF
+    x ^= (seed * 0xC2B2AE3D) & 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & 0xFFFFFFFF
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def test_exploration_draw():
+    par = ad.SelectorParams(explore_frac=0.05, explore_seed=12345)
+    nb = 20000
+    m = ad.explored_blocks(nb, 3, par)
+    for blk in (0, 1, 77, 4096, 19999):
+        assert bool(m[blk]) == (scalar_mix(blk, 3, 12345) < int(0.05 * 2 ** 32))
+    assert abs(m.mean() - 0.05) < 0.005                      # the budget is met on average
+    assert (m != ad.explored_blocks(nb, 4, par)).any()       # another group, another draw
+    assert (m != ad.explored_blocks(nb, 3, ad.SelectorParams(explore_frac=0.05, explore_seed=12346))).any()
+    assert not ad.explored_blocks(nb, 3, ad.SelectorParams()).any()
+    assert ad.explored_blocks(nb, 3, ad.SelectorParams(explore_frac=1.0)).mean() > 0.9999
+
+
+def test_canary_passes_on_sound_metadata_and_fires_on_corruption():
+    """|s_fp16 - s_int8| <= Delta_b <= Delta_h on every token (the per-token bound behind the key term),
+    so the check is silent on a sound cache; a scale that no longer describes the block's data (the
+    failure the monitor exists for) breaks the bound and raises PRECOND."""
+    oc, q = small_cache(600, n_tokens=1024 + 2, outlier=True)
+    par = ad.SelectorParams(0.9, 1, 8, 8, canary=True, explore_frac=0.05, explore_seed=7)
+    res = ad.adaptive_decode(oc, q, att.Tolerances(), par)
+    for h in range(4):
+        r = res[(0, h)]
+        assert r["score_dev"] <= r["delta_h"] * (1 + 1e-4) and not (r["flags"] & att.FLAG_PRECOND)
+        assert r["promoted"].sum() > r["selected"].size       # exploration added blocks
+    # corrupt sigma of one explored block: its INT8 reconstruction no longer matches the data
+    victim = int(np.nonzero(ad.explored_blocks(oc.n_blocks, 0, par))[0][0])
+    oc.sigma[0, 0, victim] *= 3.0
+    res = ad.adaptive_decode(oc, q, att.Tolerances(), par)
+    fired = [bool(res[(0, h)]["flags"] & att.FLAG_PRECOND) for h in range(4)]
+    assert any(fired)
+    quiet = ad.adaptive_decode(oc, q, att.Tolerances(), ad.SelectorParams(0.9, 1, 8, 8, explore_frac=0.05, explore_seed=7))
+    assert not any(quiet[(0, h)]["flags"] & att.FLAG_PRECOND for h in range(4))   # check switched off
