@@ -213,6 +213,17 @@ typedef struct cqa_selector {
   int32_t v_greedy;/* 0: promote blocks whose estimated contribution p_b eta_b       */
                    /* exceeds tol->v_tol; 1: also keep promoting, largest first,     */
                    /* until the estimated value term left is <= tol->eps_val         */
+  int32_t canary;  /* 1: score-consistency check on key-promoted blocks: a head with */
+                   /* |s_fp16 - s_int8| > Delta_h + eps_guard on any token gets       */
+                   /* PRECOND (the paper's "Instability Detection")                  */
+  float explore_frac;    /* exploration budget: this fraction of the blocks (paper:  */
+                         /* 0.01-0.05) is key-promoted on top of the selection, so    */
+                         /* the check also sees blocks the selector never picks      */
+  uint32_t explore_seed; /* counter of the draw, e.g. the decode step: a block is    */
+                         /* explored when mix32(block * 0x9E3779B1 ^ group *          */
+                         /* 0x85EBCA77 ^ seed * 0xC2B2AE3D) < explore_frac * 2^32,    */
+                         /* mix32 = the multiply-xorshift mixer with constants       */
+                         /* 0x7FEB352D, 0x846CA68B; group = batch * n_kv_heads + kvh  */
 } cqa_selector;
 
 /* One decode step of `layer` with mask-gated key precision, all on `stream`:
@@ -263,12 +274,15 @@ int32_t cqa_adaptive_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
  * log-masses of the two passes); v_count_host int32 [batch][n_q_heads] and
  * v_selected_host int32 [batch][n_q_heads][512] (the head's value selection, largest
  * contribution first); contrib_host float [batch][n_q_heads][n_blocks] (the estimated
- * contributions p_b eta_b the value selection ranked; valid when v_limit > 0).
+ * contributions p_b eta_b the value selection ranked; valid when v_limit > 0);
+ * score_dev_host float [batch][n_q_heads] (largest |s_fp16 - s_int8| the canary saw
+ * on the head's key-promoted tokens; valid when sel->canary was set).
  * Any pointer may be NULL.  n_blocks = sealed blocks of `layer`. */
 int32_t cqa_adaptive_state(cqa_cache* c, int32_t layer, int32_t* k_star_host,
                            int32_t* selected_host, uint8_t* promoted_host,
                            float* logmass_int8_host, float* logmass_mixed_host,
-                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host);
+                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host,
+                           float* score_dev_host);
 
 /* Dense FP16 decode attention on device-resident K, V (the same kernel the
  * fallback runs after paging): softmax(q K^T / sqrt(128)) V with FP32

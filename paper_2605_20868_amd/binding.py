@@ -58,11 +58,14 @@ class Tolerances(C.Structure):
 class Selector(C.Structure):
     """Parameters of the adaptive key-precision selector (cqa_selector)."""
     _fields_ = [("tau_cov", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32),
-                ("k_limit", C.c_int32), ("v_limit", C.c_int32), ("v_greedy", C.c_int32)]
+                ("k_limit", C.c_int32), ("v_limit", C.c_int32), ("v_greedy", C.c_int32),
+                ("canary", C.c_int32), ("explore_frac", C.c_float), ("explore_seed", C.c_uint32)]
 
-    def __init__(self, tau_cov=0.995, k_min=2, k_max=128, k_limit=None, v_limit=0, v_greedy=False):
+    def __init__(self, tau_cov=0.995, k_min=2, k_max=128, k_limit=None, v_limit=0, v_greedy=False,
+                 canary=False, explore_frac=0.0, explore_seed=0):
         super().__init__(tau_cov, k_min, k_max, k_max if k_limit is None else k_limit, v_limit,
-                         1 if v_greedy else 0)
+                         1 if v_greedy else 0, 1 if canary else 0, explore_frac,
+                         explore_seed & 0xFFFFFFFF)
 
 
 MAX_K_LIMIT = 512
@@ -118,7 +121,7 @@ def _load():
                                       vp, vp]),
         "cqa_adaptive_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
                                     vp, C.POINTER(i32), vp]),
-        "cqa_adaptive_state": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "cqa_adaptive_state": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "cqa_dense_attention": (i32, [vp, vp, vp, i32, i32, i32, i64, vp, vp, vp]),
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
         "cqa_time_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
@@ -269,7 +272,8 @@ def cqa_adaptive_step(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, ce
 def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):
     """Returns (k_star i32[Bt,Hq], selected i32[Bt,Hq,512], promoted u8[Bt,Hkv,NB] (bit 0 keys,
     bit 1 values), logmass_int8 f32[Bt,Hq,NB], logmass_mixed f32[Bt,Hq,NB], v_count i32[Bt,Hq],
-    v_selected i32[Bt,Hq,512], contrib f32[Bt,Hq,NB]) of the last adaptive decode."""
+    v_selected i32[Bt,Hq,512], contrib f32[Bt,Hq,NB], score_dev f32[Bt,Hq]) of the last adaptive
+    decode."""
     import numpy as np
     nb = cqa_cache_length(h, layer) // 16
     ks = np.zeros((batch, n_q_heads), np.int32)
@@ -280,9 +284,10 @@ def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):
     vc = np.zeros((batch, n_q_heads), np.int32)
     vsel = np.zeros((batch, n_q_heads, MAX_K_LIMIT), np.int32)
     contrib = np.zeros((batch, n_q_heads, nb), np.float32)
+    dev = np.zeros((batch, n_q_heads), np.float32)
     _check(_lib.cqa_adaptive_state(h, layer, _ptr(ks), _ptr(sel), _ptr(prom), _ptr(l8), _ptr(lx),
-                                   _ptr(vc), _ptr(vsel), _ptr(contrib)), "cqa_adaptive_state")
-    return ks, sel, prom, l8, lx, vc, vsel, contrib
+                                   _ptr(vc), _ptr(vsel), _ptr(contrib), _ptr(dev)), "cqa_adaptive_state")
+    return ks, sel, prom, l8, lx, vc, vsel, contrib, dev
 
 
 def cqa_dense_workspace_bytes(batch, n_q_heads, n_tokens) -> int:

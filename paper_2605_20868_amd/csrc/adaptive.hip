@@ -39,6 +39,7 @@ struct SelectArgs {
   int32_t* kstar;              // [Bt][Hq]
   uint32_t* umask;             // [Bt][Hkv][mask_words]
   float v_tol, eps_val;        // value selection: local threshold and budget
+  float* score_dev;            // [Bt][Hq] canary output, cleared here (null = no canary)
   int v_greedy;
   int64_t mask_words;
   int nb, n_q, n_kv;
@@ -309,6 +310,7 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
       }
       s_k = k;
       a.kstar[row] = k;
+      if (a.score_dev != nullptr) a.score_dev[row] = 0.0f;
     }
   } else {
     // ---- value selection: the blocks over the local threshold form a prefix of the ranking
@@ -358,7 +360,20 @@ __global__ __launch_bounds__(256) void contrib_kernel(const float* lm8, const fl
   contrib[row * nb + i] = __expf(lm8[row * nb + i] - cert[row].lse) * eta_blk[grp * nb + i];
 }
 
+// The exploration draw: 32-bit multiply-xorshift mixer over (block, KV group, seed).
+__device__ __forceinline__ uint32_t explore_mix(uint32_t blk, uint32_t grp, uint32_t seed) {
+  uint32_t x = blk * 0x9E3779B1u ^ grp * 0x85EBCA77u ^ seed * 0xC2B2AE3Du;
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
 struct CompactArgs {
+  uint32_t explore_threshold;   // a block is explored (key-promoted) when its draw is below this; 0 = off
+  uint32_t explore_seed;
   uint32_t* vmask;     // [Bt][Hkv][mask_words] value selections (null = none); cleared likewise
   uint32_t* umask;     // [Bt][Hkv][mask_words]; cleared on the way out
   int64_t mask_words;
@@ -393,6 +408,12 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
       if (vm != nullptr) {
         vbits = vm[w];
         vm[w] = 0u;
+      }
+      if (a.explore_threshold != 0u) {
+#pragma unroll 4
+        for (int j = 0; j < 32; ++j)
+          if (explore_mix((uint32_t)(w * 32 + j), (uint32_t)grp, a.explore_seed) < a.explore_threshold)
+            kbits |= 1u << j;
       }
       if (w == words - 1 && (a.nb & 31)) {      // nothing past nb
         kbits &= (1u << (a.nb & 31)) - 1u;
@@ -434,12 +455,13 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
 }
 
 struct AdaptiveReduceArgs {
-  ReduceArgs ra;
+  ReduceArgs ra{};
   const float* lm8;      // [Bt][Hq][nb]
   const float* lmx;      // [Bt][Hq][nb]
   const int32_t* slot;   // [Bt][Hkv][slot_stride]
   int64_t slot_stride;
   float* alpha_out;      // [Bt][Hq]
+  const float* score_dev;  // [Bt][Hq] canary deviations, or null
 };
 
 // One workgroup per (batch, query head): all threads scan the block log-masses of both passes
@@ -538,6 +560,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
     const bool disagree = s_ix[0] >= 0 && s_ix[0] != s_i8[0];
     const bool boundary = s_ix[0] >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > s_bx[0];
     ad.rank_fail = (disagree || boundary) ? 1 : 0;
+    ad.precond = (a.score_dev != nullptr && a.score_dev[row] > delta + ra.tol.eps_guard) ? 1 : 0;
     s_ad = ad;
     a.alpha_out[row] = ad.alpha;
   }
@@ -572,7 +595,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   }
 
   // ---- 2. selection per head (+ Rung 1), union bit mask per group
-  SelectArgs sa;
+  SelectArgs sa{};
   sa.lm8 = w.lm8;
   sa.cert = cert;
   sa.sel = w.sel;
@@ -592,6 +615,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   sa.v_tol = tol.v_tol;
   sa.eps_val = tol.eps_val;
   sa.v_greedy = sel.v_greedy;
+  sa.score_dev = sel.canary ? w.score_dev : nullptr;
   hipLaunchKernelGGL(select_kernel<false>, dim3(hq, bt), dim3(ST), 0, st, sa);
   CQA_HIP(hipGetLastError());
   const bool values = sel.v_limit > 0;
@@ -608,12 +632,18 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
     va.k_min = 0;
     va.k_max = sel.v_limit;
     va.k_limit = sel.v_limit;
+    va.score_dev = nullptr;
     hipLaunchKernelGGL(select_kernel<true>, dim3(hq, bt), dim3(ST), 0, st, va);
     CQA_HIP(hipGetLastError());
   }
 
   // ---- 3. slot map and ordered list per group
-  CompactArgs ca;
+  CompactArgs ca{};
+  {
+    const double thr = (double)sel.explore_frac * 4294967296.0;
+    ca.explore_threshold = sel.explore_frac > 0.0f ? (uint32_t)std::min(thr, 4294967295.0) : 0u;
+    ca.explore_seed = sel.explore_seed;
+  }
   ca.vmask = values ? w.vmask : nullptr;
   ca.umask = w.umask;
   ca.mask_words = w.mask_words;
@@ -631,7 +661,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   int nsplit = 0, bps = 0;
   split_geometry(c, nb, &nsplit, &bps);
   const int total = nsplit + PROM_SPLITS;
-  ReduceArgs ra;
+  ReduceArgs ra{};
   ra.partials = c->partials;
   ra.q = q;
   ra.trail_k = c->trail_k + layer_head0 * BLK * D;
@@ -647,7 +677,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   ra.r = r;
   ra.n_q = hq;
   ra.n_kv = hkv;
-  DecodeArgs a;
+  DecodeArgs a{};   // every field starts null / zero
   a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
   a.sigmax = c->sigmax + layer_head0;
   a.q = q;
@@ -667,6 +697,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
   a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
   a.eta_out = nullptr;
+  a.score_dev = sel.canary ? w.score_dev : nullptr;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
   a.score_only = 0;
@@ -677,13 +708,14 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   if (rc != CQA_OK) return rc;
 
   // ---- 5. merge, certificate with the achieved tail, ranking check
-  AdaptiveReduceArgs ar;
+  AdaptiveReduceArgs ar{};
   ar.ra = ra;
   ar.lm8 = w.lm8;
   ar.lmx = w.lmx;
   ar.slot = w.slot;
   ar.slot_stride = c->nq_cap * 4;
   ar.alpha_out = w.alpha;
+  ar.score_dev = sel.canary ? w.score_dev : nullptr;
   hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(256), 0, st, ar);
   CQA_HIP(hipGetLastError());
   return CQA_OK;

@@ -99,6 +99,7 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.contrib);
   (void)hipFree(c->ad.vsel);
   (void)hipFree(c->ad.vcount);
+  (void)hipFree(c->ad.score_dev);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
   if (c->t2_k) (void)hipHostFree(c->t2_k);
@@ -186,7 +187,7 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   if (device_bytes)
     *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
                     2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
-                    s.ad_ulist + s.ad_mask + s.ad_eta + s.ad_lm + s.ad_sel + s.ad_head;
+                    s.ad_ulist + s.ad_mask + s.ad_eta + s.ad_lm + s.ad_sel + 2 * s.ad_head;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
 }
@@ -243,6 +244,8 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_ALLOC_DEV(c->ad.contrib, s.ad_lm);
     CQA_ALLOC_DEV(c->ad.vsel, s.ad_sel);
     CQA_ALLOC_DEV(c->ad.vcount, s.ad_head);
+    CQA_ALLOC_DEV(c->ad.score_dev, s.ad_head);
+    CQA_TRY(hipMemset(c->ad.score_dev, 0, (size_t)s.ad_head));
     c->ad.mask_words = s.ad_mask_words;
     CQA_TRY(hipMemset(c->ad.umask, 0, (size_t)s.ad_mask));       // the selector ORs into it
     CQA_TRY(hipMemset(c->ad.vmask, 0, (size_t)s.ad_mask));
@@ -622,7 +625,8 @@ static int32_t check_decode_args(cqa_cache* h, int32_t layer, const void* q, con
 static int32_t check_selector(const cqa_cache* h, const cqa_selector* sel) {
   if (sel == nullptr || !(sel->tau_cov == sel->tau_cov) || sel->k_min < 0 || sel->k_max < sel->k_min ||
       sel->k_limit < sel->k_max || sel->k_limit > MAX_K_LIMIT || sel->v_limit < 0 ||
-      sel->v_limit > MAX_K_LIMIT || (sel->v_greedy != 0 && sel->v_greedy != 1))
+      sel->v_limit > MAX_K_LIMIT || (sel->v_greedy != 0 && sel->v_greedy != 1) ||
+      (sel->canary != 0 && sel->canary != 1) || !(sel->explore_frac >= 0.0f && sel->explore_frac <= 1.0f))
     return CQA_ERR_INVALID_ARG;
   if (h->impl.desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
   return CQA_OK;
@@ -664,7 +668,8 @@ int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
 int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
                            int32_t* selected_host, uint8_t* promoted_host,
                            float* logmass_int8_host, float* logmass_mixed_host,
-                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host) {
+                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host,
+                           float* score_dev_host) {
   if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers) return CQA_ERR_INVALID_ARG;
   Cache* c = &h->impl;
   if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
@@ -680,6 +685,8 @@ int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
     CQA_HIP(hipMemcpy(logmass_int8_host, c->ad.lm8, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
   if (logmass_mixed_host && nb > 0)
     CQA_HIP(hipMemcpy(logmass_mixed_host, c->ad.lmx, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+  if (score_dev_host)
+    CQA_HIP(hipMemcpy(score_dev_host, c->ad.score_dev, (size_t)rows * 4, hipMemcpyDeviceToHost));
   if (v_count_host)
     CQA_HIP(hipMemcpy(v_count_host, c->ad.vcount, (size_t)rows * 4, hipMemcpyDeviceToHost));
   if (v_selected_host)

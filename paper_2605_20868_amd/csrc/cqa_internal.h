@@ -106,6 +106,7 @@ struct AdaptiveWs {
   float* contrib;    // [Bt][Hq][nb_cap]      estimated contributions p_b eta_b
   int32_t* vsel;     // [Bt][Hq][MAX_K_LIMIT] the head's value selection
   int32_t* vcount;   // [Bt][Hq]
+  float* score_dev;  // [Bt][Hq]              canary: largest |s_fp16 - s_int8| on key-promoted tokens
   int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
   int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
   int64_t mask_words;
@@ -176,6 +177,7 @@ struct DecodeArgs {
   int split0;               // promoted-block pass: index of its first partial set
   int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
   float* eta_out;           // scoring pass: eta_b per (batch, kv-head, block), or null
+  float* score_dev;         // promoted-block pass: canary output per (batch, q-head), or null
 };
 
 

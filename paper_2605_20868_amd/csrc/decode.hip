@@ -80,6 +80,9 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   int i1[G];
   float acc[4][G];
   float vmax = 0.0f;
+  float dev[G];               // canary: largest |s_fp16 - s_int8| seen on key-promoted tokens
+#pragma unroll
+  for (int h = 0; h < G; ++h) dev[h] = 0.0f;
 #pragma unroll
   for (int h = 0; h < G; ++h) {
     m_run[h] = -INFINITY;
@@ -173,6 +176,47 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         }
       }
     }
+    if (PROM && kfp && a.score_dev != nullptr) {
+      // score-consistency check: the same tokens scored from the INT8 codes (scaled query in the
+      // LDS buffer replaced for a moment), compared token by token with the FP16 scores
+      const float2 sg8 = reinterpret_cast<const float2*>(kmb)[l];
+      const float2 zz8 = reinterpret_cast<const float2*>(kmb + D)[l];
+      float c8[G], d8[G];
+      wave_sync();
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float q0 = qv[h][0] * sg8.x, q1 = qv[h][1] * sg8.y;
+        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
+        c8[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y - 128.0f * (q0 + q1);
+        d8[h] = 0.0f;
+      }
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) c8[h] += __shfl_xor(c8[h], m);
+      }
+      wave_sync();
+#pragma unroll
+      for (int cq = 0; cq < 2; ++cq) {
+        const uint4 x = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
+        const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
+        const int c0 = cq * 64 + kg * 16;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float kf = (float)((wd[j >> 2] >> (8 * (j & 3))) & 0xffu);
+#pragma unroll
+          for (int h = 0; h < G; ++h) d8[h] = fmaf(qs[w][h][c0 + j], kf, d8[h]);
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        d8[h] += __shfl_xor(d8[h], 16);
+        d8[h] += __shfl_xor(d8[h], 32);
+        const float full = dot[h] + __shfl_xor(dot[h], 16);
+        const float s16 = (full + __shfl_xor(full, 32) + csum[h]) * inv_sqrt_d;
+        dev[h] = fmaxf(dev[h], fabsf(s16 - (d8[h] + c8[h]) * inv_sqrt_d));
+      }
+    }
     float p[G], alpha[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -243,6 +287,17 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     wave_sync();
   }
 
+  if (PROM && a.score_dev != nullptr) {
+    // deviations are non-negative floats: their bit patterns order like integers
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float d = dev[h];
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) d = fmaxf(d, __shfl_xor(d, m));
+      if (l == 0 && d > 0.0f)
+        atomicMax(reinterpret_cast<int*>(a.score_dev + (int64_t)b * a.n_q + kvh * G + h), __float_as_int(d));
+    }
+  }
   // ---- merge the four waves of the workgroup, then write one partial per q-head
   float* mo = &qs[0][0][0];  // reuse: [4][G][D]
   __syncthreads();
@@ -369,7 +424,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   int nsplit = 0, bps = 0;
   split_geometry(c, nb, &nsplit, &bps);
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
-  ReduceArgs ra;
+  ReduceArgs ra{};
   ra.partials = c->partials;
   ra.q = q;
   ra.trail_k = c->trail_k + layer_head0 * BLK * D;
@@ -387,7 +442,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   ra.n_kv = hkv;
   bool fused = false;
   if (nb > 0) {
-    DecodeArgs a;
+    DecodeArgs a{};   // every field starts null / zero
     a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
     a.sigmax = c->sigmax + layer_head0;
     a.q = q;
@@ -403,6 +458,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.t2_k = nullptr;
     a.t2_v = nullptr;
     a.eta_out = nullptr;
+    a.score_dev = nullptr;
     a.max_tokens = 0;
     a.split0 = 0;
     a.score_only = (score_only && blk_logmass != nullptr) ? 1 : 0;   // always the matrix-core kernel

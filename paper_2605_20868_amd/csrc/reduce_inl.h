@@ -127,6 +127,7 @@ struct AdaptiveIn {
   float tail_ub;     // largest unpromoted INT8 log-mass + Delta_h (-inf if none)
   int top_block;     // the promoted block with the largest FP16 log-mass (-1 if none)
   int rank_fail;     // the two rankings disagree on the top block, or the boundary test failed
+  int precond;       // the score-consistency check found a score outside its declared bound
 };
 
 // wsm: wave-private LDS scratch of at least 64 floats.  All 64 lanes of the wave must call.
@@ -294,6 +295,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     if (e_key > a.tol.eps_key) fl |= CQA_FLAG_KEY;
     if (e_val > a.tol.eps_val || maxc > a.tol.v_tol) fl |= CQA_FLAG_VAL;
     if (rank_flag) fl |= CQA_FLAG_RANK;
+    if (ad != nullptr && ad->precond != 0) fl |= CQA_FLAG_PRECOND;
     if (bad || !isfinite(e_key) || !isfinite(e_val) || !isfinite(delta) || !isfinite(vmax) ||
         !isfinite(lse))
       fl |= CQA_FLAG_PRECOND;

@@ -42,7 +42,8 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     cqa = gc.cqa
     qd = gc.to_dev(q)
     gtol = to_gpu_tol(cqa, tol)
-    gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit, sel.v_limit, sel.v_greedy)
+    gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit, sel.v_limit, sel.v_greedy,
+                        sel.canary, sel.explore_frac, sel.explore_seed)
     # the scoring pass on its own first: its certificate (lse, Delta_h, V_max) is what the selector
     # reads inside the adaptive call, bit for bit (same kernel, same inputs)
     gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
@@ -56,7 +57,7 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     state = cqa.cqa_adaptive_state(gc.h, 0, gc.bt, gc.hq, gc.hkv)
     return dict(O=O, cert=cert, flags=flags, cert0=cert0, rung=rung, k_star=state[0], selected=state[1],
                 promoted=(state[2] & 1).astype(bool), v_promoted=(state[2] & 2).astype(bool), l8=state[3],
-                lx=state[4], v_count=state[5], v_selected=state[6], contrib=state[7])
+                lx=state[4], v_count=state[5], v_selected=state[6], contrib=state[7], score_dev=state[8])
 
 
 def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
@@ -88,7 +89,7 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
                 k = int(out["k_star"][b, h])
             assert out["selected"][b, h, :k].tolist() == s["order"][:k].tolist(), ("selection", b, h)
             picks.append(s["order"][:k])
-        union = ad.group_union(picks, nb)
+        union = ad.group_union(picks, nb) | ad.explored_blocks(nb, b * oc.hkv + kh, sel)
         assert (out["promoted"][b, kh] == union).all(), ("promoted mask", b, kh)
         # ---- value promotion: decisions on the GPU's own contributions, thresholds as the GPU holds them
         vunion = np.zeros(nb, bool)
@@ -115,7 +116,9 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
             assert np.abs(out["l8"][b, h] - sc["blk_logmass"]).max() <= 1e-4, ("scoring log-masses", b, h)
             ref = ad.mixed_head(q[b, h], k_hat, oc.k16[b, kh, :nb * 16], v_hat, oc.eta[b, kh], oc.nu[b, kh],
                                 k_tr, v_tr, union, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol,
-                                v_promoted=vunion, v16_sealed=oc.v16[b, kh, :nb * 16])
+                                v_promoted=vunion, v16_sealed=oc.v16[b, kh, :nb * 16], canary=sel.canary)
+            if sel.canary:
+                assert abs(float(out["score_dev"][b, h]) - ref["score_dev"]) <= 1e-4, ("score deviation", b, h)
             w = ("adaptive", b, h)
             ct = out["cert"][b, h]
             if served and served.get((b, h)):
@@ -266,6 +269,36 @@ def test_adaptive_value_promotion():
             for h in range(8):
                 dense = oc.dense_head(q, b, h, 8)
                 assert np.linalg.norm(out["O"][b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+
+
+def test_adaptive_monitors():
+    say("adaptive: score-consistency canary and exploration budget")
+    k, v, q = make_case(6, 1, 8, 2, 4096 + 9, peaked=[(0, 3, 1000, 1.0)])
+    oc = oracle.OracleLayerCache(1, 2)
+    oc.append(k, v)
+    with GpuLayerCache(1, 8, 2, 4200) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.995, 2, 16, 16, canary=True, explore_frac=0.03, explore_seed=41)
+        tol = att.Tolerances(rank_depth=1, rank_min_mass=0.25)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        explored = np.stack([ad.explored_blocks(oc.n_blocks, g, sel) for g in range(2)])
+        assert explored.sum() > 0 and (out["promoted"][0] >= explored).all()
+        assert not (out["flags"] & att.FLAG_PRECOND).any()
+        assert (out["score_dev"] > 0).all() and (out["score_dev"] <= out["cert"]["delta_h"] * (1 + 1e-3)).all()
+        say(f"  explored blocks per group {explored.sum(axis=1).tolist()}, largest |s_fp16 - s_int8| / Delta_h = "
+            f"{float((out['score_dev'] / out['cert']['delta_h']).max()):.3f}")
+        # another seed draws other blocks
+        sel2 = ad.SelectorParams(0.995, 2, 16, 16, canary=True, explore_frac=0.03, explore_seed=42)
+        out2 = gpu_adaptive(gc, q, tol, sel2)
+        check_against_oracle(oc, q, tol, sel2, out2)
+        assert (out2["promoted"] != out["promoted"]).any()
+        # the firing path, forced from the host: a guard so negative that every deviation exceeds the
+        # bound; every head reports PRECOND and the ladder recomputes the whole layer (Rung 4)
+        tolf = att.Tolerances(eps_guard=-10.0)
+        fired = gpu_adaptive(gc, q, tolf, sel, step=True)
+        assert fired["rung"] == 4
+        check_against_oracle(oc, q, tolf, sel, fired, served={(0, h): 4 for h in range(8)})
 
 
 def test_adaptive_error_paths():

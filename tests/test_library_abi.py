@@ -29,7 +29,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(cqa.HeadCert) == 40
     assert ctypes.sizeof(cqa.Tolerances) == 44
     assert ctypes.sizeof(cqa.CacheDesc) == 40
-    assert ctypes.sizeof(cqa.Selector) == 24
+    assert ctypes.sizeof(cqa.Selector) == 36
     assert cqa.CERT_BYTES == 40
 
 
