@@ -301,6 +301,42 @@ def test_adaptive_monitors():
         check_against_oracle(oc, q, tolf, sel, fired, served={(0, h): 4 for h in range(8)})
 
 
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2), (8, 2)])
+def test_adaptive_gqa_widths_ragged_appends_and_reset(hq, hkv):
+    say(f"adaptive: {hq} query / {hkv} KV heads, appended steps with ragged block counts, reset")
+    g = hq // hkv
+    sel = ad.SelectorParams(0.9, 1, 8, 16, v_limit=8, canary=True, explore_frac=0.02, explore_seed=3)
+    tol = att.Tolerances(rank_depth=1, v_tol=0.2)
+    k, v, q = make_case(20 + hq, 1, hq, hkv, 10)
+    oc = oracle.OracleLayerCache(1, hkv)
+    with GpuLayerCache(1, hq, hkv, 700) as gc:
+        # fewer than 16 tokens: nothing is sealed, the exact trailing tokens are the whole answer
+        oc.append(k, v)
+        gc.append(k, v)
+        out = gpu_adaptive(gc, q, tol, sel)
+        ref = oc.certified_decode(q, tol)
+        for h in range(hq):
+            assert np.linalg.norm(out["O"][0, h] - ref[h]["O"]) <= 1e-3 * np.linalg.norm(ref[h]["O"]) + 1e-6
+            assert out["cert"]["E_key"][0, h] == 0 and out["cert"]["E_val"][0, h] == 0
+        # grow through ragged lengths (block counts 1, 2, 5, 6, 13, 41: partial quads, partial blocks)
+        rng = np.random.Generator(np.random.Philox(900 + hq))
+        for n_new in (7, 16, 50, 13, 120, 440):
+            ks, vs = workloads.normal_f16(rng, (1, hkv, n_new, 128)), workloads.normal_f16(rng, (1, hkv, n_new, 128))
+            oc.append(ks, vs)
+            gc.append(ks, vs)
+            qq = workloads.normal_f16(rng, (1, hq, 128))
+            out = gpu_adaptive(gc, qq, tol, sel)
+            check_against_oracle(oc, qq, tol, sel, out)
+        # reset and start over with a shorter cache: nothing of the old run may show through
+        gc.cqa.cqa_cache_reset(gc.h, 0)
+        oc2 = oracle.OracleLayerCache(1, hkv)
+        k2, v2, q2 = make_case(40 + hq, 1, hq, hkv, 100)
+        oc2.append(k2, v2)
+        gc.append(k2, v2)
+        out = gpu_adaptive(gc, q2, tol, sel)
+        check_against_oracle(oc2, q2, tol, sel, out)
+
+
 def test_adaptive_error_paths():
     cqa = load_binding()
     k, v, q = make_case(4, 1, 4, 1, 64)
