@@ -130,8 +130,8 @@ def bench_small(args, name) -> int:
         Op, certp, flagsp = O.data_ptr(), cert.data_ptr(), flags.data_ptr()
 
         def step(i, t):
-            cqa.cqa_cache_append(h, 0, kp + i * kv_stride, vp + i * kv_stride, 1, stream)
-            return cqa.cqa_decode_step(h, 0, qp + i * q_stride, t, Op, certp, flagsp, None, stream)
+            return cqa.cqa_append_decode_step(h, 0, kp + i * kv_stride, vp + i * kv_stride,
+                                              qp + i * q_stride, t, Op, certp, flagsp, stream)
 
         for i in range(W):
             step(i, tol)
@@ -221,8 +221,8 @@ def bench_stack(args) -> int:
         def step(i):
             for layer in range(L):
                 j = i * L + layer
-                cqa.cqa_cache_append(h, layer, kp + j * kv_stride, vp + j * kv_stride, 1, stream)
-                cqa.cqa_decode_step(h, layer, qp + j * q_stride, tol, Op, certp, flagsp, None, stream)
+                cqa.cqa_append_decode_step(h, layer, kp + j * kv_stride, vp + j * kv_stride,
+                                           qp + j * q_stride, tol, Op, certp, flagsp, stream)
 
         for i in range(W):
             step(i)
@@ -330,8 +330,8 @@ def main() -> int:
         Op, certp, flagsp = O.data_ptr(), cert.data_ptr(), flags.data_ptr()
 
         def step(i):
-            cqa.cqa_cache_append(h, 0, kp + i * kv_stride, vp + i * kv_stride, 1, stream)
-            return cqa.cqa_decode_step(h, 0, qp + i * q_stride, tol, Op, certp, flagsp, None, stream)
+            return cqa.cqa_append_decode_step(h, 0, kp + i * kv_stride, vp + i * kv_stride,
+                                              qp + i * q_stride, tol, Op, certp, flagsp, stream)
 
         if args.copy_probe:
             src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)

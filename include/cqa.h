@@ -198,6 +198,17 @@ int32_t cqa_decode_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
                         uint32_t* flags_dev, float* blk_logmass_dev, int32_t* rung_served,
                         void* stream);
 
+/* cqa_cache_append of ONE token per sequence followed by cqa_decode_step, as a
+ * single call (the decode-time pattern: the paper's trailing partial block takes
+ * the new token, then the step attends it).  k_fp16_dev, v_fp16_dev: device FP16
+ * [batch][n_kv_heads][1][128].  When the token does not complete a block, its
+ * stores ride on the decode launch itself (one launch fewer per step); results
+ * are identical to the two calls.  Errors as the two calls. */
+int32_t cqa_append_decode_step(cqa_cache* c, int32_t layer, const void* k_fp16_dev,
+                               const void* v_fp16_dev, const void* q_fp16_dev,
+                               const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                               uint32_t* flags_dev, int32_t* rung_served, void* stream);
+
 /* ---- adaptive key precision: the paper's "Adaptive Precision Selection",
  *      first rung of its "Fallback Ladder", the total error bound with the
  *      achieved tail mass, and its "Ranking-Consistency Check" ---------------- */

@@ -117,6 +117,8 @@ def _load():
         "cqa_dense_fallback": (i32, [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp]),
         "cqa_decode_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
                                   C.POINTER(i32), vp]),
+        "cqa_append_decode_step": (i32, [vp, i32, vp, vp, vp, C.POINTER(Tolerances), vp, vp, vp,
+                                         C.POINTER(i32), vp]),
         "cqa_adaptive_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
                                       vp, vp]),
         "cqa_adaptive_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
@@ -250,6 +252,15 @@ def cqa_decode_step(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev
     _check(_lib.cqa_decode_step(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev), _ptr(cert_dev),
                                 _ptr(flags_dev), _ptr(blk_logmass_dev), C.byref(rung),
                                 _ptr(stream)), "cqa_decode_step")
+    return rung.value
+
+
+def cqa_append_decode_step(h, layer, k_dev, v_dev, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                           stream=None) -> int:
+    rung = C.c_int32(0)
+    _check(_lib.cqa_append_decode_step(h, layer, _ptr(k_dev), _ptr(v_dev), _ptr(q_dev), C.byref(tol),
+                                       _ptr(O_dev), _ptr(cert_dev), _ptr(flags_dev), C.byref(rung),
+                                       _ptr(stream)), "cqa_append_decode_step")
     return rung.value
 
 

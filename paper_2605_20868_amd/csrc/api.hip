@@ -536,7 +536,8 @@ int32_t cqa_dense_fallback(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
 static int32_t step_with_ladder(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                                 const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                                 cqa_head_cert* cert_dev, uint32_t* flags_dev,
-                                float* blk_logmass_dev, int32_t* rung_served, void* stream) {
+                                float* blk_logmass_dev, int32_t* rung_served, void* stream,
+                                const __half* k_new = nullptr, const __half* v_new = nullptr) {
   Cache* c = &h->impl;
   hipStream_t st = (hipStream_t)stream;
   // The reduction also writes each head's flag word, tagged with this step's sequence number,
@@ -552,7 +553,7 @@ static int32_t step_with_ladder(cqa_cache* h, int32_t layer, const void* q_fp16_
                          c->flags_host, tag, st);
   else
     rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
-                          c->flags_host, tag, blk_logmass_dev, st);
+                          c->flags_host, tag, blk_logmass_dev, st, false, k_new, v_new);
   if (rc != CQA_OK) return rc;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
@@ -640,6 +641,36 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
   if (rc != CQA_OK) return rc;
   return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev,
                           blk_logmass_dev, rung_served, stream);
+}
+
+int32_t cqa_append_decode_step(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
+                               const void* v_fp16_dev, const void* q_fp16_dev,
+                               const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                               uint32_t* flags_dev, int32_t* rung_served, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || k_fp16_dev == nullptr ||
+      v_fp16_dev == nullptr || q_fp16_dev == nullptr || tol == nullptr || O_dev == nullptr ||
+      cert_dev == nullptr || flags_dev == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  const int64_t len = c->length[layer];
+  if (len + 1 > c->desc.max_tokens) return CQA_ERR_CAPACITY;
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
+    return CQA_ERR_INVALID_ARG;
+  // The new token rides on the decode launch when it neither completes a block (the seal must
+  // run first then) nor finds the cache without a sealed block (no split pass is launched
+  // then), and the matrix-core kernel is in use; otherwise: append, then step.
+  const bool ride = (len % BLK) != BLK - 1 && len >= BLK && c->variant == 0;
+  if (!ride) {
+    const int32_t rc = cqa_cache_append(h, layer, k_fp16_dev, v_fp16_dev, 1, stream);
+    if (rc != CQA_OK) return rc;
+    return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev, nullptr,
+                            rung_served, stream);
+  }
+  c->length[layer] = len + 1;
+  const int32_t rc = step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev,
+                                      nullptr, rung_served, stream, (const __half*)k_fp16_dev,
+                                      (const __half*)v_fp16_dev);
+  return rc;
 }
 
 int32_t cqa_adaptive_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,

@@ -178,6 +178,17 @@ struct DecodeArgs {
   int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
   float* eta_out;           // scoring pass: eta_b per (batch, kv-head, block), or null
   float* score_dev;         // promoted-block pass: canary output per (batch, q-head), or null
+  // one-token append carried by the decode launch (null k_new = none): the new (k, v) of every
+  // (batch, kv-head) goes to slot `ap_slot` of the trailing FP16 block and, unless ap_t2_k is
+  // null, to position ap_pos of the pinned originals
+  const __half* ap_k_new;   // [Bt][Hkv][1][128]
+  const __half* ap_v_new;
+  __half* ap_trail_k;       // layer base: [Bt * Hkv][16][128]
+  __half* ap_trail_v;
+  __half* ap_t2_k;          // layer base: [Bt * Hkv][max_tokens][128]
+  __half* ap_t2_v;
+  int ap_slot;
+  int64_t ap_pos, ap_max_tokens;
 };
 
 
@@ -201,7 +212,8 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
-                         bool score_only = false);
+                         bool score_only = false, const __half* k_new = nullptr,
+                         const __half* v_new = nullptr);
 int pick_splits(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;

@@ -416,7 +416,8 @@ int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStrea
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st, bool score_only) {
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st, bool score_only,
+                         const __half* k_new, const __half* v_new) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
@@ -463,6 +464,20 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.split0 = 0;
     a.score_only = (score_only && blk_logmass != nullptr) ? 1 : 0;   // always the matrix-core kernel
     a.eta_out = a.score_only ? c->ad.eta_blk : nullptr;
+    if (k_new != nullptr) {
+      // the caller has already counted the new token in length[layer]: it is token len - 1
+      if (c->variant != 0 || r == 0) return CQA_ERR_INVALID_ARG;   // needs this kernel and an open block
+      a.ap_k_new = k_new;
+      a.ap_v_new = v_new;
+      a.ap_trail_k = c->trail_k + layer_head0 * BLK * D;
+      a.ap_trail_v = c->trail_v + layer_head0 * BLK * D;
+      const bool t2 = c->desc.tier2_mode == CQA_TIER2_PINNED;
+      a.ap_t2_k = t2 ? c->t2_k + layer_head0 * c->desc.max_tokens * D : nullptr;
+      a.ap_t2_v = t2 ? c->t2_v + layer_head0 * c->desc.max_tokens * D : nullptr;
+      a.ap_slot = r - 1;
+      a.ap_pos = len - 1;
+      a.ap_max_tokens = c->desc.max_tokens;
+    }
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;

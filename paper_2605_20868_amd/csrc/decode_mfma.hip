@@ -166,6 +166,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
+  // A one-token append that rides on this launch: the first wave of each KV group's first
+  // workgroup stores the group's new key and value (2 x 256 bytes) into the trailing block and
+  // the pinned originals.  This pass reads sealed blocks only; the reduction, which attends the
+  // trailing tokens, runs after this launch has completed.
+  if (a.ap_k_new != nullptr && split == 0 && w == 0) {
+    const int64_t grp = (int64_t)b * a.n_kv + kvh;
+    const uint32_t kx = reinterpret_cast<const uint32_t*>(a.ap_k_new + grp * D)[l];
+    const uint32_t vx = reinterpret_cast<const uint32_t*>(a.ap_v_new + grp * D)[l];
+    reinterpret_cast<uint32_t*>(a.ap_trail_k + (grp * BLK + a.ap_slot) * D)[l] = kx;
+    reinterpret_cast<uint32_t*>(a.ap_trail_v + (grp * BLK + a.ap_slot) * D)[l] = vx;
+    if (a.ap_t2_k != nullptr) {
+      reinterpret_cast<uint32_t*>(a.ap_t2_k + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = kx;
+      reinterpret_cast<uint32_t*>(a.ap_t2_v + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = vx;
+    }
+  }
   // Wave priorities.  A SIMD holds one wave of each of the two workgroups resident on its CU and,
   // at equal priority, always issues the older wave first: left alone, the older workgroup runs
   // ~25 % faster and the younger one finishes the launch alone on a half-empty CU.  So the short

@@ -351,3 +351,38 @@ def test_t128k_steps():
             b, h = np.argwhere(cert2["served_rung"] == 3)[0]
             dense = oracle.softmax_attention(q[b, h], oc.k16[b, h // 4], oc.v16[b, h // 4])
             assert np.linalg.norm(O2[b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+
+
+def test_append_decode_step_equals_the_two_calls():
+    say("one-call append + decode step against append followed by decode step, 40 steps across seals")
+    cqa = load_binding()
+    sh = workloads.SHAPES["l8k"]
+    k, v = workloads.make_kv("l8k", seed=0, context=2048 + 5)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, 2200) as a, \
+            GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, 2200) as b:
+        a.append(k, v)
+        b.append(k, v)
+        tol = cqa.Tolerances()
+        for step in range(40):
+            ks, vs = workloads.make_step_kv("l8k", step, seed=1)
+            q = workloads.make_q("l8k", step, seed=1)
+            kd, vd, qd = a.to_dev(ks), a.to_dev(vs), a.to_dev(q)
+            a.cqa.cqa_cache_append(a.h, 0, kd, vd, 1)
+            a.cqa.cqa_decode_step(a.h, 0, qd, tol, a.O, a.cert, a.flags, None)
+            b.cqa.cqa_append_decode_step(b.h, 0, kd, vd, qd, tol, b.O, b.cert, b.flags)
+            Oa, ca, fa = a.results()
+            Ob, cb, fb = b.results()
+            assert a.length() == b.length() == 2048 + 5 + step + 1
+            assert (Oa == Ob).all() and (fa == fb).all(), ("step", step)
+            assert ca.tobytes() == cb.tobytes(), ("certificate", step)
+        # the caches hold the same blocks and the same originals: every block sealed on the way,
+        # and a forced fallback (which reads the pinned originals incl. the tokens that rode along)
+        for blk in (126, 127, 128, 129):
+            xa, xb = a.export(0, 3, blk), b.export(0, 3, blk)
+            for u, w in zip(xa, xb):
+                assert np.array_equal(np.asarray(u), np.asarray(w)), ("block", blk)
+        forced = cqa.Tolerances(force_flags=cqa.FLAG_TOTAL)
+        qd = a.to_dev(workloads.make_q("l8k", 99, seed=1))
+        a.cqa.cqa_decode_step(a.h, 0, qd, forced, a.O, a.cert, a.flags, None)
+        b.cqa.cqa_decode_step(b.h, 0, qd, forced, b.O, b.cert, b.flags, None)
+        assert (a.results()[0] == b.results()[0]).all()
