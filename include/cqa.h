@@ -335,6 +335,11 @@ int32_t cqa_decode_splits(const cqa_cache* c, int32_t layer, int32_t* n_splits);
 /* Overrides the automatic split count (0 restores it).  For tests. */
 int32_t cqa_set_splits(cqa_cache* c, int32_t n_splits);
 
+/* How the matrix-core decode kernel loads Tier-1 records: 0 = chosen from the bytes a
+ * whole decode step (all layers) streams, the default; 1 = plain loads; 2 = loads with
+ * the non-temporal hint.  Results do not depend on it.  For tests and measurement. */
+int32_t cqa_set_stream_hint(cqa_cache* c, int32_t mode);
+
 /* Chooses the split-K decode kernel: 0 = matrix-core (MFMA) kernel, the default;
  * 1 = the vector-ALU kernel (same results to rounding; kept as a cross-check).  For tests. */
 int32_t cqa_set_kernel_variant(cqa_cache* c, int32_t variant);

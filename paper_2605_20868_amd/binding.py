@@ -132,6 +132,7 @@ def _load():
         "cqa_profile_end": (i32, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]),
         "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
         "cqa_set_splits": (i32, [vp, i32]),
+        "cqa_set_stream_hint": (i32, [vp, i32]),
         "cqa_set_kernel_variant": (i32, [vp, i32]),
         "cqa_strerror": (C.c_char_p, [i32]),
         "cqa_version": (i32, []),
@@ -341,6 +342,10 @@ def cqa_decode_splits(h, layer) -> int:
 
 def cqa_set_kernel_variant(h, variant) -> None:
     _check(_lib.cqa_set_kernel_variant(h, variant), "cqa_set_kernel_variant")
+
+
+def cqa_set_stream_hint(h, mode) -> None:
+    _check(_lib.cqa_set_stream_hint(h, mode), "cqa_set_stream_hint")
 
 
 def cqa_set_splits(h, n_splits) -> None:

@@ -691,6 +691,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.n_q = hq;
   a.n_kv = hkv;
   a.debug = 0;
+  a.stream_nt = stream_nt(c, nb);
   a.slot = w.slot;
   a.ulist = w.ulist;
   a.ucount = w.ucount;

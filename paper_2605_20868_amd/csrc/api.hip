@@ -311,6 +311,12 @@ int32_t cqa_set_splits(cqa_cache* h, int32_t n_splits) {
   return CQA_OK;
 }
 
+int32_t cqa_set_stream_hint(cqa_cache* h, int32_t mode) {
+  if (h == nullptr || mode < 0 || mode > 2) return CQA_ERR_INVALID_ARG;
+  h->impl.stream_hint = mode;
+  return CQA_OK;
+}
+
 int32_t cqa_set_kernel_variant(cqa_cache* h, int32_t variant) {
   if (h == nullptr || variant < 0 || variant > 0x301) return CQA_ERR_INVALID_ARG;
   h->impl.variant = variant & 1;

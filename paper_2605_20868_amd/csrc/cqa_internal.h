@@ -151,6 +151,7 @@ struct Cache {
   int prof_cap, prof_n;
   int debug;                 // timing probes (0 in production)
   int variant;               // 0 = matrix-core split kernel (default), 1 = vector-ALU split kernel
+  int stream_hint;           // Tier-1 loads: 0 = chosen from the footprint, 1 = plain, 2 = non-temporal
   AdaptiveWs ad;             // allocated with the cache when Tier-2 is retained
 };
 
@@ -176,6 +177,7 @@ struct DecodeArgs {
   int64_t max_tokens;
   int split0;               // promoted-block pass: index of its first partial set
   int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
+  int stream_nt;            // 1 = Tier-1 loads carry the non-temporal hint (see stream_hint)
   float* eta_out;           // scoring pass: eta_b per (batch, kv-head, block), or null
   float* score_dev;         // promoted-block pass: canary output per (batch, q-head), or null
   // one-token append carried by the decode launch (null k_new = none): the new (k, v) of every
@@ -215,6 +217,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
                          bool score_only = false, const __half* k_new = nullptr,
                          const __half* v_new = nullptr);
 int pick_splits(const Cache* c, int64_t n_blocks);
+int stream_nt(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
 struct ReduceArgs;
 int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,

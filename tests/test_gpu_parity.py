@@ -386,3 +386,24 @@ def test_append_decode_step_equals_the_two_calls():
         a.cqa.cqa_decode_step(a.h, 0, qd, forced, a.O, a.cert, a.flags, None)
         b.cqa.cqa_decode_step(b.h, 0, qd, forced, b.O, b.cert, b.flags, None)
         assert (a.results()[0] == b.results()[0]).all()
+
+
+def test_stream_hint_does_not_change_results():
+    say("plain and non-temporal Tier-1 loads give the same bits")
+    rng = np.random.default_rng(23)
+    bt, hkv, hq, n = 2, 2, 8, 16 * 301 + 5
+    k = (rng.standard_normal((bt, hkv, n, 128)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    q = rng.standard_normal((bt, hq, 128)).astype(np.float16)
+    with GpuLayerCache(bt, hq, hkv, 8192) as gc:
+        gc.append(k, v)
+        out = []
+        for mode in (1, 2, 0):
+            gc.cqa.cqa_set_stream_hint(gc.h, mode)
+            O, cert, flags, lm = gc.certified_decode(q, want_logmass=True)
+            out.append((O.copy(), cert.tobytes(), flags.copy(), lm.copy()))
+        for o in out[1:]:
+            assert (o[0] == out[0][0]).all() and o[1] == out[0][1]
+            assert (o[2] == out[0][2]).all() and (o[3] == out[0][3]).all()
+        with pytest.raises(gc.cqa.CqaError):
+            gc.cqa.cqa_set_stream_hint(gc.h, 3)
