@@ -221,8 +221,8 @@ def bench_stack(args) -> int:
         def step(i):
             for layer in range(L):
                 j = i * L + layer
-                cqa.cqa_append_decode_step(h, layer, kp + j * kv_stride, vp + j * kv_stride,
-                                           qp + j * q_stride, tol, Op, certp, flagsp, stream)
+                cqa.cqa_decode_step_enqueue(h, layer, kp + j * kv_stride, vp + j * kv_stride,
+                                            qp + j * q_stride, tol, Op, certp, flagsp, stream)
 
         for i in range(W):
             step(i)
@@ -235,7 +235,8 @@ def bench_stack(args) -> int:
         cqa.cqa_profile_begin(h, K * L)
         for i in range(W, W + K):
             for layer in range(L):
-                cqa.cqa_decode_step(h, layer, qp + (i * L + layer) * q_stride, tol, Op, certp, flagsp, None, stream)
+                cqa.cqa_decode_step_enqueue(h, layer, None, None, qp + (i * L + layer) * q_stride, tol, Op,
+                                            certp, flagsp, stream)
         torch.cuda.synchronize()
         mean_ms, min_ms, n_timed = cqa.cqa_profile_end(h)
         splits = cqa.cqa_decode_splits(h, 0)
@@ -251,7 +252,7 @@ def bench_stack(args) -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"stack: {L} layers, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
                                f"context {ctx}+steps, K ~ Student-t(3), V ~ N(0,1), tolerances +inf",
-                   "step": "for each of the 32 layers: append 1 token + decode step", "splits": splits},
+                   "step": "for each of the 32 layers: append 1 token + decode step with the ladder resolved on the device (cqa_decode_step_enqueue)", "splits": splits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": None,
                      "kernel": "certified_split_mfma_kernel<4>", "kernel_mean_ms": mean_ms,
@@ -329,9 +330,12 @@ def main() -> int:
         kv_stride, q_stride = ks[0].numel() * 2, qs[0].numel() * 2
         Op, certp, flagsp = O.data_ptr(), cert.data_ptr(), flags.data_ptr()
 
+        # One step = append the new token + split pass + reduction + fallback ladder, all enqueued on
+        # the stream: the ladder is resolved by a device kernel, so the host never waits inside the
+        # loop (the timed region ends with a synchronisation).
         def step(i):
-            return cqa.cqa_append_decode_step(h, 0, kp + i * kv_stride, vp + i * kv_stride,
-                                              qp + i * q_stride, tol, Op, certp, flagsp, stream)
+            cqa.cqa_decode_step_enqueue(h, 0, kp + i * kv_stride, vp + i * kv_stride,
+                                        qp + i * q_stride, tol, Op, certp, flagsp, stream)
 
         if args.copy_probe:
             src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
@@ -353,10 +357,38 @@ def main() -> int:
         # (Kept out of the pass that yields `value`: event-carrying dispatches slow the step.)
         cqa.cqa_profile_begin(h, K)
         for i in range(W, W + K):
-            cqa.cqa_decode_step(h, 0, qp + i * q_stride, tol, Op, certp, flagsp, None, stream)
+            cqa.cqa_decode_step_enqueue(h, 0, None, None, qp + i * q_stride, tol, Op, certp, flagsp, stream)
         torch.cuda.synchronize()
         mean_ms, min_ms, n_timed = cqa.cqa_profile_end(h)
         assert n_timed == K
+        ladder_counts = cqa.cqa_ladder_counts(h)
+
+        # the same steps with the ladder resolved on the host (flag words read back through mapped
+        # pinned memory after every step, fallback by copy + dense kernel): reported apart from `value`
+        torch.cuda.synchronize()
+        th0 = time.perf_counter()
+        for i in range(W, W + K):
+            cqa.cqa_decode_step(h, 0, qp + i * q_stride, tol, Op, certp, flagsp, None, stream)
+        torch.cuda.synchronize()
+        host_ms = (time.perf_counter() - th0) * 1e3 / K
+
+        # Rung 3 through the device-resolved ladder: a tolerance between the two largest totals of
+        # this query flags exactly one head; its KV group's originals are read from pinned host RAM
+        # by the ladder kernel itself
+        cqa.cqa_certified_decode(h, 0, qp, tol, Op, certp, flagsp, None, stream)
+        torch.cuda.synchronize()
+        cv = cert.cpu().numpy().view(np.dtype(cqa.CERT_FIELDS)).ravel()
+        tot = np.sort(cv["E_key"].astype(np.float64) + cv["E_val"])
+        tight = cqa.Tolerances(eps_total=float(0.5 * (tot[-1] + tot[-2])))
+        n_fbd = 5
+        cqa.cqa_decode_step_enqueue(h, 0, None, None, qp, tight, Op, certp, flagsp, stream)
+        torch.cuda.synchronize()
+        served_heads = int((cert.cpu().numpy().view(np.dtype(cqa.CERT_FIELDS)).ravel()["served_rung"] == 3).sum())
+        td0 = time.perf_counter()
+        for i in range(n_fbd):
+            cqa.cqa_decode_step_enqueue(h, 0, None, None, qp, tight, Op, certp, flagsp, stream)
+        torch.cuda.synchronize()
+        fbd_ms = (time.perf_counter() - td0) * 1e3 / n_fbd
 
         # the ladder's cost, reported apart from `value`: the same decode with ONE of the 32 heads
         # served by Rung 3 (its KV group's FP16 originals paged in from pinned host RAM, dense
@@ -436,7 +468,8 @@ def main() -> int:
             "workload": f"t128k: 1 layer, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
                         f"d 128, context {ctx}+steps, K ~ Student-t(3), V ~ N(0,1), INT8 K / INT4 V "
                         f"(B=16, g=16), tolerances +inf, Tier-2 FP16 originals in pinned host RAM",
-            "step": "append 1 token + certified decode + reduce + flag read-back + ladder",
+            "step": "append 1 token + certified decode + reduce + fallback ladder resolved on the device "
+                    "(cqa_decode_step_enqueue; no host wait inside the loop)",
             "splits": splits,
             "final_tokens": n_tokens,
         },
@@ -459,6 +492,19 @@ def main() -> int:
             "what": "split pass + reduction, 50 back-to-back launches between two HIP events",
         },
         "adaptive_step": ad_info,
+        "host_ladder_step": {
+            "ms_per_step": host_ms,
+            "what": f"cqa_decode_step (no append): flag words read back by the host after every step, mean of {K}",
+        },
+        "ladder": {
+            "rung3_steps": ladder_counts[0], "rung4_steps": ladder_counts[1],
+            "what": "steps of the timed and the profiled pass that the device-resolved ladder served by a rung",
+        },
+        "fallback_step_device": {
+            "ms_per_step": fbd_ms, "heads_served": served_heads,
+            "what": "cqa_decode_step_enqueue with one head over its tolerance: Rung 3 by the ladder kernel, which "
+                    f"reads the KV group's originals from pinned host RAM itself, wall time, mean of {n_fbd}",
+        },
         "fallback_step": {
             "ms_per_step": fb_ms,
             "what": "certified decode + Rung 3 for 1 of 32 heads (one KV group paged from pinned host RAM: "

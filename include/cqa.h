@@ -209,6 +209,29 @@ int32_t cqa_append_decode_step(cqa_cache* c, int32_t layer, const void* k_fp16_d
                                const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
                                uint32_t* flags_dev, int32_t* rung_served, void* stream);
 
+/* The decode step as enqueue-only work: the same split pass and reduction as
+ * cqa_decode_step, followed by the paper's fallback ladder ("Fallback Ladder":
+ * Rung 3 = dense FP16 result for the flagged heads' KV groups, Rung 4 = for every
+ * head when a PRECOND flag is raised or at least tol->rung4_min_groups (> 0) groups
+ * are flagged) resolved ON THE DEVICE: a kernel launched behind the reduction reads
+ * the step's flag words, leaves at once when none is raised, and otherwise attends
+ * the FP16 originals straight from the pinned Tier-2 arrays and rewrites O, the
+ * certificate (E_key = E_val = 0, served_rung) and the rung bits of the served heads.
+ * The call never waits for the GPU and reads nothing back: results are in O_dev,
+ * cert_dev, flags_dev once `stream` has passed the enqueued work.
+ * k_fp16_dev / v_fp16_dev: device FP16 [batch][n_kv_heads][1][128], the token to
+ * append first (as cqa_append_decode_step), or both NULL for no append.
+ * Needs the Tier-2 originals (CQA_ERR_NO_TIER2 otherwise); CQA_ERR_CAPACITY when
+ * the token does not fit; CQA_ERR_INVALID_ARG for an empty cache or null pointers. */
+int32_t cqa_decode_step_enqueue(cqa_cache* c, int32_t layer, const void* k_fp16_dev,
+                                const void* v_fp16_dev, const void* q_fp16_dev,
+                                const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                                uint32_t* flags_dev, void* stream);
+
+/* How many cqa_decode_step_enqueue steps of this cache were served by Rung 3 and by
+ * Rung 4 so far (device counters; the call waits for the device).  Host pointers, may be NULL. */
+int32_t cqa_ladder_counts(cqa_cache* c, int64_t* rung3_steps, int64_t* rung4_steps);
+
 /* ---- adaptive key precision: the paper's "Adaptive Precision Selection",
  *      first rung of its "Fallback Ladder", the total error bound with the
  *      achieved tail mass, and its "Ranking-Consistency Check" ---------------- */

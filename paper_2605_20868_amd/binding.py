@@ -119,6 +119,8 @@ def _load():
                                   C.POINTER(i32), vp]),
         "cqa_append_decode_step": (i32, [vp, i32, vp, vp, vp, C.POINTER(Tolerances), vp, vp, vp,
                                          C.POINTER(i32), vp]),
+        "cqa_decode_step_enqueue": (i32, [vp, i32, vp, vp, vp, C.POINTER(Tolerances), vp, vp, vp, vp]),
+        "cqa_ladder_counts": (i32, [vp, C.POINTER(i64), C.POINTER(i64)]),
         "cqa_adaptive_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
                                       vp, vp]),
         "cqa_adaptive_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
@@ -263,6 +265,19 @@ def cqa_append_decode_step(h, layer, k_dev, v_dev, q_dev, tol: Tolerances, O_dev
                                        _ptr(O_dev), _ptr(cert_dev), _ptr(flags_dev), C.byref(rung),
                                        _ptr(stream)), "cqa_append_decode_step")
     return rung.value
+
+
+def cqa_decode_step_enqueue(h, layer, k_dev, v_dev, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                            stream=None) -> None:
+    _check(_lib.cqa_decode_step_enqueue(h, layer, _ptr(k_dev), _ptr(v_dev), _ptr(q_dev), C.byref(tol),
+                                        _ptr(O_dev), _ptr(cert_dev), _ptr(flags_dev), _ptr(stream)),
+           "cqa_decode_step_enqueue")
+
+
+def cqa_ladder_counts(h):
+    r3, r4 = C.c_int64(0), C.c_int64(0)
+    _check(_lib.cqa_ladder_counts(h, C.byref(r3), C.byref(r4)), "cqa_ladder_counts")
+    return r3.value, r4.value
 
 
 def cqa_adaptive_decode(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, cert_dev, flags_dev,

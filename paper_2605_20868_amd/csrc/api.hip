@@ -33,7 +33,7 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 }
 
 struct Sizes {
-  int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select;
+  int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select, ladder_ws;
   int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist, ad_eta;
   int max_splits;
 };
@@ -56,6 +56,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.dense_ws = dense_ws_floats(d->n_q_heads / d->n_kv_heads, d->max_tokens) * 4;
   s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
   s.select = (int64_t)d->batch * d->n_q_heads * 4;
+  s.ladder_ws = d->tier2_mode == CQA_TIER2_PINNED ? ladder_ws_floats((int64_t)d->batch * d->n_q_heads) * 4 : 0;
   // adaptive key precision (needs the originals): log-masses of two passes, selections, masks,
   // slot maps and lists, for one layer-step at a time
   const bool ad = d->tier2_mode == CQA_TIER2_PINNED;
@@ -85,6 +86,9 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->partials);
   (void)hipFree(c->dense_ws);
   (void)hipFree(c->select_dev);
+  (void)hipFree(c->ladder_ws);
+  (void)hipFree(c->ladder_tickets);
+  (void)hipFree(c->ladder_counts);
   (void)hipFree(c->ad.lm8);
   (void)hipFree(c->ad.lmx);
   (void)hipFree(c->ad.sel);
@@ -186,6 +190,7 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   const Sizes s = compute_sizes(desc, 256);
   if (device_bytes)
     *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
+                    s.ladder_ws +
                     2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
                     s.ad_ulist + s.ad_mask + s.ad_eta + s.ad_lm + s.ad_sel + 2 * s.ad_head;
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
@@ -264,6 +269,11 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   if (desc->tier2_mode == CQA_TIER2_PINNED) {
     for (int i = 0; i < 2; ++i)
       for (int j = 0; j < 2; ++j) CQA_ALLOC_DEV(c->stage[i][j], s.stage);
+    CQA_ALLOC_DEV(c->ladder_ws, s.ladder_ws);
+    CQA_ALLOC_DEV(c->ladder_tickets, (int64_t)desc->batch * desc->n_kv_heads * 4);
+    CQA_TRY(hipMemset(c->ladder_tickets, 0, (size_t)desc->batch * desc->n_kv_heads * 4));
+    CQA_ALLOC_DEV(c->ladder_counts, 8);
+    CQA_TRY(hipMemset(c->ladder_counts, 0, 8));
     CQA_ALLOC_PIN(c->t2_k, s.t2);
     CQA_ALLOC_PIN(c->t2_v, s.t2);
   }
@@ -649,6 +659,25 @@ int32_t cqa_decode_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                           blk_logmass_dev, rung_served, stream);
 }
 
+// Appends one token per sequence ahead of a decode launch.  The new token rides on the decode
+// launch itself (*ride_k / *ride_v set, length already counted) when it neither completes a block
+// (the seal must run first then) nor finds the cache without a sealed block (no split pass is
+// launched then), and the matrix-core kernel is in use; otherwise it is appended here.
+static int32_t append_or_ride(cqa_cache* h, int32_t layer, const void* k, const void* v, void* stream,
+                              const __half** ride_k, const __half** ride_v) {
+  Cache* c = &h->impl;
+  const int64_t len = c->length[layer];
+  *ride_k = nullptr;
+  *ride_v = nullptr;
+  if (len + 1 > c->desc.max_tokens) return CQA_ERR_CAPACITY;
+  const bool ride = (len % BLK) != BLK - 1 && len >= BLK && c->variant == 0;
+  if (!ride) return cqa_cache_append(h, layer, k, v, 1, stream);
+  c->length[layer] = len + 1;
+  *ride_k = (const __half*)k;
+  *ride_v = (const __half*)v;
+  return CQA_OK;
+}
+
 int32_t cqa_append_decode_step(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
                                const void* v_fp16_dev, const void* q_fp16_dev,
                                const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
@@ -657,26 +686,50 @@ int32_t cqa_append_decode_step(cqa_cache* h, int32_t layer, const void* k_fp16_d
       v_fp16_dev == nullptr || q_fp16_dev == nullptr || tol == nullptr || O_dev == nullptr ||
       cert_dev == nullptr || flags_dev == nullptr)
     return CQA_ERR_INVALID_ARG;
-  Cache* c = &h->impl;
-  const int64_t len = c->length[layer];
-  if (len + 1 > c->desc.max_tokens) return CQA_ERR_CAPACITY;
   if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
     return CQA_ERR_INVALID_ARG;
-  // The new token rides on the decode launch when it neither completes a block (the seal must
-  // run first then) nor finds the cache without a sealed block (no split pass is launched
-  // then), and the matrix-core kernel is in use; otherwise: append, then step.
-  const bool ride = (len % BLK) != BLK - 1 && len >= BLK && c->variant == 0;
-  if (!ride) {
-    const int32_t rc = cqa_cache_append(h, layer, k_fp16_dev, v_fp16_dev, 1, stream);
+  const __half *rk = nullptr, *rv = nullptr;
+  const int32_t rc = append_or_ride(h, layer, k_fp16_dev, v_fp16_dev, stream, &rk, &rv);
+  if (rc != CQA_OK) return rc;
+  return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev, nullptr,
+                          rung_served, stream, rk, rv);
+}
+
+int32_t cqa_decode_step_enqueue(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
+                                const void* v_fp16_dev, const void* q_fp16_dev,
+                                const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
+                                uint32_t* flags_dev, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
+      tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr ||
+      (k_fp16_dev == nullptr) != (v_fp16_dev == nullptr))
+    return CQA_ERR_INVALID_ARG;
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
+    return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  const __half *rk = nullptr, *rv = nullptr;
+  if (k_fp16_dev != nullptr) {
+    const int32_t rc = append_or_ride(h, layer, k_fp16_dev, v_fp16_dev, stream, &rk, &rv);
     if (rc != CQA_OK) return rc;
-    return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev, nullptr,
-                            rung_served, stream);
   }
-  c->length[layer] = len + 1;
-  const int32_t rc = step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev,
-                                      nullptr, rung_served, stream, (const __half*)k_fp16_dev,
-                                      (const __half*)v_fp16_dev);
-  return rc;
+  if (c->length[layer] <= 0) return CQA_ERR_INVALID_ARG;
+  int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
+                                nullptr, 0u, nullptr, (hipStream_t)stream, false, rk, rv);
+  if (rc != CQA_OK) return rc;
+  return launch_dense_ladder(c, layer, (const __half*)q_fp16_dev, tol->rung4_min_groups, O_dev,
+                             cert_dev, flags_dev, (hipStream_t)stream);
+}
+
+int32_t cqa_ladder_counts(cqa_cache* h, int64_t* rung3_steps, int64_t* rung4_steps) {
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  uint32_t n[2] = {0u, 0u};
+  if (h->impl.ladder_counts != nullptr) {
+    CQA_HIP(hipDeviceSynchronize());
+    CQA_HIP(hipMemcpy(n, h->impl.ladder_counts, 8, hipMemcpyDeviceToHost));
+  }
+  if (rung3_steps) *rung3_steps = n[0];
+  if (rung4_steps) *rung4_steps = n[1];
+  return CQA_OK;
 }
 
 int32_t cqa_adaptive_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,

@@ -125,6 +125,9 @@ struct Cache {
   uint8_t* t1;
   int64_t nq_cap;            // quad records of capacity per head
   uint32_t* tickets;         // [heads_total] arrival counters of the fused reduction (zero between launches)
+  float* ladder_ws;          // device-resolved ladder: split partials, arrival counters, rung counters
+  uint32_t* ladder_tickets;
+  uint32_t* ladder_counts;
   float* sigmax;             // [heads_total] running max of sigma (non-negative: ordered as ints)
   // trailing FP16 partial blocks [heads_total][16][128]
   __half* trail_k;
@@ -235,5 +238,27 @@ int32_t launch_dense_group(const __half* q_group, const __half* k, const __half*
                            cqa_head_cert* cert_group, uint32_t* flags_group, int rung,
                            float* ws, hipStream_t st);
 int64_t dense_ws_floats(int group, int64_t n_tokens);
+
+// Device-resolved fallback ladder (dense_ladder_kernel).
+constexpr int LADDER_MAX_SPLITS = 64;
+struct LadderArgs {
+  const __half* q;          // [Bt][Hq][128]
+  const __half* t2_k;       // layer base of the pinned originals: [Bt * Hkv][max_tokens][128]
+  const __half* t2_v;
+  int64_t max_tokens, n_tokens;
+  int n_rows;               // Bt * Hq
+  int nsplit, tiles_per_split;
+  int rung4_min_groups;
+  float* ws;                // [Bt * Hq][nsplit][4 + 128]
+  uint32_t* tickets;        // [Bt * Hkv], zero between launches
+  uint32_t* counts;         // [2]: steps served by Rung 3, by Rung 4
+  float* O;
+  cqa_head_cert* cert;
+  uint32_t* flags;
+};
+int ladder_splits(const Cache* c, int64_t n_tokens);
+int64_t ladder_ws_floats(int64_t rows);
+int32_t launch_dense_ladder(Cache* c, int layer, const __half* q, int rung4_min_groups, float* O,
+                            cqa_head_cert* cert, uint32_t* flags, hipStream_t st);
 
 }  // namespace cqa

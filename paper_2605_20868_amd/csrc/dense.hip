@@ -30,16 +30,18 @@ int64_t dense_ws_floats(int group, int64_t n_tokens) {
   return (int64_t)group * dense_splits(n_tokens) * DP_FLOATS;
 }
 
+// One split of the dense pass for the G heads of one KV group: tiles [split * tiles_per_split, ...)
+// of k, v ([n_tokens][128], device or mapped host memory); writes (m, l, o) per head to
+// ws[h][split].  Called by all 256 threads of a workgroup.
 template <int G>
-__global__ __launch_bounds__(256) void dense_split_kernel(const __half* __restrict__ q,
-                                                          const __half* __restrict__ k,
-                                                          const __half* __restrict__ v,
-                                                          int64_t n_tokens, int tiles_per_split,
-                                                          int nsplit, float* __restrict__ ws) {
+__device__ __forceinline__ void dense_split_work(const __half* __restrict__ q,
+                                                 const __half* __restrict__ k,
+                                                 const __half* __restrict__ v, int64_t n_tokens,
+                                                 int tiles_per_split, int nsplit, int split,
+                                                 float* __restrict__ ws) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = l & 15, kg = l >> 4;   // score phase: token of the tile, 32-channel slice
   const int vc = l & 15, vt = l >> 4;    // value phase: 8-channel slice, 4-token slice
-  const int split = blockIdx.x;
   const int64_t tiles = (n_tokens + BLK - 1) / BLK;
   const int64_t t0 = (int64_t)split * tiles_per_split;
   const int64_t t1 = min(t0 + (int64_t)tiles_per_split, tiles);
@@ -165,6 +167,149 @@ __global__ __launch_bounds__(256) void dense_split_kernel(const __half* __restri
     ws[((int64_t)h * nsplit + split) * DP_FLOATS + 0] = M;
     ws[((int64_t)h * nsplit + split) * DP_FLOATS + 1] = L;
   }
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void dense_split_kernel(const __half* __restrict__ q,
+                                                          const __half* __restrict__ k,
+                                                          const __half* __restrict__ v,
+                                                          int64_t n_tokens, int tiles_per_split,
+                                                          int nsplit, float* __restrict__ ws) {
+  dense_split_work<G>(q, k, v, n_tokens, tiles_per_split, nsplit, (int)blockIdx.x, ws);
+}
+
+// The fallback ladder resolved on the device (the paper's "Fallback Ladder": Rung 3 returns the
+// dense FP16 result for the flagged heads, Rung 4 for every head of the layer-step).  Launched
+// behind the reduction on every step, grid (splits, batch * kv heads).  Every workgroup reads
+// the step's flag words and takes the ladder decision itself -- no head flagged: nothing to do;
+// a PRECOND flag anywhere, or at least rung4_min_groups (> 0) flagged KV groups: all groups
+// are served (Rung 4); else the flagged groups (Rung 3) -- and leaves at once unless its KV
+// group is served.  The workgroups of a served group attend the group's FP16 originals
+// straight from the pinned host arrays (the device reads host memory over the link: no copy
+// call, no staging buffer, no host decision), and the last of them to arrive merges the
+// splits and rewrites O, the certificate and the rung bits of the heads that are served.
+template <int G>
+__global__ __launch_bounds__(256) void dense_ladder_kernel(LadderArgs a) {
+  const int split = blockIdx.x, grp = blockIdx.y;
+  __shared__ int s_rung, s_mine, s_last;
+  if (threadIdx.x < 64) {
+    int flagged_groups = 0;
+    bool precond = false, mine = false;
+    for (int i0 = 0; i0 < a.n_rows; i0 += 64) {   // groups never straddle a chunk: G divides 64
+      const int i = i0 + (int)threadIdx.x;
+      const uint32_t f = i < a.n_rows ? a.flags[i] : 0u;
+      const uint64_t m = __ballot((f & CQA_FLAG_ANY) != 0u);
+      precond = precond || __ballot((f & CQA_FLAG_PRECOND) != 0u) != 0ull;
+      uint64_t gm = m;
+#pragma unroll
+      for (int j = 1; j < G; ++j) gm |= m >> j;
+      gm &= G == 1 ? ~0ull : (G == 2 ? 0x5555555555555555ull : 0x1111111111111111ull);
+      flagged_groups += __popcll(gm);
+      const int r0 = grp * G - i0;
+      if (r0 >= 0 && r0 < 64) mine = mine || ((m >> r0) & ((1ull << G) - 1ull)) != 0ull;
+    }
+    int rung = flagged_groups > 0 ? 3 : 0;
+    if (rung != 0 && (precond || (a.rung4_min_groups > 0 && flagged_groups >= a.rung4_min_groups)))
+      rung = 4;
+    if (threadIdx.x == 0) {
+      s_rung = rung;
+      s_mine = (rung == 4 || mine) ? 1 : 0;
+      if (rung != 0 && split == 0 && grp == 0) atomicAdd(a.counts + (rung - 3), 1u);
+    }
+  }
+  __syncthreads();
+  const int rung = s_rung;
+  if (rung == 0 || s_mine == 0) return;
+
+  const int64_t row0 = (int64_t)grp * G;
+  float* ws = a.ws + row0 * a.nsplit * DP_FLOATS;
+  dense_split_work<G>(a.q + row0 * D, a.t2_k + (int64_t)grp * a.max_tokens * D,
+                      a.t2_v + (int64_t)grp * a.max_tokens * D, a.n_tokens, a.tiles_per_split,
+                      a.nsplit, split, ws);
+  // every thread publishes its partial stores device-wide before the workgroup draws its ticket
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* tk = a.tickets + grp;
+    const uint32_t t = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = t == (uint32_t)a.nsplit - 1u;
+    if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    s_last = last ? 1 : 0;
+  }
+  __syncthreads();
+  if (s_last == 0) return;
+  __threadfence();
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int h = idx / D, c = idx % D;
+    const int64_t row = row0 + h;
+    if (rung != 4 && (a.flags[row] & CQA_FLAG_ANY) == 0u) continue;   // Rung 3 serves flagged heads only
+    const float* part = ws + (int64_t)h * a.nsplit * DP_FLOATS;
+    float M = -INFINITY;
+    for (int sidx = 0; sidx < a.nsplit; ++sidx) M = fmaxf(M, part[sidx * DP_FLOATS]);
+    float L = 0.0f, o = 0.0f;
+    for (int sidx = 0; sidx < a.nsplit; ++sidx) {
+      const float f = __expf(part[sidx * DP_FLOATS] - M);
+      L += f * part[sidx * DP_FLOATS + 1];
+      o += f * part[sidx * DP_FLOATS + 4 + c];
+    }
+    a.O[row * D + c] = o / L;
+    if (c == 0) {
+      a.cert[row].E_key = 0.0f;
+      a.cert[row].E_val = 0.0f;
+      a.cert[row].served_rung = rung;
+      a.flags[row] = (a.flags[row] & ~(7u << CQA_RUNG_SHIFT)) | ((uint32_t)rung << CQA_RUNG_SHIFT);
+    }
+  }
+}
+
+int ladder_splits(const Cache* c, int64_t n_tokens) {
+  const int64_t groups = (int64_t)c->desc.batch * c->desc.n_kv_heads;
+  int64_t want = (2 * (int64_t)c->n_cu) / groups;
+  if (want < 4) want = 4;
+  if (want > LADDER_MAX_SPLITS) want = LADDER_MAX_SPLITS;
+  const int64_t tiles = (n_tokens + BLK - 1) / BLK;
+  if (want > tiles) want = tiles;
+  const int64_t tps = (tiles + want - 1) / want;
+  return (int)((tiles + tps - 1) / tps);
+}
+
+int64_t ladder_ws_floats(int64_t rows) { return rows * LADDER_MAX_SPLITS * DP_FLOATS; }
+
+int32_t launch_dense_ladder(Cache* c, int layer, const __half* q, int rung4_min_groups, float* O,
+                            cqa_head_cert* cert, uint32_t* flags, hipStream_t st) {
+  if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  const int64_t len = c->length[layer];
+  if (len <= 0 || q == nullptr || O == nullptr || cert == nullptr || flags == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
+  const int g = hq / hkv;
+  const int64_t layer_head0 = (int64_t)layer * bt * hkv;
+  LadderArgs a{};
+  a.q = q;
+  a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
+  a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
+  a.max_tokens = c->desc.max_tokens;
+  a.n_tokens = len;
+  a.n_rows = bt * hq;
+  a.nsplit = ladder_splits(c, len);
+  const int64_t tiles = (len + BLK - 1) / BLK;
+  a.tiles_per_split = (int)((tiles + a.nsplit - 1) / a.nsplit);
+  a.rung4_min_groups = rung4_min_groups;
+  a.ws = c->ladder_ws;
+  a.tickets = c->ladder_tickets;
+  a.counts = c->ladder_counts;
+  a.O = O;
+  a.cert = cert;
+  a.flags = flags;
+  const dim3 grid(a.nsplit, bt * hkv);
+  switch (g) {
+    case 1: hipLaunchKernelGGL(dense_ladder_kernel<1>, grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL(dense_ladder_kernel<2>, grid, dim3(256), 0, st, a); break;
+    case 4: hipLaunchKernelGGL(dense_ladder_kernel<4>, grid, dim3(256), 0, st, a); break;
+    default: return CQA_ERR_UNSUPPORTED;
+  }
+  CQA_HIP(hipGetLastError());
+  return CQA_OK;
 }
 
 __global__ __launch_bounds__(128) void dense_reduce_kernel(const float* __restrict__ ws, int nsplit,

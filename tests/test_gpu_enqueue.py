@@ -1,0 +1,157 @@
+"""GPU parity of the enqueue-only decode step: the fallback ladder resolved by a device kernel.
+
+Same bars as the host-resolved step: heads that are not served are bit-identical to the certified
+pass, served heads equal the dense FP16 result (1e-3 against the oracle, ~1e-6 against the
+host-resolved ladder, whose dense pass splits the sequence differently), flags and rungs exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import GpuLayerCache, assert_head_matches, load_binding, to_gpu_tol
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def compare_all(gc, ref, O, cert, flags, where):
+    for i, r in enumerate(ref):
+        b, h = divmod(i, gc.hq)
+        assert_head_matches(r, O[b, h], cert[b, h], flags[b, h], (where, b, h))
+
+
+def enqueue(gc, q, tol, k=None, v=None):
+    qd = gc.to_dev(q)
+    kd = None if k is None else gc.to_dev(k)
+    vd = None if v is None else gc.to_dev(v)
+    gc.cqa.cqa_decode_step_enqueue(gc.h, 0, kd, vd, qd, tol, gc.O, gc.cert, gc.flags)
+    return gc.results()
+
+
+def make(seed, bt, hkv, hq, n):
+    rng = np.random.default_rng(seed)
+    k = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    v = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    q = rng.standard_normal((bt, hq, 128)).astype(np.float16)
+    return k, v, q
+
+
+@pytest.mark.parametrize("group", [1, 2, 4])
+def test_every_rung_against_oracle_and_host_ladder(group):
+    say(f"device-resolved ladder, GQA group {group}: no flags, Rung 3 subset, Rung 4 by PRECOND and by group count")
+    bt, hkv, n = 2, 2, 16 * 90 + 11
+    hq = hkv * group
+    k, v, q = make(8 + group, bt, hkv, hq, n)
+    oc = oracle.OracleLayerCache(bt, hkv)
+    oc.append(k, v)
+    with GpuLayerCache(bt, hq, hkv, 2048) as gc:
+        cqa = gc.cqa
+        gc.append(k, v)
+        assert cqa.cqa_ladder_counts(gc.h) == (0, 0)
+        # nothing flagged: exactly the certified pass
+        Oq, certq, flagsq = gc.certified_decode(q)
+        O, cert, flags = enqueue(gc, q, cqa.Tolerances())
+        assert (O == Oq).all() and cert.tobytes() == certq.tobytes() and (flags == flagsq).all()
+        assert cqa.cqa_ladder_counts(gc.h) == (0, 0)
+        # Rung 3 for the heads whose total bound exceeds eps_total (about a third of them)
+        tot = np.sort((certq["E_key"].astype(np.float64) + certq["E_val"]).ravel())
+        cut = len(tot) - max(1, len(tot) // 3)
+        eps = 0.5 * (tot[cut] + tot[cut - 1])
+        tol = oracle.Tolerances(eps_total=eps)
+        ref = oc.decode_step(q, tol)
+        n_served = sum(r["served_rung"] == 3 for r in ref)
+        assert 0 < n_served < bt * hq
+        O, cert, flags = enqueue(gc, q, to_gpu_tol(cqa, tol))
+        compare_all(gc, ref, O, cert, flags, "rung 3")
+        served = cert["served_rung"] == 3
+        assert served.sum() == n_served
+        assert (O[~served] == Oq[~served]).all()
+        rung, Oh, certh, flagsh = gc.decode_step(q, to_gpu_tol(cqa, tol))
+        assert rung == 3 and (flagsh == flags).all() and (certh["served_rung"] == cert["served_rung"]).all()
+        assert np.abs(Oh - O).max() <= 2e-6 * np.abs(Oh).max()
+        assert cqa.cqa_ladder_counts(gc.h) == (1, 0)
+        # Rung 4: a PRECOND flag anywhere serves every head
+        tol4 = oracle.Tolerances(force_flags=oracle.FLAG_PRECOND)
+        O, cert, flags = enqueue(gc, q, to_gpu_tol(cqa, tol4))
+        compare_all(gc, oc.decode_step(q, tol4), O, cert, flags, "rung 4 precond")
+        assert (cert["served_rung"] == 4).all() and (cert["E_key"] == 0).all() and (cert["E_val"] == 0).all()
+        assert (flags == (cqa.FLAG_PRECOND | (4 << cqa.RUNG_SHIFT))).all()
+        # Rung 4 by the number of flagged KV groups
+        groups_flagged = len({(i // hq, (i % hq) // group) for i, r in enumerate(ref) if r["served_rung"] == 3})
+        tolg = oracle.Tolerances(eps_total=eps, rung4_min_groups=groups_flagged)
+        O, cert, flags = enqueue(gc, q, to_gpu_tol(cqa, tolg))
+        compare_all(gc, oc.decode_step(q, tolg), O, cert, flags, "rung 4 by groups")
+        assert (cert["served_rung"] == 4).all()
+        tolg = oracle.Tolerances(eps_total=eps, rung4_min_groups=groups_flagged + 1)
+        O, cert, flags = enqueue(gc, q, to_gpu_tol(cqa, tolg))
+        assert (cert["served_rung"] == np.where(served, 3, 0)).all()
+        assert cqa.cqa_ladder_counts(gc.h) == (2, 2)
+        # the arrival counters are back at zero: the same step again gives the same bits
+        O2, cert2, flags2 = enqueue(gc, q, to_gpu_tol(cqa, tolg))
+        assert (O2 == O).all() and cert2.tobytes() == cert.tobytes() and (flags2 == flags).all()
+
+
+def test_steps_with_appends_match_the_two_calls():
+    say("enqueue-only steps with a token appended each, across seals, one head falling back per step")
+    cqa = load_binding()
+    sh = workloads.SHAPES["l8k"]
+    k, v = workloads.make_kv("l8k", seed=0, context=2048 + 5)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, 2200) as a, \
+            GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, 2200) as b:
+        a.append(k, v)
+        b.append(k, v)
+        served_steps = 0
+        for step in range(36):
+            ks, vs = workloads.make_step_kv("l8k", step, seed=1)
+            q = workloads.make_q("l8k", step, seed=1)
+            kd, vd, qd = a.to_dev(ks), a.to_dev(vs), a.to_dev(q)
+            # tolerance between the two largest totals of this step: exactly one head is flagged
+            a.cqa.cqa_cache_append(a.h, 0, kd, vd, 1)
+            _, certq, _ = a.certified_decode(q)
+            tot = np.sort((certq["E_key"].astype(np.float64) + certq["E_val"]).ravel())
+            flagged = step % 3 != 0 and (tot[-1] - tot[-2]) > 1e-3 * tot[-1]
+            tol = cqa.Tolerances(eps_total=0.5 * (tot[-1] + tot[-2])) if flagged else cqa.Tolerances()
+            rung = a.cqa.cqa_decode_step(a.h, 0, qd, tol, a.O, a.cert, a.flags, None)
+            b.cqa.cqa_decode_step_enqueue(b.h, 0, kd, vd, qd, tol, b.O, b.cert, b.flags)
+            Oa, ca, fa = a.results()
+            Ob, cb, fb = b.results()
+            assert a.length() == b.length() == 2048 + 5 + step + 1
+            assert rung == (3 if flagged else 0)
+            assert (fa == fb).all() and (ca["served_rung"] == cb["served_rung"]).all(), ("step", step)
+            sv = ca["served_rung"] == 3
+            assert sv.sum() == (1 if flagged else 0)
+            served_steps += int(flagged)
+            assert (Oa[~sv] == Ob[~sv]).all(), ("step", step)
+            if flagged:
+                assert np.abs(Oa[sv] - Ob[sv]).max() <= 2e-6 * np.abs(Oa[sv]).max(), ("step", step)
+        assert b.cqa.cqa_ladder_counts(b.h) == (served_steps, 0)
+
+
+def test_error_paths():
+    say("enqueue-only step: error paths")
+    cqa = load_binding()
+    k, v, q = make(3, 1, 2, 8, 40)
+    with GpuLayerCache(1, 8, 2, 41, tier2=False) as gc:
+        gc.append(k, v)
+        with pytest.raises(cqa.CqaError) as e:
+            enqueue(gc, q, cqa.Tolerances())
+        assert e.value.status == cqa.ERR_NO_TIER2
+    with GpuLayerCache(1, 8, 2, 41) as gc:
+        with pytest.raises(cqa.CqaError) as e:      # empty cache, nothing appended
+            enqueue(gc, q, cqa.Tolerances())
+        assert e.value.status == cqa.ERR_INVALID_ARG
+        gc.append(k, v)
+        with pytest.raises(cqa.CqaError) as e:      # only one of k, v
+            gc.cqa.cqa_decode_step_enqueue(gc.h, 0, gc.to_dev(k[:, :, :1]), None, gc.to_dev(q),
+                                           cqa.Tolerances(), gc.O, gc.cert, gc.flags)
+        assert e.value.status == cqa.ERR_INVALID_ARG
+        enqueue(gc, q, cqa.Tolerances(), k[:, :, :1], v[:, :, :1])
+        assert gc.length() == 41
+        with pytest.raises(cqa.CqaError) as e:      # full
+            enqueue(gc, q, cqa.Tolerances(), k[:, :, :1], v[:, :, :1])
+        assert e.value.status == cqa.ERR_CAPACITY
+        assert gc.length() == 41
