@@ -299,6 +299,13 @@ int32_t cqa_adaptive_step(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
                           cqa_head_cert* cert_dev, uint32_t* flags_dev, int32_t* rung_served,
                           void* stream);
 
+/* cqa_adaptive_step as enqueue-only work: the adaptive decode followed by the
+ * device-resolved fallback ladder of cqa_decode_step_enqueue (same rules, same
+ * outputs); never waits for the GPU. */
+int32_t cqa_adaptive_step_enqueue(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                                  const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                                  cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream);
+
 /* Test hook: what the last adaptive decode decided, copied to the host after a
  * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
  * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*

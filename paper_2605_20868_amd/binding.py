@@ -125,6 +125,8 @@ def _load():
                                       vp, vp]),
         "cqa_adaptive_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
                                     vp, C.POINTER(i32), vp]),
+        "cqa_adaptive_step_enqueue": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
+                                            vp, vp]),
         "cqa_adaptive_state": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "cqa_dense_attention": (i32, [vp, vp, vp, i32, i32, i32, i64, vp, vp, vp]),
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
@@ -294,6 +296,13 @@ def cqa_adaptive_step(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, ce
                                   _ptr(cert_dev), _ptr(flags_dev), C.byref(rung), _ptr(stream)),
            "cqa_adaptive_step")
     return rung.value
+
+
+def cqa_adaptive_step_enqueue(h, layer, q_dev, tol: Tolerances, sel: Selector, O_dev, cert_dev, flags_dev,
+                              stream=None) -> None:
+    _check(_lib.cqa_adaptive_step_enqueue(h, layer, _ptr(q_dev), C.byref(tol), C.byref(sel), _ptr(O_dev),
+                                          _ptr(cert_dev), _ptr(flags_dev), _ptr(stream)),
+           "cqa_adaptive_step_enqueue")
 
 
 def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):

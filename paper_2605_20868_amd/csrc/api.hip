@@ -755,6 +755,20 @@ int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                           rung_served, stream);
 }
 
+int32_t cqa_adaptive_step_enqueue(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                                  const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
+                                  cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream) {
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  if (rc != CQA_OK) return rc;
+  rc = check_selector(h, sel);
+  if (rc != CQA_OK) return rc;
+  rc = launch_adaptive(&h->impl, layer, (const __half*)q_fp16_dev, *tol, *sel, O_dev, cert_dev,
+                       flags_dev, nullptr, 0u, (hipStream_t)stream);
+  if (rc != CQA_OK) return rc;
+  return launch_dense_ladder(&h->impl, layer, (const __half*)q_fp16_dev, tol->rung4_min_groups,
+                             O_dev, cert_dev, flags_dev, (hipStream_t)stream);
+}
+
 int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
                            int32_t* selected_host, uint8_t* promoted_host,
                            float* logmass_int8_host, float* logmass_mixed_host,

@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void dense_ladder_kernel(LadderArgs a) {
 
 int ladder_splits(const Cache* c, int64_t n_tokens) {
   const int64_t groups = (int64_t)c->desc.batch * c->desc.n_kv_heads;
-  int64_t want = (2 * (int64_t)c->n_cu) / groups;
+  int64_t want = (2 * (int64_t)c->n_cu) / groups;   // the launch's cost does not depend on it
   if (want < 4) want = 4;
   if (want > LADDER_MAX_SPLITS) want = LADDER_MAX_SPLITS;
   const int64_t tiles = (n_tokens + BLK - 1) / BLK;

@@ -49,7 +49,9 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
     _, cert0, _ = gc.results()
     rung = None
-    if step:
+    if step == "enqueue":
+        cqa.cqa_adaptive_step_enqueue(gc.h, 0, qd, gtol, gsel, gc.O, gc.cert, gc.flags)
+    elif step:
         rung = cqa.cqa_adaptive_step(gc.h, 0, qd, gtol, gsel, gc.O, gc.cert, gc.flags)
     else:
         cqa.cqa_adaptive_decode(gc.h, 0, qd, gtol, gsel, gc.O, gc.cert, gc.flags)
@@ -226,6 +228,16 @@ def test_adaptive_ranking_check_and_ladder():
         assert stepped["rung"] == 3 and (0, 5) in flagged
         check_against_oracle(oc, q, tol, sel, stepped, served=flagged)
         say(f"  heads served by Rung 3: {sorted(h for (_, h) in flagged)}")
+        # the same step with the ladder resolved on the device
+        enq = gpu_adaptive(gc, q, tol, sel, step="enqueue")
+        check_against_oracle(oc, q, tol, sel, enq, served=flagged)
+        assert (enq["flags"] == stepped["flags"]).all()
+        assert (enq["cert"]["served_rung"] == stepped["cert"]["served_rung"]).all()
+        sv = enq["cert"]["served_rung"] == 3
+        assert (enq["O"][~sv] == stepped["O"][~sv]).all()
+        # (two dense passes that split the sequence differently; the planted head's two dominant
+        # values nearly cancel, so the bar is absolute: 2e-6 of the largest value magnitude)
+        assert np.abs(enq["O"][sv] - stepped["O"][sv]).max() <= 2e-6 * float(np.abs(v.astype(np.float32)).max())
 
 
 def test_adaptive_value_promotion():

@@ -351,6 +351,21 @@ def test_t128k_steps():
             b, h = np.argwhere(cert2["served_rung"] == 3)[0]
             dense = oracle.softmax_attention(q[b, h], oc.k16[b, h // 4], oc.v16[b, h // 4])
             assert np.linalg.norm(O2[b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+            # the same step enqueue-only (the launch configuration bench.py times): the ladder
+            # kernel serves the head from the pinned originals, everything else is untouched
+            gc.cqa.cqa_decode_step_enqueue(gc.h, 0, None, None, gc.to_dev(q), gc.cqa.Tolerances(eps_total=eps),
+                                           gc.O, gc.cert, gc.flags)
+            O3, cert3, flags3 = gc.results()
+            assert (flags3 == flags2).all() and (cert3["served_rung"] == cert2["served_rung"]).all()
+            sv = cert3["served_rung"] == 3
+            assert (O3[~sv] == O2[~sv]).all() and (O3[~sv] == O[~sv]).all()
+            assert np.linalg.norm(O3[b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+            assert np.abs(O3[b, h] - O2[b, h]).max() <= 2e-6 * np.abs(O2[b, h]).max()
+        # and with nothing flagged it is the certified pass, bit for bit
+        gc.cqa.cqa_decode_step_enqueue(gc.h, 0, None, None, gc.to_dev(q), gc.cqa.Tolerances(), gc.O, gc.cert,
+                                       gc.flags)
+        O4, cert4, flags4 = gc.results()
+        assert (O4 == O).all() and cert4.tobytes() == cert.tobytes() and (flags4 == flags).all()
 
 
 def test_append_decode_step_equals_the_two_calls():
