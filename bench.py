@@ -130,8 +130,8 @@ def bench_small(args, name) -> int:
         Op, certp, flagsp = O.data_ptr(), cert.data_ptr(), flags.data_ptr()
 
         def step(i, t):
-            return cqa.cqa_append_decode_step(h, 0, kp + i * kv_stride, vp + i * kv_stride,
-                                              qp + i * q_stride, t, Op, certp, flagsp, stream)
+            cqa.cqa_decode_step_enqueue(h, 0, kp + i * kv_stride, vp + i * kv_stride,
+                                        qp + i * q_stride, t, Op, certp, flagsp, stream)
 
         for i in range(W):
             step(i, tol)
@@ -269,7 +269,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--context", type=int, default=None, help="override the context length (debug)")
-    ap.add_argument("--workload", default=WORKLOAD, choices=[WORKLOAD, "stack", "tiny", "l8k", "mixed32k"],
+    ap.add_argument("--workload", default=WORKLOAD, choices=[WORKLOAD, "stack", "tiny", "l8k", "mixed32k", "serve64"],
                     help="t128k (default, the headline line); stack: 32 layers x batch 2 x 128K, a step = append + "
                          "decode step on every layer (layer-steps/s); tiny / l8k / mixed32k: the small parity "
                          "workloads, reported for the results table only")

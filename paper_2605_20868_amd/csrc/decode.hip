@@ -501,9 +501,11 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
     if (c->variant == 0 || a.score_only) {
-      // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction
-      // (measured slower than the separate launch: the reduction is a chain of dependent
-      // device-scope round trips either way, and fused it also extends the big kernel)
+      // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction.
+      // Measured no faster than the separate launch, with many splits (60.4 against 59.7 us at
+      // 128K) and with one split per group (batch 64 x 4K tokens: 129.1 against 130.2 us per
+      // step): the reduction is a chain of dependent device-scope round trips either way, and
+      // fused it extends the big kernel.  Kept as a probe; tested for identical bits.
       fused = c->debug == 3;
       const int32_t rc = launch_split_mfma(a, ra, fused ? c->tickets + layer_head0 : nullptr,
                                            hq / hkv, grid, ev0, ev1, st);

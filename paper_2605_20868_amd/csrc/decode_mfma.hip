@@ -190,8 +190,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const int64_t grp = (int64_t)b * a.n_kv + kvh;
     const uint32_t kx = reinterpret_cast<const uint32_t*>(a.ap_k_new + grp * D)[l];
     const uint32_t vx = reinterpret_cast<const uint32_t*>(a.ap_v_new + grp * D)[l];
-    reinterpret_cast<uint32_t*>(a.ap_trail_k + (grp * BLK + a.ap_slot) * D)[l] = kx;
-    reinterpret_cast<uint32_t*>(a.ap_trail_v + (grp * BLK + a.ap_slot) * D)[l] = vx;
+    // device-scope stores: with the fused reduction a workgroup on another XCD reads them
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(a.ap_trail_k + (grp * BLK + a.ap_slot) * D) + l, kx,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(a.ap_trail_v + (grp * BLK + a.ap_slot) * D) + l, vx,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.ap_t2_k != nullptr) {
       reinterpret_cast<uint32_t*>(a.ap_t2_k + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = kx;
       reinterpret_cast<uint32_t*>(a.ap_t2_v + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = vx;

@@ -192,28 +192,48 @@ template <int G>
 __global__ __launch_bounds__(256) void dense_ladder_kernel(LadderArgs a) {
   const int split = blockIdx.x, grp = blockIdx.y;
   __shared__ int s_rung, s_mine, s_last;
-  if (threadIdx.x < 64) {
+  __shared__ int s_cnt[4], s_pre[4], s_my[4];
+  {
+    // each wave takes every fourth chunk of 64 flag words (a group's heads never straddle a
+    // chunk: G divides 64), four chunks per trip with all loads issued first
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
     int flagged_groups = 0;
     bool precond = false, mine = false;
-    for (int i0 = 0; i0 < a.n_rows; i0 += 64) {   // groups never straddle a chunk: G divides 64
-      const int i = i0 + (int)threadIdx.x;
-      const uint32_t f = i < a.n_rows ? a.flags[i] : 0u;
-      const uint64_t m = __ballot((f & CQA_FLAG_ANY) != 0u);
-      precond = precond || __ballot((f & CQA_FLAG_PRECOND) != 0u) != 0ull;
-      uint64_t gm = m;
+    for (int base = 0; base < a.n_rows; base += 1024) {
+      uint32_t f[4];
 #pragma unroll
-      for (int j = 1; j < G; ++j) gm |= m >> j;
-      gm &= G == 1 ? ~0ull : (G == 2 ? 0x5555555555555555ull : 0x1111111111111111ull);
-      flagged_groups += __popcll(gm);
-      const int r0 = grp * G - i0;
-      if (r0 >= 0 && r0 < 64) mine = mine || ((m >> r0) & ((1ull << G) - 1ull)) != 0ull;
+      for (int j = 0; j < 4; ++j) {
+        const int i = base + (j * 4 + w) * 64 + l;
+        f[j] = i < a.n_rows ? a.flags[i] : 0u;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i0 = base + (j * 4 + w) * 64;
+        const uint64_t m = __ballot((f[j] & CQA_FLAG_ANY) != 0u);
+        precond = precond || __ballot((f[j] & CQA_FLAG_PRECOND) != 0u) != 0ull;
+        uint64_t gm = m;
+#pragma unroll
+        for (int jj = 1; jj < G; ++jj) gm |= m >> jj;
+        gm &= G == 1 ? ~0ull : (G == 2 ? 0x5555555555555555ull : 0x1111111111111111ull);
+        flagged_groups += __popcll(gm);
+        const int r0 = grp * G - i0;
+        if (r0 >= 0 && r0 < 64) mine = mine || ((m >> r0) & ((1ull << G) - 1ull)) != 0ull;
+      }
     }
-    int rung = flagged_groups > 0 ? 3 : 0;
-    if (rung != 0 && (precond || (a.rung4_min_groups > 0 && flagged_groups >= a.rung4_min_groups)))
-      rung = 4;
+    if (l == 0) {
+      s_cnt[w] = flagged_groups;
+      s_pre[w] = precond ? 1 : 0;
+      s_my[w] = mine ? 1 : 0;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+      const int cnt = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+      const bool pre = (s_pre[0] | s_pre[1] | s_pre[2] | s_pre[3]) != 0;
+      const bool my = (s_my[0] | s_my[1] | s_my[2] | s_my[3]) != 0;
+      int rung = cnt > 0 ? 3 : 0;
+      if (rung != 0 && (pre || (a.rung4_min_groups > 0 && cnt >= a.rung4_min_groups))) rung = 4;
       s_rung = rung;
-      s_mine = (rung == 4 || mine) ? 1 : 0;
+      s_mine = (rung == 4 || my) ? 1 : 0;
       if (rung != 0 && split == 0 && grp == 0) atomicAdd(a.counts + (rung - 3), 1u);
     }
   }

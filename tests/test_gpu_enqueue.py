@@ -155,3 +155,40 @@ def test_error_paths():
             enqueue(gc, q, cqa.Tolerances(), k[:, :, :1], v[:, :, :1])
         assert e.value.status == cqa.ERR_CAPACITY
         assert gc.length() == 41
+
+
+def test_serve64_batched_shape():
+    say("serve64: batch 64 x 4096 tokens (one split per KV group), sampled sequences against the oracle, "
+        "ladder over 2048 heads")
+    cqa = load_binding()
+    sh = workloads.SHAPES["serve64"]
+    k, v = workloads.make_kv("serve64", seed=0)
+    q = workloads.make_q("serve64", 0, seed=0)
+    rows = [0, 17, 63]
+    oc = oracle.OracleLayerCache(len(rows), sh.n_kv_heads)
+    oc.append(k[rows], v[rows])
+    ref = oc.certified_decode(q[rows], oracle.Tolerances())
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 16) as gc:
+        gc.append(k, v)
+        assert cqa.cqa_decode_splits(gc.h, 0) == 1
+        Oq, certq, flagsq = gc.certified_decode(q)
+        for i, r in enumerate(ref):
+            b, h = rows[i // sh.n_q_heads], i % sh.n_q_heads
+            assert_head_matches(r, Oq[b, h], certq[b, h], flagsq[b, h], ("serve64", b, h))
+        # a tolerance that flags the seven heads with the largest totals; the device-resolved ladder
+        # serves exactly those, everything else stays bit-identical to the certified pass
+        tot = (certq["E_key"].astype(np.float64) + certq["E_val"]).ravel()
+        order = np.argsort(tot)
+        assert tot[order[-7]] - tot[order[-8]] > 1e-4 * tot[order[-7]]
+        eps = 0.5 * (tot[order[-7]] + tot[order[-8]])
+        O, cert, flags = enqueue(gc, q, cqa.Tolerances(eps_total=float(eps)))
+        sv = cert["served_rung"] == 3
+        assert sorted(np.flatnonzero(sv.ravel())) == sorted(order[-7:])
+        assert (O[~sv] == Oq[~sv]).all() and (flags[~sv] == flagsq[~sv]).all()
+        assert (flags[sv] == (cqa.FLAG_TOTAL | (3 << cqa.RUNG_SHIFT))).all()
+        g = sh.n_q_heads // sh.n_kv_heads
+        for b, h in np.argwhere(sv):
+            dense = oracle.softmax_attention(q[b, h], k[b, h // g], v[b, h // g])
+            assert np.linalg.norm(O[b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6, (b, h)
+            assert cert["E_key"][b, h] == 0 and cert["E_val"][b, h] == 0
+        assert cqa.cqa_ladder_counts(gc.h) == (1, 0)

@@ -422,3 +422,33 @@ def test_stream_hint_does_not_change_results():
             assert (o[2] == out[0][2]).all() and (o[3] == out[0][3]).all()
         with pytest.raises(gc.cqa.CqaError):
             gc.cqa.cqa_set_stream_hint(gc.h, 3)
+
+
+def test_fused_reduction_gives_the_same_bits():
+    say("reduction fused into the split kernel (a probe mode) against the separate launch")
+    rng = np.random.default_rng(29)
+    bt, hkv, hq, n = 2, 2, 8, 16 * 130 + 5
+    k = (rng.standard_normal((bt, hkv, n, 128)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    q = rng.standard_normal((bt, hq, 128)).astype(np.float16)
+    k1 = rng.standard_normal((bt, hkv, 1, 128)).astype(np.float16)
+    v1 = rng.standard_normal((bt, hkv, 1, 128)).astype(np.float16)
+    with GpuLayerCache(bt, hq, hkv, 4096) as a, GpuLayerCache(bt, hq, hkv, 4096) as b:
+        a.append(k, v)
+        b.append(k, v)
+        for splits, variant in ((0, 0x300), (1, 0x300), (3, 0x300)):
+            a.cqa.cqa_set_splits(a.h, splits)
+            b.cqa.cqa_set_splits(b.h, splits)
+            a.cqa.cqa_set_kernel_variant(a.h, 0)          # separate reduction
+            b.cqa.cqa_set_kernel_variant(b.h, variant)    # 0x300: fused
+            Oa, ca, fa = a.certified_decode(q)
+            Ob, cb, fb = b.certified_decode(q)
+            assert (Oa == Ob).all() and ca.tobytes() == cb.tobytes() and (fa == fb).all(), splits
+            # a token that rides on the launch is read back by the fused reduction of the same launch
+            tol = a.cqa.Tolerances()
+            a.cqa.cqa_cache_append(a.h, 0, a.to_dev(k1), a.to_dev(v1), 1)
+            a.cqa.cqa_certified_decode(a.h, 0, a.to_dev(q), tol, a.O, a.cert, a.flags, None)
+            b.cqa.cqa_append_decode_step(b.h, 0, b.to_dev(k1), b.to_dev(v1), b.to_dev(q), tol, b.O, b.cert, b.flags)
+            Oa, ca, fa = a.results()
+            Ob, cb, fb = b.results()
+            assert (Oa == Ob).all() and ca.tobytes() == cb.tobytes() and (fa == fb).all(), ("ride", splits)

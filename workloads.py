@@ -51,6 +51,8 @@ SHAPES = {
     "mixed32k": Shape("mixed32k", 4, 32, 8, 32768, 1),
     "t128k": Shape("t128k", 1, 32, 8, 131072, 16),
     "stack": Shape("stack", 2, 32, 8, 131072, 8, n_layers=32),
+    # batched serving: many short sequences, one split per KV group
+    "serve64": Shape("serve64", 64, 32, 8, 4096, 1),
 }
 
 
@@ -99,7 +101,7 @@ def make_kv(name: str, seed: int = 0, layer: int = 0, context: int | None = None
     shape = (bt, hkv, n, sh.head_dim)
     rk = _rng(seed, name, layer, "K")
     rv = _rng(seed, name, layer, "V")
-    if name in ("t128k", "stack"):
+    if name in ("t128k", "stack", "serve64"):
         k = student_t3_f16(rk, shape)
     else:
         k = normal_f16(rk, shape)
@@ -122,7 +124,7 @@ def make_step_kv(name: str, step: int, seed: int = 0, layer: int = 0,
     shape = (bt, hkv, 1, sh.head_dim)
     rk = _rng(seed, name, layer, "Kstep", step)
     rv = _rng(seed, name, layer, "Vstep", step)
-    if name in ("t128k", "stack"):
+    if name in ("t128k", "stack", "serve64"):
         k = student_t3_f16(rk, shape)
     else:
         k = normal_f16(rk, shape)
