@@ -462,6 +462,8 @@ struct AdaptiveReduceArgs {
   int64_t slot_stride;
   float* alpha_out;      // [Bt][Hq]
   const float* score_dev;  // [Bt][Hq] canary deviations, or null
+  const float* eta;      // [Bt][Hkv][nb] value annotations eta_b written by the pass over all blocks
+  int pos_set0, pos_set1;  // the promoted-block pass's positive partial sets
 };
 
 // One workgroup per (batch, query head): all threads scan the block log-masses of both passes
@@ -482,11 +484,12 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   const float lse8 = ra.cert[row].lse;
   const float delta = ra.cert[row].delta_h;
 
-  float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY;
+  const float* eta = a.eta + grp * ra.nb;
+  float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY, maxc8 = 0.0f;
   int ix = -1, i8 = -1;
-  double tail_mass = 0.0;
+  double tail_mass = 0.0, l8u = 0.0, ev8u = 0.0;
   for (int base = 0; base < ra.nb; base += 256 * BATCH) {
-    float b8[BATCH], bx[BATCH];
+    float b8[BATCH], bx[BATCH], be[BATCH];
     int bs[BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {       // all loads of the batch first
@@ -494,7 +497,8 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
       const bool in = i < ra.nb;
       b8[j] = in ? l8[i] : 0.0f;
       bs[j] = in ? slot[i] : 0;
-      bx[j] = in ? lx[i] : 0.0f;            // unpromoted blocks: the matrix-core pass's value, unused
+      bx[j] = in ? lx[i] : 0.0f;            // written for listed blocks only; used for key-promoted ones
+      be[j] = in ? eta[i] : 0.0f;
     }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
@@ -512,14 +516,22 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
           i8 = i;
         }
       } else {
+        const float mass = expf(v8 - lse8);
         tail_max = fmaxf(tail_max, v8);
-        tail_mass += (double)expf(v8 - lse8);
+        tail_mass += (double)mass;
+        if (bs[j] == 0) {
+          // not listed: the promoted-block pass does not revisit it, it keeps its INT8 mass
+          // and its eta_b
+          l8u += (double)mass;
+          ev8u += (double)(mass * be[j]);
+          maxc8 = fmaxf(maxc8, mass * be[j]);
+        }
       }
     }
   }
-  __shared__ float s_bx[256], s_b8[256], s_tm[256];
+  __shared__ float s_bx[256], s_b8[256], s_tm[256], s_mc[256];
   __shared__ int s_ix[256], s_i8[256];
-  __shared__ double s_mass[256];
+  __shared__ double s_mass[256], s_l8u[256], s_ev8u[256];
   __shared__ float wsm[64];
   __shared__ AdaptiveIn s_ad;
   s_bx[tid] = best_x;
@@ -527,7 +539,10 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   s_b8[tid] = best_8;
   s_i8[tid] = i8;
   s_tm[tid] = tail_max;
+  s_mc[tid] = maxc8;
   s_mass[tid] = tail_mass;
+  s_l8u[tid] = l8u;
+  s_ev8u[tid] = ev8u;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) {
     if (tid < s) {
@@ -545,7 +560,10 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
         s_i8[tid] = oi8;
       }
       s_tm[tid] = fmaxf(s_tm[tid], s_tm[tid + s]);
+      s_mc[tid] = fmaxf(s_mc[tid], s_mc[tid + s]);
       s_mass[tid] += s_mass[tid + s];
+      s_l8u[tid] += s_l8u[tid + s];
+      s_ev8u[tid] += s_ev8u[tid + s];
     }
     __syncthreads();
   }
@@ -561,6 +579,12 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
     const bool boundary = s_ix[0] >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > s_bx[0];
     ad.rank_fail = (disagree || boundary) ? 1 : 0;
     ad.precond = (a.score_dev != nullptr && a.score_dev[row] > delta + ra.tol.eps_guard) ? 1 : 0;
+    ad.pos_set0 = a.pos_set0;
+    ad.pos_set1 = a.pos_set1;
+    ad.L8u = (float)s_l8u[0];
+    ad.EV8u = (float)s_ev8u[0];
+    ad.maxc8 = s_mc[0];
+    ad.lse8 = lse8;
     s_ad = ad;
     a.alpha_out[row] = ad.alpha;
   }
@@ -580,19 +604,24 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   const int r = (int)(len % BLK);
   AdaptiveWs& w = c->ad;
 
-  // ---- 1. scoring pass: every threshold off (its flags are overwritten below), log-masses out
+  // ---- 1. one pass over all sealed blocks in INT8 / INT4 (the ordinary certified pass): block
+  //         log-masses, eta_b and the partial sets the promoted-block pass will correct.  Every
+  //         threshold is off: its certificate only feeds the selector (lse, Delta_h, V_max) and
+  //         is overwritten below.
+  int nsplit = 0, bps = 0;
+  split_geometry(c, nb, &nsplit, &bps);
+  const int total = nsplit + 2 * PROM_SPLITS;
   cqa_tolerances loose = tol;
   loose.eps_total = loose.eps_key = loose.eps_val = loose.v_tol = INFINITY;
   loose.rank_depth = 0;
   loose.force_flags = 0;
-  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st,
-                                /*score_only=*/nb > 0);
-  if (rc != CQA_OK) return rc;
   if (nb == 0) {
-    // nothing sealed: the scoring pass (exact trailing tokens only) is the answer; rerun it
-    // with the caller's thresholds so the flag words and the mirror are the caller's
+    // nothing sealed: the exact trailing tokens are the answer, with the caller's thresholds
     return launch_certified(c, layer, q, tol, O, cert, flags, flags_mirror, mirror_tag, nullptr, st);
   }
+  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st, false,
+                                nullptr, nullptr, total, w.eta_blk);
+  if (rc != CQA_OK) return rc;
 
   // ---- 2. selection per head (+ Rung 1), union bit mask per group
   SelectArgs sa{};
@@ -657,10 +686,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
 
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
 
-  // ---- 4. attend pass: matrix-core pass without the promoted blocks + promoted-block pass
-  int nsplit = 0, bps = 0;
-  split_geometry(c, nb, &nsplit, &bps);
-  const int total = nsplit + PROM_SPLITS;
+  // ---- 4. promoted-block pass: the listed blocks once more with the originals their flags ask
+  //         for (positive sets) and once as the first pass saw them (negated sets)
   ReduceArgs ra{};
   ra.partials = c->partials;
   ra.q = q;
@@ -691,7 +718,6 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.n_q = hq;
   a.n_kv = hkv;
   a.debug = 0;
-  a.stream_nt = stream_nt(c, nb);
   a.slot = w.slot;
   a.ulist = w.ulist;
   a.ucount = w.ucount;
@@ -702,10 +728,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
   a.score_only = 0;
-  rc = launch_split_mfma(a, ra, nullptr, g, dim3(nsplit, hkv, bt), nullptr, nullptr, st);
-  if (rc != CQA_OK) return rc;
-  CQA_HIP(hipGetLastError());
-  rc = launch_promoted_pass(a, g, dim3(PROM_SPLITS, hkv, bt), st);
+  rc = launch_promoted_pass(a, g, dim3(2 * PROM_SPLITS, hkv, bt), st);
   if (rc != CQA_OK) return rc;
 
   // ---- 5. merge, certificate with the achieved tail, ranking check
@@ -717,6 +740,9 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   ar.slot_stride = c->nq_cap * 4;
   ar.alpha_out = w.alpha;
   ar.score_dev = sel.canary ? w.score_dev : nullptr;
+  ar.eta = w.eta_blk;
+  ar.pos_set0 = nsplit;
+  ar.pos_set1 = nsplit + PROM_SPLITS;
   hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(256), 0, st, ar);
   CQA_HIP(hipGetLastError());
   return CQA_OK;

@@ -52,7 +52,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   if (ms > s.nb_cap) ms = s.nb_cap;
   if (ms < 1) ms = 1;
   s.max_splits = (int)ms;
-  s.partials = (int64_t)d->batch * d->n_q_heads * (s.max_splits + PROM_SPLITS) * PART_FLOATS * 4;
+  s.partials = (int64_t)d->batch * d->n_q_heads * (s.max_splits + 2 * PROM_SPLITS) * PART_FLOATS * 4;
   s.dense_ws = dense_ws_floats(d->n_q_heads / d->n_kv_heads, d->max_tokens) * 4;
   s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
   s.select = (int64_t)d->batch * d->n_q_heads * 4;
@@ -787,8 +787,24 @@ int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
     CQA_HIP(hipMemcpy(selected_host, c->ad.sel, (size_t)rows * MAX_K_LIMIT * 4, hipMemcpyDeviceToHost));
   if (logmass_int8_host && nb > 0)
     CQA_HIP(hipMemcpy(logmass_int8_host, c->ad.lm8, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
-  if (logmass_mixed_host && nb > 0)
+  if (logmass_mixed_host && nb > 0) {
+    // the promoted-block pass writes the log-masses of the listed blocks only: every other block
+    // keeps the one it got in the pass over all blocks
+    std::vector<float> l8((size_t)(rows * nb));
+    std::vector<int32_t> slot((size_t)nb);
     CQA_HIP(hipMemcpy(logmass_mixed_host, c->ad.lmx, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+    CQA_HIP(hipMemcpy(l8.data(), c->ad.lm8, (size_t)(rows * nb) * 4, hipMemcpyDeviceToHost));
+    const int gsz = c->desc.n_q_heads / c->desc.n_kv_heads;
+    for (int64_t gidx = 0; gidx < groups; ++gidx) {
+      CQA_HIP(hipMemcpy(slot.data(), c->ad.slot + gidx * c->nq_cap * 4, (size_t)nb * 4,
+                        hipMemcpyDeviceToHost));
+      for (int i = 0; i < gsz; ++i) {
+        const int64_t row = gidx * gsz + i;    // rows are [batch][q-head], groups [batch][kv-head]
+        for (int64_t blk = 0; blk < nb; ++blk)
+          if (slot[(size_t)blk] == 0) logmass_mixed_host[row * nb + blk] = l8[(size_t)(row * nb + blk)];
+      }
+    }
+  }
   if (score_dev_host)
     CQA_HIP(hipMemcpy(score_dev_host, c->ad.score_dev, (size_t)rows * 4, hipMemcpyDeviceToHost));
   if (v_count_host)

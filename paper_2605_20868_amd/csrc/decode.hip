@@ -55,9 +55,15 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   // blocks are dealt evenly over the splits (every split gets at least one: nsplit <= nb)
   const int64_t grp = (int64_t)b * a.n_kv + kvh;
   // PROM: positions split * 4 + w, + 4 * gridDim.x, ... of the group's list; else a block range
-  const int b0 = PROM ? split * 4 : (int)(((int64_t)split * a.nb) / a.nsplit);
+  // PROM: the second half of the workgroups (neg) walks the same list with INT8 keys and INT4
+  // values whatever the flags say and writes its partial set negated: it takes back what the one
+  // pass over all sealed blocks added for the listed blocks, the first half adds them again with
+  // the originals the flags ask for.
+  const bool neg = PROM && split >= (int)gridDim.x / 2;
+  const int psplit = PROM ? (neg ? split - (int)gridDim.x / 2 : split) : split;
+  const int b0 = PROM ? psplit * 4 : (int)(((int64_t)split * a.nb) / a.nsplit);
   const int b1 = PROM ? min(a.ucount[grp], MAX_UNION) : (int)(((int64_t)(split + 1) * a.nb) / a.nsplit);
-  const int bstep = PROM ? 4 * (int)gridDim.x : 4;
+  const int bstep = PROM ? 2 * (int)gridDim.x : 4;   // PROM: 4 waves x gridDim.x / 2 workgroups
   const int out_split = PROM ? a.split0 + split : split;
   const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
 
@@ -102,7 +108,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     const int blk = PROM ? a.ulist[grp * MAX_UNION + pos] : pos;
     if (PROM && (blk < 0 || blk >= a.nb)) continue;
     const int pf = PROM ? a.slot[grp * (a.nq_cap * 4) + blk] : 0;   // bit 0: FP16 keys, bit 1: FP16 values
-    const bool kfp = PROM && (pf & 1), vfp = PROM && (pf & 2);
+    const bool kfp = PROM && !neg && (pf & 1), vfp = PROM && !neg && (pf & 2);
     // ---- scaled query, per-block constant, per-block score-error bound
     const float* kmb = reinterpret_cast<const float*>(a.t1 + t1_offset(head_rec, blk, Q_KM, KM_BYTES));
     float2 sg = make_float2(1.0f, 1.0f), zz = make_float2(0.0f, 0.0f);
@@ -249,7 +255,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       } else if (lb > t2[h]) {
         t2[h] = lb;
       }
-      if (a.blk_logmass != nullptr && l == 0)
+      if (a.blk_logmass != nullptr && l == 0 && !neg)
         a.blk_logmass[((int64_t)b * a.n_q + kvh * G + h) * a.nb + blk] = lb;
       if (kg == 0) ps[w][tok][h] = p[h];
     }
@@ -332,7 +338,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     float o = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][h][0] - Mr) * mo[(ww * G + h) * D + c];
-    a.partials[(((int64_t)b * a.n_q + kvh * G + h) * a.pstride + out_split) * PART_FLOATS + P_O + c] = o;
+    a.partials[(((int64_t)b * a.n_q + kvh * G + h) * a.pstride + out_split) * PART_FLOATS + P_O + c] =
+        neg ? -o : o;
   }
   if (threadIdx.x < G) {
     const int h = threadIdx.x;
@@ -352,9 +359,9 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     }
     float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + h) * a.pstride + out_split) * PART_FLOATS;
     pp[P_M] = M;
-    pp[P_L] = L;
-    pp[P_EV] = EV;
-    pp[P_EVMAX] = EVM;
+    pp[P_L] = neg ? -L : L;
+    pp[P_EV] = neg ? -EV : EV;
+    pp[P_EVMAX] = neg ? 0.0f : EVM;
     pp[P_DMAX] = DM;
     pp[P_VMAX] = VM;
     pp[P_T1] = T1;
@@ -429,7 +436,7 @@ int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStrea
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st, bool score_only,
-                         const __half* k_new, const __half* v_new) {
+                         const __half* k_new, const __half* v_new, int pstride, float* eta_out) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
@@ -449,6 +456,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   ra.mirror_tag = mirror_tag;
   ra.tol = tol;
   ra.nsplit = nsplit;
+  ra.pstride = pstride;
   ra.nb = (int)nb;
   ra.r = r;
   ra.n_q = hq;
@@ -464,7 +472,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.nq_cap = c->nq_cap;
     a.nb = (int)nb;
     a.nsplit = nsplit;
-    a.pstride = nsplit;
+    a.pstride = pstride > 0 ? pstride : nsplit;
     a.slot = nullptr;
     a.ulist = nullptr;
     a.ucount = nullptr;
@@ -475,7 +483,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.max_tokens = 0;
     a.split0 = 0;
     a.score_only = (score_only && blk_logmass != nullptr) ? 1 : 0;   // always the matrix-core kernel
-    a.eta_out = a.score_only ? c->ad.eta_blk : nullptr;
+    a.eta_out = a.score_only ? c->ad.eta_blk : (blk_logmass != nullptr ? eta_out : nullptr);
     if (k_new != nullptr) {
       // the caller has already counted the new token in length[layer]: it is token len - 1
       if (c->variant != 0 || r == 0) return CQA_ERR_INVALID_ARG;   // needs this kernel and an open block
@@ -500,7 +508,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
-    if (c->variant == 0 || a.score_only) {
+    if (c->variant == 0 || a.score_only || a.eta_out != nullptr) {   // eta_b comes from this kernel only
       // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction.
       // Measured no faster than the separate launch, with many splits (60.4 against 59.7 us at
       // 128K) and with one split per group (batch 64 x 4K tokens: 129.1 against 130.2 us per

@@ -460,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
           if (live[i])
             a.blk_logmass[((int64_t)b * a.n_q + kvh * G + kg) * a.nb + qb + i] = lbv[i];
       }
-      if (SCORE && a.eta_out != nullptr && l == 0) {
+      if (a.eta_out != nullptr && l == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           if (qb + i < b1) a.eta_out[((int64_t)b * a.n_kv + kvh) * a.nb + qb + i] = an[i].x;

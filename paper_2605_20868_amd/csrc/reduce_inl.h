@@ -26,6 +26,7 @@ struct ReduceArgs {
   uint32_t mirror_tag;     // OR-ed into each mirrored word (bits 16-31): the host polls for it
   cqa_tolerances tol;
   int nsplit, nb, r, n_q, n_kv;
+  int pstride;           // partial sets per (batch, q-head) row of `partials`; 0 = nsplit
 };
 
 __device__ __forceinline__ void top2_merge_r(float& t1, int& i1, float& t2, float u1, int j1,
@@ -128,6 +129,15 @@ struct AdaptiveIn {
   int top_block;     // the promoted block with the largest FP16 log-mass (-1 if none)
   int rank_fail;     // the two rankings disagree on the top block, or the boundary test failed
   int precond;       // the score-consistency check found a score outside its declared bound
+  // The partial sets outside [pos_set0, pos_set1) -- the one pass over all sealed blocks and the
+  // negated sets that take the listed blocks back out of it -- contribute their output
+  // accumulators only.  A difference of two nearly equal sums would leave the certificate's
+  // scalars with the rounding of the large terms, so the mass, the value term and the largest
+  // rho_b eta_b of the blocks that are NOT listed come from the scan over the block log-masses
+  // instead, relative to the first pass's lse8:  L8u = sum exp(l_b - lse8),
+  // EV8u = sum exp(l_b - lse8) eta_b,  maxc8 = max exp(l_b - lse8) eta_b.
+  int pos_set0, pos_set1;
+  float L8u, EV8u, maxc8, lse8;
 };
 
 // wsm: wave-private LDS scratch of at least 64 floats.  All 64 lanes of the wave must call.
@@ -141,7 +151,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
   const int l = threadIdx.x & 63;
   const int kvh = hq / (a.n_q / a.n_kv);
   const float inv_sqrt_d = 0.08838834764831845f;
-  const float* part = a.partials + ((int64_t)b * a.n_q + hq) * a.nsplit * PART_FLOATS;
+  const float* part = a.partials + ((int64_t)b * a.n_q + hq) * (a.pstride > 0 ? a.pstride : a.nsplit) * PART_FLOATS;
 
   // trailing FP16 tokens (at most 15): request them first, they are used last.
   //   scores / norms: lane (t = l >> 2, cpart = l & 3) covers channels 32 cpart .. 32 cpart + 31 of
@@ -184,9 +194,10 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     const float fo = __expf(M - Mn);        // rescales what earlier chunks accumulated
     const float f = on ? __expf(m - Mn) : 0.0f;
     wsm[l] = f;
-    L = L * fo + wave_sum(f * sc[P_L]);
-    EV = EV * fo + wave_sum(f * sc[P_EV]);
-    EVM = fmaxf(EVM * fo, wave_max(f * sc[P_EVMAX]));
+    const float fc = (ad == nullptr || (s >= ad->pos_set0 && s < ad->pos_set1)) ? f : 0.0f;
+    L = L * fo + wave_sum(fc * sc[P_L]);
+    EV = EV * fo + wave_sum(fc * sc[P_EV]);
+    EVM = fmaxf(EVM * fo, wave_max(fc * sc[P_EVMAX]));
     DM = fmaxf(DM, wave_max(on ? sc[P_DMAX] : 0.0f));
     VM = fmaxf(VM, wave_max(on ? sc[P_VMAX] : 0.0f));
     float u1 = on ? sc[P_T1] : -INFINITY, u2 = on ? sc[P_T2] : -INFINITY;
@@ -208,6 +219,13 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (ad != nullptr) {
+    // the blocks no second pass touched: their mass and value term from the scan
+    const float g8 = __expf(ad->lse8 - M);
+    L += g8 * ad->L8u;
+    EV += g8 * ad->EV8u;
+    EVM = fmaxf(EVM, g8 * ad->maxc8);
   }
   float L_sealed = L;
 
@@ -264,8 +282,8 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
   if (l == 0) {
     // certificate scalars in FP32 (a handful of operations; their rounding is ~1e-7 relative)
     const float e_val = EV / L;
-    const float maxc = EVM / L;
     const float lse = M + logf(L);
+    const float maxc = EVM / L;
     const float alpha_hat = ad != nullptr ? ad->alpha : L_sealed / L;
     const float delta = ad != nullptr ? ad->delta : DM;
     const float vmax = VM;
