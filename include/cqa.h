@@ -261,8 +261,9 @@ typedef struct cqa_selector {
 } cqa_selector;
 
 /* One decode step of `layer` with mask-gated key precision, all on `stream`:
- *  1. scoring pass over the INT8 keys only (no value reads): the INT8 block
- *     log-masses l_b, the total log-mass, Delta_h and V_max of every head;
+ *  1. the certified pass over all sealed blocks (INT8 keys, INT4 values): the
+ *     INT8 block log-masses l_b, the total log-mass, Delta_h and V_max of every
+ *     head, and the partial results that step 4 corrects;
  *  2. selection per head: blocks ranked by l_b (ties: lower index), K* = the
  *     smallest k whose blocks, with the exact trailing tokens, hold >= tau_cov
  *     of the estimated mass, clamped; Rung 1: K doubles (up to k_limit) while
@@ -271,13 +272,15 @@ typedef struct cqa_selector {
  *     selections; value promotion (the ladder's second rung, sel->v_limit > 0)
  *     is decided the same way from the estimated contributions p_b eta_b and
  *     is likewise per group;
- *  4. attend pass: as cqa_certified_decode, but promoted blocks are scored
- *     with their FP16 keys, which the device reads straight from the pinned
- *     Tier-2 originals (no host step, no staging); values are INT4 except
+ *  4. the result is that of cqa_certified_decode with the promoted blocks
+ *     scored from their FP16 keys, which the device reads straight from the
+ *     pinned Tier-2 originals (no host step, no staging); values are INT4 except
  *     in value-promoted blocks, which are attended from their FP16 originals
- *     and count with eta_b = 0; E_val uses the masses of this pass;
- *     E_key uses alpha_hat_T = the scoring pass's estimated mass of the blocks
- *     the group left in INT8, and the scoring pass's Delta_h;
+ *     and count with eta_b = 0.  It is formed without a second pass over
+ *     Tier-1: a small pass revisits the promoted blocks only, adds them with
+ *     their originals and takes their step-1 contribution back out.  E_val uses
+ *     the masses of the corrected result; E_key uses alpha_hat_T = step 1's
+ *     estimated mass of the blocks the group left in INT8, and step 1's Delta_h;
  *  5. ranking check at depth 1 (if tol->rank_depth >= 1): RANK is set when the
  *     promoted block with the largest FP16 log-mass is not the one with the
  *     largest INT8 log-mass, or when an unpromoted block has

@@ -8,12 +8,15 @@
 // verification, at depth 1.  Key precision is chosen per KV group (the union of the group's
 // query heads' selections): the paper's per-KV-group selection variant.
 //
-// Sequence on one stream (launch_adaptive): scoring pass (the certified decode kernel in a form that
-// only reads keys and emits the INT8 block log-masses) -> select_kernel (per head) ->
-// compact_kernel (per group: union bit mask -> slot map and ordered list) -> attend pass =
-// matrix-core split pass that leaves promoted blocks out + promoted-block pass, which reads the
-// FP16 keys of the listed blocks straight from the pinned Tier-2 originals over the host link ->
-// adaptive_reduce_kernel.
+// Sequence on one stream (launch_adaptive): the certified pass over all sealed blocks in INT8 /
+// INT4 (it emits the block log-masses, eta_b and the usual partial sets, and its reduction the
+// total log-mass, Delta_h and V_max the selector needs) -> select_kernel (per head) ->
+// compact_kernel (per group: union bit mask -> per-block flags and ordered list) -> promoted-block
+// pass over the listed blocks only: positive partial sets computed with the originals the flags ask
+// for (read straight from the pinned Tier-2 arrays over the host link) and negated sets computed as
+// the first pass did, so that the merge replaces those blocks' contribution -> adaptive_reduce_kernel.
+// Tier-1 is read once per step; the paper's two passes (score, then attend) become one pass plus a
+// correction for a few dozen blocks.
 #include <algorithm>
 
 #include "cqa_internal.h"
@@ -34,7 +37,7 @@ __device__ __forceinline__ uint32_t ord32(float f) {
 
 struct SelectArgs {
   const float* lm8;            // [Bt][Hq][nb]: the row that is ranked (log-masses, or contributions)
-  const cqa_head_cert* cert;   // scoring pass: lse, delta_h, v_max
+  const cqa_head_cert* cert;   // first pass: lse, delta_h, v_max
   int32_t* sel;                // [Bt][Hq][MAX_K_LIMIT]
   int32_t* kstar;              // [Bt][Hq]
   uint32_t* umask;             // [Bt][Hkv][mask_words]
@@ -479,7 +482,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   const float* l8 = a.lm8 + row * ra.nb;
   const float* lx = a.lmx + row * ra.nb;
   const int32_t* slot = a.slot + grp * a.slot_stride;
-  // the scoring pass left its certificate in the caller's array; read what is needed before
+  // the first pass left its certificate in the caller's array; read what is needed before
   // the first wave overwrites it
   const float lse8 = ra.cert[row].lse;
   const float delta = ra.cert[row].delta_h;
@@ -619,8 +622,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
     // nothing sealed: the exact trailing tokens are the answer, with the caller's thresholds
     return launch_certified(c, layer, q, tol, O, cert, flags, flags_mirror, mirror_tag, nullptr, st);
   }
-  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st, false,
-                                nullptr, nullptr, total, w.eta_blk);
+  int32_t rc = launch_certified(c, layer, q, loose, O, cert, flags, nullptr, 0u, w.lm8, st, nullptr, nullptr,
+                                total, w.eta_blk);
   if (rc != CQA_OK) return rc;
 
   // ---- 2. selection per head (+ Rung 1), union bit mask per group
@@ -727,7 +730,6 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.score_dev = sel.canary ? w.score_dev : nullptr;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
-  a.score_only = 0;
   rc = launch_promoted_pass(a, g, dim3(2 * PROM_SPLITS, hkv, bt), st);
   if (rc != CQA_OK) return rc;
 

@@ -569,7 +569,7 @@ static int32_t step_with_ladder(cqa_cache* h, int32_t layer, const void* q_fp16_
                          c->flags_host, tag, st);
   else
     rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
-                          c->flags_host, tag, blk_logmass_dev, st, false, k_new, v_new);
+                          c->flags_host, tag, blk_logmass_dev, st, k_new, v_new);
   if (rc != CQA_OK) return rc;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
@@ -714,7 +714,7 @@ int32_t cqa_decode_step_enqueue(cqa_cache* h, int32_t layer, const void* k_fp16_
   }
   if (c->length[layer] <= 0) return CQA_ERR_INVALID_ARG;
   int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
-                                nullptr, 0u, nullptr, (hipStream_t)stream, false, rk, rv);
+                                nullptr, 0u, nullptr, (hipStream_t)stream, rk, rv);
   if (rc != CQA_OK) return rc;
   return launch_dense_ladder(c, layer, (const __half*)q_fp16_dev, tol->rung4_min_groups, O_dev,
                              cert_dev, flags_dev, (hipStream_t)stream);

@@ -94,7 +94,7 @@ constexpr int PROM_SPLITS = 8;              // workgroups (= partial sets) of th
 
 // Workspace of the adaptive path, shared by all layers (one decode step at a time).
 struct AdaptiveWs {
-  float* lm8;        // [Bt][Hq][nb_cap]      INT8 block log-masses of the scoring pass
+  float* lm8;        // [Bt][Hq][nb_cap]      INT8 block log-masses of the pass over all blocks
   float* lmx;        // [Bt][Hq][nb_cap]      block log-masses of the attend pass (FP16 keys where promoted)
   int32_t* sel;      // [Bt][Hq][MAX_K_LIMIT] the head's own selection, best first
   int32_t* kstar;    // [Bt][Hq]              its size after Rung-1 growth
@@ -102,7 +102,7 @@ struct AdaptiveWs {
   uint32_t* umask;   // [Bt][Hkv][mask_words] union of the group's key selections, one bit per block
   uint32_t* vmask;   // [Bt][Hkv][mask_words] union of its value selections
   int32_t* slot;     // [Bt][Hkv][4 nq_cap]   per block: bit 0 = FP16 keys, bit 1 = FP16 values (0 = neither)
-  float* eta_blk;    // [Bt][Hkv][nb_cap]     eta_b as read by the scoring pass
+  float* eta_blk;    // [Bt][Hkv][nb_cap]     eta_b as read by the pass over all blocks
   float* contrib;    // [Bt][Hq][nb_cap]      estimated contributions p_b eta_b
   int32_t* vsel;     // [Bt][Hq][MAX_K_LIMIT] the head's value selection
   int32_t* vcount;   // [Bt][Hq]
@@ -179,9 +179,8 @@ struct DecodeArgs {
   const __half* t2_v;       // value originals, same layout
   int64_t max_tokens;
   int split0;               // promoted-block pass: index of its first partial set
-  int score_only;           // 1 = scoring pass: no value reads, zero partial outputs
   int stream_nt;            // 1 = Tier-1 loads carry the non-temporal hint (see stream_hint)
-  float* eta_out;           // scoring pass: eta_b per (batch, kv-head, block), or null
+  float* eta_out;           // eta_b per (batch, kv-head, block) written alongside the log-masses, or null
   float* score_dev;         // promoted-block pass: canary output per (batch, q-head), or null
   // one-token append carried by the decode launch (null k_new = none): the new (k, v) of every
   // (batch, kv-head) goes to slot `ap_slot` of the trailing FP16 block and, unless ap_t2_k is
@@ -217,7 +216,7 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
-                         bool score_only = false, const __half* k_new = nullptr,
+                         const __half* k_new = nullptr,
                          const __half* v_new = nullptr, int pstride = 0, float* eta_out = nullptr);
 int pick_splits(const Cache* c, int64_t n_blocks);
 int stream_nt(const Cache* c, int64_t n_blocks);

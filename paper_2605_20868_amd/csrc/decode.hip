@@ -435,7 +435,7 @@ int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStrea
 
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
-                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st, bool score_only,
+                         uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
                          const __half* k_new, const __half* v_new, int pstride, float* eta_out) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int64_t len = c->length[layer];
@@ -482,8 +482,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.score_dev = nullptr;
     a.max_tokens = 0;
     a.split0 = 0;
-    a.score_only = (score_only && blk_logmass != nullptr) ? 1 : 0;   // always the matrix-core kernel
-    a.eta_out = a.score_only ? c->ad.eta_blk : (blk_logmass != nullptr ? eta_out : nullptr);
+    a.eta_out = blk_logmass != nullptr ? eta_out : nullptr;
     if (k_new != nullptr) {
       // the caller has already counted the new token in length[layer]: it is token len - 1
       if (c->variant != 0 || r == 0) return CQA_ERR_INVALID_ARG;   // needs this kernel and an open block
@@ -508,7 +507,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
-    if (c->variant == 0 || a.score_only || a.eta_out != nullptr) {   // eta_b comes from this kernel only
+    if (c->variant == 0 || a.eta_out != nullptr) {   // eta_b comes from this kernel only
       // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction.
       // Measured no faster than the separate launch, with many splits (60.4 against 59.7 us at
       // 128K) and with one split per group (batch 64 x 4K tokens: 129.1 against 130.2 us per

@@ -127,14 +127,9 @@ constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: b
 constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
 constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
 
-// MIX: attend pass with gated key precision.  Blocks whose group promoted them to FP16 keys are
-// left out here (their scores get the same huge negative value as blocks past the end, so every
-// weight and mass they produce vanishes, and their log-mass is not written); a second, small
-// kernel attends them from the FP16 keys and adds its own partial sets.
-// SCORE: scoring pass only (the first phase of the two-phase path): no value codes or value
-// metadata are read and no output is accumulated; block log-masses, the softmax mass, Delta_b,
-// nu_b and eta_b statistics are produced as usual and the partial outputs are written as zeros.
-template <int G, bool LM, bool MIX, bool SCORE, bool NT>
+// LM: also writes the block log-masses (and, when asked, eta_b per block) for callers that rank
+// blocks afterwards.  NT: Tier-1 loads carry the non-temporal hint.
+template <int G, bool LM, bool NT>
 __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
                                                                       uint32_t* tickets) {
   const int l = threadIdx.x & 63;
@@ -242,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       kraw[i][CQ] = ld_stream4<NT>(rec + i * KC_BYTES + lo16);                               \
   }
 #define CQA_LOAD_V(QB, P)                                                                \
-  if (!SCORE) {                                                                          \
+  {                                                                                      \
     const uint8_t* rec = CQA_REC(QB) + (Q_VC + (P) * 2 * VC_BYTES);                      \
     vraw[P][0] = ld_stream4<NT>(rec + vo16);                                                 \
     vraw[P][1] = ld_stream4<NT>(rec + 256 + vo16);                                           \
@@ -254,10 +249,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       km_n[i] = ld_stream<NT>(rec + (Q_KM + i * KM_BYTES) + lo16);                           \
       an_n[i] = *reinterpret_cast<const float2*>(rec + (Q_AN + i * AN_BYTES));           \
     }                                                                                    \
-    if (!SCORE) {                                                                        \
-      _Pragma("unroll") for (int P = 0; P < 2; ++P)                                      \
-        vm_n[P] = ld_stream<NT>(rec + (Q_VM + P * 2 * VM_BYTES) + lo16);                     \
-    }                                                                                    \
+    _Pragma("unroll") for (int P = 0; P < 2; ++P)                                        \
+      vm_n[P] = ld_stream<NT>(rec + (Q_VM + P * 2 * VM_BYTES) + lo16);                   \
   }
 
   // The first quad is requested before anything else, so the query set-up below runs under the
@@ -316,23 +309,20 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #ifdef CQA_PROBE_TIMESTAMPS
   if (ts_on) ts[1] = wall_clock64();
 #endif
-  const int32_t* slotrow = MIX ? a.slot + ((int64_t)b * a.n_kv + kvh) * (a.nq_cap * 4) : nullptr;
   for (; qb < b1; qb += 4) {
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
-    bool live[4];   // block is inside this wave's run and scored from its INT8 keys in this pass
+    bool live[4];   // block is inside this wave's run
 #pragma unroll
-    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1 && (!MIX || slotrow[qb + i] == 0);
+    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1;
     float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       an[i] = an_n[i];
       reinterpret_cast<u32x4*>(&kmbuf[w][i][0])[l] = km_n[i];
     }
-    if (!SCORE) {
 #pragma unroll
-      for (int P = 0; P < 2; ++P)
-        reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
-    }
+    for (int P = 0; P < 2; ++P)
+      reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
     CQA_LOAD_META(qb + 4)
     wave_sync_m();
 
@@ -451,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       t2 = g1 ? t1 : (g2 ? lb : t2);
       i1 = g1 ? qb + i : i1;
       t1 = g1 ? lb : t1;
-      if (!SCORE) pbuf[w][kg][i * BLK + n] = ptv[i] * f;
+      pbuf[w][kg][i * BLK + n] = ptv[i] * f;
     }
     if (LM) {
       if (n == 0 && kg < G) {
@@ -470,7 +460,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     wave_sync_m();
 
     __builtin_amdgcn_s_setprio(0);
-    if (SCORE) continue;   // scoring pass: nothing below applies (the K prefetch sits above)
     // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
     if (__any(alpha != 1.0f)) {
 #pragma unroll
@@ -645,23 +634,13 @@ int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* t
 #else
   const bool lm = a.blk_logmass != nullptr;
 #endif
-  const bool mix = a.slot != nullptr;
-  const bool score = a.score_only != 0;
-  if ((mix || score) && !lm) return CQA_ERR_INVALID_ARG;   // both always report block log-masses
-  if (mix && score) return CQA_ERR_INVALID_ARG;
 #define CQA_LAUNCH_NT(GG, NTV)                                                                   \
-  if (score)                                                                                     \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false, true, NTV>), grid,        \
-                          dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);                        \
-  else if (mix)                                                                                  \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, true, false, NTV>), grid,        \
-                          dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);                        \
-  else if (lm)                                                                                   \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, false, false, NTV>), grid,       \
-                          dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);                        \
+  if (lm)                                                                                        \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV>), grid, dim3(256), 0, st,   \
+                          ev0, ev1, 0, a, ra, tickets);                                          \
   else                                                                                           \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, false, false, NTV>), grid,      \
-                          dim3(256), 0, st, ev0, ev1, 0, a, ra, tickets);
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV>), grid, dim3(256), 0, st,  \
+                          ev0, ev1, 0, a, ra, tickets);
 #define CQA_LAUNCH(GG)                                                                           \
   if (a.stream_nt) { CQA_LAUNCH_NT(GG, true) } else { CQA_LAUNCH_NT(GG, false) }
   switch (group) {

@@ -119,11 +119,11 @@ __device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
 
 // What the attend pass with gated key precision substitutes in the certificate (the paper's total
 // error bound with the achieved tail mass, and its ranking-consistency check): the estimated mass
-// of the blocks left in INT8 and Delta_h come from the scoring pass, the ranking verdict from a scan
+// of the blocks left in INT8 and Delta_h come from the first (all-INT8) pass, the ranking verdict from a scan
 // over the block log-masses of both passes.
 struct AdaptiveIn {
-  float alpha;       // sum over unpromoted blocks of the scoring pass's normalised masses
-  float delta;       // Delta_h of the scoring pass
+  float alpha;       // sum over unpromoted blocks of the first pass's normalised masses
+  float delta;       // Delta_h of the first pass
   float top_fp16;    // largest FP16 log-mass among promoted blocks (-inf if none)
   float tail_ub;     // largest unpromoted INT8 log-mass + Delta_h (-inf if none)
   int top_block;     // the promoted block with the largest FP16 log-mass (-1 if none)
