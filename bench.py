@@ -433,12 +433,32 @@ def main() -> int:
         torch.cuda.synchronize()
         adv_ms = (time.perf_counter() - tv0) * 1e3 / n_ad
         vstate = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
+        # the optional FP16-key scratch (off above): switched on, the 20 queries once with an empty
+        # scratch (every promoted block is read from pinned host RAM and kept) and once more (every
+        # promoted block is now held on the device)
+        def timed_adaptive(first, tl, sl):
+            torch.cuda.synchronize()
+            tt = time.perf_counter()
+            for i in range(n_ad):
+                cqa.cqa_adaptive_step(h, 0, qp + (first + i) * q_stride, tl, sl, Op, certp, flagsp, stream)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - tt) * 1e3 / n_ad
+        cqa.cqa_set_scratch_slots(h, 1024)
+        ad_cold_ms = timed_adaptive(W, atol, sel)
+        ad_warm_ms = timed_adaptive(W, atol, sel)
+        sc_slots, sc_hits, sc_misses = cqa.cqa_scratch_stats(h)
+        cqa.cqa_set_scratch_slots(h, 0)
         ad_info = {"ms_per_step": ad_ms, "ms_per_step_with_value_promotion": adv_ms,
+                   "key_scratch": {"ms_per_step_filling": ad_cold_ms, "ms_per_step_all_hits": ad_warm_ms,
+                                   "slots_per_kv_head": sc_slots, "hits": sc_hits, "misses": sc_misses},
                    "value_blocks_per_head_median": float(np.median(vstate[5])), "steps_with_fallback": int(sum(1 for r in rungs if r)),
                    "k_star_median": float(np.median(kst)), "k_star_max": int(kst.max()),
                    "promoted_blocks_per_group_max": int(prom.sum(axis=2).max()),
                    "what": f"cqa_adaptive_step, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
-                           "check on, rank_min_mass 0.25; steps that fall back include the dense recompute)"}
+                           "check on, rank_min_mass 0.25; steps that fall back include the dense recompute); "
+                           "promoted keys are read from pinned host RAM by the kernel; key_scratch: the same "
+                           "20 queries with the optional device-resident FP16-key scratch switched on, "
+                           "first filling it, then hitting it"}
 
         # kernel-only rate: split pass + reduction back to back, no host synchronisation in between
         ko_ms = cqa.cqa_time_certified_decode(h, 0, qs[0], tol, O, cert, flags, None, 50, stream)

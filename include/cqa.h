@@ -309,6 +309,24 @@ int32_t cqa_adaptive_step_enqueue(cqa_cache* c, int32_t layer, const void* q_fp1
                                   const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                                   cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream);
 
+/* FP16-key scratch (the paper's VRAM scratch cache of promoted keys, LRU); off
+ * unless switched on here.  Per (layer, batch, kv-head) it keeps up to n_slots
+ * blocks of FP16 keys on the device (at most min(1024, capacity in blocks rounded
+ * up to a power of two); 4 KB per slot).  An adaptive decode then reads a promoted
+ * block's keys from there when it holds them, else from the pinned originals over
+ * the host link, and keeps them in the least recently used slot that the step does
+ * not use.  Results do not depend on it (the same FP16 bits either way).  On this
+ * hardware the kernel's direct reads of pinned host memory are as fast for the few
+ * dozen blocks a step promotes, which is why it is off by default.
+ * cqa_set_scratch_slots: 0 = off; the first non-zero call allocates; every call
+ * empties the scratch and waits for the device.
+ * cqa_scratch_stats: slots per head in use and, since the cache was created, how many
+ * key-promoted blocks were found in the scratch / were not; waits for the device.
+ * Host pointers, may be NULL.  Errors: INVALID_ARG (n_slots out of range), NO_TIER2,
+ * OOM_DEVICE, HIP. */
+int32_t cqa_set_scratch_slots(cqa_cache* c, int32_t n_slots);
+int32_t cqa_scratch_stats(cqa_cache* c, int32_t* slots_per_head, int64_t* hits, int64_t* misses);
+
 /* Test hook: what the last adaptive decode decided, copied to the host after a
  * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
  * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*

@@ -127,6 +127,8 @@ def _load():
                                     vp, C.POINTER(i32), vp]),
         "cqa_adaptive_step_enqueue": (i32, [vp, i32, vp, C.POINTER(Tolerances), C.POINTER(Selector), vp, vp,
                                             vp, vp]),
+        "cqa_set_scratch_slots": (i32, [vp, i32]),
+        "cqa_scratch_stats": (i32, [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]),
         "cqa_adaptive_state": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "cqa_dense_attention": (i32, [vp, vp, vp, i32, i32, i32, i64, vp, vp, vp]),
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
@@ -303,6 +305,17 @@ def cqa_adaptive_step_enqueue(h, layer, q_dev, tol: Tolerances, sel: Selector, O
     _check(_lib.cqa_adaptive_step_enqueue(h, layer, _ptr(q_dev), C.byref(tol), C.byref(sel), _ptr(O_dev),
                                           _ptr(cert_dev), _ptr(flags_dev), _ptr(stream)),
            "cqa_adaptive_step_enqueue")
+
+
+def cqa_set_scratch_slots(h, n_slots) -> None:
+    _check(_lib.cqa_set_scratch_slots(h, n_slots), "cqa_set_scratch_slots")
+
+
+def cqa_scratch_stats(h):
+    """(slots per head in use, hits, misses)"""
+    n, hit, miss = C.c_int32(0), C.c_int64(0), C.c_int64(0)
+    _check(_lib.cqa_scratch_stats(h, C.byref(n), C.byref(hit), C.byref(miss)), "cqa_scratch_stats")
+    return n.value, hit.value, miss.value
 
 
 def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):

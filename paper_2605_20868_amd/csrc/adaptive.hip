@@ -385,6 +385,14 @@ struct CompactArgs {
   int32_t* ulist;      // [Bt][Hkv][MAX_UNION]
   int32_t* ucount;     // [Bt][Hkv]
   int nb;
+  // FP16-key scratch of the layer (sc_slots = 0: off)
+  int32_t* sc_map;     // [Bt][Hkv][sc_map_stride]
+  int64_t sc_map_stride;
+  int32_t* sc_tag;     // [Bt][Hkv][sc_cap]
+  uint32_t* sc_age;    // [Bt][Hkv][sc_cap]
+  uint32_t* sc_stats;  // [2]
+  int sc_cap, sc_slots;
+  uint32_t sc_step;    // stamp of this step (larger than every stamp before it, never 0)
 };
 
 // One workgroup per KV group: the two bit masks (FP16 keys, FP16 values) -> per-block flags
@@ -455,6 +463,122 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     __syncthreads();
   }
   if (tid == 0) a.ucount[grp] = min(s_base, MAX_UNION);
+  if (a.sc_slots <= 0) return;
+
+  // ---- FP16-key scratch: which listed blocks are held on the device, and where the others go.
+  // A key-promoted block found in the map keeps its slot (stamped with this step).  The others
+  // take over the least recently used slots -- found by a radix selection over the slots' stamps,
+  // only in steps that miss -- never one used in this step; the pass that reads
+  // their keys from the host stores them into the slot (SLOT_FILL).  Misses beyond the free
+  // slots are read from the host without being kept.
+  const int n = min(s_base, MAX_UNION);
+  int32_t* map = a.sc_map + grp * a.sc_map_stride;
+  int32_t* tag = a.sc_tag + grp * (int64_t)a.sc_cap;
+  uint32_t* age = a.sc_age + grp * (int64_t)a.sc_cap;
+  __shared__ int s_hits, s_nmiss, s_elig;
+  __shared__ int misslist[SC_MAX_SLOTS];
+  if (tid == 0) {
+    s_hits = 0;
+    s_nmiss = 0;
+    s_elig = 0;
+  }
+  __syncthreads();
+  for (int i = tid; i < n; i += 256) {
+    const int blk = ulist[i];
+    const int f = slot[blk];
+    if (f & SLOT_KEYS) {
+      const int m = map[blk];
+      if (m > 0 && m <= a.sc_slots && tag[m - 1] == blk) {
+        age[m - 1] = a.sc_step;
+        slot[blk] = f | (m << SLOT_SC_SHIFT);
+        atomicAdd(&s_hits, 1);
+      } else {
+        const int k = atomicAdd(&s_nmiss, 1);
+        if (k < SC_MAX_SLOTS) misslist[k] = blk;
+      }
+    }
+  }
+  __syncthreads();
+  const int nmiss = min(s_nmiss, SC_MAX_SLOTS);
+  if (tid == 0) {
+    atomicAdd(a.sc_stats + 0, (uint32_t)s_hits);
+    atomicAdd(a.sc_stats + 1, (uint32_t)s_nmiss);
+  }
+  if (nmiss == 0) return;
+  // The `usable` least recently used slots, ties to the lower slot index: radix selection over
+  // the 32-bit stamps of the slots that this step does not use (four 8-bit passes: histogram,
+  // scan, descend), then two scans in slot order rank the chosen slots.  Thread t owns slots
+  // 4t .. 4t+3.
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_need;
+  __shared__ int itot[4];
+  __shared__ uint32_t utot[4];
+  uint32_t st4[4];
+  bool el4[4];
+  int elig = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = tid * 4 + j;
+    st4[j] = i < a.sc_slots ? age[i] : 0xFFFFFFFFu;
+    el4[j] = i < a.sc_slots && st4[j] != a.sc_step;
+    elig += el4[j] ? 1 : 0;
+  }
+  atomicAdd(&s_elig, elig);
+  __syncthreads();
+  const int usable = min(nmiss, s_elig);
+  if (usable == 0) return;
+  if (tid == 0) {
+    s_prefix = 0u;
+    s_need = (uint32_t)usable;
+  }
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0u;
+    __syncthreads();
+    const uint32_t prefix = s_prefix, need = s_need;
+    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (el4[j] && (st4[j] & himask) == prefix) atomicAdd(&hist[(st4[j] >> shift) & 255u], 1u);
+    __syncthreads();
+    const uint32_t mine = hist[tid];
+    const uint32_t upto = block_scan_incl<uint32_t>(mine, utot, tid);
+    if (upto >= need && upto - mine < need) {      // the bin where the count first reaches `need`
+      s_need = need - (upto - mine);
+      s_prefix = prefix | ((uint32_t)tid << shift);
+    }
+    __syncthreads();
+  }
+  const uint32_t T = s_prefix;          // stamp of the last slot taken
+  const int need_eq = (int)s_need;      // how many slots with exactly that stamp are taken
+  int eq = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) eq += (el4[j] && st4[j] == T) ? 1 : 0;
+  int eq_before = block_scan_incl<int>(eq, itot, tid) - eq;
+  bool take[4];
+  int nt = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const bool is_eq = el4[j] && st4[j] == T;
+    take[j] = el4[j] && (st4[j] < T || (is_eq && eq_before < need_eq));
+    eq_before += is_eq ? 1 : 0;
+    nt += take[j] ? 1 : 0;
+  }
+  int rank = block_scan_incl<int>(nt, itot, tid) - nt;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (!take[j]) continue;
+    if (rank < usable) {
+      const int v = tid * 4 + j;
+      const int blk = misslist[rank];
+      const int old = tag[v];
+      if (old >= 0 && old < a.nb && map[old] == v + 1) map[old] = 0;
+      tag[v] = blk;
+      map[blk] = v + 1;
+      age[v] = a.sc_step;
+      slot[blk] |= ((v + 1) << SLOT_SC_SHIFT) | SLOT_FILL;
+    }
+    ++rank;
+  }
 }
 
 struct AdaptiveReduceArgs {
@@ -684,10 +808,20 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   ca.ulist = w.ulist;
   ca.ucount = w.ucount;
   ca.nb = (int)nb;
+  const int64_t layer_head0 = head_index(c, layer, 0, 0);
+  ca.sc_slots = w.sc_slots;
+  if (w.sc_slots > 0) {
+    w.sc_step += 1u;
+    ca.sc_map = w.sc_map + layer_head0 * c->nb_cap;
+    ca.sc_map_stride = c->nb_cap;
+    ca.sc_tag = w.sc_tag + layer_head0 * w.sc_cap;
+    ca.sc_age = w.sc_age + layer_head0 * w.sc_cap;
+    ca.sc_stats = w.sc_stats;
+    ca.sc_cap = w.sc_cap;
+    ca.sc_step = w.sc_step;
+  }
   hipLaunchKernelGGL(compact_kernel, dim3(hkv, bt), dim3(256), 0, st, ca);
   CQA_HIP(hipGetLastError());
-
-  const int64_t layer_head0 = head_index(c, layer, 0, 0);
 
   // ---- 4. promoted-block pass: the listed blocks once more with the originals their flags ask
   //         for (positive sets) and once as the first pass saw them (negated sets)
@@ -722,6 +856,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.n_kv = hkv;
   a.debug = 0;
   a.slot = w.slot;
+  a.sc_k = w.sc_slots > 0 ? w.sc_k + layer_head0 * w.sc_cap * BLK * D : nullptr;
+  a.sc_cap = w.sc_cap;
   a.ulist = w.ulist;
   a.ucount = w.ucount;
   a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;

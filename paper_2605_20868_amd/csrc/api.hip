@@ -35,6 +35,8 @@ static int32_t check_desc(const cqa_cache_desc* d) {
 struct Sizes {
   int64_t nb_cap, nq_cap, heads, t1, trail, t2, partials, dense_ws, stage, select, ladder_ws;
   int64_t ad_lm, ad_sel, ad_head, ad_mask_words, ad_mask, ad_slot, ad_group, ad_ulist, ad_eta;
+  int64_t sc_k, sc_map, sc_tag;
+  int sc_cap;
   int max_splits;
 };
 
@@ -70,6 +72,13 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.ad_group = ad ? groups * 4 : 0;
   s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
   s.ad_eta = ad ? groups * s.nb_cap * 4 : 0;
+  // FP16-key scratch: a power of two of slots per head, at most SC_MAX_SLOTS, no more than needed
+  int cap = 1;
+  while (cap < SC_MAX_SLOTS && cap < s.nb_cap) cap <<= 1;
+  s.sc_cap = ad ? cap : 0;
+  s.sc_k = ad ? s.heads * cap * (int64_t)BLK * D * 2 : 0;
+  s.sc_map = ad ? s.heads * s.nb_cap * 4 : 0;
+  s.sc_tag = ad ? s.heads * cap * 4 : 0;
   return s;
 }
 
@@ -104,6 +113,11 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.vsel);
   (void)hipFree(c->ad.vcount);
   (void)hipFree(c->ad.score_dev);
+  (void)hipFree(c->ad.sc_k);
+  (void)hipFree(c->ad.sc_map);
+  (void)hipFree(c->ad.sc_tag);
+  (void)hipFree(c->ad.sc_age);
+  (void)hipFree(c->ad.sc_stats);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
   if (c->t2_k) (void)hipHostFree(c->t2_k);
@@ -258,6 +272,12 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_TRY(hipMemset(c->ad.vcount, 0, (size_t)s.ad_head));
     CQA_TRY(hipMemset(c->ad.ucount, 0, (size_t)s.ad_group));
     CQA_TRY(hipMemset(c->ad.kstar, 0, (size_t)s.ad_head));
+    // FP16-key scratch: off until cqa_set_scratch_slots asks for it (allocated then)
+    CQA_ALLOC_DEV(c->ad.sc_stats, 8);
+    CQA_TRY(hipMemset(c->ad.sc_stats, 0, 8));
+    c->ad.sc_cap = s.sc_cap;
+    c->ad.sc_slots = 0;
+    c->ad.sc_step = 0u;
   }
   CQA_ALLOC_PIN(c->flags_host, s.select);
   memset(c->flags_host, 0, s.select);
@@ -311,7 +331,67 @@ int32_t cqa_cache_reset(cqa_cache* h, int32_t layer) {
   // unsealed blocks must read as zeros (the decode pass loads whole records and relies on it)
   CQA_HIP(hipMemset(c->t1 + head_index(c, layer, 0, 0) * c->nq_cap * QUAD_BYTES, 0,
                     (size_t)c->desc.batch * c->desc.n_kv_heads * c->nq_cap * QUAD_BYTES));
+  if (c->ad.sc_map != nullptr) {
+    // the layer's blocks are gone: nothing of it stays in the FP16-key scratch
+    const int64_t h0 = head_index(c, layer, 0, 0), nh = (int64_t)c->desc.batch * c->desc.n_kv_heads;
+    CQA_HIP(hipMemset(c->ad.sc_map + h0 * c->nb_cap, 0, (size_t)(nh * c->nb_cap) * 4));
+    CQA_HIP(hipMemset(c->ad.sc_tag + h0 * c->ad.sc_cap, 0xFF, (size_t)(nh * c->ad.sc_cap) * 4));
+    CQA_HIP(hipMemset(c->ad.sc_age + h0 * c->ad.sc_cap, 0, (size_t)(nh * c->ad.sc_cap) * 4));
+  }
   c->length[layer] = 0;
+  return CQA_OK;
+}
+
+int32_t cqa_set_scratch_slots(cqa_cache* h, int32_t n_slots) {
+  if (h == nullptr || n_slots < 0) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
+  if (n_slots > c->ad.sc_cap) return CQA_ERR_INVALID_ARG;
+  CQA_HIP(hipDeviceSynchronize());
+  const int64_t cap = c->ad.sc_cap;
+  if (n_slots > 0 && c->ad.sc_k == nullptr) {
+    // first use: the scratch and its maps
+    __half* k = nullptr;
+    int32_t *map = nullptr, *tag = nullptr;
+    uint32_t* age = nullptr;
+    hipError_t e = hipMalloc((void**)&k, (size_t)(c->heads_total * cap) * BLK * D * 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&map, (size_t)(c->heads_total * c->nb_cap) * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&tag, (size_t)(c->heads_total * cap) * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&age, (size_t)(c->heads_total * cap) * 4);
+    if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      (void)hipGetLastError();
+      (void)hipFree(k);
+      (void)hipFree(map);
+      (void)hipFree(tag);
+      (void)hipFree(age);
+      return e == hipErrorOutOfMemory ? CQA_ERR_OOM_DEVICE : CQA_ERR_HIP;
+    }
+    c->ad.sc_k = k;
+    c->ad.sc_map = map;
+    c->ad.sc_tag = tag;
+    c->ad.sc_age = age;
+  }
+  if (c->ad.sc_k != nullptr) {
+    CQA_HIP(hipMemset(c->ad.sc_map, 0, (size_t)(c->heads_total * c->nb_cap) * 4));
+    CQA_HIP(hipMemset(c->ad.sc_tag, 0xFF, (size_t)(c->heads_total * cap) * 4));   // -1: empty
+    CQA_HIP(hipMemset(c->ad.sc_age, 0, (size_t)(c->heads_total * cap) * 4));
+  }
+  c->ad.sc_slots = n_slots;
+  return CQA_OK;
+}
+
+int32_t cqa_scratch_stats(cqa_cache* h, int32_t* slots_per_head, int64_t* hits, int64_t* misses) {
+  if (h == nullptr) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  uint32_t n[2] = {0u, 0u};
+  if (c->ad.sc_stats != nullptr) {
+    CQA_HIP(hipDeviceSynchronize());
+    CQA_HIP(hipMemcpy(n, c->ad.sc_stats, 8, hipMemcpyDeviceToHost));
+  }
+  if (slots_per_head) *slots_per_head = c->ad.sc_slots;
+  if (hits) *hits = n[0];
+  if (misses) *misses = n[1];
   return CQA_OK;
 }
 

@@ -110,7 +110,23 @@ struct AdaptiveWs {
   int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
   int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
   int64_t mask_words;
+  // FP16-key scratch (the paper's VRAM scratch cache of promoted keys, LRU): per (layer, batch,
+  // kv-head) `sc_cap` slots of one block's keys each.  sc_map: block -> slot + 1 (0 = not held);
+  // sc_tag: slot -> block (-1 = empty); sc_age: slot -> step stamp of its last use.
+  __half* sc_k;      // [heads_total][sc_cap][16][128]
+  int32_t* sc_map;   // [heads_total][nb_cap]
+  int32_t* sc_tag;   // [heads_total][sc_cap]
+  uint32_t* sc_age;  // [heads_total][sc_cap]
+  uint32_t* sc_stats;  // [2] key-promoted blocks found in the scratch / not found, over all steps
+  int sc_cap;        // allocated slots per head (a power of two <= SC_MAX_SLOTS)
+  int sc_slots;      // slots in use (test hook may lower it; 0 = scratch off)
+  uint32_t sc_step;  // stamp of the last adaptive step
 };
+
+constexpr int SC_MAX_SLOTS = 1024;
+// per-block word of AdaptiveWs::slot: bit 0 FP16 keys, bit 1 FP16 values, bit 2 the keys are to
+// be stored into the scratch slot by the pass that reads them, bits 8.. scratch slot + 1 (0 = none)
+constexpr int SLOT_KEYS = 1, SLOT_VALUES = 2, SLOT_FILL = 4, SLOT_SC_SHIFT = 8;
 
 struct Cache {
   cqa_cache_desc desc;
@@ -173,6 +189,8 @@ struct DecodeArgs {
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
   // attend pass with gated key precision (null slot = every block uses its INT8 keys)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
+  __half* sc_k;             // layer base of the FP16-key scratch [Bt * Hkv][sc_cap][16][128], or null
+  int sc_cap;
   const int32_t* ulist;     // [Bt][Hkv][MAX_UNION]: promoted blocks of the group, ascending
   const int32_t* ucount;    // [Bt][Hkv]
   const __half* t2_k;       // pinned FP16 key originals of the layer: [Bt * Hkv][max_tokens][128]

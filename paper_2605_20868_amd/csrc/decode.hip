@@ -151,13 +151,24 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
     if (kfp) {
-      // FP16 keys of the block in the host-resident originals: [token][128 channels]
-      const __half* kf16 = a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
+      // FP16 keys of the block, [token][128 channels]: from its slot of the device-resident
+      // scratch if it is held there, else from the host-resident originals -- and then, if the
+      // block has just been given a slot, stored into it on the way
+      const int sc0 = pf >> SLOT_SC_SHIFT;
+      const int sc = (a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
+      const bool fill = sc > 0 && (pf & SLOT_FILL);
+      __half* sck = sc > 0 ? a.sc_k + (((grp * a.sc_cap + (sc - 1)) * BLK) + tok) * D : nullptr;
+      const __half* kf16 = (sc > 0 && !fill) ? sck
+                                             : a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
         const int c0 = cq * 64 + kg * 16;
         const uint4 x0 = *reinterpret_cast<const uint4*>(kf16 + c0);
         const uint4 x1 = *reinterpret_cast<const uint4*>(kf16 + c0 + 8);
+        if (fill) {
+          *reinterpret_cast<uint4*>(sck + c0) = x0;
+          *reinterpret_cast<uint4*>(sck + c0 + 8) = x1;
+        }
         const __half2* h0 = reinterpret_cast<const __half2*>(&x0);
         const __half2* h1 = reinterpret_cast<const __half2*>(&x1);
 #pragma unroll

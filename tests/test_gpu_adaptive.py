@@ -393,3 +393,61 @@ def test_adaptive_128k_sampled_heads():
         check_against_oracle(oc, q, tol, sel, out, heads=[(0, 8), (0, 9), (0, 11)])
         say(f"  K* min/median/max {out['k_star'].min()}/{int(np.median(out['k_star']))}/{out['k_star'].max()}, "
             f"promoted per group {out['promoted'].sum(axis=2).ravel().tolist()} of {nb}")
+
+
+def test_key_scratch_does_not_change_results_and_holds_recent_blocks():
+    say("adaptive: FP16-key scratch on the device (hits, misses, eviction) gives the same bits as reading the host")
+    k, v, q = make_case(21, 2, 8, 2, 16 * 300 + 9, peaked=[(0, 1, 1500, 0.9), (1, 6, 40, 1.0)])
+    rng = np.random.Generator(np.random.Philox(77))
+    qs = [q] + [workloads.normal_f16(rng, q.shape) for _ in range(3)]
+    sel = ad.SelectorParams(0.9, 4, 64, 64)
+    tol = att.Tolerances(rank_depth=1)
+    with GpuLayerCache(2, 8, 2, 16 * 300 + 64) as gc:
+        cqa = gc.cqa
+        gc.append(k, v)
+        assert cqa.cqa_scratch_stats(gc.h) == (0, 0, 0)    # off until asked for
+        # reference: scratch off, every promoted block read from the pinned originals
+        ref = [gpu_adaptive(gc, x, tol, sel) for x in qs]
+        assert cqa.cqa_scratch_stats(gc.h) == (0, 0, 0)
+        promoted = [int(r["promoted"].sum()) for r in ref]
+
+        def same(a, b, w):
+            assert (a["O"] == b["O"]).all() and a["cert"].tobytes() == b["cert"].tobytes(), w
+            assert (a["flags"] == b["flags"]).all() and (a["promoted"] == b["promoted"]).all(), w
+            assert (a["lx"] == b["lx"]).all(), w
+
+        # (i) room for everything (capacity 304 blocks -> at most 512 slots): first use misses,
+        # the same query again hits every block
+        cqa.cqa_set_scratch_slots(gc.h, 512)
+        same(gpu_adaptive(gc, qs[0], tol, sel), ref[0], "cold")
+        assert cqa.cqa_scratch_stats(gc.h) == (512, 0, promoted[0])
+        same(gpu_adaptive(gc, qs[0], tol, sel), ref[0], "warm")
+        assert cqa.cqa_scratch_stats(gc.h) == (512, promoted[0], promoted[0])
+        for i in (1, 2, 3, 1):
+            same(gpu_adaptive(gc, qs[i], tol, sel), ref[i], ("other queries", i))
+        # (ii) fewer slots than one step promotes per group: the overflow is read from the host,
+        # later steps evict the least recently used slots; results stay the same
+        per_group = ref[0]["promoted"].sum(axis=2).max()
+        small = max(2, int(per_group) // 2)
+        cqa.cqa_set_scratch_slots(gc.h, small)
+        _, h1, m1 = cqa.cqa_scratch_stats(gc.h)
+        for rep in range(2):
+            for i in (0, 1, 0, 2, 3):
+                same(gpu_adaptive(gc, qs[i], tol, sel), ref[i], ("small scratch", rep, i))
+        _, h2, m2 = cqa.cqa_scratch_stats(gc.h)
+        assert h2 > h1 and m2 > m1
+        say(f"  {small} slots per head: {h2 - h1} hits, {m2 - m1} misses over 10 steps")
+        # (iii) a reset empties the layer's scratch: appending other keys must not find the old ones
+        cqa.cqa_set_scratch_slots(gc.h, 512)
+        gpu_adaptive(gc, qs[0], tol, sel)
+        cqa.cqa_cache_reset(gc.h, 0)
+        k2, v2, _ = make_case(22, 2, 8, 2, 16 * 300 + 9)
+        gc.append(k2, v2)
+        oc2 = oracle.OracleLayerCache(2, 2)
+        oc2.append(k2, v2)
+        out = gpu_adaptive(gc, qs[0], tol, sel)
+        check_against_oracle(oc2, qs[0], tol, sel, out)
+        out = gpu_adaptive(gc, qs[0], tol, sel)          # now from the scratch
+        check_against_oracle(oc2, qs[0], tol, sel, out)
+        with pytest.raises(cqa.CqaError):
+            cqa.cqa_set_scratch_slots(gc.h, 513)
