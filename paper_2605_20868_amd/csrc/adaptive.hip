@@ -862,7 +862,11 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.ucount = w.ucount;
   a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
   a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
+#ifdef CQA_PROBE_PROM
+  a.eta_out = w.contrib;   // build-time probe: the promoted-block pass stamps its phases here
+#else
   a.eta_out = nullptr;
+#endif
   a.score_dev = sel.canary ? w.score_dev : nullptr;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;

@@ -45,8 +45,19 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
 //               block is attended from its FP16 values and counts with eta_b = 0; both kinds of
 //               originals are read by the device straight from the pinned Tier-2 arrays over the
 //               host link.  Writes partial sets split0 + blockIdx.x.
+#ifdef CQA_PROBE_PROM
+#define CQA_PSTAMP(N)                                                                        \
+  if (PROM && a.eta_out != nullptr && l == 0 && (N) < 8)                                     \
+    reinterpret_cast<int*>(a.eta_out)[((((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + w) * 8 + (N)] = \
+        (int)(wall_clock64() - ts0);
+#else
+#define CQA_PSTAMP(N)
+#endif
 template <int G, bool PROM>
 __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
+#ifdef CQA_PROBE_PROM
+  const uint64_t ts0 = wall_clock64();
+#endif
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = l & 15, kg = l >> 4;              // roles in the score phase
   const int vn = l & 15, vgh = (l >> 4) & 1, vo = l >> 5;  // roles in the value phase
@@ -103,29 +114,80 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     for (int gq = 0; gq < 4; ++gq) acc[gq][h] = 0.0f;
   }
 
+  CQA_PSTAMP(0)
+  // the list entry of the next iteration is requested one iteration ahead
+  int blk_next = (PROM && b0 + w < b1) ? a.ulist[grp * MAX_UNION + b0 + w] : b0 + w;
   for (int pos = b0 + w; pos < b1; pos += bstep) {
     // every index is bounded on the way in: a list entry outside [0, nb) is skipped
-    const int blk = PROM ? a.ulist[grp * MAX_UNION + pos] : pos;
+    const int blk = blk_next;
+    blk_next = (PROM && pos + bstep < b1) ? a.ulist[grp * MAX_UNION + pos + bstep] : pos + bstep;
     if (PROM && (blk < 0 || blk >= a.nb)) continue;
+    if (pos == b0 + w) { CQA_PSTAMP(1) }
+    // Every load of the block is requested here, before anything is consumed: the block sits at
+    // an address nothing else in this launch touches, so each dependent load costs a full
+    // memory (and page-walk) latency.  First everything whose address follows from blk alone
+    // (flags, INT8 codes, key and value metadata, INT4 codes), then the originals the flags ask
+    // for.
     const int pf = PROM ? a.slot[grp * (a.nq_cap * 4) + blk] : 0;   // bit 0: FP16 keys, bit 1: FP16 values
-    const bool kfp = PROM && !neg && (pf & 1), vfp = PROM && !neg && (pf & 2);
-    // ---- scaled query, per-block constant, per-block score-error bound
     const float* kmb = reinterpret_cast<const float*>(a.t1 + t1_offset(head_rec, blk, Q_KM, KM_BYTES));
-    float2 sg = make_float2(1.0f, 1.0f), zz = make_float2(0.0f, 0.0f);
-    if (!kfp) {
-      sg = reinterpret_cast<const float2*>(kmb)[l];
-      zz = reinterpret_cast<const float2*>(kmb + D)[l];
-    }
+    const float2 sg8 = reinterpret_cast<const float2*>(kmb)[l];
+    const float2 zz8 = reinterpret_cast<const float2*>(kmb + D)[l];
     float2 an = *reinterpret_cast<const float2*>(a.t1 + t1_offset(head_rec, blk, Q_AN, AN_BYTES));
+    const uint8_t* kcb = a.t1 + t1_offset(head_rec, blk, Q_KC, KC_BYTES);
+    uint4 kc8[2];
+#pragma unroll
+    for (int cq = 0; cq < 2; ++cq) kc8[cq] = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
+    const uint4 vx = reinterpret_cast<const uint4*>(a.t1 + t1_offset(head_rec, blk, Q_VC, VC_BYTES))[l];
+    const __half* vmb = reinterpret_cast<const __half*>(a.t1 + t1_offset(head_rec, blk, Q_VM, VM_BYTES));
+    uint4 sraw4[4], oraw4[4];
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      const int g = vgh * 4 + gq;
+      sraw4[gq] = *reinterpret_cast<const uint4*>(vmb + vo * 64 + g * 8);
+      oraw4[gq] = *reinterpret_cast<const uint4*>(vmb + BLK * NG + vo * 64 + g * 8);
+    }
+    const bool kfp = PROM && !neg && (pf & 1), vfp = PROM && !neg && (pf & 2);
+    // FP16 keys of the block, [token][128 channels]: from its slot of the device-resident
+    // scratch if it is held there, else from the host-resident originals -- and then, if the
+    // block has just been given a slot, stored into it on the way
+    uint4 k16[2][2];
+    if (kfp) {
+      const int sc0 = pf >> SLOT_SC_SHIFT;
+      const int sc = (a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
+      const bool fill = sc > 0 && (pf & SLOT_FILL);
+      __half* sck = sc > 0 ? a.sc_k + (((grp * a.sc_cap + (sc - 1)) * BLK) + tok) * D : nullptr;
+      const __half* kf16 = (sc > 0 && !fill) ? sck
+                                             : a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
+#pragma unroll
+      for (int cq = 0; cq < 2; ++cq) {
+        const int c0 = cq * 64 + kg * 16;
+        k16[cq][0] = *reinterpret_cast<const uint4*>(kf16 + c0);
+        k16[cq][1] = *reinterpret_cast<const uint4*>(kf16 + c0 + 8);
+      }
+      if (fill) {
+#pragma unroll
+        for (int cq = 0; cq < 2; ++cq) {
+          const int c0 = cq * 64 + kg * 16;
+          *reinterpret_cast<uint4*>(sck + c0) = k16[cq][0];
+          *reinterpret_cast<uint4*>(sck + c0 + 8) = k16[cq][1];
+        }
+      }
+    }
     if (vfp) {
       an.x = 0.0f;     // exact values: the block adds nothing to the value term
       // its FP16 values, row-major [token][128], coalesced into this wave's LDS buffer
       const __half* v16 = a.t2_v + (grp * a.max_tokens + (int64_t)blk * BLK + (l >> 2)) * D + (l & 3) * 32;
+      uint4 v16r[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v16r[j] = *reinterpret_cast<const uint4*>(v16 + j * 8);
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) =
-            *reinterpret_cast<const uint4*>(v16 + j * 8);
+        *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) = v16r[j];
     }
+    if (pos == b0 + w && pf >= 0) { CQA_PSTAMP(2) }
+    // ---- scaled query, per-block constant, per-block score-error bound
+    const float2 sg = kfp ? make_float2(1.0f, 1.0f) : sg8;
+    const float2 zz = kfp ? make_float2(0.0f, 0.0f) : zz8;
     float csum[G], dsum[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -146,31 +208,15 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     wave_sync();
 
     // ---- scores: lane (tok, kg) covers channels cq*64 + kg*16 + 0..15, cq = 0, 1
-    const uint8_t* kcb = a.t1 + t1_offset(head_rec, blk, Q_KC, KC_BYTES);
     float dot[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) dot[h] = 0.0f;
     if (kfp) {
-      // FP16 keys of the block, [token][128 channels]: from its slot of the device-resident
-      // scratch if it is held there, else from the host-resident originals -- and then, if the
-      // block has just been given a slot, stored into it on the way
-      const int sc0 = pf >> SLOT_SC_SHIFT;
-      const int sc = (a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
-      const bool fill = sc > 0 && (pf & SLOT_FILL);
-      __half* sck = sc > 0 ? a.sc_k + (((grp * a.sc_cap + (sc - 1)) * BLK) + tok) * D : nullptr;
-      const __half* kf16 = (sc > 0 && !fill) ? sck
-                                             : a.t2_k + ((grp * a.max_tokens + (int64_t)blk * BLK) + tok) * D;
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
         const int c0 = cq * 64 + kg * 16;
-        const uint4 x0 = *reinterpret_cast<const uint4*>(kf16 + c0);
-        const uint4 x1 = *reinterpret_cast<const uint4*>(kf16 + c0 + 8);
-        if (fill) {
-          *reinterpret_cast<uint4*>(sck + c0) = x0;
-          *reinterpret_cast<uint4*>(sck + c0 + 8) = x1;
-        }
-        const __half2* h0 = reinterpret_cast<const __half2*>(&x0);
-        const __half2* h1 = reinterpret_cast<const __half2*>(&x1);
+        const __half2* h0 = reinterpret_cast<const __half2*>(&k16[cq][0]);
+        const __half2* h1 = reinterpret_cast<const __half2*>(&k16[cq][1]);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           const __half2 pr = (j < 8) ? h0[j >> 1] : h1[(j - 8) >> 1];
@@ -182,8 +228,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     } else {
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
-        const uint4 x = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
-        const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
+        const uint32_t wd[4] = {kc8[cq].x, kc8[cq].y, kc8[cq].z, kc8[cq].w};
         const int c0 = cq * 64 + kg * 16;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -196,8 +241,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     if (PROM && kfp && a.score_dev != nullptr) {
       // score-consistency check: the same tokens scored from the INT8 codes (scaled query in the
       // LDS buffer replaced for a moment), compared token by token with the FP16 scores
-      const float2 sg8 = reinterpret_cast<const float2*>(kmb)[l];
-      const float2 zz8 = reinterpret_cast<const float2*>(kmb + D)[l];
       float c8[G], d8[G];
       wave_sync();
 #pragma unroll
@@ -215,8 +258,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       wave_sync();
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
-        const uint4 x = reinterpret_cast<const uint4*>(kcb + cq * 1024)[l];
-        const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
+        const uint32_t wd[4] = {kc8[cq].x, kc8[cq].y, kc8[cq].z, kc8[cq].w};
         const int c0 = cq * 64 + kg * 16;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -234,6 +276,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         dev[h] = fmaxf(dev[h], fabsf(s16 - (d8[h] + c8[h]) * inv_sqrt_d));
       }
     }
+    if (pos == b0 + w && dot[0] == dot[0]) { CQA_PSTAMP(3) }
     float p[G], alpha[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -274,9 +317,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     wave_sync();
 
     // ---- values: lane (vo, vgh, vn) covers tokens vo*8..+7 of channels (vgh*4+gq)*16 + vn
-    const uint4 vx = reinterpret_cast<const uint4*>(a.t1 + t1_offset(head_rec, blk, Q_VC, VC_BYTES))[l];
     const uint32_t vw[4] = {vx.x, vx.y, vx.z, vx.w};
-    const __half* vmb = reinterpret_cast<const __half*>(a.t1 + t1_offset(head_rec, blk, Q_VM, VM_BYTES));
     float pi[8][G];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -285,10 +326,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
 #pragma unroll
     for (int gq = 0; gq < 4; ++gq) {
       const int g = vgh * 4 + gq;
-      const uint4 sraw = *reinterpret_cast<const uint4*>(vmb + vo * 64 + g * 8);
-      const uint4 oraw = *reinterpret_cast<const uint4*>(vmb + BLK * NG + vo * 64 + g * 8);
-      const __half2* sh = reinterpret_cast<const __half2*>(&sraw);
-      const __half2* oh = reinterpret_cast<const __half2*>(&oraw);
+      const __half2* sh = reinterpret_cast<const __half2*>(&sraw4[gq]);
+      const __half2* oh = reinterpret_cast<const __half2*>(&oraw4[gq]);
 #pragma unroll
       for (int h = 0; h < G; ++h) acc[gq][h] *= alpha[h];
 #pragma unroll
@@ -302,6 +341,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       }
     }
     wave_sync();
+    if (pos == b0 + w) { CQA_PSTAMP(4) }
   }
 
   if (PROM && a.score_dev != nullptr) {
@@ -315,6 +355,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         atomicMax(reinterpret_cast<int*>(a.score_dev + (int64_t)b * a.n_q + kvh * G + h), __float_as_int(d));
     }
   }
+  CQA_PSTAMP(5)
   // ---- merge the four waves of the workgroup, then write one partial per q-head
   float* mo = &qs[0][0][0];  // reuse: [4][G][D]
   __syncthreads();
@@ -379,6 +420,7 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     pp[P_T2] = T2;
     pp[P_I1] = __int_as_float(I1);
   }
+  CQA_PSTAMP(6)
 }
 
 // Stand-alone cross-split reduction: one wave per (batch, query head).
