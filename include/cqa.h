@@ -85,7 +85,8 @@ typedef struct cqa_tolerances {
   float v_tol;              /* on max_b rho_b eta_b (per-block value test)       */
   float rank_min_mass;      /* ranking test only if the top block holds >= this  */
   float eps_guard;          /* additive slack of the ranking test                */
-  int32_t rank_depth;       /* r: 0 = ranking test off, 1 = top-1 block          */
+  int32_t rank_depth;       /* r: 0 = ranking test off, 1 = top-1 block (the      */
+                            /* paper's default); r > 1: CQA_ERR_UNSUPPORTED      */
   int32_t mass_exp;         /* c in e^{c Delta}: 2 (theorems) or 3 (paper impl.)  */
   int32_t key_bound_mode;   /* 0 min(tanh, tail), 1 tail form only, 2 tanh only  */
   int32_t rung4_min_groups; /* >0: that many flagged KV groups => Rung 4         */

@@ -211,6 +211,15 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   return CQA_OK;
 }
 
+// Range checks of a tolerance set.  The ranking test is built at depth 1 (the paper's default);
+// a larger depth is refused rather than silently served by the depth-1 test.
+static int32_t check_tolerances(const cqa_tolerances* tol) {
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2 || tol->rank_depth < 0)
+    return CQA_ERR_INVALID_ARG;
+  if (tol->rank_depth > 1) return CQA_ERR_UNSUPPORTED;
+  return CQA_OK;
+}
+
 int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   if (out == nullptr) return CQA_ERR_INVALID_ARG;
   const int32_t st = check_desc(desc);
@@ -503,8 +512,7 @@ int32_t cqa_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev
       tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr)
     return CQA_ERR_INVALID_ARG;
   if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
-    return CQA_ERR_INVALID_ARG;
+  if (const int32_t trc = check_tolerances(tol)) return trc;
   return launch_certified(&h->impl, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
                           flags_dev, nullptr, 0u, blk_logmass_dev, (hipStream_t)stream);
 }
@@ -714,8 +722,7 @@ static int32_t check_decode_args(cqa_cache* h, int32_t layer, const void* q, con
       tol == nullptr || O == nullptr || cert == nullptr || flags == nullptr)
     return CQA_ERR_INVALID_ARG;
   if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
-    return CQA_ERR_INVALID_ARG;
+  if (const int32_t trc = check_tolerances(tol)) return trc;
   return CQA_OK;
 }
 
@@ -766,8 +773,7 @@ int32_t cqa_append_decode_step(cqa_cache* h, int32_t layer, const void* k_fp16_d
       v_fp16_dev == nullptr || q_fp16_dev == nullptr || tol == nullptr || O_dev == nullptr ||
       cert_dev == nullptr || flags_dev == nullptr)
     return CQA_ERR_INVALID_ARG;
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
-    return CQA_ERR_INVALID_ARG;
+  if (const int32_t trc = check_tolerances(tol)) return trc;
   const __half *rk = nullptr, *rv = nullptr;
   const int32_t rc = append_or_ride(h, layer, k_fp16_dev, v_fp16_dev, stream, &rk, &rv);
   if (rc != CQA_OK) return rc;
@@ -783,8 +789,7 @@ int32_t cqa_decode_step_enqueue(cqa_cache* h, int32_t layer, const void* k_fp16_
       tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr ||
       (k_fp16_dev == nullptr) != (v_fp16_dev == nullptr))
     return CQA_ERR_INVALID_ARG;
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2)
-    return CQA_ERR_INVALID_ARG;
+  if (const int32_t trc = check_tolerances(tol)) return trc;
   Cache* c = &h->impl;
   if (c->desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
   const __half *rk = nullptr, *rv = nullptr;

@@ -201,6 +201,14 @@ def test_error_paths():
         with pytest.raises(cqa.CqaError) as e:
             cqa.cqa_certified_decode(gc.h, 3, gc.to_dev(q), cqa.Tolerances(), gc.O, gc.cert, gc.flags)
         assert e.value.status == cqa.ERR_INVALID_ARG
+        # tolerance sets out of range; a ranking depth above 1 is refused, not served at depth 1
+        for bad, status in ((cqa.Tolerances(mass_exp=-1), cqa.ERR_INVALID_ARG),
+                            (cqa.Tolerances(key_bound_mode=3), cqa.ERR_INVALID_ARG),
+                            (cqa.Tolerances(rank_depth=-1), cqa.ERR_INVALID_ARG),
+                            (cqa.Tolerances(rank_depth=2), cqa.ERR_UNSUPPORTED)):
+            with pytest.raises(cqa.CqaError) as e:
+                cqa.cqa_certified_decode(gc.h, 0, gc.to_dev(q), bad, gc.O, gc.cert, gc.flags)
+            assert e.value.status == status
     with pytest.raises(cqa.CqaError) as e:
         cqa.cqa_cache_create(1, 1, 24, 8, 1024)
     assert e.value.status == cqa.ERR_UNSUPPORTED
