@@ -20,8 +20,15 @@
  * FP16 partial blocks, the split workspace, the fallback staging buffer and one
  * side stream with its events.  The caller owns q, O, cert, flags, blk_logmass
  * and the main stream.  All kernels are enqueued on the caller's stream; only
- * cqa_decode_step and cqa_dense_fallback (when it has to read device-resident
- * head selectors) may block the host.
+ * the host-resolved steps (cqa_decode_step, cqa_append_decode_step,
+ * cqa_adaptive_step), which read the flag words back, the test hooks and the
+ * statistics getters wait for the device; cqa_decode_step_enqueue and
+ * cqa_adaptive_step_enqueue never do.
+ *
+ * Concurrency: the decode calls of one handle share its workspaces (split
+ * partials, fallback partials and arrival counters, selector state), whatever
+ * the layer.  Calls on one handle must therefore be ordered -- issue them on one
+ * stream, or order the streams with events; two handles are independent.
  */
 #ifndef CQA_H
 #define CQA_H
