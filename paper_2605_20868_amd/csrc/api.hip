@@ -130,6 +130,7 @@ static void release(cqa_cache* h) {
     if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
   }
   if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+  if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
   if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
   if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
   if (c->prof_ev) {
@@ -312,6 +313,7 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_TRY(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
   }
   CQA_TRY(hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+  CQA_TRY(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
   CQA_TRY(hipEventCreate(&c->ev_t0));
   CQA_TRY(hipEventCreate(&c->ev_t1));
   *out = h;
@@ -451,12 +453,21 @@ int32_t cqa_cache_append(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
     const size_t rows = (size_t)c->desc.batch * c->desc.n_kv_heads;
     const size_t width = (size_t)n_new * D * 2;
     const size_t dpitch = (size_t)c->desc.max_tokens * D * 2;
+    // on the side stream, so that the copy engines run while the seal kernel quantizes: the side
+    // stream starts when the caller's stream has reached this point (the inputs are ready), and
+    // the caller's stream goes on past the seal only when the copies are done (the caller may
+    // then reuse k and v, and later kernels may read the originals)
+    CQA_HIP(hipEventRecord(c->ev_main, st));
+    CQA_HIP(hipStreamWaitEvent(c->side, c->ev_main, 0));
     CQA_HIP(hipMemcpy2DAsync(c->t2_k + (head0 * c->desc.max_tokens + len) * D, dpitch, k, width,
-                             width, rows, hipMemcpyDeviceToHost, st));
+                             width, rows, hipMemcpyDeviceToHost, c->side));
     CQA_HIP(hipMemcpy2DAsync(c->t2_v + (head0 * c->desc.max_tokens + len) * D, dpitch, v, width,
-                             width, rows, hipMemcpyDeviceToHost, st));
+                             width, rows, hipMemcpyDeviceToHost, c->side));
+    CQA_HIP(hipEventRecord(c->ev_copy, c->side));
   }
   const int32_t rc = launch_seal(c, layer, k, v, n_new, len, t2_by_kernel, st);
+  if (c->desc.tier2_mode == CQA_TIER2_PINNED && !t2_by_kernel)
+    CQA_HIP(hipStreamWaitEvent(st, c->ev_copy, 0));
   if (rc != CQA_OK) return rc;
   c->length[layer] = len + n_new;
   return CQA_OK;

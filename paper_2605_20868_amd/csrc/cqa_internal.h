@@ -163,6 +163,7 @@ struct Cache {
   hipEvent_t ev_ready[2];    // staging buffer filled (recorded on side)
   hipEvent_t ev_free[2];     // staging buffer consumed (recorded on main)
   hipEvent_t ev_main;        // main-stream marker the side stream waits on
+  hipEvent_t ev_copy;         // bulk append: the copies of the originals on the side stream are done
   hipEvent_t ev_t0, ev_t1;   // timing
   bool free_valid[2];
   // optional per-launch timing of the split kernel (pairs of events on the launch stream)

@@ -31,6 +31,43 @@ struct SealArgs {
   int layer, batch, n_kv;
 };
 
+// All-reduce over the 16 lanes of a row by DPP moves (quad xor 1, quad xor 2, half-row mirror,
+// row mirror): no LDS round trip.  Minima and maxima do not depend on the order; the FP64 sums
+// below are annotations compared at 1e-6.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __uint_as_float(
+      (uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double x) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, true);
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ float row_min_f(float x) {
+  x = fminf(x, dpp_f<0xB1>(x));
+  x = fminf(x, dpp_f<0x4E>(x));
+  x = fminf(x, dpp_f<0x141>(x));
+  x = fminf(x, dpp_f<0x140>(x));
+  return x;
+}
+__device__ __forceinline__ float row_max_f(float x) {
+  x = fmaxf(x, dpp_f<0xB1>(x));
+  x = fmaxf(x, dpp_f<0x4E>(x));
+  x = fmaxf(x, dpp_f<0x141>(x));
+  x = fmaxf(x, dpp_f<0x140>(x));
+  return x;
+}
+__device__ __forceinline__ double row_sum_d(double x) {
+  x += dpp_d<0xB1>(x);
+  x += dpp_d<0x4E>(x);
+  x += dpp_d<0x141>(x);
+  x += dpp_d<0x140>(x);
+  return x;
+}
+
 __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   const int c = threadIdx.x;            // channel
   const int j = blockIdx.x;             // new block index
@@ -42,7 +79,7 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   __shared__ __align__(16) uint8_t kbuf[KC_BYTES];
   __shared__ uint8_t vnib[BLK][D];
   __shared__ __align__(16) __half vmeta[2 * BLK * NG];
-  __shared__ double red[2][BLK][2];
+  __shared__ double red[8][BLK][2];   // [row of 16 channels][token][err^2 | norm^2]
 
   float kf[BLK], vf[BLK];
 #pragma unroll
@@ -85,19 +122,20 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
     float smax = sigma;
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) smax = fmaxf(smax, __shfl_xor(smax, m));
-    if ((c & 63) == 0) atomicMax(reinterpret_cast<int*>(a.sigmax + head), __float_as_int(smax));
+    // thousands of blocks of one head would queue up on the same word: the running maximum is
+    // read first (it only grows, so a stale value merely costs a redundant atomic) and the atomic
+    // is issued only by a block that raises it
+    if ((c & 63) == 0 && __float_as_int(smax) > __hip_atomic_load(reinterpret_cast<int*>(a.sigmax + head),
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(reinterpret_cast<int*>(a.sigmax + head), __float_as_int(smax));
   }
 
   // ---- values: per-token, per-group asymmetric INT4
   const int g = c >> 4;
 #pragma unroll
   for (int t = 0; t < BLK; ++t) {
-    float vlo = vf[t], vhi = vf[t];
-#pragma unroll
-    for (int m = 1; m < VG; m <<= 1) {
-      vlo = fminf(vlo, __shfl_xor(vlo, m));
-      vhi = fmaxf(vhi, __shfl_xor(vhi, m));
-    }
+    // a value group is one row of 16 lanes
+    const float vlo = row_min_f(vf[t]), vhi = row_max_f(vf[t]);
     const __half sh = __float2half_rn((vhi - vlo) / 15.0f);
     const float s = __half2float(sh);
     int code = 0;
@@ -113,16 +151,11 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
     }
     // annotations in double: squared reconstruction error and squared norm of this token
     const double vh = (double)code * (double)s + (double)vlo;
-    double e2 = (vh - (double)vf[t]) * (vh - (double)vf[t]);
-    double n2 = (double)vf[t] * (double)vf[t];
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      e2 += __shfl_xor(e2, m);
-      n2 += __shfl_xor(n2, m);
-    }
-    if ((c & 63) == 0) {
-      red[c >> 6][t][0] = e2;
-      red[c >> 6][t][1] = n2;
+    const double e2 = row_sum_d((vh - (double)vf[t]) * (vh - (double)vf[t]));
+    const double n2 = row_sum_d((double)vf[t] * (double)vf[t]);
+    if ((c & 15) == 0) {
+      red[c >> 4][t][0] = e2;
+      red[c >> 4][t][1] = n2;
     }
   }
   __syncthreads();
@@ -148,8 +181,13 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   if (c == 0) {
     double eta2 = 0.0, nu2 = 0.0;
     for (int t = 0; t < BLK; ++t) {
-      eta2 = fmax(eta2, red[0][t][0] + red[1][t][0]);
-      nu2 = fmax(nu2, red[0][t][1] + red[1][t][1]);
+      double e = 0.0, n = 0.0;
+      for (int r = 0; r < 8; ++r) {
+        e += red[r][t][0];
+        n += red[r][t][1];
+      }
+      eta2 = fmax(eta2, e);
+      nu2 = fmax(nu2, n);
     }
     float* an = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_AN, AN_BYTES));
     an[0] = (float)sqrt(eta2);
