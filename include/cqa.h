@@ -116,6 +116,19 @@ typedef struct cqa_head_cert {
 
 /* ---- cache lifetime ------------------------------------------------------ */
 
+/* As cqa_cache_create with tier2_mode = CQA_TIER2_PINNED, but the FP16 originals
+ * live in two pinned host arrays the CALLER provides and keeps alive until the
+ * cache is destroyed (e.g. one pinned pool shared with the rest of a serving
+ * stack): t2_k_host, t2_v_host, each of at least bytes_each >= n_layers * batch *
+ * n_kv_heads * max_tokens * 256 bytes, laid out [layer][batch][kv_head][max_tokens]
+ * [128] FP16.  They must be pinned host memory that the device can address
+ * (hipHostMalloc or a framework's pinned allocation; checked with
+ * hipPointerGetAttributes): the library's kernels read and write them in place.
+ * The library never frees them.  Errors: INVALID_ARG (null, too small, not pinned
+ * host memory, wrong tier2_mode), otherwise as cqa_cache_create. */
+int32_t cqa_cache_create_caller_tier2(const cqa_cache_desc* desc, void* t2_k_host, void* t2_v_host,
+                                      int64_t bytes_each, cqa_cache** out);
+
 /* Allocates every buffer up front on the current HIP device (the paper's
  * "allocated at load, never released"): Tier-1, Tier-2 (unless NONE), trailing
  * blocks, split workspace, staging for one layer.  *out is set only on success.

@@ -107,6 +107,7 @@ def _load():
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     sig = {
         "cqa_cache_create": (i32, [C.POINTER(CacheDesc), C.POINTER(vp)]),
+        "cqa_cache_create_caller_tier2": (i32, [C.POINTER(CacheDesc), vp, vp, i64, C.POINTER(vp)]),
         "cqa_cache_destroy": (i32, [vp]),
         "cqa_workspace_bytes": (i32, [C.POINTER(CacheDesc), C.POINTER(i64), C.POINTER(i64)]),
         "cqa_cache_append": (i32, [vp, i32, vp, vp, i64, vp]),
@@ -196,6 +197,17 @@ def cqa_cache_create(n_layers, batch, n_q_heads, n_kv_heads, max_tokens, tier2_m
                      tier2_mode, max_tokens)
     h = C.c_void_p(None)
     _check(_lib.cqa_cache_create(C.byref(desc), C.byref(h)), "cqa_cache_create")
+    return h
+
+
+def cqa_cache_create_caller_tier2(n_layers, batch, n_q_heads, n_kv_heads, max_tokens, t2_k_host, t2_v_host,
+                                  bytes_each, head_dim=128, block_tokens=16, v_group=16):
+    """t2_k_host / t2_v_host: pinned host memory (address, or an object with data_ptr())."""
+    desc = CacheDesc(n_layers, batch, n_q_heads, n_kv_heads, head_dim, block_tokens, v_group,
+                     TIER2_PINNED, max_tokens)
+    h = C.c_void_p(None)
+    _check(_lib.cqa_cache_create_caller_tier2(C.byref(desc), _ptr(t2_k_host), _ptr(t2_v_host), bytes_each,
+                                              C.byref(h)), "cqa_cache_create_caller_tier2")
     return h
 
 

@@ -120,8 +120,8 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.sc_stats);
   for (int i = 0; i < 2; ++i)
     for (int j = 0; j < 2; ++j) (void)hipFree(c->stage[i][j]);
-  if (c->t2_k) (void)hipHostFree(c->t2_k);
-  if (c->t2_v) (void)hipHostFree(c->t2_v);
+  if (c->t2_k && !c->t2_borrowed) (void)hipHostFree(c->t2_k);
+  if (c->t2_v && !c->t2_borrowed) (void)hipHostFree(c->t2_v);
   if (c->flags_host) (void)hipHostFree(c->flags_host);
   delete[] c->need;
   if (c->side) (void)hipStreamDestroy(c->side);
@@ -221,7 +221,10 @@ static int32_t check_tolerances(const cqa_tolerances* tol) {
   return CQA_OK;
 }
 
-int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
+// caller_k / caller_v: pinned host arrays the caller provides for the originals (and keeps
+// alive until the cache is destroyed), or null for library-owned ones.
+static int32_t create_cache(const cqa_cache_desc* desc, __half* caller_k, __half* caller_v,
+                            cqa_cache** out) {
   if (out == nullptr) return CQA_ERR_INVALID_ARG;
   const int32_t st = check_desc(desc);
   if (st != CQA_OK) return st;
@@ -230,6 +233,7 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   Cache* c = &h->impl;
   memset(c, 0, sizeof(Cache));
   c->desc = *desc;
+  c->t2_borrowed = caller_k != nullptr;
   c->length = new (std::nothrow) int64_t[desc->n_layers];
   if (c->length == nullptr) {
     delete h;
@@ -304,8 +308,13 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
     CQA_TRY(hipMemset(c->ladder_tickets, 0, (size_t)desc->batch * desc->n_kv_heads * 4));
     CQA_ALLOC_DEV(c->ladder_counts, 8);
     CQA_TRY(hipMemset(c->ladder_counts, 0, 8));
-    CQA_ALLOC_PIN(c->t2_k, s.t2);
-    CQA_ALLOC_PIN(c->t2_v, s.t2);
+    if (c->t2_borrowed) {
+      c->t2_k = caller_k;
+      c->t2_v = caller_v;
+    } else {
+      CQA_ALLOC_PIN(c->t2_k, s.t2);
+      CQA_ALLOC_PIN(c->t2_v, s.t2);
+    }
   }
   CQA_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
   for (int i = 0; i < 2; ++i) {
@@ -318,6 +327,31 @@ int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
   CQA_TRY(hipEventCreate(&c->ev_t1));
   *out = h;
   return CQA_OK;
+}
+
+int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out) {
+  return create_cache(desc, nullptr, nullptr, out);
+}
+
+int32_t cqa_cache_create_caller_tier2(const cqa_cache_desc* desc, void* t2_k_host, void* t2_v_host,
+                                      int64_t bytes_each, cqa_cache** out) {
+  if (desc == nullptr || t2_k_host == nullptr || t2_v_host == nullptr) return CQA_ERR_INVALID_ARG;
+  if (desc->tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_INVALID_ARG;
+  const int32_t st = check_desc(desc);
+  if (st != CQA_OK) return st;
+  const int64_t need = (int64_t)desc->n_layers * desc->batch * desc->n_kv_heads * desc->max_tokens * D * 2;
+  if (bytes_each < need) return CQA_ERR_INVALID_ARG;
+  // both arrays must be pinned host memory the device can address (hipHostMalloc, or a framework's
+  // pinned allocation): the kernels read and write them in place
+  for (void* p : {t2_k_host, t2_v_host}) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+      (void)hipGetLastError();
+      return CQA_ERR_INVALID_ARG;
+    }
+    if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return CQA_ERR_INVALID_ARG;
+  }
+  return create_cache(desc, (__half*)t2_k_host, (__half*)t2_v_host, out);
 }
 
 int32_t cqa_cache_destroy(cqa_cache* h) {

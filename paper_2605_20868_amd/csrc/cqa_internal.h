@@ -151,6 +151,7 @@ struct Cache {
   // Tier-2 (pinned host) [heads_total][max_tokens][128]
   __half* t2_k;
   __half* t2_v;
+  bool t2_borrowed;           // the originals' arrays belong to the caller (not freed here)
   // workspaces
   float* partials;           // [batch][Hq][max_splits][PART_FLOATS]
   float* dense_ws;           // dense partials for one (batch, kv-head) group x 2 buffers

@@ -192,3 +192,56 @@ def test_serve64_batched_shape():
             assert np.linalg.norm(O[b, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6, (b, h)
             assert cert["E_key"][b, h] == 0 and cert["E_val"][b, h] == 0
         assert cqa.cqa_ladder_counts(gc.h) == (1, 0)
+
+
+def test_caller_provided_tier2():
+    say("originals in pinned host arrays the caller provides: filled in place, used by every fallback path")
+    import torch
+    cqa = load_binding()
+    bt, hkv, hq, n, cap = 2, 2, 8, 16 * 40 + 7, 1024
+    k, v, q = make(31, bt, hkv, hq, n)
+    elems = bt * hkv * cap * 128
+    t2k = torch.zeros(elems, dtype=torch.float16, pin_memory=True)
+    t2v = torch.zeros(elems, dtype=torch.float16, pin_memory=True)
+    with pytest.raises(cqa.CqaError) as e:          # too small
+        cqa.cqa_cache_create_caller_tier2(1, bt, hq, hkv, cap, t2k, t2v, elems * 2 - 2)
+    assert e.value.status == cqa.ERR_INVALID_ARG
+    plain = np.zeros(elems, dtype=np.float16)       # ordinary pageable memory is refused
+    with pytest.raises(cqa.CqaError) as e:
+        cqa.cqa_cache_create_caller_tier2(1, bt, hq, hkv, cap, plain.ctypes.data, t2v, elems * 2)
+    assert e.value.status == cqa.ERR_INVALID_ARG
+    h = cqa.cqa_cache_create_caller_tier2(1, bt, hq, hkv, cap, t2k, t2v, elems * 2)
+    dev = torch.device("cuda:0")
+    try:
+        O = torch.zeros((bt, hq, 128), dtype=torch.float32, device=dev)
+        cert = torch.zeros((bt * hq, cqa.CERT_BYTES), dtype=torch.uint8, device=dev)
+        flags = torch.zeros((bt * hq,), dtype=torch.int32, device=dev)
+        kd, vd, qd = (torch.from_numpy(x).to(dev) for x in (k, v, q))
+        cqa.cqa_cache_append(h, 0, kd[:, :, :600].contiguous(), vd[:, :, :600].contiguous(), 600)   # copy engines
+        for t in range(600, n):                                                                  # kernel stores
+            cqa.cqa_decode_step_enqueue(h, 0, kd[:, :, t:t + 1].contiguous(), vd[:, :, t:t + 1].contiguous(), qd,
+                                        cqa.Tolerances(), O, cert, flags)
+        torch.cuda.synchronize()
+        got_k = t2k.numpy().reshape(bt, hkv, cap, 128)[:, :, :n]
+        got_v = t2v.numpy().reshape(bt, hkv, cap, 128)[:, :, :n]
+        assert (got_k.view(np.uint16) == k.view(np.uint16)).all()
+        assert (got_v.view(np.uint16) == v.view(np.uint16)).all()
+        assert not t2k.numpy().reshape(bt, hkv, cap, 128)[:, :, n:].any()
+        forced = cqa.Tolerances(force_flags=cqa.FLAG_TOTAL)
+        outs = []
+        cqa.cqa_decode_step_enqueue(h, 0, None, None, qd, forced, O, cert, flags)      # ladder kernel
+        torch.cuda.synchronize()
+        outs.append(O.cpu().numpy().astype(np.float64))
+        rung = cqa.cqa_decode_step(h, 0, qd, forced, O, cert, flags, None)             # host ladder, copy + kernel
+        torch.cuda.synchronize()
+        assert rung == 3
+        outs.append(O.cpu().numpy().astype(np.float64))
+        for o in outs:
+            for b in range(bt):
+                for hh in range(hq):
+                    dense = oracle.softmax_attention(q[b, hh], k[b, hh // 4], v[b, hh // 4])
+                    assert np.linalg.norm(o[b, hh] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+    finally:
+        cqa.cqa_cache_destroy(h)
+    # the arrays are the caller's: still there, still holding the originals
+    assert (t2k.numpy().reshape(bt, hkv, cap, 128)[:, :, :n].view(np.uint16) == k.view(np.uint16)).all()
