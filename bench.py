@@ -240,6 +240,16 @@ def bench_stack(args) -> int:
         torch.cuda.synchronize()
         mean_ms, min_ms, n_timed = cqa.cqa_profile_end(h)
         splits = cqa.cqa_decode_splits(h, 0)
+        # streaming-read ceiling: the load-only kernel, one launch per layer in turn (fresh memory
+        # every launch, as in the step loop)
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        sr_total, sr_bytes = 0.0, 0
+        for rep in range(2):
+            for layer in range(L):
+                ms1, sr_bytes = cqa.cqa_time_stream_read(h, layer, 1, stream)
+                sr_total += ms1
+        sr_ms = sr_total / (2 * L)
     finally:
         cqa.cqa_cache_destroy(h)
     nb_mid = (ctx + W + K // 2) // 16
@@ -256,7 +266,11 @@ def bench_stack(args) -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, "traffic": None,
                      "kernel": "certified_split_mfma_kernel<4>", "kernel_mean_ms": mean_ms,
-                     "kernel_min_ms": min_ms, "algorithmic_bytes_per_launch": alg_bytes},
+                     "kernel_min_ms": min_ms, "algorithmic_bytes_per_launch": alg_bytes,
+                     "stream_ceiling": {"GBps": sr_bytes / (sr_ms * 1e-3) / 1e9, "ms": sr_ms,
+                                        "frac_of_ceiling": (alg_bytes / (mean_ms * 1e-3)) / (sr_bytes / (sr_ms * 1e-3)),
+                                        "what": "load-only kernel with the split kernel's launch shape and load "
+                                                "instructions, one launch per layer in turn"}},
         "cpu_baseline": None,
     }))
     return 0
@@ -460,6 +474,9 @@ def main() -> int:
                            "20 queries with the optional device-resident FP16-key scratch switched on, "
                            "first filling it, then hitting it"}
 
+        # the streaming-read ceiling for this access pattern: the same records, launch shape and load
+        # instructions, no arithmetic
+        sr_ms, sr_bytes = cqa.cqa_time_stream_read(h, 0, 50, stream)
         # kernel-only rate: split pass + reduction back to back, no host synchronisation in between
         ko_ms = cqa.cqa_time_certified_decode(h, 0, qs[0], tol, O, cert, flags, None, 50, stream)
         splits = cqa.cqa_decode_splits(h, 0)
@@ -505,6 +522,14 @@ def main() -> int:
             "kernel_timing": f"HIP events attached to each of {K} dispatches (second pass of the same steps)",
             "kernel_min_ms": min_ms,
             "algorithmic_bytes_per_launch": alg_bytes,
+            "stream_ceiling": {
+                "GBps": sr_bytes / (sr_ms * 1e-3) / 1e9, "ms": sr_ms, "bytes": sr_bytes,
+                "frac_of_ceiling": (alg_bytes / (mean_ms * 1e-3)) / (sr_bytes / (sr_ms * 1e-3)),
+                "what": "a load-only kernel over the same Tier-1 records with the split kernel's launch shape "
+                        "and load instructions, 50 back-to-back launches: what the memory system delivers "
+                        "for this access pattern (one 303 MB layer read repeatedly: part of it is served "
+                        "by the memory-side cache)",
+            },
         },
         "kernel_only": {
             "ms_per_step": ko_ms,

@@ -381,6 +381,15 @@ int64_t cqa_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int64_t n_to
 
 /* ---- measurement and misc ------------------------------------------------ */
 
+/* The streaming-read ceiling of the split pass: launches, `iters` times back to back,
+ * a kernel that loads the Tier-1 records of `layer` with the split pass's launch
+ * shape and load instructions and computes nothing, and returns its mean duration
+ * (milliseconds, host) and the bytes one launch reads (host, may be NULL).  For
+ * benchmarks: achieved bandwidth of the split pass / this = how much of what the
+ * memory system delivers for this access pattern the pass reaches. */
+int32_t cqa_time_stream_read(cqa_cache* c, int32_t layer, int32_t iters, float* ms_per_launch,
+                             int64_t* bytes_per_launch, void* stream);
+
 /* Launches cqa_certified_decode `iters` times back to back on `stream`,
  * bracketed by HIP events recorded on that same stream, synchronises, and
  * returns the mean duration of one step in milliseconds in *ms_per_step

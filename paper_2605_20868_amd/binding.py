@@ -135,6 +135,7 @@ def _load():
         "cqa_dense_workspace_bytes": (i64, [i32, i32, i64]),
         "cqa_time_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
                                             i32, C.POINTER(C.c_float), vp]),
+        "cqa_time_stream_read": (i32, [vp, i32, i32, C.POINTER(C.c_float), C.POINTER(i64), vp]),
         "cqa_profile_begin": (i32, [vp, i32]),
         "cqa_profile_end": (i32, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]),
         "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
@@ -370,6 +371,14 @@ def cqa_time_certified_decode(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev,
                                           iters, C.byref(ms), _ptr(stream)),
            "cqa_time_certified_decode")
     return ms.value
+
+
+def cqa_time_stream_read(h, layer, iters, stream=None):
+    """(ms per launch, bytes per launch) of the load-only kernel with the split pass's access pattern."""
+    ms, nbytes = C.c_float(0.0), C.c_int64(0)
+    _check(_lib.cqa_time_stream_read(h, layer, iters, C.byref(ms), C.byref(nbytes), _ptr(stream)),
+           "cqa_time_stream_read")
+    return ms.value, nbytes.value
 
 
 def cqa_profile_begin(h, max_launches) -> None:

@@ -584,6 +584,38 @@ int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp1
   return CQA_OK;
 }
 
+int32_t cqa_time_stream_read(cqa_cache* h, int32_t layer, int32_t iters, float* ms_per_launch,
+                             int64_t* bytes_per_launch, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || iters < 1 ||
+      ms_per_launch == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  const int64_t nb = c->length[layer] / BLK;
+  if (nb < 1) return CQA_ERR_INVALID_ARG;
+  int nsplit = 0, bps = 0;
+  split_geometry(c, nb, &nsplit, &bps);
+  hipStream_t st = (hipStream_t)stream;
+  const dim3 grid(nsplit, c->desc.n_kv_heads, c->desc.batch);
+  const uint8_t* t1 = c->t1 + head_index(c, layer, 0, 0) * c->nq_cap * QUAD_BYTES;
+  const bool nt = stream_nt(c, nb) != 0;
+  // the select flags buffer doubles as the (never written) sink
+  int32_t rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, c->select_dev, st);   // warm-up
+  if (rc != CQA_OK) return rc;
+  CQA_HIP(hipEventRecord(c->ev_t0, st));
+  for (int i = 0; i < iters; ++i) {
+    rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, c->select_dev, st);
+    if (rc != CQA_OK) return rc;
+  }
+  CQA_HIP(hipEventRecord(c->ev_t1, st));
+  CQA_HIP(hipEventSynchronize(c->ev_t1));
+  float ms = 0.0f;
+  CQA_HIP(hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+  *ms_per_launch = ms / (float)iters;
+  if (bytes_per_launch)
+    *bytes_per_launch = (int64_t)c->desc.batch * c->desc.n_kv_heads * ((nb + 3) / 4) * (18 * 1024);
+  return CQA_OK;
+}
+
 int32_t cqa_profile_begin(cqa_cache* h, int32_t max_launches) {
   if (h == nullptr || max_launches < 1 || max_launches > 65536) return CQA_ERR_INVALID_ARG;
   Cache* c = &h->impl;

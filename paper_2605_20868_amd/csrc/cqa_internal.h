@@ -248,6 +248,9 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
                           dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st);
 
+int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
+                           uint32_t* sink, hipStream_t st);
+
 int dense_splits(int64_t n_tokens);
 // Dense FP16 attention for the G query heads of ONE kv group: k, v point at [n_tokens][128];
 // q_group at the group's first query head.  O rows are written only where select (device,

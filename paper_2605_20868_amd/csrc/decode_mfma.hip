@@ -624,6 +624,47 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #undef CQA_LOAD_V
 #undef CQA_LOAD_META
 
+// Measurement only: reads the same Tier-1 records with the same launch shape, dealing of quads
+// and load instructions as the split kernel (18 x 16 bytes per lane and quad, the next quad
+// requested while the current one is consumed) and does nothing else with them.  Its duration is
+// the ceiling the memory system sets for this access pattern.
+template <bool NT>
+__global__ __launch_bounds__(256, 2) void stream_read_kernel(const uint8_t* t1, int64_t nq_cap, int nb,
+                                                             int nsplit, uint32_t* sink) {
+  const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int split = blockIdx.x;
+  const int64_t head = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  const int nquads = (nb + 3) >> 2;
+  const int gw = split * 4 + w, nw = nsplit * 4;
+  const int q0 = (int)(((int64_t)gw * nquads) / nw), q1 = (int)(((int64_t)(gw + 1) * nquads) / nw);
+  if (q0 >= q1) return;
+  const uint8_t* base = t1 + head * nq_cap * QUAD_BYTES;
+  u32x4 buf[18], acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 18; ++i) buf[i] = ld_stream<NT>(base + (int64_t)q0 * QUAD_BYTES + i * 1024 + l * 16);
+  for (int q = q0; q < q1; ++q) {
+    const uint8_t* nxt = base + (int64_t)min(q + 1, q1 - 1) * QUAD_BYTES;
+#pragma unroll
+    for (int i = 0; i < 18; ++i) {
+      acc ^= buf[i];
+      buf[i] = ld_stream<NT>(nxt + i * 1024 + l * 16);
+    }
+  }
+  // keeps the loads alive: a 128-bit coincidence that does not occur in practice
+  if (acc.x == 0x9E3779B9u && acc.y == 0x85EBCA6Bu && acc.z == 0xC2B2AE35u && acc.w == 0x27D4EB2Fu)
+    sink[0] = acc.x;
+}
+
+int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
+                           uint32_t* sink, hipStream_t st) {
+  if (nt)
+    hipLaunchKernelGGL(stream_read_kernel<true>, grid, dim3(256), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
+  else
+    hipLaunchKernelGGL(stream_read_kernel<false>, grid, dim3(256), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
+  CQA_HIP(hipGetLastError());
+  return CQA_OK;
+}
+
 // ev0 / ev1 (both or neither): HIP events attached to the dispatch itself, so their elapsed time
 // is the kernel's own execution time (what a kernel trace reports), not launch overhead.
 int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
