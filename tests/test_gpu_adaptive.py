@@ -17,7 +17,7 @@ import workloads
 from oracle import adaptive as ad
 from oracle import attention as att
 from oracle import quantizer as qz
-from helpers import GpuLayerCache, load_binding, to_gpu_tol
+from helpers import GpuLayerCache, assert_head_matches, load_binding, to_gpu_tol
 
 pytestmark = pytest.mark.gpu
 
@@ -451,3 +451,37 @@ def test_key_scratch_does_not_change_results_and_holds_recent_blocks():
         check_against_oracle(oc2, qs[0], tol, sel, out)
         with pytest.raises(cqa.CqaError):
             cqa.cqa_set_scratch_slots(gc.h, 513)
+
+
+def test_long_context_beyond_the_selector_lds_window():
+    say("long context: 16 * 20500 + 11 tokens, one KV head (the selector re-reads rows that do not fit its "
+        "LDS key buffer; indices beyond 2^18 tokens), one-pass path and adaptive path against the oracle")
+    n = 16 * 20500 + 11
+    k, v, q = make_case(33, 1, 4, 1, n, student=True, peaked=[(0, 2, n - 5000, 0.8)])
+    oc = oracle.OracleLayerCache(1, 1)
+    oc.append(k, v)
+    with GpuLayerCache(1, 4, 1, n + 16) as gc:
+        for pos in range(0, n, 100000):            # appended in pieces: ragged joins between them
+            gc.append(k[:, :, pos:pos + 100000], v[:, :, pos:pos + 100000])
+        assert gc.length() == n
+        O, cert, flags, lm = gc.certified_decode(q, want_logmass=True)
+        ref = oc.certified_decode(q, att.Tolerances())
+        for h, r in enumerate(ref):
+            assert_head_matches(r, O[0, h], cert[0, h], flags[0, h], ("long", h))
+            assert np.abs(lm[0, h] - r["blk_logmass"]).max() <= 1e-4
+        for sel in (ad.SelectorParams(0.995, 2, 128, 128), ad.SelectorParams(0.9999, 8, 512, 512)):
+            tol = att.Tolerances(rank_depth=1, rank_min_mass=0.25, v_tol=0.05)
+            out = gpu_adaptive(gc, q, tol, sel)
+            check_against_oracle(oc, q, tol, sel, out)
+            say(f"  K* {out['k_star'].ravel().tolist()}, promoted {int(out['promoted'].sum())} of {oc.n_blocks}")
+        # the enqueue-only step with one head over its tolerance
+        tot = np.sort((cert["E_key"].astype(np.float64) + cert["E_val"]).ravel())
+        if tot[-1] - tot[-2] > 1e-3 * tot[-1]:
+            gtol = gc.cqa.Tolerances(eps_total=float(0.5 * (tot[-1] + tot[-2])))
+            gc.cqa.cqa_decode_step_enqueue(gc.h, 0, None, None, gc.to_dev(q), gtol, gc.O, gc.cert, gc.flags)
+            O2, cert2, _ = gc.results()
+            sv = cert2["served_rung"] == 3
+            assert sv.sum() == 1 and (O2[~sv] == O[~sv]).all()
+            h = int(np.argwhere(sv)[0][1])
+            dense = oracle.softmax_attention(q[0, h], k[0, 0], v[0, 0])
+            assert np.linalg.norm(O2[0, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
