@@ -485,3 +485,20 @@ def test_long_context_beyond_the_selector_lds_window():
             h = int(np.argwhere(sv)[0][1])
             dense = oracle.softmax_attention(q[0, h], k[0, 0], v[0, 0])
             assert np.linalg.norm(O2[0, h] - dense) <= 1e-3 * np.linalg.norm(dense) + 1e-6
+
+
+def test_long_context_diffuse_heads_rung1_to_the_limit():
+    say("long context, diffuse heads (normal keys): K* at K_max, Rung 1 doubling to k_limit = 512 on rows the "
+        "selector re-reads")
+    n = 16 * 10600 + 3
+    k, v, q = make_case(34, 1, 4, 1, n)
+    oc = oracle.OracleLayerCache(1, 1)
+    oc.append(k, v)
+    with GpuLayerCache(1, 4, 1, n + 16) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.995, 2, 128, 512)
+        tol = att.Tolerances(eps_key=1e-3, rank_depth=1)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out)
+        assert (out["k_star"] == 512).all()
+        say(f"  promoted {int(out['promoted'].sum())} of {oc.n_blocks}")
