@@ -854,8 +854,13 @@ int32_t cqa_append_decode_step(cqa_cache* h, int32_t layer, const void* k_fp16_d
   const __half *rk = nullptr, *rv = nullptr;
   const int32_t rc = append_or_ride(h, layer, k_fp16_dev, v_fp16_dev, stream, &rk, &rv);
   if (rc != CQA_OK) return rc;
-  return step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev, nullptr,
-                          rung_served, stream, rk, rv);
+  const int64_t len_before = h->impl.length[layer];
+  const int32_t src = step_with_ladder(h, layer, q_fp16_dev, tol, nullptr, O_dev, cert_dev, flags_dev,
+                                       nullptr, rung_served, stream, rk, rv);
+  // a failure before the split launch (the launch that stores a riding token) leaves the cache as
+  // it was; later failures (a fallback without originals) keep the token
+  if (src == CQA_ERR_INVALID_ARG && rk != nullptr) h->impl.length[layer] = len_before - 1;
+  return src;
 }
 
 int32_t cqa_decode_step_enqueue(cqa_cache* h, int32_t layer, const void* k_fp16_dev,
@@ -877,7 +882,10 @@ int32_t cqa_decode_step_enqueue(cqa_cache* h, int32_t layer, const void* k_fp16_
   if (c->length[layer] <= 0) return CQA_ERR_INVALID_ARG;
   int32_t rc = launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
                                 nullptr, 0u, nullptr, (hipStream_t)stream, rk, rv);
-  if (rc != CQA_OK) return rc;
+  if (rc != CQA_OK) {
+    if (rk != nullptr) c->length[layer] -= 1;   // the launch that was to store the token did not happen
+    return rc;
+  }
   return launch_dense_ladder(c, layer, (const __half*)q_fp16_dev, tol->rung4_min_groups, O_dev,
                              cert_dev, flags_dev, (hipStream_t)stream);
 }
