@@ -502,3 +502,23 @@ def test_long_context_diffuse_heads_rung1_to_the_limit():
         check_against_oracle(oc, q, tol, sel, out)
         assert (out["k_star"] == 512).all()
         say(f"  promoted {int(out['promoted'].sum())} of {oc.n_blocks}")
+
+
+def test_adaptive_batched_serving_shape():
+    say("adaptive: batch 64 x 4096 tokens (2048 selector workgroups, 512 KV groups), three sampled sequences "
+        "against the oracle")
+    sh = workloads.SHAPES["serve64"]
+    k, v = workloads.make_kv("serve64", seed=0)
+    q = workloads.make_q("serve64", 1, seed=0)
+    rows = [0, 31, 63]
+    oc = oracle.OracleLayerCache(len(rows), sh.n_kv_heads)
+    oc.append(k[rows], v[rows])
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 16) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.995, 2, 64, 64, v_limit=32)
+        tol = att.Tolerances(rank_depth=1, rank_min_mass=0.25, v_tol=0.05)
+        out = gpu_adaptive(gc, q, tol, sel)
+        sub = {name: (val[rows] if isinstance(val, np.ndarray) else val) for name, val in out.items()}
+        check_against_oracle(oc, q[rows], tol, sel, sub)
+        say(f"  K* median {int(np.median(out['k_star']))} max {out['k_star'].max()}, "
+            f"promoted per group max {out['promoted'].sum(axis=2).max()}")
