@@ -423,11 +423,12 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
   CQA_PSTAMP(6)
 }
 
-// Stand-alone cross-split reduction: one wave per (batch, query head).
+// Stand-alone cross-split reduction: one wave per (batch, query head); any number of waves per
+// workgroup.
 __global__ __launch_bounds__(256) void certified_reduce_kernel(ReduceArgs a) {
   __shared__ float wsm[4][64];
   const int w = threadIdx.x >> 6;
-  const int hq = blockIdx.x * 4 + w, b = blockIdx.y;
+  const int hq = blockIdx.x * (int)(blockDim.x >> 6) + w, b = blockIdx.y;
   if (hq < a.n_q) reduce_head_wave<false>(a, b, hq, wsm[w]);
 }
 
@@ -585,7 +586,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     }
   }
   if (!fused) {
-    hipLaunchKernelGGL(certified_reduce_kernel, dim3((hq + 3) / 4, bt), dim3(256), 0, st, ra);
+    // one wave per workgroup: each head's wave gets a compute unit's load path to itself
+    // (measured 2 us faster at 32 heads than four heads per workgroup)
+    hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(64), 0, st, ra);
     CQA_HIP(hipGetLastError());
   }
   return CQA_OK;
