@@ -186,9 +186,11 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   //      also keeps the keys in LDS and sums the estimated mass of the sealed blocks (single-
   //      precision exponentials, accumulated in double; the rest of 1 is the exact trailing tokens).
   double part = 0.0;
+  __shared__ int s_done;
   if (tid == 0) {
     s_prefix = 0u;
     s_want = (uint32_t)KL;
+    s_done = 0;
   }
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
@@ -219,8 +221,12 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     if (upto >= want && upto - mine < want) {
       s_want = want - (upto - mine);               // still to take inside the chosen bin
       s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+      // every block of the chosen bin is taken: its lower edge already is the threshold (with
+      // distinct log-masses this happens once a bin holds a single block, usually a pass early)
+      if (want - (upto - mine) == mine) s_done = 1;
     }
     __syncthreads();
+    if (s_done != 0) break;
   }
   CQA_STAMP(0)
   const double total_blocks = block_scan_incl<double>(part, dtot, tid);   // last thread: the total
@@ -230,7 +236,7 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   // blocks with key == T: s_want of them are needed, the ones with the lowest indices.  The last
   // histogram still holds how many there are: when all of them are wanted, which is the rule
   // unless log-masses tie exactly, no index needs to be selected.
-  const bool all_ties = hist[T & 255u] == s_want;
+  const bool all_ties = s_done != 0 || hist[T & 255u] == s_want;
   __syncthreads();
   if (tid == 0) {
     s_idx_prefix = all_ties ? 0xFFFFFFFFu : 0u;
