@@ -522,3 +522,34 @@ def test_adaptive_batched_serving_shape():
         check_against_oracle(oc, q[rows], tol, sel, sub)
         say(f"  K* median {int(np.median(out['k_star']))} max {out['k_star'].max()}, "
             f"promoted per group max {out['promoted'].sum(axis=2).max()}")
+
+
+def test_random_small_shapes_and_selectors():
+    say("24 seeded random small shapes and selector settings (keys and values promoted, canary, exploration) "
+        "against the oracle")
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        bt = int(rng.integers(1, 3))
+        hkv = int(rng.integers(1, 3))
+        group = int(rng.choice([1, 2, 4]))
+        hq = hkv * group
+        n = int(rng.choice([16, 17, 33, 160, 161, 500, 1023, 1024, 2000]))
+        k, v, q = make_case(1000 + case, bt, hq, hkv, n, student=bool(rng.integers(0, 2)))
+        oc = oracle.OracleLayerCache(bt, hkv)
+        oc.append(k, v)
+        k_min = int(rng.integers(0, 4))
+        k_max = int(k_min + rng.integers(0, 40))
+        sel = ad.SelectorParams(float(rng.choice([0.5, 0.9, 0.995, 1.0])), k_min, k_max,
+                                int(k_max + rng.integers(0, 64)), v_limit=int(rng.choice([0, 0, 16, 64])),
+                                v_greedy=bool(rng.integers(0, 2)), canary=bool(rng.integers(0, 2)),
+                                explore_frac=float(rng.choice([0.0, 0.0, 0.03])), explore_seed=case)
+        tol = att.Tolerances(eps_key=float(rng.choice([np.inf, 0.05, 0.5])), v_tol=float(rng.choice([np.inf, 0.05])),
+                             eps_val=float(rng.choice([np.inf, 0.2])), rank_depth=int(rng.integers(0, 2)),
+                             rank_min_mass=float(rng.choice([0.0, 0.25])))
+        with GpuLayerCache(bt, hq, hkv, n + 8) as gc:
+            gc.append(k, v)
+            out = gpu_adaptive(gc, q, tol, sel)
+            try:
+                check_against_oracle(oc, q, tol, sel, out)
+            except AssertionError as e:
+                raise AssertionError(("case", case, bt, hkv, group, n, sel, tol)) from e

@@ -245,3 +245,39 @@ def test_caller_provided_tier2():
         cqa.cqa_cache_destroy(h)
     # the arrays are the caller's: still there, still holding the originals
     assert (t2k.numpy().reshape(bt, hkv, cap, 128)[:, :, :n].view(np.uint16) == k.view(np.uint16)).all()
+
+
+def test_random_small_shapes_against_oracle():
+    say("40 seeded random small shapes (batch, GQA width, lengths incl. < 16, = 16 k, ragged), random tolerance: "
+        "enqueue-only step with append against the oracle's append + decode_step")
+    cqa = load_binding()
+    rng = np.random.default_rng(2024)
+    lengths = [1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 64, 100, 255, 256, 257, 1000]
+    for case in range(40):
+        bt = int(rng.integers(1, 4))
+        hkv = int(rng.integers(1, 4))
+        group = int(rng.choice([1, 2, 4]))
+        hq = hkv * group
+        n = int(lengths[case % len(lengths)] if case < 2 * len(lengths) else rng.integers(1, 700))
+        k = (rng.standard_normal((bt, hkv, n + 1, 128)) * rng.choice([0.5, 1.0, 3.0])).astype(np.float16)
+        v = rng.standard_normal((bt, hkv, n + 1, 128)).astype(np.float16)
+        q = rng.standard_normal((bt, hq, 128)).astype(np.float16)
+        oc = oracle.OracleLayerCache(bt, hkv)
+        oc.append(k[:, :, :n], v[:, :, :n])
+        oc.append(k[:, :, n:], v[:, :, n:])
+        ref0 = oc.certified_decode(q, oracle.Tolerances())
+        tot = np.sort([r["E_key"] + r["E_val"] for r in ref0])
+        # a tolerance in the widest gap between the heads' totals (none: everything passes)
+        tol = oracle.Tolerances()
+        if len(tot) > 1:
+            gaps = np.diff(tot)
+            j = int(np.argmax(gaps))
+            if gaps[j] > 1e-3 * tot[j + 1]:
+                tol = oracle.Tolerances(eps_total=float(0.5 * (tot[j] + tot[j + 1])),
+                                        rung4_min_groups=int(rng.choice([0, 0, 2])))
+        ref = oc.decode_step(q, tol)
+        with GpuLayerCache(bt, hq, hkv, n + 8) as gc:
+            gc.append(k[:, :, :n], v[:, :, :n])
+            O, cert, flags = enqueue(gc, q, to_gpu_tol(cqa, tol), k[:, :, n:], v[:, :, n:])
+            assert gc.length() == n + 1
+            compare_all(gc, ref, O, cert, flags, ("case", case, bt, hkv, group, n))
