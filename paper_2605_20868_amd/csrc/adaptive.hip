@@ -603,7 +603,8 @@ struct AdaptiveReduceArgs {
 // (estimated mass left in INT8, best promoted block under either ranking, best unpromoted
 // block), then the first wave merges the partial sets of the attend pass and finalises the
 // certificate with these substituted.
-__global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs a) {
+constexpr int ART = 512;   // threads of the adaptive reduction: 8192 blocks in one trip of 16 per thread
+__global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs a) {
   const int tid = threadIdx.x;
   const int hq = blockIdx.x, b = blockIdx.y;
   const ReduceArgs& ra = a.ra;
@@ -621,12 +622,12 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY, maxc8 = 0.0f;
   int ix = -1, i8 = -1;
   double tail_mass = 0.0, l8u = 0.0, ev8u = 0.0;
-  for (int base = 0; base < ra.nb; base += 256 * BATCH) {
+  for (int base = 0; base < ra.nb; base += ART * BATCH) {
     float b8[BATCH], bx[BATCH], be[BATCH];
     int bs[BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {       // all loads of the batch first
-      const int i = base + j * 256 + tid;
+      const int i = base + j * ART + tid;
       const bool in = i < ra.nb;
       b8[j] = in ? l8[i] : 0.0f;
       bs[j] = in ? slot[i] : 0;
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
     }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const int i = base + j * 256 + tid;
+      const int i = base + j * ART + tid;
       if (i >= ra.nb) continue;
       const float v8 = b8[j];
       if (bs[j] & 1) {
@@ -662,9 +663,9 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
       }
     }
   }
-  __shared__ float s_bx[256], s_b8[256], s_tm[256], s_mc[256];
-  __shared__ int s_ix[256], s_i8[256];
-  __shared__ double s_mass[256], s_l8u[256], s_ev8u[256];
+  __shared__ float s_bx[ART], s_b8[ART], s_tm[ART], s_mc[ART];
+  __shared__ int s_ix[ART], s_i8[ART];
+  __shared__ double s_mass[ART], s_l8u[ART], s_ev8u[ART];
   __shared__ float wsm[64];
   __shared__ AdaptiveIn s_ad;
   s_bx[tid] = best_x;
@@ -677,7 +678,7 @@ __global__ __launch_bounds__(256) void adaptive_reduce_kernel(AdaptiveReduceArgs
   s_l8u[tid] = l8u;
   s_ev8u[tid] = ev8u;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
+  for (int s = ART / 2; s > 0; s >>= 1) {
     if (tid < s) {
       // larger value wins; equal values: the lower block index (-1 = nothing seen loses)
       const float ox = s_bx[tid + s];
@@ -891,7 +892,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   ar.eta = w.eta_blk;
   ar.pos_set0 = nsplit;
   ar.pos_set1 = nsplit + PROM_SPLITS;
-  hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(256), 0, st, ar);
+  hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(ART), 0, st, ar);
   CQA_HIP(hipGetLastError());
   return CQA_OK;
 }
