@@ -173,22 +173,30 @@ def group_union(selections, nb: int) -> np.ndarray:
 
 
 def ranking_check(l_int8: np.ndarray, l_fp16: np.ndarray, promoted: np.ndarray, delta_h: float,
-                  eps_guard: float) -> dict:
-    """Depth-1 ranking consistency plus boundary verification for one head.
+                  eps_guard: float, depth: int = 1) -> dict:
+    """Ranking consistency at depth r plus boundary verification for one head (the paper's
+    "Ranking-Consistency Check": the two top-r rankings over the promoted set must agree, and no
+    tail block may have an upper-bounded log-mass above the r-th highest FP16 log-mass).
 
     l_fp16 holds FP16 log-masses on promoted blocks (its values elsewhere are ignored).
+    Order: larger log-mass first, equal log-masses by lower block index.  With fewer than r
+    promoted blocks the depth is the number of promoted blocks.  Returns the two rankings
+    (block indices, best first), their heads top_fp16 / top_int8, and the two verdicts.
     """
     promoted = np.asarray(promoted, dtype=bool)
     if not promoted.any():
-        return dict(disagree=False, boundary=False, top_fp16=-1, top_int8=-1)
+        return dict(disagree=False, boundary=False, top_fp16=-1, top_int8=-1, rank_fp16=[], rank_int8=[],
+                    kth_fp16=-math.inf)
     idx = np.nonzero(promoted)[0]
-    top_fp16 = int(idx[np.argmax(l_fp16[idx])])          # first maximum = lowest index
-    top_int8 = int(idx[np.argmax(l_int8[idx])])
-    best = float(l_fp16[top_fp16])
+    r = max(1, min(int(depth), len(idx)))
+    # stable sort on the negated log-masses: ties keep ascending block order
+    rank_fp16 = [int(b) for b in idx[np.argsort(-l_fp16[idx], kind="stable")][:r]]
+    rank_int8 = [int(b) for b in idx[np.argsort(-l_int8[idx], kind="stable")][:r]]
+    kth = float(l_fp16[rank_fp16[-1]])
     tail = ~promoted
-    boundary = bool(tail.any() and float(l_int8[tail].max()) + delta_h + eps_guard > best)
-    return dict(disagree=top_fp16 != top_int8, boundary=boundary, top_fp16=top_fp16,
-                top_int8=top_int8)
+    boundary = bool(tail.any() and float(l_int8[tail].max()) + delta_h + eps_guard > kth)
+    return dict(disagree=rank_fp16 != rank_int8, boundary=boundary, top_fp16=rank_fp16[0],
+                top_int8=rank_int8[0], rank_fp16=rank_fp16, rank_int8=rank_int8, kth_fp16=kth)
 
 
 def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat: np.ndarray,
@@ -244,7 +252,8 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     alpha_hat = float(np.exp(np.asarray(l_int8, dtype=np.float64)[~promoted] - lse_int8).sum())
     e_key = att.key_term(delta_h, alpha_hat, v_max, tol.mass_exp, tol.key_bound_mode)
 
-    rk = ranking_check(np.asarray(l_int8, dtype=np.float64), l_b, promoted, delta_h, tol.eps_guard)
+    rk = ranking_check(np.asarray(l_int8, dtype=np.float64), l_b, promoted, delta_h, tol.eps_guard,
+                       max(1, tol.rank_depth))
     # score-consistency check: FP16 against INT8 scores on the key-promoted tokens
     score_dev = 0.0
     if nb and tok_prom.any():

@@ -346,3 +346,52 @@ def test_canary_passes_on_sound_metadata_and_fires_on_corruption():
     assert any(fired)
     quiet = ad.adaptive_decode(oc, q, att.Tolerances(), ad.SelectorParams(0.9, 1, 8, 8, explore_frac=0.05, explore_seed=7))
     assert not any(quiet[(0, h)]["flags"] & att.FLAG_PRECOND for h in range(4))   # check switched off
+
+
+def test_ranking_check_at_depth_r():
+    """Depth r of the paper's ranking-consistency check: hand cases, then an independent
+    formulation (sorted() on tuples) on random inputs, and depth 1 as the special case."""
+    l8 = np.array([5.0, 4.0, 3.0, 2.0, 1.0, 0.5])
+    prom = np.array([True, True, True, True, False, False])
+    # the top block agrees, the second and third are swapped by the FP16 scores
+    lx = np.array([5.2, 3.1, 3.9, 2.0, 0, 0])
+    d1 = ad.ranking_check(l8, lx, prom, 0.1, 1e-6, depth=1)
+    d2 = ad.ranking_check(l8, lx, prom, 0.1, 1e-6, depth=2)
+    d3 = ad.ranking_check(l8, lx, prom, 0.1, 1e-6, depth=3)
+    assert not d1["disagree"] and d1["rank_fp16"] == [0]
+    assert d2["disagree"] and d2["rank_fp16"] == [0, 2] and d2["rank_int8"] == [0, 1]
+    assert d3["disagree"] and d3["rank_fp16"] == [0, 2, 1] and d3["rank_int8"] == [0, 1, 2]
+    # the boundary moves with the depth: the tail's best (1.0 + 0.1) is below the 3rd FP16 log-mass
+    # (3.1) but above a 4th one lowered to 1.05
+    lx4 = np.array([5.2, 4.1, 3.1, 1.05, 0, 0])
+    assert not ad.ranking_check(l8, lx4, prom, 0.1, 1e-6, depth=3)["boundary"]
+    b4 = ad.ranking_check(l8, lx4, prom, 0.1, 1e-6, depth=4)
+    assert b4["boundary"] and not b4["disagree"] and b4["kth_fp16"] == 1.05
+    # more depth than promoted blocks: the depth is the size of the promoted set
+    assert ad.ranking_check(l8, lx4, prom, 0.1, 1e-6, depth=9)["rank_fp16"] == [0, 1, 2, 3]
+    # ties go to the lower block index under both rankings
+    t = ad.ranking_check(np.array([2.0, 2.0, 2.0, 0.0]), np.array([1.0, 1.0, 1.0, 0.0]),
+                         np.array([True, True, True, False]), 0.1, 0.0, depth=2)
+    assert t["rank_fp16"] == [0, 1] and t["rank_int8"] == [0, 1] and not t["disagree"]
+    rng = np.random.default_rng(5)
+    for trial in range(300):
+        nb = int(rng.integers(2, 40))
+        l8r = np.round(rng.normal(0, 2, nb), 1)              # rounded: ties occur
+        lxr = np.round(l8r + rng.normal(0, 0.15, nb), 1)
+        pr = rng.random(nb) < 0.4
+        r = int(rng.integers(1, 6))
+        delta, guard = 0.2, 1e-6
+        got = ad.ranking_check(l8r, lxr, pr, delta, guard, depth=r)
+        F = [b for b in range(nb) if pr[b]]
+        if not F:
+            assert not got["disagree"] and not got["boundary"]
+            continue
+        rr = min(r, len(F))
+        by_x = sorted(F, key=lambda b: (-lxr[b], b))[:rr]
+        by_8 = sorted(F, key=lambda b: (-l8r[b], b))[:rr]
+        assert got["rank_fp16"] == by_x and got["rank_int8"] == by_8
+        assert got["disagree"] == (by_x != by_8)
+        tail = [l8r[b] for b in range(nb) if not pr[b]]
+        assert got["boundary"] == (bool(tail) and max(tail) + delta + guard > lxr[by_x[-1]])
+        one = ad.ranking_check(l8r, lxr, pr, delta, guard)
+        assert one["rank_fp16"] == by_x[:1] and one["top_fp16"] == by_x[0]
