@@ -93,7 +93,8 @@ typedef struct cqa_tolerances {
   float rank_min_mass;      /* ranking test only if the top block holds >= this  */
   float eps_guard;          /* additive slack of the ranking test                */
   int32_t rank_depth;       /* r: 0 = ranking test off, 1 = top-1 block (the      */
-                            /* paper's default); r > 1: CQA_ERR_UNSUPPORTED      */
+                            /* paper's default); the adaptive calls take r <= 8,  */
+                            /* the one-pass calls r <= 1 (else UNSUPPORTED)       */
   int32_t mass_exp;         /* c in e^{c Delta}: 2 (theorems) or 3 (paper impl.)  */
   int32_t key_bound_mode;   /* 0 min(tanh, tail), 1 tail form only, 2 tanh only  */
   int32_t rung4_min_groups; /* >0: that many flagged KV groups => Rung 4         */
@@ -302,14 +303,15 @@ typedef struct cqa_selector {
  *     their originals and takes their step-1 contribution back out.  E_val uses
  *     the masses of the corrected result; E_key uses alpha_hat_T = step 1's
  *     estimated mass of the blocks the group left in INT8, and step 1's Delta_h;
- *  5. ranking check at depth 1 (if tol->rank_depth >= 1): RANK is set when the
- *     promoted block with the largest FP16 log-mass is not the one with the
- *     largest INT8 log-mass, or when an unpromoted block has
- *     l_b + Delta_h + eps_guard > that largest FP16 log-mass (gated by
- *     tol->rank_min_mass on the top block's mass).
+ *  5. ranking check at depth r = tol->rank_depth (1..8; 0 = off): RANK is set
+ *     when the r promoted blocks with the largest FP16 log-masses are not, in the
+ *     same order, the r with the largest INT8 log-masses (larger first, equal
+ *     ones by lower index; fewer than r promoted blocks: r = their number), or
+ *     when an unpromoted block has l_b + Delta_h + eps_guard > the r-th largest
+ *     FP16 log-mass (gated by tol->rank_min_mass on the top block's mass).
  * Outputs as cqa_certified_decode; cert.alpha_tail_hat is the achieved tail,
  * cert.top_block the promoted block with the largest FP16 log-mass,
- * cert.rank_margin = that log-mass - (largest unpromoted l_b + Delta_h).
+ * cert.rank_margin = the r-th largest FP16 log-mass - (largest unpromoted l_b + Delta_h).
  * Flags only REQUEST a fallback (Rung 3 / 4), as in cqa_certified_decode.
  * Needs the Tier-2 originals.  Asynchronous; shares the handle's workspaces.
  * Errors: INVALID_ARG (incl. selector out of range), NO_TIER2, HIP. */

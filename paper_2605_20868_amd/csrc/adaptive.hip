@@ -597,6 +597,8 @@ struct AdaptiveReduceArgs {
   const float* score_dev;  // [Bt][Hq] canary deviations, or null
   const float* eta;      // [Bt][Hkv][nb] value annotations eta_b written by the pass over all blocks
   int pos_set0, pos_set1;  // the promoted-block pass's positive partial sets
+  const int32_t* ulist;  // [Bt][Hkv][MAX_UNION] listed blocks of the group (ranking depth > 1)
+  const int32_t* ucount; // [Bt][Hkv]
 };
 
 // One workgroup per (batch, query head): all threads scan the block log-masses of both passes
@@ -701,16 +703,97 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
     }
     __syncthreads();
   }
+  // ---- ranking check (the paper's "Ranking-Consistency Check" with its boundary verification)
+  //      at depth r: the r best promoted blocks under the FP16 and under the INT8 log-masses must
+  //      be the same blocks in the same order, and no unpromoted block may reach the r-th FP16
+  //      log-mass with its upper-bounded one.  Depth 1 is what the scan has found; each further
+  //      place is one more arg-max over the group's listed blocks (a few dozen, held in registers),
+  //      restricted to what comes after the previous place in the order (larger log-mass first,
+  //      equal log-masses by lower index).  Fewer promoted blocks than r: the depth is their number.
+  const float top_x = s_bx[0], top_8 = s_b8[0];
+  const int top_ix = s_ix[0], top_i8 = s_i8[0];
+  bool disagree = top_ix >= 0 && top_ix != top_i8;
+  float kth_x = top_x;
+  const int depth = min(ra.tol.rank_depth, MAX_RANK_DEPTH);
+  if (depth > 1 && top_ix >= 0) {          // uniform over the workgroup
+    constexpr int CAND = MAX_UNION / ART;
+    float cx[CAND], c8[CAND];
+    int cb[CAND];
+    const int n = min(a.ucount[grp], MAX_UNION);
+    const int32_t* ulist = a.ulist + grp * MAX_UNION;
+#pragma unroll
+    for (int j = 0; j < CAND; ++j) {
+      const int i = j * ART + tid;
+      const int blk = i < n ? ulist[i] : -1;
+      const bool keyp = blk >= 0 && blk < ra.nb && (slot[blk] & 1);
+      cb[j] = keyp ? blk : -1;
+      cx[j] = keyp ? lx[blk] : 0.0f;
+      c8[j] = keyp ? l8[blk] : 0.0f;
+    }
+    float px = top_x, p8 = top_8;
+    int pix = top_ix, pi8 = top_i8;
+    __syncthreads();                        // every thread has read the depth-1 results
+    for (int k = 1; k < depth; ++k) {
+      float bx = -INFINITY, b8 = -INFINITY;
+      int jx = -1, j8 = -1;
+#pragma unroll
+      for (int j = 0; j < CAND; ++j) {
+        if (cb[j] < 0) continue;
+        if ((cx[j] < px || (cx[j] == px && cb[j] > pix)) &&
+            (jx < 0 || cx[j] > bx || (cx[j] == bx && cb[j] < jx))) {
+          bx = cx[j];
+          jx = cb[j];
+        }
+        if ((c8[j] < p8 || (c8[j] == p8 && cb[j] > pi8)) &&
+            (j8 < 0 || c8[j] > b8 || (c8[j] == b8 && cb[j] < j8))) {
+          b8 = c8[j];
+          j8 = cb[j];
+        }
+      }
+      s_bx[tid] = bx;
+      s_ix[tid] = jx;
+      s_b8[tid] = b8;
+      s_i8[tid] = j8;
+      __syncthreads();
+      for (int st = ART / 2; st > 0; st >>= 1) {
+        if (tid < st) {
+          const float ox = s_bx[tid + st];
+          const int oix = s_ix[tid + st];
+          if (oix >= 0 && (s_ix[tid] < 0 || ox > s_bx[tid] || (ox == s_bx[tid] && oix < s_ix[tid]))) {
+            s_bx[tid] = ox;
+            s_ix[tid] = oix;
+          }
+          const float o8 = s_b8[tid + st];
+          const int oi8 = s_i8[tid + st];
+          if (oi8 >= 0 && (s_i8[tid] < 0 || o8 > s_b8[tid] || (o8 == s_b8[tid] && oi8 < s_i8[tid]))) {
+            s_b8[tid] = o8;
+            s_i8[tid] = oi8;
+          }
+        }
+        __syncthreads();
+      }
+      const float nx = s_bx[0], n8 = s_b8[0];
+      const int nix = s_ix[0], ni8 = s_i8[0];
+      __syncthreads();                      // read before the next round overwrites
+      if (nix < 0) break;                   // fewer promoted blocks than the depth (uniform)
+      disagree = disagree || nix != ni8;
+      kth_x = nx;
+      px = nx;
+      pix = nix;
+      p8 = n8;
+      pi8 = ni8;
+    }
+  }
   if (tid == 0) {
     AdaptiveIn ad;
     ad.alpha = (float)s_mass[0];
     ad.delta = delta;
-    ad.top_block = s_ix[0];
-    ad.top_fp16 = s_ix[0] >= 0 ? s_bx[0] : -INFINITY;
+    ad.top_block = top_ix;
+    ad.top_fp16 = top_ix >= 0 ? top_x : -INFINITY;
+    ad.kth_fp16 = top_ix >= 0 ? kth_x : -INFINITY;
     const bool has_tail = s_tm[0] > -INFINITY;
     ad.tail_ub = has_tail ? s_tm[0] + delta : -INFINITY;
-    const bool disagree = s_ix[0] >= 0 && s_ix[0] != s_i8[0];
-    const bool boundary = s_ix[0] >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > s_bx[0];
+    const bool boundary = top_ix >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > kth_x;
     ad.rank_fail = (disagree || boundary) ? 1 : 0;
     ad.precond = (a.score_dev != nullptr && a.score_dev[row] > delta + ra.tol.eps_guard) ? 1 : 0;
     ad.pos_set0 = a.pos_set0;
@@ -892,6 +975,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   ar.eta = w.eta_blk;
   ar.pos_set0 = nsplit;
   ar.pos_set1 = nsplit + PROM_SPLITS;
+  ar.ulist = w.ulist;
+  ar.ucount = w.ucount;
   hipLaunchKernelGGL(adaptive_reduce_kernel, dim3(hq, bt), dim3(ART), 0, st, ar);
   CQA_HIP(hipGetLastError());
   return CQA_OK;

@@ -213,12 +213,13 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   return CQA_OK;
 }
 
-// Range checks of a tolerance set.  The ranking test is built at depth 1 (the paper's default);
-// a larger depth is refused rather than silently served by the depth-1 test.
-static int32_t check_tolerances(const cqa_tolerances* tol) {
+// Range checks of a tolerance set.  The one-pass path tests the ranking at depth 1 (the paper's
+// default) and the adaptive path up to MAX_RANK_DEPTH; a larger depth is refused rather than
+// silently served by a shallower test.
+static int32_t check_tolerances(const cqa_tolerances* tol, int max_rank_depth = 1) {
   if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2 || tol->rank_depth < 0)
     return CQA_ERR_INVALID_ARG;
-  if (tol->rank_depth > 1) return CQA_ERR_UNSUPPORTED;
+  if (tol->rank_depth > max_rank_depth) return CQA_ERR_UNSUPPORTED;
   return CQA_OK;
 }
 
@@ -808,12 +809,13 @@ static int32_t step_with_ladder(cqa_cache* h, int32_t layer, const void* q_fp16_
 }
 
 static int32_t check_decode_args(cqa_cache* h, int32_t layer, const void* q, const cqa_tolerances* tol,
-                                 float* O, cqa_head_cert* cert, uint32_t* flags) {
+                                 float* O, cqa_head_cert* cert, uint32_t* flags,
+                                 int max_rank_depth = 1) {
   if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q == nullptr ||
       tol == nullptr || O == nullptr || cert == nullptr || flags == nullptr)
     return CQA_ERR_INVALID_ARG;
   if (h->impl.length[layer] <= 0) return CQA_ERR_INVALID_ARG;
-  if (const int32_t trc = check_tolerances(tol)) return trc;
+  if (const int32_t trc = check_tolerances(tol, max_rank_depth)) return trc;
   return CQA_OK;
 }
 
@@ -919,7 +921,7 @@ int32_t cqa_ladder_counts(cqa_cache* h, int64_t* rung3_steps, int64_t* rung4_ste
 int32_t cqa_adaptive_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                             const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                             cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream) {
-  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev, MAX_RANK_DEPTH);
   if (rc != CQA_OK) return rc;
   rc = check_selector(h, sel);
   if (rc != CQA_OK) return rc;
@@ -931,7 +933,7 @@ int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                           const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                           cqa_head_cert* cert_dev, uint32_t* flags_dev, int32_t* rung_served,
                           void* stream) {
-  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev, MAX_RANK_DEPTH);
   if (rc != CQA_OK) return rc;
   rc = check_selector(h, sel);
   if (rc != CQA_OK) return rc;
@@ -942,7 +944,7 @@ int32_t cqa_adaptive_step(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
 int32_t cqa_adaptive_step_enqueue(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
                                   const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                                   cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream) {
-  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev);
+  int32_t rc = check_decode_args(h, layer, q_fp16_dev, tol, O_dev, cert_dev, flags_dev, MAX_RANK_DEPTH);
   if (rc != CQA_OK) return rc;
   rc = check_selector(h, sel);
   if (rc != CQA_OK) return rc;

@@ -123,6 +123,7 @@ struct AdaptiveWs {
   uint32_t sc_step;  // stamp of the last adaptive step
 };
 
+constexpr int MAX_RANK_DEPTH = 8;   // largest depth r of the ranking check (adaptive path)
 constexpr int SC_MAX_SLOTS = 1024;
 // per-block word of AdaptiveWs::slot: bit 0 FP16 keys, bit 1 FP16 values, bit 2 the keys are to
 // be stored into the scratch slot by the pass that reads them, bits 8.. scratch slot + 1 (0 = none)

@@ -125,6 +125,7 @@ struct AdaptiveIn {
   float alpha;       // sum over unpromoted blocks of the first pass's normalised masses
   float delta;       // Delta_h of the first pass
   float top_fp16;    // largest FP16 log-mass among promoted blocks (-inf if none)
+  float kth_fp16;    // the r-th largest (r = ranking depth; = top_fp16 at depth 1)
   float tail_ub;     // largest unpromoted INT8 log-mass + Delta_h (-inf if none)
   int top_block;     // the promoted block with the largest FP16 log-mass (-1 if none)
   int rank_fail;     // the two rankings disagree on the top block, or the boundary test failed
@@ -303,7 +304,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
                      margin <= 2.0f * delta + a.tol.eps_guard;
     if (ad != nullptr) {
       const bool any = ad->top_block >= 0;
-      margin = any ? ad->top_fp16 - ad->tail_ub : INFINITY;
+      margin = any ? ad->kth_fp16 - ad->tail_ub : INFINITY;
       rho_top = any ? expf(ad->top_fp16 - lse) : 0.0f;
       rank_flag = a.tol.rank_depth >= 1 && any && rho_top >= a.tol.rank_min_mass && ad->rank_fail != 0;
       I1 = ad->top_block;

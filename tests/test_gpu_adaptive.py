@@ -544,7 +544,7 @@ def test_random_small_shapes_and_selectors():
                                 v_greedy=bool(rng.integers(0, 2)), canary=bool(rng.integers(0, 2)),
                                 explore_frac=float(rng.choice([0.0, 0.0, 0.03])), explore_seed=case)
         tol = att.Tolerances(eps_key=float(rng.choice([np.inf, 0.05, 0.5])), v_tol=float(rng.choice([np.inf, 0.05])),
-                             eps_val=float(rng.choice([np.inf, 0.2])), rank_depth=int(rng.integers(0, 2)),
+                             eps_val=float(rng.choice([np.inf, 0.2])), rank_depth=int(rng.choice([0, 1, 2, 3, 8])),
                              rank_min_mass=float(rng.choice([0.0, 0.25])))
         with GpuLayerCache(bt, hq, hkv, n + 8) as gc:
             gc.append(k, v)
@@ -553,3 +553,57 @@ def test_random_small_shapes_and_selectors():
                 check_against_oracle(oc, q, tol, sel, out)
             except AssertionError as e:
                 raise AssertionError(("case", case, bt, hkv, group, n, sel, tol)) from e
+
+
+def test_ranking_check_at_depth_r():
+    say("adaptive: ranking check at depths 1..8 on diffuse heads, flags and margins against the oracle")
+    k, v, q = make_case(41, 2, 8, 2, 16 * 220 + 5)
+    oc = oracle.OracleLayerCache(2, 2)
+    oc.append(k, v)
+    with GpuLayerCache(2, 8, 2, 16 * 220 + 16) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.5, 4, 24, 24)
+        flagged = {}
+        for depth in (1, 2, 3, 5, 8):
+            tol = att.Tolerances(rank_depth=depth, rank_min_mass=0.0, eps_guard=0.0)
+            out = gpu_adaptive(gc, q, tol, sel)
+            check_against_oracle(oc, q, tol, sel, out)
+            flagged[depth] = (out["flags"] & att.FLAG_RANK) != 0
+        say("  heads with RANK by depth: " + ", ".join(f"{d}: {int(f.sum())}" for d, f in flagged.items()))
+        # a group with fewer promoted blocks than the depth: the depth is their number
+        sel2 = ad.SelectorParams(0.0, 2, 2, 2)
+        tol = att.Tolerances(rank_depth=8, rank_min_mass=0.0)
+        out = gpu_adaptive(gc, q, tol, sel2)
+        check_against_oracle(oc, q, tol, sel2, out)
+        with pytest.raises(gc.cqa.CqaError) as e:
+            gpu_adaptive(gc, q, att.Tolerances(rank_depth=9), sel)
+        assert e.value.status == gc.cqa.ERR_UNSUPPORTED
+
+
+def test_ranking_depth_two_catches_a_swap_below_the_top_block():
+    say("adaptive: a dominant block, then two nearly tied blocks that the INT8 scores order the other way round: "
+        "certified at depth 1, RANK at depth 2 and deeper")
+    # the tied pair of test_adaptive_ranking_check_and_ladder (with this seed the INT8 scores swap it) ...
+    k, v, q = make_case(10, 1, 8, 2, 4096 + 3)
+    p1, p2 = workloads.plant_near_tie(k, v, q, 0, 5, 8, seed=10, gap=12.0, nudge=0.002)
+    # ... under a third key along the same direction whose logit lies 3 above the pair's
+    qf = q[0, 5].astype(np.float64)
+    base = k[0, 1, p1].astype(np.float64)
+    l1 = float(qf @ base) / math.sqrt(128.0)
+    p0 = 16 * 100 + 7
+    assert p0 // 16 not in (p1 // 16, p2 // 16)
+    k[0, 1, p0] = (base * (1.0 + 3.0 / l1)).astype(np.float16)
+    oc = oracle.OracleLayerCache(1, 2)
+    oc.append(k, v)
+    with GpuLayerCache(1, 8, 2, 4200) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.995, 3, 32, 32)
+        got = {}
+        for depth in (1, 2, 3):
+            tol = att.Tolerances(rank_depth=depth, rank_min_mass=0.25)
+            out = gpu_adaptive(gc, q, tol, sel)
+            check_against_oracle(oc, q, tol, sel, out)
+            got[depth] = bool(out["flags"][0, 5] & att.FLAG_RANK)
+            assert int(out["cert"]["top_block"][0, 5]) == p0 // 16
+            assert out["promoted"][0, 1, [p0 // 16, p1 // 16, p2 // 16]].all()
+        assert got == {1: False, 2: True, 3: True}
