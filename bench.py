@@ -4,8 +4,8 @@
 A step = one pass of the whole hot path over the 128K single-layer workload:
 append one (k, v) token per KV head (trailing FP16 block, Tier-2 copy, block seal
 when 16 tokens have arrived), the split-K certified decode over the packed
-cache, the cross-split reduction with the certificate, the flag read-back and
-the fallback ladder (tolerances +inf in the headline run, so no head falls back).
+cache, the cross-split reduction with the certificate, and the fallback ladder resolved
+by a device kernel (tolerances +inf in the headline run, so no head falls back).
 
 Prints ONE JSON line.  `value` is whole-step throughput (steps/s for the one
 layer) with all inputs resident in HBM; `roofline` prices the dominant kernel
@@ -424,14 +424,15 @@ def main() -> int:
         atol = cqa.Tolerances(rank_depth=1, rank_min_mass=0.25)
         n_ad = 20
         for i in range(3):
-            cqa.cqa_adaptive_step(h, 0, qp + i * q_stride, atol, sel, Op, certp, flagsp, stream)
+            cqa.cqa_adaptive_step_enqueue(h, 0, qp + i * q_stride, atol, sel, Op, certp, flagsp, stream)
         torch.cuda.synchronize()
+        lc0 = cqa.cqa_ladder_counts(h)
         ta0 = time.perf_counter()
-        rungs = []
         for i in range(n_ad):
-            rungs.append(cqa.cqa_adaptive_step(h, 0, qp + (W + i) * q_stride, atol, sel, Op, certp, flagsp, stream))
+            cqa.cqa_adaptive_step_enqueue(h, 0, qp + (W + i) * q_stride, atol, sel, Op, certp, flagsp, stream)
         torch.cuda.synchronize()
         ad_ms = (time.perf_counter() - ta0) * 1e3 / n_ad
+        lc1 = cqa.cqa_ladder_counts(h)
         kst, _, prom, *_ = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
         prom = prom & 1
         # the same with value promotion (second rung) on: blocks whose estimated contribution exceeds
@@ -439,11 +440,11 @@ def main() -> int:
         vsel = cqa.Selector(0.995, 2, 128, 128, v_limit=128)
         vtol = cqa.Tolerances(rank_depth=1, rank_min_mass=0.25, v_tol=0.05)
         for i in range(3):
-            cqa.cqa_adaptive_step(h, 0, qp + i * q_stride, vtol, vsel, Op, certp, flagsp, stream)
+            cqa.cqa_adaptive_step_enqueue(h, 0, qp + i * q_stride, vtol, vsel, Op, certp, flagsp, stream)
         torch.cuda.synchronize()
         tv0 = time.perf_counter()
         for i in range(n_ad):
-            cqa.cqa_adaptive_step(h, 0, qp + (W + i) * q_stride, vtol, vsel, Op, certp, flagsp, stream)
+            cqa.cqa_adaptive_step_enqueue(h, 0, qp + (W + i) * q_stride, vtol, vsel, Op, certp, flagsp, stream)
         torch.cuda.synchronize()
         adv_ms = (time.perf_counter() - tv0) * 1e3 / n_ad
         vstate = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
@@ -454,7 +455,7 @@ def main() -> int:
             torch.cuda.synchronize()
             tt = time.perf_counter()
             for i in range(n_ad):
-                cqa.cqa_adaptive_step(h, 0, qp + (first + i) * q_stride, tl, sl, Op, certp, flagsp, stream)
+                cqa.cqa_adaptive_step_enqueue(h, 0, qp + (first + i) * q_stride, tl, sl, Op, certp, flagsp, stream)
             torch.cuda.synchronize()
             return (time.perf_counter() - tt) * 1e3 / n_ad
         cqa.cqa_set_scratch_slots(h, 1024)
@@ -465,10 +466,10 @@ def main() -> int:
         ad_info = {"ms_per_step": ad_ms, "ms_per_step_with_value_promotion": adv_ms,
                    "key_scratch": {"ms_per_step_filling": ad_cold_ms, "ms_per_step_all_hits": ad_warm_ms,
                                    "slots_per_kv_head": sc_slots, "hits": sc_hits, "misses": sc_misses},
-                   "value_blocks_per_head_median": float(np.median(vstate[5])), "steps_with_fallback": int(sum(1 for r in rungs if r)),
+                   "value_blocks_per_head_median": float(np.median(vstate[5])), "steps_with_fallback": int(sum(lc1) - sum(lc0)),
                    "k_star_median": float(np.median(kst)), "k_star_max": int(kst.max()),
                    "promoted_blocks_per_group_max": int(prom.sum(axis=2).max()),
-                   "what": f"cqa_adaptive_step, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
+                   "what": f"cqa_adaptive_step_enqueue, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
                            "check on, rank_min_mass 0.25; steps that fall back include the dense recompute); "
                            "promoted keys are read from pinned host RAM by the kernel; key_scratch: the same "
                            "20 queries with the optional device-resident FP16-key scratch switched on, "
