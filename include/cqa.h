@@ -125,7 +125,10 @@ typedef struct cqa_head_cert {
  * [128] FP16.  They must be pinned host memory that the device can address
  * (hipHostMalloc or a framework's pinned allocation; checked with
  * hipPointerGetAttributes): the library's kernels read and write them in place.
- * The library never frees them.  Errors: INVALID_ARG (null, too small, not pinned
+ * The library never frees them and writes to them only what it appends (with its
+ * own arrays it also gives every page a first copy-engine access at creation;
+ * arrays that no copy has touched yet make the first bulk append slower).
+ * Errors: INVALID_ARG (null, too small, not pinned
  * host memory, wrong tier2_mode), otherwise as cqa_cache_create. */
 int32_t cqa_cache_create_caller_tier2(const cqa_cache_desc* desc, void* t2_k_host, void* t2_v_host,
                                       int64_t bytes_each, cqa_cache** out);
