@@ -359,7 +359,7 @@ int32_t cqa_scratch_stats(cqa_cache* c, int32_t* slots_per_head, int64_t* hits, 
  * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (bit 0 = the
  * group scored this block with FP16 keys, bit 1 = it attended its FP16 values);
  * logmass_int8_host / logmass_mixed_host float [batch][n_q_heads][n_blocks] (block
- * log-masses of the two passes); v_count_host int32 [batch][n_q_heads] and
+ * log-masses of step 1, and of step 4 where a block was revisited, else step 1's); v_count_host int32 [batch][n_q_heads] and
  * v_selected_host int32 [batch][n_q_heads][512] (the head's value selection, largest
  * contribution first); contrib_host float [batch][n_q_heads][n_blocks] (the estimated
  * contributions p_b eta_b the value selection ranked; valid when v_limit > 0);

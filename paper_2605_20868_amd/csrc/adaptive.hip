@@ -603,7 +603,8 @@ struct AdaptiveReduceArgs {
 
 // One workgroup per (batch, query head): all threads scan the block log-masses of both passes
 // (estimated mass left in INT8, best promoted block under either ranking, best unpromoted
-// block), then the first wave merges the partial sets of the attend pass and finalises the
+// block), then the first wave merges the partial sets of the pass over all blocks and of the
+// promoted-block pass and finalises the
 // certificate with these substituted.
 constexpr int ART = 512;   // threads of the adaptive reduction: 8192 blocks in one trip of 16 per thread
 __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs a) {

@@ -60,7 +60,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.stage = d->tier2_mode == CQA_TIER2_PINNED ? d->max_tokens * D * 2 : 0;
   s.select = (int64_t)d->batch * d->n_q_heads * 4;
   s.ladder_ws = d->tier2_mode == CQA_TIER2_PINNED ? ladder_ws_floats((int64_t)d->batch * d->n_q_heads) * 4 : 0;
-  // adaptive key precision (needs the originals): log-masses of two passes, selections, masks,
+  // adaptive key precision (needs the originals): log-masses of the pass over all blocks and of the promoted-block pass, selections, masks,
   // slot maps and lists, for one layer-step at a time
   const bool ad = d->tier2_mode == CQA_TIER2_PINNED;
   const int64_t rows = (int64_t)d->batch * d->n_q_heads, groups = (int64_t)d->batch * d->n_kv_heads;

@@ -95,7 +95,7 @@ constexpr int PROM_SPLITS = 32;             // workgroups (= partial sets) per K
 // Workspace of the adaptive path, shared by all layers (one decode step at a time).
 struct AdaptiveWs {
   float* lm8;        // [Bt][Hq][nb_cap]      INT8 block log-masses of the pass over all blocks
-  float* lmx;        // [Bt][Hq][nb_cap]      block log-masses of the attend pass (FP16 keys where promoted)
+  float* lmx;        // [Bt][Hq][nb_cap]      log-masses of the listed blocks as the promoted-block pass computed them (FP16 keys where promoted)
   int32_t* sel;      // [Bt][Hq][MAX_K_LIMIT] the head's own selection, best first
   int32_t* kstar;    // [Bt][Hq]              its size after Rung-1 growth
   float* alpha;      // [Bt][Hq]              estimated mass of the blocks its group left in INT8
@@ -190,7 +190,7 @@ struct DecodeArgs {
   int n_q, n_kv;
   int debug;           // 0 in production; 1 = every load of a wave hits its first block (timing probe)
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
-  // attend pass with gated key precision (null slot = every block uses its INT8 keys)
+  // promoted-block pass of the adaptive decode (null slot = not that pass)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
   __half* sc_k;             // layer base of the FP16-key scratch [Bt * Hkv][sc_cap][16][128], or null
   int sc_cap;

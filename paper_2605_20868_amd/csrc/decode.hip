@@ -39,7 +39,7 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
 }
 
 // PROM = false: the vector-ALU split pass over a contiguous range of sealed blocks (INT8 keys).
-// PROM = true : the promoted-block pass of the attend pass with gated precision: the workgroups
+// PROM = true : the promoted-block pass of the adaptive decode (gated precision): the workgroups
 //               of a KV group walk the group's list of promoted blocks.  A key-promoted block is
 //               scored from its FP16 keys (sigma = 1, z = 0, no score error), a value-promoted
 //               block is attended from its FP16 values and counts with eta_b = 0; both kinds of
@@ -472,7 +472,7 @@ int pick_splits(const Cache* c, int64_t n_blocks) {
   return nsplit;
 }
 
-// Promoted-block pass of the attend pass with gated key precision (see certified_split_kernel).
+// Promoted-block pass of the adaptive decode (see certified_split_kernel).
 int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStream_t st) {
   if (a.ulist == nullptr || a.ucount == nullptr || a.slot == nullptr || a.t2_k == nullptr ||
       a.t2_v == nullptr)

@@ -117,7 +117,7 @@ __device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
   }
 }
 
-// What the attend pass with gated key precision substitutes in the certificate (the paper's total
+// What the adaptive decode (gated key precision) substitutes in the certificate (the paper's total
 // error bound with the achieved tail mass, and its ranking-consistency check): the estimated mass
 // of the blocks left in INT8 and Delta_h come from the first (all-INT8) pass, the ranking verdict from a scan
 // over the block log-masses of both passes.
