@@ -49,7 +49,8 @@ enum {
   CQA_ERR_NO_TIER2 = -4,
   CQA_ERR_CAPACITY = -5,
   CQA_ERR_HIP = -6,
-  CQA_ERR_UNSUPPORTED = -7
+  CQA_ERR_UNSUPPORTED = -7,
+  CQA_ERR_SCRATCH = -8   /* the shape needs more than the fixed scratch of a no-allocation call */
 };
 
 /* Where the FP16 originals live (the paper's Tier 2). */
@@ -196,6 +197,30 @@ int32_t cqa_cache_export_block(const cqa_cache* c, int32_t layer, int32_t batch,
 int32_t cqa_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
                              const cqa_tolerances* tol, float* O_dev, cqa_head_cert* cert_dev,
                              uint32_t* flags_dev, float* blk_logmass_dev, void* stream);
+
+/* cqa_certified_decode for callers that cannot allocate device memory or have it
+ * allocated on their behalf: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels, same results and the same
+ * arguments (without the optional log-mass output); the only difference is where
+ * the per-split partial results live between the split pass and the reduction:
+ * not in the cache's workspace but in a fixed array of CQA_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (each GPU the library runs on holds
+ * its own copy from load until the process ends; its address on the cache's GPU
+ * is resolved when the cache is created).  The call itself allocates nothing and
+ * calls no allocating routine; inputs and outputs are the caller's as before.
+ * Limit: batch * n_q_heads * splits * 576 bytes must fit the array, where splits
+ * is what cqa_decode_splits reports (about 2 * compute units / (batch * n_kv_heads),
+ * so any shape fits unless cqa_set_splits forces more); beyond it the call fails
+ * with CQA_ERR_SCRATCH and touches nothing.  Every such call on one GPU uses that
+ * GPU's one array, whatever the cache: calls that overlap on a GPU (two streams,
+ * two caches) race and must be ordered by the caller.  The array keeps the last
+ * call's contents; every word a call reads it has written first, so nothing needs
+ * clearing.  The current device must be the cache's.
+ * Errors: as cqa_certified_decode, plus CQA_ERR_SCRATCH. */
+#define CQA_STATIC_SCRATCH_BYTES (4 * 1024 * 1024)
+int32_t cqa_certified_decode_noalloc(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
+                                     const cqa_tolerances* tol, float* O_dev,
+                                     cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream);
 
 /* The paper's Rung 3 / Rung 4 body: recomputes dense FP16 attention (FP32
  * accumulation) from the Tier-2 originals for the selected heads and overwrites

@@ -23,6 +23,8 @@ ERR_NO_TIER2 = -4
 ERR_CAPACITY = -5
 ERR_HIP = -6
 ERR_UNSUPPORTED = -7
+ERR_SCRATCH = -8
+STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
 
 TIER2_PINNED = 0
 TIER2_NONE = 1
@@ -115,6 +117,7 @@ def _load():
         "cqa_cache_reset": (i32, [vp, i32]),
         "cqa_cache_export_block": (i32, [vp, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]),
         "cqa_certified_decode": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp, vp]),
+        "cqa_certified_decode_noalloc": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp]),
         "cqa_dense_fallback": (i32, [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp]),
         "cqa_decode_step": (i32, [vp, i32, vp, C.POINTER(Tolerances), vp, vp, vp, vp,
                                   C.POINTER(i32), vp]),
@@ -257,6 +260,13 @@ def cqa_certified_decode(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flag
     _check(_lib.cqa_certified_decode(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev),
                                      _ptr(cert_dev), _ptr(flags_dev), _ptr(blk_logmass_dev),
                                      _ptr(stream)), "cqa_certified_decode")
+
+
+def cqa_certified_decode_noalloc(h, layer, q_dev, tol: Tolerances, O_dev, cert_dev, flags_dev,
+                                 stream=None) -> None:
+    _check(_lib.cqa_certified_decode_noalloc(h, layer, _ptr(q_dev), C.byref(tol), _ptr(O_dev),
+                                             _ptr(cert_dev), _ptr(flags_dev), _ptr(stream)),
+           "cqa_certified_decode_noalloc")
 
 
 def cqa_dense_fallback(h, layer, q_dev, head_select_host, all_heads, rung, O_dev, cert_dev=None,

@@ -195,6 +195,7 @@ const char* cqa_strerror(int32_t status) {
     case CQA_ERR_CAPACITY: return "cache capacity exceeded";
     case CQA_ERR_HIP: return "HIP runtime error (see cqa_last_hip_error)";
     case CQA_ERR_UNSUPPORTED: return "unsupported geometry";
+    case CQA_ERR_SCRATCH: return "shape exceeds the fixed scratch of the no-allocation call";
     default: return "unknown status";
   }
 }
@@ -329,6 +330,16 @@ static int32_t create_cache(const cqa_cache_desc* desc, __half* caller_k, __half
                                  hipMemcpyDeviceToHost, nullptr));
       }
       CQA_TRY(hipDeviceSynchronize());
+    }
+  }
+  {
+    // this device's copy of the fixed scratch of the no-allocation decode: resolve its address now,
+    // so that the call itself only looks it up
+    void* p = nullptr;
+    const int32_t src = static_scratch(c->device, &p);
+    if (src != CQA_OK) {
+      release(h);
+      return src;
     }
   }
   CQA_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
@@ -575,6 +586,30 @@ int32_t cqa_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev
   if (const int32_t trc = check_tolerances(tol)) return trc;
   return launch_certified(&h->impl, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev,
                           flags_dev, nullptr, 0u, blk_logmass_dev, (hipStream_t)stream);
+}
+
+int32_t cqa_certified_decode_noalloc(cqa_cache* h, int32_t layer, const void* q_fp16_dev,
+                                     const cqa_tolerances* tol, float* O_dev,
+                                     cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream) {
+  if (h == nullptr || layer < 0 || layer >= h->impl.desc.n_layers || q_fp16_dev == nullptr ||
+      tol == nullptr || O_dev == nullptr || cert_dev == nullptr || flags_dev == nullptr)
+    return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  if (c->length[layer] <= 0) return CQA_ERR_INVALID_ARG;
+  if (const int32_t trc = check_tolerances(tol)) return trc;
+  int cur = -1;
+  CQA_HIP(hipGetDevice(&cur));
+  if (cur != c->device) return CQA_ERR_INVALID_ARG;
+  // the partial sets of this launch: [batch * q heads][splits][PART_FLOATS] floats
+  const int64_t nsplit = pick_splits(c, c->length[layer] / BLK);
+  const int64_t need = (int64_t)c->desc.batch * c->desc.n_q_heads * std::max<int64_t>(nsplit, 1) * PART_FLOATS * 4;
+  if (need > CQA_STATIC_SCRATCH_BYTES) return CQA_ERR_SCRATCH;
+  void* sp = nullptr;
+  const int32_t src = static_scratch(c->device, &sp);   // resolved at cache creation: a lookup
+  if (src != CQA_OK) return src;
+  return launch_certified(c, layer, (const __half*)q_fp16_dev, *tol, O_dev, cert_dev, flags_dev,
+                          nullptr, 0u, nullptr, (hipStream_t)stream, nullptr, nullptr, 0, nullptr,
+                          (float*)sp);
 }
 
 int32_t cqa_time_certified_decode(cqa_cache* h, int32_t layer, const void* q_fp16_dev,

@@ -238,7 +238,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
                          const __half* k_new = nullptr,
-                         const __half* v_new = nullptr, int pstride = 0, float* eta_out = nullptr);
+                         const __half* v_new = nullptr, int pstride = 0, float* eta_out = nullptr,
+                         float* partials = nullptr);   // null = the cache's own split workspace
+int32_t static_scratch(int device, void** out);
 int pick_splits(const Cache* c, int64_t n_blocks);
 int stream_nt(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);

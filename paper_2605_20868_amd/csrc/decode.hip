@@ -12,6 +12,8 @@
 //   the reduction merges the splits, attends the trailing FP16 tokens exactly and
 //   evaluates  E_key = 2 V_max min(tanh Delta_h, min{1, e^{c Delta_h} alpha_hat}(e^{2 Delta_h} - 1)),
 //   E_val = sum_b rho_b eta_b  and the flag word.
+#include <mutex>
+
 #include "cqa_internal.h"
 #include "reduce_inl.h"
 
@@ -487,11 +489,41 @@ int32_t launch_promoted_pass(const DecodeArgs& a, int group, dim3 grid, hipStrea
   return CQA_OK;
 }
 
+// Split partials of callers that must not allocate: one array per GPU, placed by the loader when
+// the code object is loaded on that GPU and held until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress; kernels receive the resolved address.
+constexpr int64_t STATIC_SCRATCH_BYTES = CQA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];   // per device: address of its copy of `scratch` (null = not resolved yet)
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of the static scratch; resolved once per device, with that
+// device current (cqa_cache_create does it for the device it creates the cache on).
+int32_t static_scratch(int device, void** out) {
+  if (device < 0 || device >= MAX_DEVICES) return CQA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    int cur = -1;
+    CQA_HIP(hipGetDevice(&cur));
+    if (cur != device) return CQA_ERR_INVALID_ARG;
+    void* p = nullptr;
+    CQA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return CQA_ERR_HIP;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return CQA_OK;
+}
+
 int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_tolerances& tol, float* O,
                          cqa_head_cert* cert, uint32_t* flags, uint32_t* flags_mirror,
                          uint32_t mirror_tag, float* blk_logmass, hipStream_t st,
-                         const __half* k_new, const __half* v_new, int pstride, float* eta_out) {
+                         const __half* k_new, const __half* v_new, int pstride, float* eta_out,
+                         float* partials) {
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
+  if (partials == nullptr) partials = c->partials;
   const int64_t len = c->length[layer];
   const int64_t nb = len / BLK;
   const int r = (int)(len % BLK);
@@ -499,7 +531,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   split_geometry(c, nb, &nsplit, &bps);
   const int64_t layer_head0 = head_index(c, layer, 0, 0);
   ReduceArgs ra{};
-  ra.partials = c->partials;
+  ra.partials = partials;
   ra.q = q;
   ra.trail_k = c->trail_k + layer_head0 * BLK * D;
   ra.trail_v = c->trail_v + layer_head0 * BLK * D;
@@ -521,7 +553,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
     a.sigmax = c->sigmax + layer_head0;
     a.q = q;
-    a.partials = c->partials;
+    a.partials = partials;
     a.blk_logmass = blk_logmass;
     a.nq_cap = c->nq_cap;
     a.nb = (int)nb;
