@@ -21,8 +21,8 @@
  * side stream with its events.  The caller owns q, O, cert, flags, blk_logmass
  * and the main stream.  All kernels are enqueued on the caller's stream; only
  * the host-resolved steps (cqa_decode_step, cqa_append_decode_step,
- * cqa_adaptive_step), which read the flag words back, the test hooks and the
- * statistics getters wait for the device; cqa_decode_step_enqueue and
+ * cqa_adaptive_step), which read the flag words back, and the statistics getters
+ * wait for the device (as do the test hooks of cqa_test.h); cqa_decode_step_enqueue and
  * cqa_adaptive_step_enqueue never do.
  *
  * Concurrency: the decode calls of one handle share its workspaces (split
@@ -210,7 +210,7 @@ int32_t cqa_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev
  * calls no allocating routine; inputs and outputs are the caller's as before.
  * Limit: batch * n_q_heads * splits * 576 bytes must fit the array, where splits
  * is what cqa_decode_splits reports (about 2 * compute units / (batch * n_kv_heads),
- * so any shape fits unless cqa_set_splits forces more); beyond it the call fails
+ * so any shape fits unless a test hook forces more splits); beyond it the call fails
  * with CQA_ERR_SCRATCH and touches nothing.  Every such call on one GPU uses that
  * GPU's one array, whatever the cache: calls that overlap on a GPU (two streams,
  * two caches) race and must be ordered by the caller.  The array keeps the last
@@ -378,25 +378,6 @@ int32_t cqa_adaptive_step_enqueue(cqa_cache* c, int32_t layer, const void* q_fp1
 int32_t cqa_set_scratch_slots(cqa_cache* c, int32_t n_slots);
 int32_t cqa_scratch_stats(cqa_cache* c, int32_t* slots_per_head, int64_t* hits, int64_t* misses);
 
-/* Test hook: what the last adaptive decode decided, copied to the host after a
- * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
- * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*
- * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (bit 0 = the
- * group scored this block with FP16 keys, bit 1 = it attended its FP16 values);
- * logmass_int8_host / logmass_mixed_host float [batch][n_q_heads][n_blocks] (block
- * log-masses of step 1, and of step 4 where a block was revisited, else step 1's); v_count_host int32 [batch][n_q_heads] and
- * v_selected_host int32 [batch][n_q_heads][512] (the head's value selection, largest
- * contribution first); contrib_host float [batch][n_q_heads][n_blocks] (the estimated
- * contributions p_b eta_b the value selection ranked; valid when v_limit > 0);
- * score_dev_host float [batch][n_q_heads] (largest |s_fp16 - s_int8| the canary saw
- * on the head's key-promoted tokens; valid when sel->canary was set).
- * Any pointer may be NULL.  n_blocks = sealed blocks of `layer`. */
-int32_t cqa_adaptive_state(cqa_cache* c, int32_t layer, int32_t* k_star_host,
-                           int32_t* selected_host, uint8_t* promoted_host,
-                           float* logmass_int8_host, float* logmass_mixed_host,
-                           int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host,
-                           float* score_dev_host);
-
 /* Dense FP16 decode attention on device-resident K, V (the same kernel the
  * fallback runs after paging): softmax(q K^T / sqrt(128)) V with FP32
  * accumulation.  q [batch][n_q_heads][128] FP16; k, v [batch][n_kv_heads]
@@ -409,51 +390,12 @@ int32_t cqa_dense_attention(const void* q_fp16_dev, const void* k_fp16_dev,
                             void* workspace_dev, void* stream);
 int64_t cqa_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int64_t n_tokens);
 
-/* ---- measurement and misc ------------------------------------------------ */
-
-/* The streaming-read ceiling of the split pass: launches, `iters` times back to back,
- * a kernel that loads the Tier-1 records of `layer` with the split pass's launch
- * shape and load instructions and computes nothing, and returns its mean duration
- * (milliseconds, host) and the bytes one launch reads (host, may be NULL).  For
- * benchmarks: achieved bandwidth of the split pass / this = how much of what the
- * memory system delivers for this access pattern the pass reaches. */
-int32_t cqa_time_stream_read(cqa_cache* c, int32_t layer, int32_t iters, float* ms_per_launch,
-                             int64_t* bytes_per_launch, void* stream);
-
-/* Launches cqa_certified_decode `iters` times back to back on `stream`,
- * bracketed by HIP events recorded on that same stream, synchronises, and
- * returns the mean duration of one step in milliseconds in *ms_per_step
- * (host).  For benchmarks; the outputs hold the last iteration's results. */
-int32_t cqa_time_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev,
-                                  const cqa_tolerances* tol, float* O_dev,
-                                  cqa_head_cert* cert_dev, uint32_t* flags_dev,
-                                  float* blk_logmass_dev, int32_t iters, float* ms_per_step,
-                                  void* stream);
-
-/* Per-launch timing of the split-K decode kernel (the dominant kernel), taken
- * with HIP event pairs attached to its dispatch on the stream each
- * cqa_certified_decode / cqa_decode_step call launches it on (the pair brackets
- * the kernel's execution, not the launch overhead).  begin arms up to max_launches pairs
- * (<= 65536); end synchronises on them and returns the mean and minimum kernel
- * duration in milliseconds and the number of launches timed (host pointers,
- * any may be NULL).  For benchmarks. */
-int32_t cqa_profile_begin(cqa_cache* c, int32_t max_launches);
-int32_t cqa_profile_end(cqa_cache* c, float* mean_ms, float* min_ms, int32_t* n_launches);
+/* ---- misc ------------------------------------------------------------------ */
 
 /* Split count the decode pass uses for the current length of `layer`
- * (for reporting; chosen from the device's compute-unit count). */
+ * (for reporting and for sizing the no-allocation call; chosen from the device's
+ * compute-unit count). */
 int32_t cqa_decode_splits(const cqa_cache* c, int32_t layer, int32_t* n_splits);
-/* Overrides the automatic split count (0 restores it).  For tests. */
-int32_t cqa_set_splits(cqa_cache* c, int32_t n_splits);
-
-/* How the matrix-core decode kernel loads Tier-1 records: 0 = chosen from the bytes a
- * whole decode step (all layers) streams, the default; 1 = plain loads; 2 = loads with
- * the non-temporal hint.  Results do not depend on it.  For tests and measurement. */
-int32_t cqa_set_stream_hint(cqa_cache* c, int32_t mode);
-
-/* Chooses the split-K decode kernel: 0 = matrix-core (MFMA) kernel, the default;
- * 1 = the vector-ALU kernel (same results to rounding; kept as a cross-check).  For tests. */
-int32_t cqa_set_kernel_variant(cqa_cache* c, int32_t variant);
 
 const char* cqa_strerror(int32_t status);
 int32_t cqa_version(void);

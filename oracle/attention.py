@@ -37,6 +37,10 @@ Readings where the paper is silent (the HIP path follows the same ones):
   block is certified iff  l_(1) - l_(2) > 2 Delta_h + eps_guard.  The check is
   skipped for heads whose top block holds less than rank_min_mass.  Ties in
   l_b go to the lower block index.
+* The certificate is reported in binary32 (the paper's policy table keeps the
+  certificate's accumulators in FP32): a key term whose value exceeds the
+  binary32 range (2 Delta_h beyond ~88.7 in the tail form) is +inf, which is a
+  non-finite certificate quantity and raises PRECOND.
 * Flag word: bit0 KEY (E_key > eps_key), bit1 VAL (E_val > eps_val or
   max_b rho_b eta_b > v_tol), bit2 RANK, bit3 PRECOND (a non-finite certificate
   quantity), bit4 TOTAL (E_key + E_val > eps_total); force_flags is OR-ed in.
@@ -56,6 +60,7 @@ FLAG_PRECOND = 8
 FLAG_TOTAL = 16
 FLAG_ANY = FLAG_KEY | FLAG_VAL | FLAG_RANK | FLAG_PRECOND | FLAG_TOTAL
 RUNG_SHIFT = 8
+FLT_MAX = float(np.finfo(np.float32).max)   # certificates are reported in binary32
 
 
 @dataclasses.dataclass
@@ -90,8 +95,9 @@ def key_term(delta_h: float, alpha_hat: float, v_max: float, mass_exp: int = 2,
     if alpha_hat <= 0.0 or delta_h == 0.0:
         t_tail = 0.0
     else:
-        grow = math.exp(min(mass_exp * delta_h, 700.0))
-        widen = math.expm1(min(2.0 * delta_h, 700.0))
+        # beyond the binary64 range the factors are +inf; the cap keeps math.exp from raising
+        grow = math.exp(mass_exp * delta_h) if mass_exp * delta_h < 700.0 else math.inf
+        widen = math.expm1(2.0 * delta_h) if 2.0 * delta_h < 700.0 else math.inf
         t_tail = min(1.0, grow * alpha_hat) * widen
     t_full = math.tanh(delta_h)
     if mode == 0:
@@ -100,7 +106,8 @@ def key_term(delta_h: float, alpha_hat: float, v_max: float, mass_exp: int = 2,
         tv = t_tail
     else:
         tv = t_full
-    return 2.0 * v_max * tv
+    e_key = 2.0 * v_max * tv
+    return e_key if abs(e_key) <= FLT_MAX else math.copysign(math.inf, e_key)
 
 
 def certified_head(q16: np.ndarray, k_hat: np.ndarray, v_hat: np.ndarray, sigma: np.ndarray,

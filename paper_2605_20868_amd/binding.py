@@ -1,6 +1,7 @@
 """Thin ctypes binding of libcqa.so: argument marshalling only.
 
-Function names mirror the C ABI in include/cqa.h.  Pointers are accepted as
+Function names mirror the C ABI in include/cqa.h (the product boundary) and
+include/cqa_test.h (test hooks and measurement helpers).  Pointers are accepted as
 Python ints, ctypes pointers or any object with a `data_ptr()` method (e.g. a
 torch tensor used purely as device memory).  Every computation runs in the HIP
 library; there is no CPU fallback: if the library is missing or fails to load,
@@ -141,6 +142,7 @@ def _load():
         "cqa_time_stream_read": (i32, [vp, i32, i32, C.POINTER(C.c_float), C.POINTER(i64), vp]),
         "cqa_profile_begin": (i32, [vp, i32]),
         "cqa_profile_end": (i32, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]),
+        "cqa_profile_durations": (i32, [vp, vp, i32, C.POINTER(i32)]),
         "cqa_decode_splits": (i32, [vp, i32, C.POINTER(i32)]),
         "cqa_set_splits": (i32, [vp, i32]),
         "cqa_set_stream_hint": (i32, [vp, i32]),
@@ -400,6 +402,16 @@ def cqa_profile_end(h):
     mean, mn, n = C.c_float(0), C.c_float(0), C.c_int32(0)
     _check(_lib.cqa_profile_end(h, C.byref(mean), C.byref(mn), C.byref(n)), "cqa_profile_end")
     return mean.value, mn.value, n.value
+
+
+def cqa_profile_durations(h):
+    """numpy float32 array: duration in ms of every launch timed by the last begin / end pair."""
+    import numpy as np
+    n = C.c_int32(0)
+    _check(_lib.cqa_profile_durations(h, None, 0, C.byref(n)), "cqa_profile_durations")
+    out = np.zeros(max(n.value, 1), np.float32)
+    _check(_lib.cqa_profile_durations(h, _ptr(out), n.value, C.byref(n)), "cqa_profile_durations")
+    return out[:n.value]
 
 
 def cqa_decode_splits(h, layer) -> int:

@@ -173,12 +173,6 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     if (tid == 0) a.kstar[row] = 0;
     return;
   }
-#ifdef CQA_PROBE_SELECT
-  const uint64_t ts0 = wall_clock64();
-#define CQA_STAMP(N) if (tid == 0) a.sel[row * MAX_K_LIMIT + 500 + (N)] = (int)(wall_clock64() - ts0);
-#else
-#define CQA_STAMP(N)
-#endif
   const double lse = (double)a.cert[row].lse;
   const float lse_f = a.cert[row].lse;
 
@@ -228,7 +222,6 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     __syncthreads();
     if (s_done != 0) break;
   }
-  CQA_STAMP(0)
   const double total_blocks = block_scan_incl<double>(part, dtot, tid);   // last thread: the total
   __shared__ double s_total;
   if (tid == ST - 1) s_total = total_blocks;
@@ -264,7 +257,6 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     __syncthreads();
   }
   __syncthreads();
-  CQA_STAMP(1)
   const uint32_t Tidx = s_idx_prefix;            // largest index taken among the ties
   const double total = s_total;
 
@@ -277,7 +269,6 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     }
   })
   __syncthreads();
-  CQA_STAMP(2)
   const int n = (int)min(s_cnt, (uint32_t)KL);
   // ---- rank sort: a winner's place is the number of winners that precede it (keys are distinct)
   for (int i = tid; i < n; i += ST) {
@@ -287,13 +278,11 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     sorted_idx[rank] = (int)(0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull));
   }
   __syncthreads();
-  CQA_STAMP(3)
   // ---- masses of the winners, best first, and their inclusive prefix sums: thread t owns place t
   const double m0 = tid < n ? (VALUES ? (double)lm[sorted_idx[tid]] : exp((double)lm[sorted_idx[tid]] - lse)) : 0.0;
   const double upto1 = block_scan_incl<double>(m0, dtot, tid);
   if (tid < MAX_K_LIMIT) pm[tid] = upto1;
   __syncthreads();
-  CQA_STAMP(4)
   if (!VALUES) {
     // ---- covering prefix: C_k = rho_trail + (mass of the k best); K* never exceeds k_max, so
     //      the search stops there; then clamps and Rung-1 growth
@@ -346,7 +335,6 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
     }
   }
   __syncthreads();
-  CQA_STAMP(5)
   const int k = s_k;
   uint32_t* um = a.umask + ((int64_t)b * a.n_kv + hq / (a.n_q / a.n_kv)) * a.mask_words;
   for (int i = tid; i < k; i += ST) {
@@ -807,7 +795,7 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
     a.alpha_out[row] = ad.alpha;
   }
   __syncthreads();
-  if (tid < 64) reduce_head_wave<false>(ra, b, hq, wsm, &s_ad);
+  if (tid < 64) reduce_head_wave(ra, b, hq, wsm, &s_ad);
 }
 
 }  // namespace
@@ -945,7 +933,6 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.bps = bps;
   a.n_q = hq;
   a.n_kv = hkv;
-  a.debug = 0;
   a.slot = w.slot;
   a.sc_k = w.sc_slots > 0 ? w.sc_k + layer_head0 * w.sc_cap * BLK * D : nullptr;
   a.sc_cap = w.sc_cap;
@@ -953,11 +940,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.ucount = w.ucount;
   a.t2_k = c->t2_k + layer_head0 * c->desc.max_tokens * D;
   a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
-#ifdef CQA_PROBE_PROM
-  a.eta_out = w.contrib;   // build-time probe: the promoted-block pass stamps its phases here
-#else
   a.eta_out = nullptr;
-#endif
   a.score_dev = sel.canary ? w.score_dev : nullptr;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;

@@ -90,7 +90,6 @@ static void release(cqa_cache* h) {
   (void)hipDeviceSynchronize();
   (void)hipFree(c->t1);
   (void)hipFree(c->sigmax);
-  (void)hipFree(c->tickets);
   (void)hipFree(c->trail_k);
   (void)hipFree(c->trail_v);
   (void)hipFree(c->partials);
@@ -139,6 +138,7 @@ static void release(cqa_cache* h) {
       if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
     delete[] c->prof_ev;
   }
+  delete[] c->prof_ms;
   delete[] c->length;
   delete h;
 }
@@ -258,8 +258,6 @@ static int32_t create_cache(const cqa_cache_desc* desc, __half* caller_k, __half
   CQA_TRY(hipMemset(c->t1, 0, (size_t)s.t1));
   CQA_ALLOC_DEV(c->sigmax, s.heads * 4);
   CQA_TRY(hipMemset(c->sigmax, 0, (size_t)s.heads * 4));
-  CQA_ALLOC_DEV(c->tickets, s.heads * 4);
-  CQA_TRY(hipMemset(c->tickets, 0, (size_t)s.heads * 4));
   CQA_ALLOC_DEV(c->trail_k, s.trail);
   CQA_ALLOC_DEV(c->trail_v, s.trail);
   CQA_ALLOC_DEV(c->partials, s.partials);
@@ -479,9 +477,8 @@ int32_t cqa_set_stream_hint(cqa_cache* h, int32_t mode) {
 }
 
 int32_t cqa_set_kernel_variant(cqa_cache* h, int32_t variant) {
-  if (h == nullptr || variant < 0 || variant > 0x301) return CQA_ERR_INVALID_ARG;
-  h->impl.variant = variant & 1;
-  h->impl.debug = variant >> 8;
+  if (h == nullptr || variant < 0 || variant > 1) return CQA_ERR_INVALID_ARG;
+  h->impl.variant = variant;
   return CQA_OK;
 }
 
@@ -694,10 +691,16 @@ int32_t cqa_profile_end(cqa_cache* h, float* mean_ms, float* min_ms, int32_t* n_
   const int n = c->prof_n;
   double sum = 0.0;
   float mn = 0.0f;
+  delete[] c->prof_ms;
+  c->prof_ms = new (std::nothrow) float[(size_t)(n > 0 ? n : 1)];
+  c->prof_ms_n = 0;
+  if (c->prof_ms == nullptr) return CQA_ERR_INVALID_ARG;
   for (int i = 0; i < n; ++i) {
     CQA_HIP(hipEventSynchronize(c->prof_ev[2 * i + 1]));
     float ms = 0.0f;
     CQA_HIP(hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    c->prof_ms[i] = ms;
+    c->prof_ms_n = i + 1;
     sum += ms;
     mn = (i == 0 || ms < mn) ? ms : mn;
   }
@@ -705,6 +708,15 @@ int32_t cqa_profile_end(cqa_cache* h, float* mean_ms, float* min_ms, int32_t* n_
   if (min_ms) *min_ms = mn;
   if (n_launches) *n_launches = n;
   c->prof_n = c->prof_cap;  // stop recording until the next begin
+  return CQA_OK;
+}
+
+int32_t cqa_profile_durations(cqa_cache* h, float* ms_host, int32_t cap, int32_t* n_launches) {
+  if (h == nullptr || cap < 0 || (cap > 0 && ms_host == nullptr)) return CQA_ERR_INVALID_ARG;
+  Cache* c = &h->impl;
+  const int n = c->prof_ms != nullptr ? c->prof_ms_n : 0;
+  for (int i = 0; i < n && i < cap; ++i) ms_host[i] = c->prof_ms[i];
+  if (n_launches) *n_launches = n;
   return CQA_OK;
 }
 

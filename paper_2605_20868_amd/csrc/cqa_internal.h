@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/cqa.h"
+#include "../../include/cqa_test.h"
 
 namespace cqa {
 
@@ -141,7 +142,6 @@ struct Cache {
   // Tier-1: quad records, [heads_total][nq_cap][QUAD_BYTES]
   uint8_t* t1;
   int64_t nq_cap;            // quad records of capacity per head
-  uint32_t* tickets;         // [heads_total] arrival counters of the fused reduction (zero between launches)
   float* ladder_ws;          // device-resolved ladder: split partials, arrival counters, rung counters
   uint32_t* ladder_tickets;
   uint32_t* ladder_counts;
@@ -171,7 +171,8 @@ struct Cache {
   // optional per-launch timing of the split kernel (pairs of events on the launch stream)
   hipEvent_t* prof_ev;
   int prof_cap, prof_n;
-  int debug;                 // timing probes (0 in production)
+  float* prof_ms;            // host: durations of the launches timed by the last begin / end pair
+  int prof_ms_n;
   int variant;               // 0 = matrix-core split kernel (default), 1 = vector-ALU split kernel
   int stream_hint;           // Tier-1 loads: 0 = chosen from the footprint, 1 = plain, 2 = non-temporal
   AdaptiveWs ad;             // allocated with the cache when Tier-2 is retained
@@ -188,7 +189,6 @@ struct DecodeArgs {
   int nsplit;
   int bps;             // blocks per split
   int n_q, n_kv;
-  int debug;           // 0 in production; 1 = every load of a wave hits its first block (timing probe)
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
   // promoted-block pass of the adaptive decode (null slot = not that pass)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
@@ -244,12 +244,11 @@ int32_t static_scratch(int device, void** out);
 int pick_splits(const Cache* c, int64_t n_blocks);
 int stream_nt(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
-struct ReduceArgs;
 int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
                         const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
                         uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st);
-int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
-                          dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st);
+int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t ev0, hipEvent_t ev1,
+                          hipStream_t st);
 
 int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
                            uint32_t* sink, hipStream_t st);

@@ -19,27 +19,6 @@
 
 namespace cqa {
 
-__device__ __forceinline__ void wave_sync() {
-  // LDS operations of one wave execute in order; this only stops the compiler from
-  // moving LDS accesses across the point where lanes exchange data.
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-
-// merges top-2 state (t1, i1, t2) with (u1, j1, u2); ties go to the lower block index
-__device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float u1, int j1, float u2) {
-  const bool keep = (t1 > u1) || (t1 == u1 && (unsigned)i1 <= (unsigned)j1);
-  if (keep) {
-    t2 = fmaxf(t2, u1);
-  } else {
-    t2 = fmaxf(u2, t1);
-    t1 = u1;
-    i1 = j1;
-  }
-}
-
 // PROM = false: the vector-ALU split pass over a contiguous range of sealed blocks (INT8 keys).
 // PROM = true : the promoted-block pass of the adaptive decode (gated precision): the workgroups
 //               of a KV group walk the group's list of promoted blocks.  A key-promoted block is
@@ -47,19 +26,8 @@ __device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float 
 //               block is attended from its FP16 values and counts with eta_b = 0; both kinds of
 //               originals are read by the device straight from the pinned Tier-2 arrays over the
 //               host link.  Writes partial sets split0 + blockIdx.x.
-#ifdef CQA_PROBE_PROM
-#define CQA_PSTAMP(N)                                                                        \
-  if (PROM && a.eta_out != nullptr && l == 0 && (N) < 8)                                     \
-    reinterpret_cast<int*>(a.eta_out)[((((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + w) * 8 + (N)] = \
-        (int)(wall_clock64() - ts0);
-#else
-#define CQA_PSTAMP(N)
-#endif
 template <int G, bool PROM>
 __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
-#ifdef CQA_PROBE_PROM
-  const uint64_t ts0 = wall_clock64();
-#endif
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int tok = l & 15, kg = l >> 4;              // roles in the score phase
   const int vn = l & 15, vgh = (l >> 4) & 1, vo = l >> 5;  // roles in the value phase
@@ -116,7 +84,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     for (int gq = 0; gq < 4; ++gq) acc[gq][h] = 0.0f;
   }
 
-  CQA_PSTAMP(0)
   // the list entry of the next iteration is requested one iteration ahead
   int blk_next = (PROM && b0 + w < b1) ? a.ulist[grp * MAX_UNION + b0 + w] : b0 + w;
   for (int pos = b0 + w; pos < b1; pos += bstep) {
@@ -124,7 +91,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     const int blk = blk_next;
     blk_next = (PROM && pos + bstep < b1) ? a.ulist[grp * MAX_UNION + pos + bstep] : pos + bstep;
     if (PROM && (blk < 0 || blk >= a.nb)) continue;
-    if (pos == b0 + w) { CQA_PSTAMP(1) }
     // Every load of the block is requested here, before anything is consumed: the block sits at
     // an address nothing else in this launch touches, so each dependent load costs a full
     // memory (and page-walk) latency.  First everything whose address follows from blk alone
@@ -186,7 +152,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       for (int j = 0; j < 4; ++j)
         *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) = v16r[j];
     }
-    if (pos == b0 + w && pf >= 0) { CQA_PSTAMP(2) }
     // ---- scaled query, per-block constant, per-block score-error bound
     const float2 sg = kfp ? make_float2(1.0f, 1.0f) : sg8;
     const float2 zz = kfp ? make_float2(0.0f, 0.0f) : zz8;
@@ -278,7 +243,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         dev[h] = fmaxf(dev[h], fabsf(s16 - (d8[h] + c8[h]) * inv_sqrt_d));
       }
     }
-    if (pos == b0 + w && dot[0] == dot[0]) { CQA_PSTAMP(3) }
     float p[G], alpha[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -343,7 +307,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       }
     }
     wave_sync();
-    if (pos == b0 + w) { CQA_PSTAMP(4) }
   }
 
   if (PROM && a.score_dev != nullptr) {
@@ -357,7 +320,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         atomicMax(reinterpret_cast<int*>(a.score_dev + (int64_t)b * a.n_q + kvh * G + h), __float_as_int(d));
     }
   }
-  CQA_PSTAMP(5)
   // ---- merge the four waves of the workgroup, then write one partial per q-head
   float* mo = &qs[0][0][0];  // reuse: [4][G][D]
   __syncthreads();
@@ -422,7 +384,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     pp[P_T2] = T2;
     pp[P_I1] = __int_as_float(I1);
   }
-  CQA_PSTAMP(6)
 }
 
 // Stand-alone cross-split reduction: one wave per (batch, query head); any number of waves per
@@ -431,7 +392,7 @@ __global__ __launch_bounds__(256) void certified_reduce_kernel(ReduceArgs a) {
   __shared__ float wsm[4][64];
   const int w = threadIdx.x >> 6;
   const int hq = blockIdx.x * (int)(blockDim.x >> 6) + w, b = blockIdx.y;
-  if (hq < a.n_q) reduce_head_wave<false>(a, b, hq, wsm[w]);
+  if (hq < a.n_q) reduce_head_wave(a, b, hq, wsm[w]);
 }
 
 // Workgroups ("splits") per (batch, kv-head) and, for the vector-ALU kernel, blocks per split.
@@ -547,7 +508,6 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
   ra.r = r;
   ra.n_q = hq;
   ra.n_kv = hkv;
-  bool fused = false;
   if (nb > 0) {
     DecodeArgs a{};   // every field starts null / zero
     a.t1 = c->t1 + layer_head0 * c->nq_cap * QUAD_BYTES;
@@ -586,7 +546,6 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.bps = bps;
     a.n_q = hq;
     a.n_kv = hkv;
-    a.debug = c->debug;
     a.stream_nt = stream_nt(c, nb);
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
@@ -594,14 +553,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
     if (c->variant == 0 || a.eta_out != nullptr) {   // eta_b comes from this kernel only
-      // debug 3: the last workgroup of each (batch, kv-head) to finish also runs the reduction.
-      // Measured no faster than the separate launch, with many splits (60.4 against 59.7 us at
-      // 128K) and with one split per group (batch 64 x 4K tokens: 129.1 against 130.2 us per
-      // step): the reduction is a chain of dependent device-scope round trips either way, and
-      // fused it extends the big kernel.  Kept as a probe; tested for identical bits.
-      fused = c->debug == 3;
-      const int32_t rc = launch_split_mfma(a, ra, fused ? c->tickets + layer_head0 : nullptr,
-                                           hq / hkv, grid, ev0, ev1, st);
+      const int32_t rc = launch_split_mfma(a, hq / hkv, grid, ev0, ev1, st);
       if (rc != CQA_OK) return rc;
     } else {
       switch (hq / hkv) {
@@ -617,12 +569,10 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
       ++c->prof_n;
     }
   }
-  if (!fused) {
-    // one wave per workgroup: each head's wave gets a compute unit's load path to itself
-    // (measured 2 us faster at 32 heads than four heads per workgroup)
-    hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(64), 0, st, ra);
-    CQA_HIP(hipGetLastError());
-  }
+  // one wave per workgroup: each head's wave gets a compute unit's load path to itself
+  // (measured 2 us faster at 32 heads than four heads per workgroup)
+  hipLaunchKernelGGL(certified_reduce_kernel, dim3(hq, bt), dim3(64), 0, st, ra);
+  CQA_HIP(hipGetLastError());
   return CQA_OK;
 }
 

@@ -50,7 +50,6 @@ union HF8 {
   uint32_t u[4];
 };
 
-// two FP32 values -> packed FP16, round toward zero (never overflows to infinity); x0 in the low half
 // Loads of Tier-1 records, which a launch reads exactly once.  NT = with the non-temporal hint.
 // Measured on a pure read stream of this shape: when every launch reads memory that no recent
 // launch has touched (a layer stack, or one layer beyond ~500 MB) the hinted loads reach
@@ -67,6 +66,7 @@ __device__ __forceinline__ uint4 ld_stream4(const uint8_t* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// two FP32 values -> packed FP16, round toward zero (never overflows to infinity); x0 in the low half
 __device__ __forceinline__ f16x2 pack_f16_rtz(float x0, float x1) {
   return __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(x0, x1));
 }
@@ -77,12 +77,6 @@ __device__ __forceinline__ uint32_t bytes_to_f16_codes(uint32_t d) {
   const uint32_t m = __builtin_amdgcn_perm(0x64646464u, d, SEL);
   const f16x2 c = {(_Float16)-1152.0f, (_Float16)-1152.0f};
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, m) + c);
-}
-
-__device__ __forceinline__ void wave_sync_m() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // two FP32 values -> their upper 16 bits packed (x0 in the low half): bf16 by truncation
@@ -111,18 +105,6 @@ __device__ __forceinline__ float trunc_bf16(float x) {
   return __uint_as_float(__float_as_uint(x) & 0xffff0000u);
 }
 
-__device__ __forceinline__ void top2_merge_m(float& t1, int& i1, float& t2, float u1, int j1,
-                                             float u2) {
-  const bool keep = (t1 > u1) || (t1 == u1 && (unsigned)i1 <= (unsigned)j1);
-  if (keep) {
-    t2 = fmaxf(t2, u1);
-  } else {
-    t2 = fmaxf(u2, t1);
-    t1 = u1;
-    i1 = j1;
-  }
-}
-
 constexpr int KM_ROW = 2 * D + 4;       // floats per staged K-meta block (+4: bank spread over blocks)
 constexpr int VM_ROW = 2 * BLK * NG + 32;  // halves per staged V-meta block (+32: bank spread)
 constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability buffer
@@ -130,8 +112,7 @@ constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability bu
 // LM: also writes the block log-masses (and, when asked, eta_b per block) for callers that rank
 // blocks afterwards.  NT: Tier-1 loads carry the non-temporal hint.
 template <int G, bool LM, bool NT>
-__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a, ReduceArgs ra,
-                                                                      uint32_t* tickets) {
+__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
@@ -156,15 +137,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int b0 = 4 * q0;
   const int b1 = min(4 * (q0 + base + mine), a.nb);
   const float inv_sqrt_d = 0.08838834764831845f;
-#ifdef CQA_PROBE_TIMESTAMPS
-  // Build-time probe (off in the library): with -DCQA_PROBE_TIMESTAMPS every wave stamps the
-  // 100 MHz wall clock at start, loop entry, loop exit and end into the buffer passed as
-  // blk_logmass ([waves][4] uint64), which shows launch skew, per-XCD speed and the tail.
-  uint64_t* ts = reinterpret_cast<uint64_t*>(a.blk_logmass) +
-                 ((((int64_t)b * a.n_kv + kvh) * a.nsplit + split) * 4 + w) * 4;
-  const bool ts_on = a.blk_logmass != nullptr && l == 0;   // no buffer given: no stamps
-  if (ts_on) ts[0] = wall_clock64();
-#endif
 
   __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
   __shared__ __align__(16) __half vmbuf[4][4][VM_ROW];   // [wave][block of quad][scale | offset]
@@ -173,7 +145,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
   __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
   __shared__ float sbuf[4];                              // [head] 1 / S_h
-  __shared__ int lastflag;
   __shared__ __align__(16) float mo[4][G][D];
   __shared__ float ms[4][G][12];
 
@@ -185,11 +156,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const int64_t grp = (int64_t)b * a.n_kv + kvh;
     const uint32_t kx = reinterpret_cast<const uint32_t*>(a.ap_k_new + grp * D)[l];
     const uint32_t vx = reinterpret_cast<const uint32_t*>(a.ap_v_new + grp * D)[l];
-    // device-scope stores: with the fused reduction a workgroup on another XCD reads them
-    __hip_atomic_store(reinterpret_cast<uint32_t*>(a.ap_trail_k + (grp * BLK + a.ap_slot) * D) + l, kx,
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(reinterpret_cast<uint32_t*>(a.ap_trail_v + (grp * BLK + a.ap_slot) * D) + l, vx,
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    reinterpret_cast<uint32_t*>(a.ap_trail_k + (grp * BLK + a.ap_slot) * D)[l] = kx;
+    reinterpret_cast<uint32_t*>(a.ap_trail_v + (grp * BLK + a.ap_slot) * D)[l] = vx;
     if (a.ap_t2_k != nullptr) {
       reinterpret_cast<uint32_t*>(a.ap_t2_k + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = kx;
       reinterpret_cast<uint32_t*>(a.ap_t2_v + (grp * a.ap_max_tokens + a.ap_pos) * D)[l] = vx;
@@ -224,8 +192,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
   //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
   //             2P + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
-  const int ql = a.debug == 1 ? b0 : max((b1 - 1) & ~3, b0);   // first block of the wave's last quad
-  const int park = a.debug == 1 ? (b0 >> 2) : 0;   // record that absorbs the unused last prefetch
+  const int ql = max((b1 - 1) & ~3, b0);   // first block of the wave's last quad
+  const int park = 0;                      // record that absorbs the unused last prefetch
   const uint8_t* const head_base = a.t1 + head_rec * QUAD_BYTES;
   const uint32_t lo16 = (uint32_t)l * 16u;
   const uint32_t vo16 = (uint32_t)kg * 512u + (uint32_t)n * 16u;
@@ -306,9 +274,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
   for (int g = 0; g < 8; ++g) acc[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-#ifdef CQA_PROBE_TIMESTAMPS
-  if (ts_on) ts[1] = wall_clock64();
-#endif
   for (; qb < b1; qb += 4) {
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
     bool live[4];   // block is inside this wave's run
@@ -324,10 +289,10 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     for (int P = 0; P < 2; ++P)
       reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
     CQA_LOAD_META(qb + 4)
-    wave_sync_m();
+    wave_sync();
 
-    // ---- scores.  A operand: scaled query of column-role (h, j), three bf16 terms;
-    //      B operand: the 16 tokens of block i as exact bf16 integers (code + 128).
+    // ---- scores.  A operand: scaled query of row-role (h, j), two FP16 terms (hi + lo);
+    //      B operand: the 16 tokens of block i, their signed codes as exact FP16 integers.
     //      C_i[row (head kg, block v)][col token n]: row v == i is the one kept.
     f32x4 C[4];
 #pragma unroll
@@ -398,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     // (all four kg lanes of a column hold the same sums and store the same words: no branch)
     cbuf[w][0][h][j] = cb;
     cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d) * unscale_op;
-    wave_sync_m();
+    wave_sync();
     const float4 cb4 = *reinterpret_cast<const float4*>(&cbuf[w][0][kg][0]);
     const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
     const float cbs[4] = {cb4.x, cb4.y, cb4.z, cb4.w};
@@ -457,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       }
     }
     abuf[w][kg] = alpha;   // every lane of the row stores the same word
-    wave_sync_m();
+    wave_sync();
 
     __builtin_amdgcn_s_setprio(0);
     // ---- rescale the accumulators (an accumulator lane's head is kg, its own softmax head)
@@ -529,12 +494,9 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    wave_sync_m();
+    wave_sync();
   }
 
-#ifdef CQA_PROBE_TIMESTAMPS
-  if (ts_on) ts[2] = wall_clock64();
-#endif
   // ---- per-wave epilogue: fold the offset sums in; the softmax state of head kg is already
   //      complete in every lane of row kg
 #pragma unroll
@@ -569,7 +531,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float o = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - M) * mo[ww][hh][c];
-    st_agent(a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c, o);
+    a.partials[(((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c] = o;
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
@@ -584,39 +546,19 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       EVM = fmaxf(EVM, fw * ms[ww][hh][3]);
       DM = fmaxf(DM, ms[ww][hh][4]);
       VM = fmaxf(VM, ms[ww][hh][5]);
-      top2_merge_m(T1, I1, T2, ms[ww][hh][6], __float_as_int(ms[ww][hh][8]), ms[ww][hh][7]);
+      top2_merge(T1, I1, T2, ms[ww][hh][6], __float_as_int(ms[ww][hh][8]), ms[ww][hh][7]);
     }
     float* pp = a.partials + (((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS;
-    st_agent(pp + P_M, M);
-    st_agent(pp + P_L, L);
-    st_agent(pp + P_EV, EV);
-    st_agent(pp + P_EVMAX, EVM);
-    st_agent(pp + P_DMAX, DM);
-    st_agent(pp + P_VMAX, VM);
-    st_agent(pp + P_T1, T1);
-    st_agent(pp + P_T2, T2);
-    st_agent(pp + P_I1, __int_as_float(I1));
+    pp[P_M] = M;
+    pp[P_L] = L;
+    pp[P_EV] = EV;
+    pp[P_EVMAX] = EVM;
+    pp[P_DMAX] = DM;
+    pp[P_VMAX] = VM;
+    pp[P_T1] = T1;
+    pp[P_T2] = T2;
+    pp[P_I1] = __int_as_float(I1);
   }
-
-  // ---- fused cross-split reduction: the workgroup that arrives last for this (batch, kv-head)
-  //      merges all partials.  The partials are written and read with device-coherent accesses;
-  //      every thread waits until its own stores have been acknowledged before the ticket is
-  //      taken, so whoever draws the last ticket finds every partial in place.
-#ifdef CQA_PROBE_TIMESTAMPS
-  if (ts_on) ts[3] = wall_clock64();
-#endif
-  if (tickets == nullptr) return;   // the reduction runs as its own launch
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t* tk = tickets + (int64_t)b * a.n_kv + kvh;
-    const uint32_t t = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const bool last = t == (uint32_t)a.nsplit - 1u;
-    if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
-    lastflag = last ? 1 : 0;
-  }
-  __syncthreads();
-  if (lastflag && w < G && a.debug != 2) reduce_head_wave<true>(ra, b, kvh * G + w, &kmbuf[w][0][0]);
 }
 
 #undef CQA_REC
@@ -667,21 +609,16 @@ int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid,
 
 // ev0 / ev1 (both or neither): HIP events attached to the dispatch itself, so their elapsed time
 // is the kernel's own execution time (what a kernel trace reports), not launch overhead.
-int32_t launch_split_mfma(const DecodeArgs& a, const ReduceArgs& ra, uint32_t* tickets, int group,
-                          dim3 grid, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
-  static_assert(4 * KM_ROW >= 64, "reduction scratch aliases one wave's K-meta staging");
-#ifdef CQA_PROBE_TIMESTAMPS
-  const bool lm = false;
-#else
+int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t ev0, hipEvent_t ev1,
+                          hipStream_t st) {
   const bool lm = a.blk_logmass != nullptr;
-#endif
 #define CQA_LAUNCH_NT(GG, NTV)                                                                   \
   if (lm)                                                                                        \
     hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV>), grid, dim3(256), 0, st,   \
-                          ev0, ev1, 0, a, ra, tickets);                                          \
+                          ev0, ev1, 0, a);                                          \
   else                                                                                           \
     hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV>), grid, dim3(256), 0, st,  \
-                          ev0, ev1, 0, a, ra, tickets);
+                          ev0, ev1, 0, a);
 #define CQA_LAUNCH(GG)                                                                           \
   if (a.stream_nt) { CQA_LAUNCH_NT(GG, true) } else { CQA_LAUNCH_NT(GG, false) }
   switch (group) {

@@ -4,18 +4,13 @@
 // FP16 K, V of [n_tokens][128]; split over the sequence, merged by a second
 // kernel that also rewrites the served heads' certificates.
 #include "cqa_internal.h"
+#include "reduce_inl.h"
 
 namespace cqa {
 
 constexpr int DP_FLOATS = 4 + D;  // m, l, pad, pad, o[128]
 constexpr int DENSE_TILES_PER_SPLIT = 8;
 constexpr int DENSE_MAX_SPLITS = 1024;
-
-__device__ __forceinline__ void wave_sync_d() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 int dense_splits(int64_t n_tokens) {
   const int64_t tiles = (n_tokens + BLK - 1) / BLK;
@@ -103,7 +98,7 @@ __device__ __forceinline__ void dense_split_work(const __half* __restrict__ q,
       m_run[h] = m_new;
       if (kg == 0) ps[w][tok][h] = p;
     }
-    wave_sync_d();
+    wave_sync();
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
@@ -128,7 +123,7 @@ __device__ __forceinline__ void dense_split_work(const __half* __restrict__ q,
         }
       }
     }
-    wave_sync_d();
+    wave_sync();
   }
 
 #pragma unroll

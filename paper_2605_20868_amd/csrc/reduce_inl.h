@@ -7,7 +7,7 @@
 //   E_val = sum_b rho_b eta_b,   E_key = 2 V_max min(tanh Delta_h, min{1, e^{c Delta_h} alpha_hat}(e^{2 Delta_h} - 1))
 // (key_bound_mode 1 / 2 select the second / first factor alone), the interval form of the
 // ranking test  l_(1) - l_(2) <= 2 Delta_h + eps_guard,  and the flag word.
-// Used by the stand-alone reduction kernel and by the last workgroup of the matrix-core pass.
+// Used by the reduction kernels of the one-pass and of the adaptive decode.
 #pragma once
 
 #include "cqa_internal.h"
@@ -29,8 +29,17 @@ struct ReduceArgs {
   int pstride;           // partial sets per (batch, q-head) row of `partials`; 0 = nsplit
 };
 
-__device__ __forceinline__ void top2_merge_r(float& t1, int& i1, float& t2, float u1, int j1,
-                                             float u2) {
+// LDS operations of one wave execute in order; this only stops the compiler from moving LDS
+// accesses across a point where the lanes of a wave exchange data through LDS.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// merges top-2 state (t1, i1, t2) with (u1, j1, u2); ties go to the lower block index
+__device__ __forceinline__ void top2_merge(float& t1, int& i1, float& t2, float u1, int j1,
+                                           float u2) {
   const bool keep = (t1 > u1) || (t1 == u1 && (unsigned)i1 <= (unsigned)j1);
   if (keep) {
     t2 = fmaxf(t2, u1);
@@ -39,26 +48,6 @@ __device__ __forceinline__ void top2_merge_r(float& t1, int& i1, float& t2, floa
     t1 = u1;
     i1 = j1;
   }
-}
-// Device-coherent accesses for data exchanged between workgroups of ONE launch: relaxed
-// agent-scope atomics go straight to the device's coherence point, so no cache-wide
-// write-back or invalidate is needed around them.
-__device__ __forceinline__ void st_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <bool COHERENT>
-__device__ __forceinline__ float ld_part(const float* p) {
-  if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return *p;
-}
-template <bool COHERENT>
-__device__ __forceinline__ float2 ld_part2(const float* p) {
-  if (COHERENT) {
-    const uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
-  }
-  return *reinterpret_cast<const float2*>(p);
 }
 // DPP move inside a row of 16 lanes (no LDS round trip)
 template <int CTRL>
@@ -102,7 +91,7 @@ template <int CTRL>
 __device__ __forceinline__ void top2_step_dpp(float& t1, int& i1, float& t2) {
   const float u1 = dpp_mov<CTRL>(t1), u2 = dpp_mov<CTRL>(t2);
   const int j1 = dpp_movi<CTRL>(i1);
-  top2_merge_r(t1, i1, t2, u1, j1, u2);
+  top2_merge(t1, i1, t2, u1, j1, u2);
 }
 __device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
   top2_step_dpp<0xB1>(t1, i1, t2);
@@ -113,7 +102,7 @@ __device__ __forceinline__ void wave_top2(float& t1, int& i1, float& t2) {
   for (int m = 16; m < 64; m <<= 1) {
     const float u1 = __shfl_xor(t1, m), u2 = __shfl_xor(t2, m);
     const int j1 = __shfl_xor(i1, m);
-    top2_merge_r(t1, i1, t2, u1, j1, u2);
+    top2_merge(t1, i1, t2, u1, j1, u2);
   }
 }
 
@@ -142,11 +131,9 @@ struct AdaptiveIn {
 };
 
 // wsm: wave-private LDS scratch of at least 64 floats.  All 64 lanes of the wave must call.
-// COHERENT: the partials were written by other workgroups of the same launch.
 // This code runs on the critical tail of the launch: it is written for few dependent memory
 // round trips (all loads of a chunk of 64 splits are issued before anything is consumed) and
 // short cross-lane chains, not for few instructions.
-template <bool COHERENT>
 __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int hq, float* wsm,
                                                  const AdaptiveIn* ad = nullptr) {
   const int l = threadIdx.x & 63;
@@ -184,11 +171,11 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     const float* ps = part + (int64_t)(on ? s : a.nsplit - 1) * PART_FLOATS;
     float sc[9];
 #pragma unroll
-    for (int i = 0; i < 9; ++i) sc[i] = ld_part<COHERENT>(ps + i);
+    for (int i = 0; i < 9; ++i) sc[i] = ps[i];
     float2 x[64];
 #pragma unroll
     for (int i = 0; i < 64; ++i)
-      x[i] = ld_part2<COHERENT>(part + (int64_t)min(s0 + i, a.nsplit - 1) * PART_FLOATS + P_O + 2 * l);
+      x[i] = *reinterpret_cast<const float2*>(part + (int64_t)min(s0 + i, a.nsplit - 1) * PART_FLOATS + P_O + 2 * l);
 
     const float m = on ? sc[P_M] : -INFINITY;
     const float Mn = fmaxf(M, wave_max(m));
@@ -204,11 +191,9 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     float u1 = on ? sc[P_T1] : -INFINITY, u2 = on ? sc[P_T2] : -INFINITY;
     int j1 = on ? __float_as_int(sc[P_I1]) : -1;
     wave_top2(u1, j1, u2);
-    top2_merge_r(T1, I1, T2, u1, j1, u2);
+    top2_merge(T1, I1, T2, u1, j1, u2);
     M = Mn;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_sync();
     o2.x *= fo;
     o2.y *= fo;
 #pragma unroll
@@ -217,9 +202,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
       o2.x = fmaf(fi, x[i].x, o2.x);
       o2.y = fmaf(fi, x[i].y, o2.y);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_sync();
   }
   if (ad != nullptr) {
     // the blocks no second pass touched: their mass and value term from the scan
@@ -264,9 +247,7 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     L_sealed = L;
     L += wave_sum(pt) * 0.25f;      // every token is held by four lanes
     if (cpart == 0) wsm[l >> 2] = pt;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_sync();
 #pragma unroll
     for (int t = 0; t < BLK - 1; ++t) {
       const float p = wsm[t];       // zero for t >= r
@@ -288,10 +269,13 @@ __device__ __forceinline__ void reduce_head_wave(const ReduceArgs& a, int b, int
     const float alpha_hat = ad != nullptr ? ad->alpha : L_sealed / L;
     const float delta = ad != nullptr ? ad->delta : DM;
     const float vmax = VM;
+    // No cap on the exponents: beyond the binary32 range the factors are +inf, the tail form of
+    // the key term with them, and a non-finite key term raises PRECOND below (in the default
+    // mode the tanh form, at most 1, still wins the min).
     float t_tail = 0.0f;
     if (alpha_hat > 0.0f && delta != 0.0f) {
-      const float grow = expf(fminf((float)a.tol.mass_exp * delta, 80.0f));
-      const float widen = expm1f(fminf(2.0f * delta, 80.0f));
+      const float grow = expf((float)a.tol.mass_exp * delta);
+      const float widen = expm1f(2.0f * delta);
       t_tail = fminf(1.0f, grow * alpha_hat) * widen;
     }
     const float t_full = tanhf(delta);

@@ -100,15 +100,22 @@ def to_gpu_tol(cqa, tol):
 
 
 CERT_REL = 1e-4      # bounds: |gpu - oracle| <= 1e-4 |oracle| + 1e-9
-O_REL = 1e-3         # outputs: ||gpu - oracle|| <= 1e-3 ||oracle|| + 1e-6
+O_REL = 1e-3         # outputs: ||gpu - oracle|| <= 1e-3 ||oracle|| + 1e-6, and element-wise
+                     # |gpu_c - oracle_c| <= 1e-3 max_c |oracle_c| + 1e-6 (a few wrong channels
+                     # cannot hide in the norm of a head with a large output)
 
 
 def assert_head_matches(ref, O_row, cert_row, flags_word, where, check_flags=True):
     err = np.linalg.norm(O_row - ref["O"])
     assert err <= O_REL * np.linalg.norm(ref["O"]) + 1e-6, (where, "O", err, np.linalg.norm(ref["O"]))
+    worst = np.abs(O_row - ref["O"]).max()
+    assert worst <= O_REL * np.abs(ref["O"]).max() + 1e-6, (where, "O element", worst, np.abs(ref["O"]).max())
     served = ref.get("served_rung", 0)
     for name in ("E_key", "E_val"):
         a, b = float(cert_row[name]), ref[name]
+        if math.isinf(b):
+            assert a == b, (where, name, a, b)      # a bound beyond binary32 is +inf on both sides
+            continue
         assert abs(a - b) <= CERT_REL * abs(b) + 1e-9, (where, name, a, b)
     if served == 0:
         for name in ("delta_h", "v_max", "alpha_tail_hat", "max_block_contrib"):
@@ -116,7 +123,10 @@ def assert_head_matches(ref, O_row, cert_row, flags_word, where, check_flags=Tru
             assert abs(a - b) <= CERT_REL * abs(b) + 1e-9, (where, name, a, b)
         assert abs(float(cert_row["lse"]) - ref["lse"]) <= 1e-4 * max(1.0, abs(ref["lse"])), (where, "lse")
         if math.isfinite(ref["rank_margin"]):
-            assert abs(float(cert_row["rank_margin"]) - ref["rank_margin"]) <= 2e-4, (where, "margin")
+            # a difference of two FP32 log-masses: 2e-4 absolute at ordinary logit sizes, relative to
+            # the log-masses' own magnitude when the logits are in the thousands
+            assert abs(float(cert_row["rank_margin"]) - ref["rank_margin"]) <= 2e-4 * max(1.0, abs(ref["lse"])), \
+                (where, "margin", float(cert_row["rank_margin"]), ref["rank_margin"])
             if ref["rank_margin"] > 1e-3:
                 assert int(cert_row["top_block"]) == ref["top_block"], (where, "top_block")
         else:

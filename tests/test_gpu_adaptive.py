@@ -607,3 +607,65 @@ def test_ranking_depth_two_catches_a_swap_below_the_top_block():
             assert int(out["cert"]["top_block"][0, 5]) == p0 // 16
             assert out["promoted"][0, 1, [p0 // 16, p1 // 16, p2 // 16]].all()
         assert got == {1: False, 2: True, 3: True}
+
+
+def test_adaptive_end_to_end_from_raw_inputs_where_margins_are_clear():
+    """No GPU number enters the oracle here: oracle.adaptive.adaptive_decode runs on the raw FP16
+    inputs (its own scoring pass, its own selection, its own attend pass) and the GPU's decisions
+    and results are compared with it.  Every head is peaked on planted keys so that the selection
+    is decided by wide margins (coverage far from tau_cov on both sides of K*, log-mass gaps at the
+    selection boundary far above the 1e-4 accuracy of the log-masses); the test checks that the
+    margins really are wide before it compares."""
+    say("adaptive: end to end against the oracle on raw inputs (clear selection margins)")
+    bt, hq, hkv, n = 2, 8, 2, 4000 + 9
+    g = hq // hkv
+    rng = np.random.Generator(np.random.Philox(77))
+    k = workloads.normal_f16(rng, (bt, hkv, n, 128))
+    v = workloads.normal_f16(rng, (bt, hkv, n, 128))
+    q = np.zeros((bt, hq, 128), np.float16)
+    for b in range(bt):
+        for h in range(hq):
+            kh = h // g
+            p1 = 16 * (7 + 11 * h + 3 * b) + (h % 16)          # distinct blocks per head
+            p2 = 16 * (100 + 13 * h + 5 * b) + ((3 * h) % 16)
+            if h % 2:                                           # odd heads: a second key, slightly weaker
+                k[b, kh, p2] = (k[b, kh, p1].astype(np.float32) * 0.97).astype(np.float16)
+            q[b, h] = (k[b, kh, p1].astype(np.float32) * 1.3).astype(np.float16)
+    oc = oracle.OracleLayerCache(bt, hkv)
+    oc.append(k, v)
+    sel = ad.SelectorParams(0.9, 1, 8, 8)
+    tol = att.Tolerances(rank_depth=1)
+    ref = ad.adaptive_decode(oc, q, tol, sel)
+    # the margins that make the comparison meaningful
+    for (b, h), r in ref.items():
+        s = ad.select_blocks(r["scoring"]["blk_logmass"], r["scoring"]["lse"], sel)
+        kk = r["k_star"]
+        assert kk == (2 if h % 2 else 1), (b, h, kk)
+        cov = s["rho_trail"] + np.concatenate([[0.0], np.cumsum(s["p_sorted"])])
+        assert cov[kk] - sel.tau_cov > 1e-3 and (kk == sel.k_min or sel.tau_cov - cov[kk - 1] > 1e-3), (b, h)
+        lsort = r["scoring"]["blk_logmass"][s["order"]]
+        assert (lsort[:kk] - lsort[1:kk + 1]).min() > 0.05, (b, h)      # every rank up to the boundary is clear
+    with GpuLayerCache(bt, hq, hkv, n + 64) as gc:
+        gc.append(k, v)
+        out = gpu_adaptive(gc, q, tol, sel)
+        for (b, h), r in ref.items():
+            w = ("raw adaptive", b, h)
+            kk = r["k_star"]
+            assert int(out["k_star"][b, h]) == kk, w
+            assert out["selected"][b, h, :kk].tolist() == [int(x) for x in r["selected"]], w
+            assert (out["promoted"][b, h // g] == r["promoted"]).all(), w
+            assert not out["v_promoted"][b, h // g].any(), w
+            ct = out["cert"][b, h]
+            err = np.linalg.norm(out["O"][b, h] - r["O"])
+            assert err <= 1e-3 * np.linalg.norm(r["O"]) + 2e-6 * r["v_max"], (w, "O", err)
+            assert np.abs(out["O"][b, h] - r["O"]).max() <= 1e-3 * np.abs(r["O"]).max() + 2e-6 * r["v_max"], (w, "O element")
+            for name in ("E_key", "E_val", "delta_h", "v_max", "alpha_tail_hat", "max_block_contrib"):
+                x, y = float(ct[name]), r[name]
+                assert abs(x - y) <= 1e-4 * abs(y) + 1e-9, (w, name, x, y)
+            assert abs(float(ct["lse"]) - r["lse"]) <= 1e-4 * max(1.0, abs(r["lse"])), (w, "lse")
+            assert np.abs(out["l8"][b, h] - r["scoring"]["blk_logmass"]).max() <= 1e-4, (w, "scoring log-masses")
+            assert np.abs(out["lx"][b, h] - r["blk_logmass"]).max() <= 1e-4, (w, "attend log-masses")
+            assert int(ct["top_block"]) == r["ranking"]["top_fp16"], (w, "top block")
+            assert int(out["flags"][b, h]) == r["flags"], (w, "flags", int(out["flags"][b, h]), r["flags"])
+            # the key term shrank with the tail
+            assert float(ct["E_key"]) < 0.2 * float(out["cert0"]["E_key"][b, h]), w

@@ -7,9 +7,23 @@ from helpers import ROOT, load_binding
 
 
 def declared_functions():
+    """Every function that any header under include/ declares."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert "cqa.h" in headers and "cqa_test.h" in headers
+    for f in headers:
+        text = open(os.path.join(inc, f)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(cqa_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_the_product_header_holds_no_test_hooks():
     text = open(os.path.join(ROOT, "include", "cqa.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cqa_[a-z0-9_]+)\s*\(", text)))
+    for hook in ("cqa_set_splits", "cqa_set_kernel_variant", "cqa_set_stream_hint", "cqa_adaptive_state",
+                 "cqa_time_", "cqa_profile_"):
+        assert hook not in text, hook
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -18,7 +32,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     assert len(names) >= 15
     lib = ctypes.CDLL(cqa.LIB_PATH)
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in include/cqa.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
         assert n in cqa.EXPORTED, f"{n} has no ctypes signature in the binding"
         assert hasattr(cqa, n), f"{n} has no Python wrapper"
     assert cqa.cqa_version() == 100

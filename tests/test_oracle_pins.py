@@ -183,6 +183,13 @@ def test_worked_numbers_from_the_paper():
     # overflow-safe for saturated Delta
     assert key_term(500.0, 1.0, 2.0, 2, 0) == 4.0
     assert key_term(0.0, 1.0, 2.0, 2, 0) == 0.0
+    # the tail form with a large Delta: exact below the binary32 range of the certificate
+    # (2 V_max (e^{2 Delta} - 1) once the mass factor has saturated at 1), +inf beyond it
+    assert key_term(42.0, 0.5, 3.0, 2, 1) == pytest.approx(6.0 * math.expm1(84.0), rel=1e-12)
+    assert key_term(42.0, 1e-40, 3.0, 2, 1) == pytest.approx(6.0 * math.exp(84.0) * 1e-40 * math.expm1(84.0), rel=1e-12)
+    assert key_term(50.0, 0.5, 3.0, 2, 1) == math.inf
+    assert key_term(400.0, 0.5, 3.0, 2, 1) == math.inf
+    assert key_term(400.0, 0.5, 3.0, 2, 0) == 6.0        # the default mode still takes the tanh form
 
 
 # --------------------------------------------------------------------------- attention + certificate
@@ -211,6 +218,16 @@ def run_case(c, tol=None):
     n = c["n"]
     return certified_head(c["q16"], c["k_hat"], c["v_hat"], c["sigma"], c["eta"], c["nu"],
                           c["k16"][n:], c["v16"][n:], tol or Tolerances())
+
+
+def test_key_term_beyond_binary32_raises_precond():
+    """A head whose tail-form key term leaves the binary32 range reports +inf and PRECOND."""
+    c = build_case(3, 64, k_scale=900.0)
+    res = run_case(c, Tolerances(key_bound_mode=1))
+    assert res["delta_h"] > 45.0
+    assert res["E_key"] == math.inf and res["flags"] & 8
+    res0 = run_case(c, Tolerances(key_bound_mode=0))
+    assert math.isfinite(res0["E_key"]) and not res0["flags"] & 8
 
 
 @pytest.mark.parametrize("seed,n,trail,q_scale,k_scale,adv", [
