@@ -553,7 +553,8 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     hipEvent_t ev1 = prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr;
     if (prof && c->variant != 0) CQA_HIP(hipEventRecord(ev0, st));
     if (c->variant == 0 || a.eta_out != nullptr) {   // eta_b comes from this kernel only
-      const int32_t rc = launch_split_mfma(a, hq / hkv, grid, ev0, ev1, st);
+      // one-dimensional grid: the kernel decodes (head, partial set) from the linear index
+      const int32_t rc = launch_split_mfma(a, hq / hkv, dim3((unsigned)nsplit * hkv * bt), ev0, ev1, st);
       if (rc != CQA_OK) return rc;
     } else {
       switch (hq / hkv) {

@@ -6,7 +6,10 @@
 //
 //  scores   S[(h, j)][token] = sum_c q~[(h, j)][c] * code[token][c]            (FP16 inputs)
 //           One wave takes four consecutive blocks (a "quad") per iteration.
-//           B = the 16 tokens of block i, codes as exact FP16 integers;
+//           B = the 16 tokens of block i as the exact FP16 integers 1152 + code (the stored byte
+//           dropped into the mantissa of 1024.0: one operation per two codes); the bias leaves
+//           through one more product of the same A operand with a column of ones, which yields
+//           sum_c q~[(h, j)][c] for every row, so it cancels exactly whatever A was rounded to;
 //           A = 16 rows = 4 query heads x the 4 blocks of the quad, each row holding that
 //           block's scaled query q~ = q (.) sigma as TWO FP16 terms (hi + lo, 22 significant
 //           bits), q pre-scaled per head by a power of two so that q~ cannot overflow FP16;
@@ -15,8 +18,9 @@
 //  values   O[(h, g')][c] = sum_t w[t][(h, g')] * (16 + code[t][c])               (bf16 inputs)
 //           w = p_t * scale_{t,g} as TWO bf16 terms, K = 32 tokens (two blocks),
 //           one 16-channel value group per tile; the bias 16 (which makes the
-//           4-bit code an exact bf16 by bit insertion) and the group offsets are
-//           folded into  sum_t p_t (offset_{t,g} - 16 scale_{t,g}),  accumulated on the VALU.
+//           4-bit code an exact bf16 by bit insertion) leaves through a product of the same
+//           weights with a column of ones (sum_t w[t][(h, g')], so it cancels exactly), and the
+//           group offsets are added as  sum_t p_t offset_{t,g},  accumulated on the VALU.
 //
 // Lane roles (l = lane, n = l & 15, kg = l >> 4, h = n >> 2, j = g' = n & 3):
 //   operand forming: scaled query of row (head h, block j), channels of slice kg;
@@ -70,14 +74,13 @@ __device__ __forceinline__ uint4 ld_stream4(const uint8_t* p) {
 __device__ __forceinline__ f16x2 pack_f16_rtz(float x0, float x1) {
   return __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(x0, x1));
 }
-// bytes (b_lo, b_hi) of a dword -> FP16 pair (b_lo - 128, b_hi - 128): the byte is dropped into the
-// mantissa of 1024.0 (0x6400 | b = 1024 + b exactly) and 1152 is subtracted, both exact
+// stored bytes (b_lo, b_hi) of a dword, b = code + 128 -> FP16 pair (1152 + code_lo, 1152 + code_hi):
+// the byte is dropped into the mantissa of 1024.0 (0x6400 | b = 1024 + b exactly)
 template <uint32_t SEL>
-__device__ __forceinline__ uint32_t bytes_to_f16_codes(uint32_t d) {
-  const uint32_t m = __builtin_amdgcn_perm(0x64646464u, d, SEL);
-  const f16x2 c = {(_Float16)-1152.0f, (_Float16)-1152.0f};
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, m) + c);
+__device__ __forceinline__ uint32_t bytes_to_f16_biased(uint32_t d) {
+  return __builtin_amdgcn_perm(0x64646464u, d, SEL);
 }
+constexpr float K_BIAS = 1152.0f;
 
 // two FP32 values -> their upper 16 bits packed (x0 in the low half): bf16 by truncation
 __device__ __forceinline__ uint32_t pack_hi16(float x1, float x0) {
@@ -117,25 +120,32 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
   const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int64_t head_rec = ((int64_t)b * a.n_kv + kvh) * a.nq_cap;
-  // This wave's contiguous run of quads.  The head's quads are dealt out over all 4 * nsplit waves
-  // that work on it: everyone gets floor(nquads / waves), and the remainder goes, one quad each, to
-  // the waves of odd-numbered workgroups first (in order), then to even-numbered ones.  Workgroups
-  // go round-robin to the 8 XCDs, and odd-numbered XCDs have been measured ~8 % faster on this
-  // kernel than even-numbered ones, so they absorb the extra iteration; if that does not hold on
-  // some machine the choice is merely as good as any other.  Runs stay contiguous and in order.
+  // Workgroup -> (head, partial set) and this wave's contiguous run of quads: the head's quads are
+  // dealt evenly over its 4 * nsplit waves, in block order, sizes differing by at most one.
+  // (Measured and not adopted: handing the quads out from per-head counters, so that faster XCDs
+  // and earlier workgroups take more -- per-wave clock stamps show the waves of a launch finishing
+  // up to 10 us apart.  Atomics on one address are served at ~130 ns each across XCDs, far too
+  // slow for one draw per quad, and a simulation on the measured per-wave speeds showed that at
+  // a granularity of one quad (~4.5 us of work) even an ideal greedy schedule gains < 1 us.
+  // Likewise an uneven static deal, long runs for the first workgroup of every compute unit and
+  // short ones for the second, measured no faster.)
   const int nquads = (a.nb + 3) >> 2;
-  const int nw = a.nsplit * 4;
-  const int base = nquads / nw, rem = nquads - base * nw;
-  const int n_odd = 4 * (a.nsplit >> 1);                       // waves in odd-numbered workgroups
-  const int e_odd = min(rem, n_odd), e_even = rem - e_odd;     // extras handed to each class
-  const int odd_before = 4 * (split >> 1) + ((split & 1) ? w : 0);
-  const int even_before = 4 * ((split + 1) >> 1) + ((split & 1) ? 0 : w);
-  const int mine = (split & 1) ? (odd_before < e_odd) : (even_before < e_even);
-  const int q0 = base * (split * 4 + w) + min(odd_before, e_odd) + min(even_before, e_even);
-  const int b0 = 4 * q0;
-  const int b1 = min(4 * (q0 + base + mine), a.nb);
+  const int L = blockIdx.x;
+  const int head = L / a.nsplit, split = L - head * a.nsplit;
+  const bool younger = 2 * L >= (int)gridDim.x;
+  constexpr int Q_NONE = 0x40000000;   // "no quad": larger than any quad index
+  int q_cur, q_next, q_stop;
+  {
+    const int nw = 4 * a.nsplit, ci = 4 * split + w;
+    const int base = nquads / nw, rem = nquads - base * nw;
+    const int nmine = base + (ci < rem ? 1 : 0);
+    const int q0 = ci * base + min(ci, rem);
+    q_stop = q0 + nmine;
+    q_cur = nmine > 0 ? q0 : Q_NONE;
+    q_next = nmine > 1 ? q0 + 1 : Q_NONE;
+  }
+  const int b = head / a.n_kv, kvh = head - b * a.n_kv;
+  const int64_t head_rec = (int64_t)head * a.nq_cap;
   const float inv_sqrt_d = 0.08838834764831845f;
 
   __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
@@ -171,8 +181,6 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   // the presumably younger workgroup (second half of the launch order) one level above the older
   // one in the high phase: of the four phase combinations each wave then wins two.
   __builtin_amdgcn_s_setprio(3);
-  const int wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  const bool younger = 2 * wg_lin >= (int)(gridDim.x * gridDim.y * gridDim.z);
   // This wave's query row (head w of the group), requested before the bulk loads: loads return in
   // order, so the row arrives first and the set-up below does not wait for a whole quad.
   __half2 q_in = __floats2half2_rn(0.0f, 0.0f);
@@ -192,12 +200,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   //   V codes : pair P, group set gs; lane (channel n, 8-token slice kg)
   //   metadata: each byte once per wave -- K meta of block i bytes [16 l, +16); V meta of blocks
   //             2P + (l >> 5) bytes [16 (l & 31), +16); (eta, nu) of block i (wave-uniform)
-  const int ql = max((b1 - 1) & ~3, b0);   // first block of the wave's last quad
-  const int park = 0;                      // record that absorbs the unused last prefetch
   const uint8_t* const head_base = a.t1 + head_rec * QUAD_BYTES;
   const uint32_t lo16 = (uint32_t)l * 16u;
   const uint32_t vo16 = (uint32_t)kg * 512u + (uint32_t)n * 16u;
-#define CQA_REC(QB) (head_base + (int64_t)((QB) <= ql ? (QB) >> 2 : park) * QUAD_BYTES)
+// QI: a quad index, or Q_NONE (then the head's first record absorbs the load)
+#define CQA_REC(QI) (head_base + (int64_t)((QI) < nquads ? (QI) : 0) * QUAD_BYTES)
 #define CQA_LOAD_K(QB, CQ)                                                               \
   {                                                                                      \
     const uint8_t* rec = CQA_REC(QB) + (Q_KC + (CQ) * 1024);                             \
@@ -231,13 +238,12 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   uint4 kraw[4][2], vraw[2][2];
   u32x4 km_n[4], vm_n[2];
   float2 an_n[4];
-  int qb = b0;
-  if (qb < b1) {
-    CQA_LOAD_META(qb)
-    CQA_LOAD_K(qb, 0)
-    CQA_LOAD_K(qb, 1)
-    CQA_LOAD_V(qb, 0)
-    CQA_LOAD_V(qb, 1)
+  if (q_cur < nquads) {
+    CQA_LOAD_META(q_cur)
+    CQA_LOAD_K(q_cur, 0)
+    CQA_LOAD_K(q_cur, 1)
+    CQA_LOAD_V(q_cur, 0)
+    CQA_LOAD_V(q_cur, 1)
   }
 
   // Queries of the group as FP32 in LDS, rows of absent heads zero, each head pre-scaled by a
@@ -263,22 +269,34 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   }
   __syncthreads();
   const float unscale_op = sbuf[h];                // 1 / S of my operand head
-  const float score_scale = sbuf[kg] * inv_sqrt_d; // raw MFMA sum -> logit, for my softmax head
+  // raw MFMA sum -> logit in units of ln 2 (the softmax state below is kept in base 2: v_exp_f32
+  // and v_log_f32 are base-2 instructions), for my softmax head
+  const float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+  const float score_scale = sbuf[kg] * (inv_sqrt_d * LOG2E);
+  HF8 ones_h;
+  BF8 ones_b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ones_h.u[i] = 0x3C003C00u;   // FP16 1.0
+    ones_b.u[i] = 0x3F803F80u;   // bf16 1.0
+  }
 
   // softmax state of head kg (replicated over the 16 lanes of the row)
   float m_run = -INFINITY, l_run = 0.0f, ev = 0.0f, evmax = 0.0f, dmax = 0.0f, vmax = 0.0f;
   float t1 = -INFINITY, t2 = -INFINITY;
   int i1 = -1;
-  float offacc[2] = {0.0f, 0.0f};   // offset sums of (head h, groups g', 4 + g'), operand role
-  f32x4 acc[8];
+  float offacc[2] = {0.0f, 0.0f};   // sum_t p_t offset_t of (head h, groups g', 4 + g'), operand role
+  f32x4 acc[8], accw[2];             // accw[gs][v]: sum_t w_t of (head kg, group 4 gs + v), every column
 #pragma unroll
   for (int g = 0; g < 8; ++g) acc[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  accw[0] = accw[1] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  for (; qb < b1; qb += 4) {
+  while (q_cur < nquads) {
     if (younger) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(1);
-    bool live[4];   // block is inside this wave's run
+    const int qb = 4 * q_cur;   // first block of the quad
+    bool live[4];               // block exists (the head's last quad may be ragged)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) live[i] = qb + i < b1;
+    for (int i = 0; i < 4; ++i) live[i] = qb + i < a.nb;
     float2 an[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -288,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
     for (int P = 0; P < 2; ++P)
       reinterpret_cast<u32x4*>(&vmbuf[w][2 * P + (l >> 5)][0])[l & 31] = vm_n[P];
-    CQA_LOAD_META(qb + 4)
+    CQA_LOAD_META(q_next)
     wave_sync();
 
     // ---- scores.  A operand: scaled query of row-role (h, j), two FP16 terms (hi + lo);
@@ -297,6 +315,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     f32x4 C[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 R = f32x4{0.0f, 0.0f, 0.0f, 0.0f};   // R[v] = sum_c q~ of row (head kg, block v), every column
     float csum = 0.0f, dsum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -326,15 +345,15 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
         qh2.u[p] = __builtin_bit_cast(uint32_t, hp);
         ql2.u[p] = __builtin_bit_cast(uint32_t, lp);
       }
-      HF8 kv[4];      // the 8 codes of my token and channel slice in each block, exact in FP16
+      HF8 kv[4];      // 1152 + code for the 8 codes of my token and channel slice in each block
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint4 kx = kraw[i][u >> 1];
         const uint32_t d0 = (u & 1) ? kx.z : kx.x, d1 = (u & 1) ? kx.w : kx.y;
-        kv[i].u[0] = bytes_to_f16_codes<0x04010400u>(d0);
-        kv[i].u[1] = bytes_to_f16_codes<0x04030402u>(d0);
-        kv[i].u[2] = bytes_to_f16_codes<0x04010400u>(d1);
-        kv[i].u[3] = bytes_to_f16_codes<0x04030402u>(d1);
+        kv[i].u[0] = bytes_to_f16_biased<0x04010400u>(d0);
+        kv[i].u[1] = bytes_to_f16_biased<0x04030402u>(d0);
+        kv[i].u[2] = bytes_to_f16_biased<0x04010400u>(d1);
+        kv[i].u[3] = bytes_to_f16_biased<0x04030402u>(d1);
       }
       // consecutive MFMAs go to different accumulators, so none waits for its predecessor
 #pragma unroll
@@ -343,13 +362,15 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv[i].v, C[i], 0, 0, 0);
+      R = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, ones_h.v, R, 0, 0, 0);
+      R = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, ones_h.v, R, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
       if (u == 1) {
-        CQA_LOAD_K(qb + 4, 0)
+        CQA_LOAD_K(q_next, 0)
         __builtin_amdgcn_sched_barrier(0);
       }
       if (u == 3) {
-        CQA_LOAD_K(qb + 4, 1)
+        CQA_LOAD_K(q_next, 1)
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -377,14 +398,14 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float mq = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float s = live[i] ? (C[i][i] + cbs[i]) * score_scale : -1.0e30f;
+      const float s = live[i] ? (C[i][i] + fmaf(-K_BIAS, R[i], cbs[i])) * score_scale : -1.0e30f;
       mbv[i] = row_max(s);
-      ptv[i] = __expf(s - mbv[i]);
+      ptv[i] = __builtin_amdgcn_exp2f(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
       mq = fmaxf(mq, mbv[i]);
     }
     const float m_new = fmaxf(m_run, mq);
-    const float alpha = __expf(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     l_run *= alpha;
     ev *= alpha;
     evmax *= alpha;
@@ -392,20 +413,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float lbv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float f = __expf(mbv[i] - m_new);
+      const float f = __builtin_amdgcn_exp2f(mbv[i] - m_new);
       const float sf = sbv[i] * f;
       const float ce = sf * an[i].x;
-      const float lb = mbv[i] + __logf(sbv[i]);
+      const float lb = (mbv[i] + __builtin_amdgcn_logf(sbv[i])) * LN2;   // natural units
       lbv[i] = lb;
       l_run += sf;
       ev += ce;
       evmax = fmaxf(evmax, ce);
       dmax = fmaxf(dmax, dls[i]);
       vmax = fmaxf(vmax, an[i].y);
-      const bool g1 = lb > t1, g2 = lb > t2;   // blocks arrive in increasing order: ties keep the lower index
-      t2 = g1 ? t1 : (g2 ? lb : t2);
-      i1 = g1 ? qb + i : i1;
-      t1 = g1 ? lb : t1;
+      // blocks arrive in increasing order: ties keep the lower index; the second largest of
+      // (t1, t2, l_b), t1 >= t2, is their median
+      i1 = lb > t1 ? qb + i : i1;
+      t2 = __builtin_amdgcn_fmed3f(t1, t2, lb);
+      t1 = fmaxf(t1, lb);
       pbuf[w][kg][i * BLK + n] = ptv[i] * f;
     }
     if (LM) {
@@ -418,7 +440,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       if (a.eta_out != nullptr && l == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (qb + i < b1) a.eta_out[((int64_t)b * a.n_kv + kvh) * a.nb + qb + i] = an[i].x;
+          if (live[i]) a.eta_out[((int64_t)b * a.n_kv + kvh) * a.nb + qb + i] = an[i].x;
       }
     }
     abuf[w][kg] = alpha;   // every lane of the row stores the same word
@@ -431,6 +453,11 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
       for (int g = 0; g < 8; ++g)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[g][v] *= alpha;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        accw[0][v] *= alpha;
+        accw[1][v] *= alpha;
+      }
     }
     const float alpha_op = abuf[w][h];
     offacc[0] *= alpha_op;
@@ -457,8 +484,8 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
           const float of0 = __low2float(oh[e]), of1 = __high2float(oh[e]);
           wv[2 * e] = p8[2 * e] * sc0;
           wv[2 * e + 1] = p8[2 * e + 1] * sc1;
-          offacc[gs] = fmaf(p8[2 * e], fmaf(-16.0f, sc0, of0), offacc[gs]);
-          offacc[gs] = fmaf(p8[2 * e + 1], fmaf(-16.0f, sc1, of1), offacc[gs]);
+          offacc[gs] = fmaf(p8[2 * e], of0, offacc[gs]);
+          offacc[gs] = fmaf(p8[2 * e + 1], of1, offacc[gs]);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) wr[e] = wv[e] - trunc_bf16(wv[e]);
@@ -485,16 +512,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 #pragma unroll
         for (int t = 0; t < 4; ++t)
           acc[4 * gs + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, bv[t].v, acc[4 * gs + t], 0, 0, 0);
+        accw[gs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.v, ones_b.v, accw[gs], 0, 0, 0);
+        accw[gs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.v, ones_b.v, accw[gs], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (P == 0) {
-        CQA_LOAD_V(qb + 4, 0)
+        CQA_LOAD_V(q_next, 0)
       } else {
-        CQA_LOAD_V(qb + 4, 1)
+        CQA_LOAD_V(q_next, 1)
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     wave_sync();
+    // advance: the quad whose data was requested during this iteration becomes current
+    q_cur = q_next;
+    q_next = q_next + 1 < q_stop ? q_next + 1 : Q_NONE;
   }
 
   // ---- per-wave epilogue: fold the offset sums in; the softmax state of head kg is already
@@ -508,11 +540,14 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   for (int g = 0; g < 8; ++g) {
     const float off = __shfl(offacc[g >> 2], kg * 4 + (g & 3));
     const float val = (g & 3) == 0 ? acc[g][0] : ((g & 3) == 1 ? acc[g][1] : ((g & 3) == 2 ? acc[g][2] : acc[g][3]));
-    if (kg < G) mo[w][kg < G ? kg : 0][g * 16 + n] = val + off;
+    const f32x4 ws = accw[g >> 2];
+    const float wsum = (g & 3) == 0 ? ws[0] : ((g & 3) == 1 ? ws[1] : ((g & 3) == 2 ? ws[2] : ws[3]));
+    // sum_t w_t (16 + code) - 16 sum_t w_t + sum_t p_t offset_t
+    if (kg < G) mo[w][kg < G ? kg : 0][g * 16 + n] = fmaf(-16.0f, wsum, val) + off;
   }
   if (n == 0 && kg < G) {
     float* m = ms[w][kg < G ? kg : 0];
-    m[0] = m_run;
+    m[0] = m_run * LN2;   // the running maximum was kept in base 2
     m[1] = l_run;
     m[2] = ev;
     m[3] = evmax;
@@ -528,19 +563,21 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float M = -INFINITY;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    const float Mr = (M == -INFINITY) ? 0.0f : M;   // a workgroup that drew no quad writes zeros
     float o = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - M) * mo[ww][hh][c];
+    for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - Mr) * mo[ww][hh][c];
     a.partials[(((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c] = o;
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
     float M = -INFINITY;
     for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    const float Mr = (M == -INFINITY) ? 0.0f : M;
     float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f, T1 = -INFINITY, T2 = -INFINITY;
     int I1 = -1;
     for (int ww = 0; ww < 4; ++ww) {
-      const float fw = __expf(ms[ww][hh][0] - M);
+      const float fw = __expf(ms[ww][hh][0] - Mr);
       L += fw * ms[ww][hh][1];
       EV += fw * ms[ww][hh][2];
       EVM = fmaxf(EVM, fw * ms[ww][hh][3]);
