@@ -41,6 +41,21 @@ Readings where the paper is silent (the HIP path follows the same ones):
   certificate's accumulators in FP32): a key term whose value exceeds the
   binary32 range (2 Delta_h beyond ~88.7 in the tail form) is +inf, which is a
   non-finite certificate quantity and raises PRECOND.
+* INT8 x INT8 scoring (Tolerances.int8_query; the paper's "Per-Channel Key
+  Scoring" offers it as the tensor-core alternative to FP16 scoring and names the
+  quantisation of the scaled query as a third error source).  Per sealed block the
+  scaled query q~_c = q_c sigma_c is quantised symmetrically to 8 bits with one
+  scale per block, s_q = max_c |q~_c| / 127, T_c = round(q~_c / s_q) in
+  [-127, 127]; the block's logits are (s_q sum_c T_c code_c + q . z) / sqrt(d).
+  The paper budgets "one more Delta" for this (its e^{3 Delta} substitution) without
+  bounding it; here the third source gets an explicit term: every code has
+  magnitude <= 128, so the scores move by at most
+      Delta^q_b = (128 / sqrt d) sum_c |q~_c - s_q T_c|
+  (<= 64 sqrt(d) s_q), and the block's score-error bound becomes
+  Delta_b + Delta^q_b; Delta_h, E_key and the ranking test use that sum, so every
+  theorem applies unchanged.  The integer decisions T_c are taken in binary32, as
+  the kernel takes them: q~ = fl(q sigma), inv = fl(127 / max|q~|),
+  T = round-half-even(q~ inv) on the exact product, s_q = fl(max|q~| / 127).
 * Flag word: bit0 KEY (E_key > eps_key), bit1 VAL (E_val > eps_val or
   max_b rho_b eta_b > v_tol), bit2 RANK, bit3 PRECOND (a non-finite certificate
   quantity), bit4 TOTAL (E_key + E_val > eps_total); force_flags is OR-ed in.
@@ -76,6 +91,7 @@ class Tolerances:
     key_bound_mode: int = 0
     rung4_min_groups: int = 0
     force_flags: int = 0
+    int8_query: bool = False      # INT8 x INT8 scoring of a quantised scaled query
 
 
 def softmax_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
@@ -110,14 +126,34 @@ def key_term(delta_h: float, alpha_hat: float, v_max: float, mass_exp: int = 2,
     return e_key if abs(e_key) <= FLT_MAX else math.copysign(math.inf, e_key)
 
 
+def quantize_scaled_query(q16: np.ndarray, sigma: np.ndarray):
+    """INT8 quantisation of the scaled query, one scale per sealed block (see header).
+
+    q16 float16 [d]; sigma float32 [NB, d].  Returns (T int8 [NB, d], s_q float32 [NB]).
+    The decisions are binary32's: the product q sigma and the two quotients are rounded to
+    binary32; T rounds the exact product q~ inv (which binary64 holds exactly) half to even.
+    """
+    q32 = q16.astype(np.float32)
+    qt = (q32[None, :] * sigma.astype(np.float32)).astype(np.float32)       # one rounding per element
+    amax = np.abs(qt).max(axis=1).astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        inv = np.where(amax > 0, np.float32(127.0) / amax, np.float32(0.0)).astype(np.float32)
+        s_q = (amax / np.float32(127.0)).astype(np.float32)
+    t = np.rint(qt.astype(np.float64) * inv.astype(np.float64)[:, None])
+    assert np.abs(t).max(initial=0.0) <= 127
+    return t.astype(np.int8), s_q
+
+
 def certified_head(q16: np.ndarray, k_hat: np.ndarray, v_hat: np.ndarray, sigma: np.ndarray,
                    eta: np.ndarray, nu: np.ndarray, k_trail16: np.ndarray,
-                   v_trail16: np.ndarray, tol: Tolerances) -> dict:
+                   v_trail16: np.ndarray, tol: Tolerances, k_codes: np.ndarray = None,
+                   z: np.ndarray = None) -> dict:
     """One head, one step.
 
     q16 float16 [d]; k_hat, v_hat float64 [NB*B, d] (reconstructions of the sealed
     tokens); sigma float32 [NB, d]; eta, nu float32 [NB]; k_trail16, v_trail16
-    float16 [r, d] (r may be 0).
+    float16 [r, d] (r may be 0).  tol.int8_query also needs the stored key codes
+    k_codes int8 [NB, B, d] and zero points z float32 [NB, d].
     """
     q = q16.astype(np.float64)
     d = q.shape[0]
@@ -127,6 +163,15 @@ def certified_head(q16: np.ndarray, k_hat: np.ndarray, v_hat: np.ndarray, sigma:
     inv = 1.0 / math.sqrt(d)
 
     s_seal = (k_hat @ q) * inv if nb else np.zeros(0)
+    delta_q = np.zeros(nb)
+    if tol.int8_query and nb:
+        t_q, s_q = quantize_scaled_query(q16, sigma)
+        codes = k_codes.astype(np.float64)                                   # [NB, B, d]
+        dots = np.einsum("btc,bc->bt", codes, t_q.astype(np.float64))       # exact integers
+        c_b = z.astype(np.float64) @ q                                       # q . z per block
+        s_seal = ((s_q.astype(np.float64)[:, None] * dots + c_b[:, None]) * inv).reshape(-1)
+        resid = np.abs(q[None, :] * sigma.astype(np.float64) - s_q.astype(np.float64)[:, None] * t_q)
+        delta_q = resid.sum(axis=1) * (128.0 * inv)
     kt = k_trail16.astype(np.float64)
     vt = v_trail16.astype(np.float64)
     s_trail = (kt @ q) * inv if r else np.zeros(0)
@@ -145,7 +190,7 @@ def certified_head(q16: np.ndarray, k_hat: np.ndarray, v_hat: np.ndarray, sigma:
         s_b = np.exp(sb - m_b[:, None]).sum(axis=1)
         l_b = m_b + np.log(s_b)
         rho = np.exp(l_b - lse)
-        delta_b = (np.abs(q)[None, :] * sigma.astype(np.float64)).sum(axis=1) * (0.5 * inv)
+        delta_b = (np.abs(q)[None, :] * sigma.astype(np.float64)).sum(axis=1) * (0.5 * inv) + delta_q
         delta_h = float(delta_b.max())
         contrib = rho * eta.astype(np.float64)
         e_val = float(contrib.sum())
@@ -193,4 +238,4 @@ def certified_head(q16: np.ndarray, k_hat: np.ndarray, v_hat: np.ndarray, sigma:
     return dict(O=o, E_key=e_key, E_val=e_val, delta_h=delta_h, v_max=v_max,
                 alpha_tail_hat=alpha_hat, lse=lse, max_block_contrib=max_contrib,
                 rank_margin=margin, top_block=top, flags=flags, blk_logmass=l_b,
-                weights=a)
+                weights=a, delta_q=delta_q, scores_sealed=s_seal)

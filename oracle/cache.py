@@ -100,7 +100,8 @@ class OracleLayerCache:
             k_hat, v_hat = cache_kv[(b, kh)]
             out[(b, h)] = att.certified_head(
                 q16[b, h], k_hat, v_hat, self.sigma[b, kh], self.eta[b, kh], self.nu[b, kh],
-                self.k16[b, kh, nb * qz.B:], self.v16[b, kh, nb * qz.B:], tol)
+                self.k16[b, kh, nb * qz.B:], self.v16[b, kh, nb * qz.B:], tol,
+                k_codes=self.k_codes[b, kh], z=self.z[b, kh])
         return [out[key] for key in todo]
 
     def dense_head(self, q16: np.ndarray, b: int, h: int, n_q_heads: int) -> np.ndarray:
