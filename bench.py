@@ -391,6 +391,17 @@ def main() -> int:
         p90_ms = float(kdur[int(0.9 * (len(kdur) - 1))])
         ladder_counts = cqa.cqa_ladder_counts(h)
 
+        # the optional INT8 x INT8 scoring mode (quantised scaled query on the INT8 matrix cores):
+        # the same event-timed loop, reported next to the default kernel's figure
+        tol8 = cqa.Tolerances(int8_query=True)
+        cqa.cqa_profile_begin(h, 110)
+        for i in range(110):
+            cqa.cqa_decode_step_enqueue(h, 0, None, None, qp + ((W + i) % n_in) * q_stride, tol8, Op, certp,
+                                        flagsp, stream)
+        torch.cuda.synchronize()
+        cqa.cqa_profile_end(h)
+        q8_median_ms = float(np.median(cqa.cqa_profile_durations(h)[ROOF_DROP:]))
+
         # the same steps with the ladder resolved on the host (flag words read back through mapped
         # pinned memory after every step, fallback by copy + dense kernel): reported apart from `value`
         torch.cuda.synchronize()
@@ -596,6 +607,12 @@ def main() -> int:
             "ms_per_step": ko_ms,
             "steps_per_s": 1e3 / ko_ms,
             "what": "split pass + reduction, 50 back-to-back launches between two HIP events",
+        },
+        "int8_query_scoring": {
+            "kernel_median_ms": q8_median_ms,
+            "what": "split kernel with cqa_tolerances.int8_query = 1 (scaled query quantised to 8 bits per block, "
+                    "mfma_i32_16x16x64_i8 scoring, explicit third error term in Delta_h), event-timed over 100 "
+                    "dispatches of the step loop, median; compare roofline.kernel_median_ms",
         },
         "adaptive_step": ad_info,
         "host_ladder_step": {

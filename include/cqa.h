@@ -100,6 +100,18 @@ typedef struct cqa_tolerances {
   int32_t key_bound_mode;   /* 0 min(tanh, tail), 1 tail form only, 2 tanh only  */
   int32_t rung4_min_groups; /* >0: that many flagged KV groups => Rung 4         */
   uint32_t force_flags;     /* OR-ed into every head's flag word (test hook)     */
+  int32_t int8_query;       /* 1: INT8 x INT8 scoring (the paper's optional tensor-core scoring
+                               mode): per sealed block the scaled query q~ = q . sigma is
+                               quantised to 8 bits, one scale s_q = max_c |q~_c| / 127 per
+                               (head, block), T_c = round(q~_c / s_q), and scored against the
+                               stored key codes on the INT8 matrix cores.  The paper budgets
+                               "one more Delta" for this third error source (mass_exp = 3);
+                               here the block's score bound also gets the explicit term
+                               (128 / sqrt d) sum_c |q~_c - s_q T_c|, so delta_h, E_key and the
+                               ranking test stay valid with mass_exp = 2.  One-pass calls with
+                               the matrix-core kernel only (the adaptive calls and the
+                               vector-ALU cross-check return CQA_ERR_UNSUPPORTED).  0: the
+                               scaled query is used unquantised (default).                */
 } cqa_tolerances;
 
 /* Per-(batch, query head) certificate of one decode step.  40 bytes. */

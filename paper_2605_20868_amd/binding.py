@@ -49,13 +49,13 @@ class Tolerances(C.Structure):
     _fields_ = [("eps_total", C.c_float), ("eps_key", C.c_float), ("eps_val", C.c_float),
                 ("v_tol", C.c_float), ("rank_min_mass", C.c_float), ("eps_guard", C.c_float),
                 ("rank_depth", C.c_int32), ("mass_exp", C.c_int32), ("key_bound_mode", C.c_int32),
-                ("rung4_min_groups", C.c_int32), ("force_flags", C.c_uint32)]
+                ("rung4_min_groups", C.c_int32), ("force_flags", C.c_uint32), ("int8_query", C.c_int32)]
 
     def __init__(self, eps_total=math.inf, eps_key=math.inf, eps_val=math.inf, v_tol=math.inf,
                  rank_min_mass=0.0, eps_guard=1e-6, rank_depth=0, mass_exp=2, key_bound_mode=0,
-                 rung4_min_groups=0, force_flags=0):
+                 rung4_min_groups=0, force_flags=0, int8_query=False):
         super().__init__(eps_total, eps_key, eps_val, v_tol, rank_min_mass, eps_guard, rank_depth,
-                         mass_exp, key_bound_mode, rung4_min_groups, force_flags)
+                         mass_exp, key_bound_mode, rung4_min_groups, force_flags, 1 if int8_query else 0)
 
 
 class Selector(C.Structure):

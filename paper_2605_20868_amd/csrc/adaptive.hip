@@ -803,6 +803,9 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
 int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
                         const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
                         uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st) {
+  // the promoted-block pass re-scores blocks with the unquantised scaled query: the quantised-query
+  // mode exists in the one-pass calls only
+  if (tol.int8_query != 0) return CQA_ERR_UNSUPPORTED;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
   const int64_t len = c->length[layer];

@@ -218,7 +218,8 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
 // default) and the adaptive path up to MAX_RANK_DEPTH; a larger depth is refused rather than
 // silently served by a shallower test.
 static int32_t check_tolerances(const cqa_tolerances* tol, int max_rank_depth = 1) {
-  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2 || tol->rank_depth < 0)
+  if (tol->mass_exp < 0 || tol->key_bound_mode < 0 || tol->key_bound_mode > 2 || tol->rank_depth < 0 ||
+      (tol->int8_query != 0 && tol->int8_query != 1))
     return CQA_ERR_INVALID_ARG;
   if (tol->rank_depth > max_rank_depth) return CQA_ERR_UNSUPPORTED;
   return CQA_OK;

@@ -190,6 +190,7 @@ struct DecodeArgs {
   int bps;             // blocks per split
   int n_q, n_kv;
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
+  int int8_query;      // matrix-core pass: 1 = INT8 x INT8 scoring of the quantised scaled query
   // promoted-block pass of the adaptive decode (null slot = not that pass)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
   __half* sc_k;             // layer base of the FP16-key scratch [Bt * Hkv][sc_cap][16][128], or null

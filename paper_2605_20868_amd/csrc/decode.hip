@@ -547,6 +547,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.n_q = hq;
     a.n_kv = hkv;
     a.stream_nt = stream_nt(c, nb);
+    a.int8_query = tol.int8_query;
+    // the quantised-query scoring exists in the matrix-core pass only
+    if (tol.int8_query != 0 && (c->variant != 0 || eta_out != nullptr)) return CQA_ERR_UNSUPPORTED;
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
     hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;

@@ -41,6 +41,7 @@ namespace cqa {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -114,7 +115,11 @@ constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability bu
 
 // LM: also writes the block log-masses (and, when asked, eta_b per block) for callers that rank
 // blocks afterwards.  NT: Tier-1 loads carry the non-temporal hint.
-template <int G, bool LM, bool NT>
+// Q8: INT8 x INT8 scoring (the paper's optional tensor-core scoring mode): per block the scaled
+//     query is quantised to 8 bits with one scale per (head, block) row, s_q = max_c |q~_c| / 127,
+//     and scored against the stored key codes by mfma_i32_16x16x64_i8; the block's score bound
+//     grows by the explicit term (128 / sqrt d) sum_c |q~_c - s_q T_c|.
+template <int G, bool LM, bool NT, bool Q8>
 __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
   __shared__ __align__(16) __half vmbuf[4][4][VM_ROW];   // [wave][block of quad][scale | offset]
   __shared__ __align__(16) float pbuf[4][4][P_HEAD];     // [wave][head][block of quad][token]
-  __shared__ __align__(16) float cbuf[4][2][4][4];       // [wave][c_b | Delta_b][head][block]
+  __shared__ __align__(16) float cbuf[4][3][4][4];       // [wave][c_b | Delta_b | s_q][head][block]
   __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
   __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
   __shared__ float sbuf[4];                              // [head] 1 / S_h
@@ -309,70 +314,148 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     CQA_LOAD_META(q_next)
     wave_sync();
 
-    // ---- scores.  A operand: scaled query of row-role (h, j), two FP16 terms (hi + lo);
-    //      B operand: the 16 tokens of block i, their signed codes as exact FP16 integers.
-    //      C_i[row (head kg, block v)][col token n]: row v == i is the one kept.
-    f32x4 C[4];
+    float craw[4];                  // raw score sum of (head kg, block i, token n), before c_b
+    float csum = 0.0f, dsum = 0.0f, qres = 0.0f, sq = 1.0f;
+    if constexpr (!Q8) {
+      // ---- scores.  A operand: scaled query of row-role (h, j), two FP16 terms (hi + lo);
+      //      B operand: the 16 tokens of block i, their signed codes as exact FP16 integers.
+      //      C_i[row (head kg, block v)][col token n]: row v == i is the one kept.
+      f32x4 C[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    f32x4 R = f32x4{0.0f, 0.0f, 0.0f, 0.0f};   // R[v] = sum_c q~ of row (head kg, block v), every column
-    float csum = 0.0f, dsum = 0.0f;
+      for (int i = 0; i < 4; ++i) C[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      f32x4 R = f32x4{0.0f, 0.0f, 0.0f, 0.0f};   // R[v] = sum_c q~ of row (head kg, block v), every column
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
-      const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
-      const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
-      const float4 z0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0]);
-      const float4 z1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0 + 4]);
-      const float4 q0 = *reinterpret_cast<const float4*>(&qbuf[h][c0]);
-      const float4 q1 = *reinterpret_cast<const float4*>(&qbuf[h][c0 + 4]);
-      const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-      const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
-      const float qq[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-      float qt[8];
+      for (int u = 0; u < 4; ++u) {
+        const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
+        const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
+        const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
+        const float4 z0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0]);
+        const float4 z1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0 + 4]);
+        const float4 q0 = *reinterpret_cast<const float4*>(&qbuf[h][c0]);
+        const float4 q1 = *reinterpret_cast<const float4*>(&qbuf[h][c0 + 4]);
+        const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+        const float qq[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        float qt[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float qv = qq[e];
-        qt[e] = qv * sg[e];
-        csum = fmaf(qv, zz[e], csum);
-        dsum = fmaf(fabsf(qv), sg[e], dsum);
+        for (int e = 0; e < 8; ++e) {
+          const float qv = qq[e];
+          qt[e] = qv * sg[e];
+          csum = fmaf(qv, zz[e], csum);
+          dsum = fmaf(fabsf(qv), sg[e], dsum);
+        }
+        HF8 qh2, ql2;   // scaled query = hi + lo, two FP16 terms (22 significant bits)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const f16x2 hp = pack_f16_rtz(qt[2 * p], qt[2 * p + 1]);
+          const f16x2 lp = pack_f16_rtz(qt[2 * p] - (float)hp[0], qt[2 * p + 1] - (float)hp[1]);
+          qh2.u[p] = __builtin_bit_cast(uint32_t, hp);
+          ql2.u[p] = __builtin_bit_cast(uint32_t, lp);
+        }
+        HF8 kv[4];      // 1152 + code for the 8 codes of my token and channel slice in each block
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint4 kx = kraw[i][u >> 1];
+          const uint32_t d0 = (u & 1) ? kx.z : kx.x, d1 = (u & 1) ? kx.w : kx.y;
+          kv[i].u[0] = bytes_to_f16_biased<0x04010400u>(d0);
+          kv[i].u[1] = bytes_to_f16_biased<0x04030402u>(d0);
+          kv[i].u[2] = bytes_to_f16_biased<0x04010400u>(d1);
+          kv[i].u[3] = bytes_to_f16_biased<0x04030402u>(d1);
+        }
+        // consecutive MFMAs go to different accumulators, so none waits for its predecessor
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, kv[i].v, C[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv[i].v, C[i], 0, 0, 0);
+        R = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, ones_h.v, R, 0, 0, 0);
+        R = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, ones_h.v, R, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
+        if (u == 1) {
+          CQA_LOAD_K(q_next, 0)
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (u == 3) {
+          CQA_LOAD_K(q_next, 1)
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-      HF8 qh2, ql2;   // scaled query = hi + lo, two FP16 terms (22 significant bits)
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const f16x2 hp = pack_f16_rtz(qt[2 * p], qt[2 * p + 1]);
-        const f16x2 lp = pack_f16_rtz(qt[2 * p] - (float)hp[0], qt[2 * p + 1] - (float)hp[1]);
-        qh2.u[p] = __builtin_bit_cast(uint32_t, hp);
-        ql2.u[p] = __builtin_bit_cast(uint32_t, lp);
+      for (int i = 0; i < 4; ++i) craw[i] = fmaf(-K_BIAS, R[i], C[i][i]);
+    } else {
+      // ---- scores, INT8 x INT8.  Pass 1: the 32 scaled-query elements of my row (h, j), their
+      //      sums c_b, Delta_b and the row maximum; pass 2: T = round(q~ * 127 / max), packed
+      //      four to a dword in channel order, and the residual sum of the third error term.
+      float qt[32];
+      float amax = 0.0f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c0 = (u >> 1) * 64 + kg * 16 + (u & 1) * 8;
+        const float4 s0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0]);
+        const float4 s1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][c0 + 4]);
+        const float4 z0 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0]);
+        const float4 z1 = *reinterpret_cast<const float4*>(&kmbuf[w][j][D + c0 + 4]);
+        const float4 q0 = *reinterpret_cast<const float4*>(&qbuf[h][c0]);
+        const float4 q1 = *reinterpret_cast<const float4*>(&qbuf[h][c0 + 4]);
+        const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+        const float qq[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float qv = qq[e];
+          const float t = qv * sg[e];
+          qt[u * 8 + e] = t;
+          csum = fmaf(qv, zz[e], csum);
+          dsum = fmaf(fabsf(qv), sg[e], dsum);
+          amax = fmaxf(amax, fabsf(t));
+        }
       }
-      HF8 kv[4];      // 1152 + code for the 8 codes of my token and channel slice in each block
+      amax = fmaxf(amax, __shfl_xor(amax, 16));
+      amax = fmaxf(amax, __shfl_xor(amax, 32));
+      // binary32, correctly rounded quotients (the power-of-two pre-scale of q commutes with both)
+      const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+      sq = amax / 127.0f;
+      const float MAGIC = 12582912.0f;   // 1.5 * 2^23: fl(x + MAGIC) - MAGIC = round-half-even(x), |x| < 2^22
+      v4i aq[2];                        // A operand per channel half: 16 codes T, two's complement bytes
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 kx = kraw[i][u >> 1];
-        const uint32_t d0 = (u & 1) ? kx.z : kx.x, d1 = (u & 1) ? kx.w : kx.y;
-        kv[i].u[0] = bytes_to_f16_biased<0x04010400u>(d0);
-        kv[i].u[1] = bytes_to_f16_biased<0x04030402u>(d0);
-        kv[i].u[2] = bytes_to_f16_biased<0x04010400u>(d1);
-        kv[i].u[3] = bytes_to_f16_biased<0x04030402u>(d1);
+      for (int g4 = 0; g4 < 8; ++g4) {
+        uint32_t bits[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x = qt[4 * g4 + e];
+          const float r = fmaf(x, inv, MAGIC);              // one rounding: the exact product, rounded to an integer
+          const float tf = r - MAGIC;
+          qres += fabsf(fmaf(-sq, tf, x));
+          bits[e] = __float_as_uint(r);                     // low byte = T mod 256
+        }
+        const uint32_t lo2 = __builtin_amdgcn_perm(bits[1], bits[0], 0x0c0c0400u);
+        const uint32_t hi2 = __builtin_amdgcn_perm(bits[3], bits[2], 0x0c0c0400u);
+        aq[g4 >> 2][g4 & 3] = (int)__builtin_amdgcn_perm(hi2, lo2, 0x05040100u);
       }
-      // consecutive MFMAs go to different accumulators, so none waits for its predecessor
+      v4i Ci[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, kv[i].v, C[i], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) Ci[i] = v4i{0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        C[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, kv[i].v, C[i], 0, 0, 0);
-      R = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh2.v, ones_h.v, R, 0, 0, 0);
-      R = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql2.v, ones_h.v, R, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);   // keep the four channel slices apart (register pressure)
-      if (u == 1) {
-        CQA_LOAD_K(q_next, 0)
+      for (int cq = 0; cq < 2; ++cq) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          // stored bytes are code + 128: flipping the top bit gives the two's complement code
+          const uint4 kx = kraw[i][cq];
+          const v4i kb = {(int)(kx.x ^ 0x80808080u), (int)(kx.y ^ 0x80808080u), (int)(kx.z ^ 0x80808080u),
+                          (int)(kx.w ^ 0x80808080u)};
+          Ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aq[cq], kb, Ci[i], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (cq == 0) {
+          CQA_LOAD_K(q_next, 0)
+        } else {
+          CQA_LOAD_K(q_next, 1)
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (u == 3) {
-        CQA_LOAD_K(q_next, 1)
-        __builtin_amdgcn_sched_barrier(0);
-      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) craw[i] = (float)Ci[i][i];
     }
     // per-block constant c_b = q.z and Delta_b (both still times S_h): summed over the four
     // channel slices, then handed to the rows that own head kg
@@ -381,6 +464,12 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     cb += __shfl_xor(cb, 32);
     dsum += __shfl_xor(dsum, 16);
     dsum += __shfl_xor(dsum, 32);
+    if constexpr (Q8) {
+      qres += __shfl_xor(qres, 16);
+      qres += __shfl_xor(qres, 32);
+      dsum = fmaf(256.0f, qres, dsum);   // Delta_b + Delta^q_b = (sum |q| sigma + 256 sum |q~ - s_q T|) / (2 sqrt d)
+      cbuf[w][2][h][j] = sq;
+    }
     // (all four kg lanes of a column hold the same sums and store the same words: no branch)
     cbuf[w][0][h][j] = cb;
     cbuf[w][1][h][j] = dsum * (0.5f * inv_sqrt_d) * unscale_op;
@@ -389,6 +478,13 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     const float4 dl4 = *reinterpret_cast<const float4*>(&cbuf[w][1][kg][0]);
     const float cbs[4] = {cb4.x, cb4.y, cb4.z, cb4.w};
     const float dls[4] = {dl4.x, dl4.y, dl4.z, dl4.w};
+    if constexpr (Q8) {
+      const float4 sq4 = *reinterpret_cast<const float4*>(&cbuf[w][2][kg][0]);
+      craw[0] *= sq4.x;
+      craw[1] *= sq4.y;
+      craw[2] *= sq4.z;
+      craw[3] *= sq4.w;
+    }
 
     // ---- block statistics and online softmax of head kg; this lane is token n of each block.
     //      Branch-free.  Blocks past the end of the head (only in its last quad) hold zeros --
@@ -398,7 +494,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     float mq = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float s = live[i] ? (C[i][i] + fmaf(-K_BIAS, R[i], cbs[i])) * score_scale : -1.0e30f;
+      const float s = live[i] ? (craw[i] + cbs[i]) * score_scale : -1.0e30f;
       mbv[i] = row_max(s);
       ptv[i] = __builtin_amdgcn_exp2f(s - mbv[i]);
       sbv[i] = row_sum(ptv[i]);
@@ -649,14 +745,16 @@ int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid,
 int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t ev0, hipEvent_t ev1,
                           hipStream_t st) {
   const bool lm = a.blk_logmass != nullptr;
-#define CQA_LAUNCH_NT(GG, NTV)                                                                   \
-  if (lm)                                                                                        \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV>), grid, dim3(256), 0, st,   \
-                          ev0, ev1, 0, a);                                          \
-  else                                                                                           \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV>), grid, dim3(256), 0, st,  \
-                          ev0, ev1, 0, a);
-#define CQA_LAUNCH(GG)                                                                           \
+#define CQA_LAUNCH_Q(GG, NTV, Q8V)                                                                 \
+  if (lm)                                                                                          \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV, Q8V>), grid, dim3(256), 0, st, \
+                          ev0, ev1, 0, a);                                                         \
+  else                                                                                             \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV, Q8V>), grid, dim3(256), 0,   \
+                          st, ev0, ev1, 0, a);
+#define CQA_LAUNCH_NT(GG, NTV)                                                                     \
+  if (a.int8_query) { CQA_LAUNCH_Q(GG, NTV, true) } else { CQA_LAUNCH_Q(GG, NTV, false) }
+#define CQA_LAUNCH(GG)                                                                             \
   if (a.stream_nt) { CQA_LAUNCH_NT(GG, true) } else { CQA_LAUNCH_NT(GG, false) }
   switch (group) {
     case 1: CQA_LAUNCH(1) break;
@@ -666,6 +764,7 @@ int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t 
   }
 #undef CQA_LAUNCH
 #undef CQA_LAUNCH_NT
+#undef CQA_LAUNCH_Q
   return CQA_OK;
 }
 

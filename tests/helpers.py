@@ -96,7 +96,7 @@ def to_gpu_tol(cqa, tol):
     """oracle.Tolerances -> binding.Tolerances (same fields)."""
     return cqa.Tolerances(tol.eps_total, tol.eps_key, tol.eps_val, tol.v_tol, tol.rank_min_mass,
                           tol.eps_guard, tol.rank_depth, tol.mass_exp, tol.key_bound_mode,
-                          tol.rung4_min_groups, tol.force_flags)
+                          tol.rung4_min_groups, tol.force_flags, tol.int8_query)
 
 
 CERT_REL = 1e-4      # bounds: |gpu - oracle| <= 1e-4 |oracle| + 1e-9

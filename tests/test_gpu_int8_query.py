@@ -1,0 +1,101 @@
+"""GPU parity of the INT8 x INT8 scoring mode (cqa_tolerances.int8_query: the scaled query quantised
+to 8 bits per block and scored on the INT8 matrix cores) against the oracle's, through the C ABI.
+
+The integer decisions (the 8-bit codes of the scaled query) are taken in binary32 on both sides, so
+block log-masses agree to 1e-4 as in the default mode -- one differing code would move a block's
+scores by ~1e-2.  Delta_h carries the explicit third error term and is held to 1e-4 relative like
+every certificate scalar.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import GpuLayerCache, assert_head_matches, to_gpu_tol
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def compare(gc, oc, q, tol, where, heads=None, lm=None):
+    gtol = to_gpu_tol(gc.cqa, tol)
+    O, cert, flags, glm = gc.certified_decode(q, gtol, want_logmass=True)
+    bt, hq, _ = q.shape
+    heads = heads or [(b, h) for b in range(bt) for h in range(hq)]
+    ref = oc.certified_decode(q, tol, heads=heads)
+    for (b, h), r in zip(heads, ref):
+        assert_head_matches(r, O[b, h], cert[b, h], flags[b, h], (where, b, h))
+        assert np.abs(glm[b, h] - r["blk_logmass"]).max() <= 1e-4, (where, "block log-masses", b, h)
+    return O, cert, flags, ref
+
+
+def test_tiny_and_group_sizes():
+    say("int8 query: tiny (GQA 4) and GQA 1 / 2, ragged tails")
+    for hq, hkv, n, seed in ((4, 1, 1024 + 5, 0), (2, 2, 16 * 37 + 9, 1), (4, 2, 16 * 130 + 15, 2)):
+        rng = np.random.default_rng(seed)
+        k = (rng.standard_normal((2, hkv, n, 128)) * (1.0 + seed)).astype(np.float16)
+        v = rng.standard_normal((2, hkv, n, 128)).astype(np.float16)
+        q = (rng.standard_normal((2, hq, 128)) * (1.0 + 0.5 * seed)).astype(np.float16)
+        oc = oracle.OracleLayerCache(2, hkv)
+        oc.append(k, v)
+        with GpuLayerCache(2, hq, hkv, n + 32) as gc:
+            gc.append(k, v)
+            O8, c8, _, ref8 = compare(gc, oc, q, oracle.Tolerances(int8_query=True, rank_depth=1), ("int8", hq, hkv))
+            O0, c0, _, ref0 = compare(gc, oc, q, oracle.Tolerances(rank_depth=1), ("exact", hq, hkv))
+            # the mode is really on: the certificate widens, the output moves (a little)
+            assert (c8["delta_h"] > c0["delta_h"]).all()
+            assert (O8 != O0).any()
+            for mass_exp, mode in ((3, 1), (2, 2)):
+                compare(gc, oc, q, oracle.Tolerances(int8_query=True, mass_exp=mass_exp, key_bound_mode=mode),
+                        ("int8", hq, hkv, mass_exp, mode))
+
+
+def test_l8k_outlier_channels_with_steps():
+    say("int8 query: l8k (outlier channels x20), 20 steps across a seal")
+    sh = workloads.SHAPES["l8k"]
+    k, v = workloads.make_kv("l8k", seed=0, context=8192 - 6)
+    oc = oracle.OracleLayerCache(sh.batch, sh.n_kv_heads)
+    oc.append(k, v)
+    tol = oracle.Tolerances(int8_query=True)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, 8192 + 64) as gc:
+        gc.append(k, v)
+        for step in range(20):
+            ks, vs = workloads.make_step_kv("l8k", step, seed=0)
+            q = workloads.make_q("l8k", step, seed=0)
+            oc.append(ks, vs)
+            gc.append(ks, vs)
+            if step in (0, 5, 6, 19):
+                heads = [(0, h) for h in range(sh.n_q_heads)] if step == 6 else [(0, 0), (0, 13), (0, 31)]
+                compare(gc, oc, q, tol, ("l8k", step), heads=heads)
+
+
+def test_t128k_sampled_heads_and_error_paths():
+    say("int8 query: t128k (Student-t keys), sampled heads; unsupported combinations")
+    sh = workloads.SHAPES["t128k"]
+    k, v = workloads.make_kv("t128k", seed=0)
+    q = workloads.make_q("t128k", 2, seed=0)
+    oc = oracle.OracleLayerCache(sh.batch, sh.n_kv_heads)
+    oc.append(k, v)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 64) as gc:
+        gc.append(k, v)
+        compare(gc, oc, q, oracle.Tolerances(int8_query=True), "t128k", heads=[(0, 2), (0, 17), (0, 28)])
+        cqa = gc.cqa
+        qd = gc.to_dev(q)
+        # the vector-ALU cross-check kernel and the adaptive calls do not have the mode
+        cqa.cqa_set_kernel_variant(gc.h, 1)
+        with pytest.raises(cqa.CqaError) as e:
+            cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(int8_query=True), gc.O, gc.cert, gc.flags, None)
+        assert e.value.status == cqa.ERR_UNSUPPORTED
+        cqa.cqa_set_kernel_variant(gc.h, 0)
+        with pytest.raises(cqa.CqaError) as e:
+            cqa.cqa_adaptive_decode(gc.h, 0, qd, cqa.Tolerances(int8_query=True), cqa.Selector(), gc.O, gc.cert,
+                                    gc.flags)
+        assert e.value.status == cqa.ERR_UNSUPPORTED
+        # the enqueue-only step takes it (split pass + reduction + device-resolved ladder)
+        cqa.cqa_decode_step_enqueue(gc.h, 0, None, None, qd, cqa.Tolerances(int8_query=True), gc.O, gc.cert, gc.flags)
+        O, cert, flags = gc.results()
+        ref = oc.certified_decode(q, oracle.Tolerances(int8_query=True), heads=[(0, 9)])[0]
+        assert_head_matches(ref, O[0, 9], cert[0, 9], flags[0, 9], ("t128k enqueue", 9))

@@ -41,7 +41,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 def test_struct_layouts_match_the_header():
     cqa = load_binding()
     assert ctypes.sizeof(cqa.HeadCert) == 40
-    assert ctypes.sizeof(cqa.Tolerances) == 44
+    assert ctypes.sizeof(cqa.Tolerances) == 48
     assert ctypes.sizeof(cqa.CacheDesc) == 40
     assert ctypes.sizeof(cqa.Selector) == 36
     assert cqa.CERT_BYTES == 40
