@@ -320,6 +320,14 @@ typedef struct cqa_selector {
                          /* 0x85EBCA77 ^ seed * 0xC2B2AE3D) < explore_frac * 2^32,    */
                          /* mix32 = the multiply-xorshift mixer with constants       */
                          /* 0x7FEB352D, 0x846CA68B; group = batch * n_kv_heads + kvh  */
+  int32_t per_head;      /* 0: precision is chosen per KV group -- a block is promoted for all  */
+                         /* heads of the group when any of them selects it (the paper's       */
+                         /* per-KV-group selection variant; one set of FP16 scores serves the  */
+                         /* group and every head's tail only shrinks).  1: the paper's         */
+                         /* default -- each head's promoted set F is its own selection (plus   */
+                         /* the explored blocks), for keys and for values; its achieved tail   */
+                         /* and its ranking check run over its own F.  The FP16 originals of a */
+                         /* block are still read once per group when any head asks for them.   */
 } cqa_selector;
 
 /* One decode step of `layer` with mask-gated key precision, all on `stream`:
@@ -331,9 +339,10 @@ typedef struct cqa_selector {
  *     of the estimated mass, clamped; Rung 1: K doubles (up to k_limit) while
  *     the key term of the achieved tail exceeds tol->eps_key;
  *  3. the promoted set of a (batch, kv-head) group is the union of its heads'
- *     selections; value promotion (the ladder's second rung, sel->v_limit > 0)
- *     is decided the same way from the estimated contributions p_b eta_b and
- *     is likewise per group;
+ *     selections (sel->per_head = 0) or every head keeps its own (sel->per_head
+ *     = 1); value promotion (the ladder's second rung, sel->v_limit > 0) is
+ *     decided the same way from the estimated contributions p_b eta_b and
+ *     follows the same switch;
  *  4. the result is that of cqa_certified_decode with the promoted blocks
  *     scored from their FP16 keys, which the device reads straight from the
  *     pinned Tier-2 originals (no host step, no staging); values are INT4 except

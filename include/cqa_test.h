@@ -21,8 +21,9 @@ extern "C" {
 /* What the last adaptive decode decided, copied to the host after a
  * device synchronise.  k_star_host int32 [batch][n_q_heads]; selected_host int32
  * [batch][n_q_heads][512] (the head's own blocks, best first; entries past K*
- * are unspecified); promoted_host uint8 [batch][n_kv_heads][n_blocks] (bit 0 = the
- * group scored this block with FP16 keys, bit 1 = it attended its FP16 values);
+ * are unspecified); promoted_host uint16 [batch][n_kv_heads][n_blocks] (bit 0 = some head
+ * of the group scored this block with FP16 keys, bit 1 = some head attended its FP16 values,
+ * bits 4-7 / 8-11 = which of the group's heads did, head i of the group at bit 4 + i / 8 + i);
  * logmass_int8_host / logmass_mixed_host float [batch][n_q_heads][n_blocks] (block
  * log-masses of step 1, and of step 4 where a block was revisited, else step 1's); v_count_host int32 [batch][n_q_heads] and
  * v_selected_host int32 [batch][n_q_heads][512] (the head's value selection, largest
@@ -32,7 +33,7 @@ extern "C" {
  * on the head's key-promoted tokens; valid when sel->canary was set).
  * Any pointer may be NULL.  n_blocks = sealed blocks of `layer`. */
 int32_t cqa_adaptive_state(cqa_cache* c, int32_t layer, int32_t* k_star_host,
-                           int32_t* selected_host, uint8_t* promoted_host,
+                           int32_t* selected_host, uint16_t* promoted_host,
                            float* logmass_int8_host, float* logmass_mixed_host,
                            int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host,
                            float* score_dev_host);

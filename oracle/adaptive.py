@@ -20,10 +20,14 @@ Readings where the paper is silent or offers a choice (the HIP path follows the 
 * Rung 1: while the key term computed from the achieved alpha_hat_T exceeds
   eps_key and K can still grow, K doubles (capped at k_limit >= K_max, the
   scratch capacity, and at the number of blocks).
-* Key precision is chosen per KV group: the promoted set of a group is the union
-  of its query heads' selections (the paper's per-KV-group selection variant).
-  A head's tail is then the complement of the union, which only shrinks
-  alpha_hat_T; the bound stays valid.
+* Key precision is chosen per KV group by default: the promoted set of a group is
+  the union of its query heads' selections (the paper's per-KV-group selection
+  variant).  A head's tail is then the complement of the union, which only shrinks
+  alpha_hat_T; the bound stays valid.  With SelectorParams.per_head the promoted set
+  F of a head is its OWN selection (the paper's default: steps 1-6 of "Adaptive
+  Precision Selection" and the ranking check run per head over the head's F); the
+  blocks the exploration budget draws are promoted for every head of the group in
+  either mode.  Value promotion follows the same switch.
 * Delta in the bound is Delta_h of the scoring pass (maximum over all sealed
   blocks): the global-max-shift factor of the mass theorem ranges over all blocks.
 * Value promotion (the ladder's second rung) is decided from the scoring pass too: a block's
@@ -74,6 +78,7 @@ class SelectorParams:
     canary: bool = False        # score-consistency check on key-promoted blocks
     explore_frac: float = 0.0   # exploration budget: fraction of blocks key-promoted at random
     explore_seed: int = 0       # counter of the draw (e.g. the decode step)
+    per_head: bool = False      # promoted sets per query head (the paper's default) instead of per KV group
 
 
 def rank_blocks(logmass: np.ndarray) -> np.ndarray:
@@ -315,16 +320,21 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
             picks.append(sel["order"][:k])
             ks.append(k)
             vpicks.append(select_value_blocks(sc["blk_logmass"], sc["lse"], cache.eta[b, kh], tol, par))
-        union = group_union(picks, nb) | explored_blocks(nb, b * cache.hkv + kh, par)
+        explored = explored_blocks(nb, b * cache.hkv + kh, par)
+        union = group_union(picks, nb) | explored
         vunion = group_union(vpicks, nb)
         for i in range(g):
             h = kh * g + i
             sc = scoring[i]
+            # the head's promoted sets: its own selection, or the group's union
+            f_keys = (group_union([picks[i]], nb) | explored) if par.per_head else union
+            f_vals = group_union([vpicks[i]], nb) if par.per_head else vunion
             res = mixed_head(q16[b, h], k_hat, cache.k16[b, kh, :nb * qz.B], v_hat, cache.eta[b, kh],
-                             cache.nu[b, kh], k_tr, v_tr, union, sc["blk_logmass"], sc["lse"],
-                             sc["delta_h"], tol, v_promoted=vunion,
+                             cache.nu[b, kh], k_tr, v_tr, f_keys, sc["blk_logmass"], sc["lse"],
+                             sc["delta_h"], tol, v_promoted=f_vals,
                              v16_sealed=cache.v16[b, kh, :nb * qz.B], canary=par.canary)
-            res.update(k_star=ks[i], selected=picks[i], promoted=union, scoring=sc,
-                       v_selected=vpicks[i], v_promoted=vunion)
+            res.update(k_star=ks[i], selected=picks[i], promoted=f_keys, scoring=sc,
+                       v_selected=vpicks[i], v_promoted=f_vals, group_promoted=union,
+                       group_v_promoted=vunion)
             out[(b, h)] = res
     return out

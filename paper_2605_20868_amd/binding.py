@@ -62,13 +62,14 @@ class Selector(C.Structure):
     """Parameters of the adaptive key-precision selector (cqa_selector)."""
     _fields_ = [("tau_cov", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32),
                 ("k_limit", C.c_int32), ("v_limit", C.c_int32), ("v_greedy", C.c_int32),
-                ("canary", C.c_int32), ("explore_frac", C.c_float), ("explore_seed", C.c_uint32)]
+                ("canary", C.c_int32), ("explore_frac", C.c_float), ("explore_seed", C.c_uint32),
+                ("per_head", C.c_int32)]
 
     def __init__(self, tau_cov=0.995, k_min=2, k_max=128, k_limit=None, v_limit=0, v_greedy=False,
-                 canary=False, explore_frac=0.0, explore_seed=0):
+                 canary=False, explore_frac=0.0, explore_seed=0, per_head=False):
         super().__init__(tau_cov, k_min, k_max, k_max if k_limit is None else k_limit, v_limit,
                          1 if v_greedy else 0, 1 if canary else 0, explore_frac,
-                         explore_seed & 0xFFFFFFFF)
+                         explore_seed & 0xFFFFFFFF, 1 if per_head else 0)
 
 
 MAX_K_LIMIT = 512
@@ -344,15 +345,15 @@ def cqa_scratch_stats(h):
 
 
 def cqa_adaptive_state(h, layer, batch, n_q_heads, n_kv_heads):
-    """Returns (k_star i32[Bt,Hq], selected i32[Bt,Hq,512], promoted u8[Bt,Hkv,NB] (bit 0 keys,
-    bit 1 values), logmass_int8 f32[Bt,Hq,NB], logmass_mixed f32[Bt,Hq,NB], v_count i32[Bt,Hq],
+    """Returns (k_star i32[Bt,Hq], selected i32[Bt,Hq,512], promoted u16[Bt,Hkv,NB] (bit 0 keys,
+    bit 1 values for some head of the group; bits 4-7 / 8-11: for which heads), logmass_int8 f32[Bt,Hq,NB], logmass_mixed f32[Bt,Hq,NB], v_count i32[Bt,Hq],
     v_selected i32[Bt,Hq,512], contrib f32[Bt,Hq,NB], score_dev f32[Bt,Hq]) of the last adaptive
     decode."""
     import numpy as np
     nb = cqa_cache_length(h, layer) // 16
     ks = np.zeros((batch, n_q_heads), np.int32)
     sel = np.zeros((batch, n_q_heads, MAX_K_LIMIT), np.int32)
-    prom = np.zeros((batch, n_kv_heads, nb), np.uint8)
+    prom = np.zeros((batch, n_kv_heads, nb), np.uint16)
     l8 = np.zeros((batch, n_q_heads, nb), np.float32)
     lx = np.zeros((batch, n_q_heads, nb), np.float32)
     vc = np.zeros((batch, n_q_heads), np.int32)

@@ -40,7 +40,7 @@ struct SelectArgs {
   const cqa_head_cert* cert;   // first pass: lse, delta_h, v_max
   int32_t* sel;                // [Bt][Hq][MAX_K_LIMIT]
   int32_t* kstar;              // [Bt][Hq]
-  uint32_t* umask;             // [Bt][Hkv][mask_words]
+  uint32_t* umask;             // [Bt][Hq][mask_words]: the head's own selection
   float v_tol, eps_val;        // value selection: local threshold and budget
   float* score_dev;            // [Bt][Hq] canary output, cleared here (null = no canary)
   int v_greedy;
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(ST) void select_kernel(SelectArgs a) {
   }
   __syncthreads();
   const int k = s_k;
-  uint32_t* um = a.umask + ((int64_t)b * a.n_kv + hq / (a.n_q / a.n_kv)) * a.mask_words;
+  uint32_t* um = a.umask + row * a.mask_words;
   for (int i = tid; i < k; i += ST) {
     const int idx = sorted_idx[i];
     a.sel[row * MAX_K_LIMIT + i] = idx;
@@ -371,9 +371,11 @@ __device__ __forceinline__ uint32_t explore_mix(uint32_t blk, uint32_t grp, uint
 struct CompactArgs {
   uint32_t explore_threshold;   // a block is explored (key-promoted) when its draw is below this; 0 = off
   uint32_t explore_seed;
-  uint32_t* vmask;     // [Bt][Hkv][mask_words] value selections (null = none); cleared likewise
-  uint32_t* umask;     // [Bt][Hkv][mask_words]; cleared on the way out
+  uint32_t* vmask;     // [Bt][Hq][mask_words] value selections per head (null = none); cleared likewise
+  uint32_t* umask;     // [Bt][Hq][mask_words] key selections per head; cleared on the way out
   int64_t mask_words;
+  int group;           // query heads per KV group
+  int per_head;        // 1: a head's promoted sets are its own selections; 0: the group's unions
   int32_t* slot;       // [Bt][Hkv][slot_stride]
   int64_t slot_stride;
   int32_t* ulist;      // [Bt][Hkv][MAX_UNION]
@@ -389,14 +391,15 @@ struct CompactArgs {
   uint32_t sc_step;    // stamp of this step (larger than every stamp before it, never 0)
 };
 
-// One workgroup per KV group: the two bit masks (FP16 keys, FP16 values) -> per-block flags
-// (bit 0 keys, bit 1 values, 0 = neither) and the ascending list of blocks with any flag.
-// Clears the masks.
+// One workgroup per KV group: the heads' bit masks (FP16 keys, FP16 values) -> per-block flags
+// (bit 0: some head scores the block with FP16 keys, bit 1: some head attends its FP16 values,
+// bits 24-27 / 28-31: which heads; 0 = neither) and the ascending list of blocks with any flag.
+// Per-group promotion gives every head the union's bits.  Clears the masks.
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   const int tid = threadIdx.x;
   const int64_t grp = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-  uint32_t* um = a.umask + grp * a.mask_words;
-  uint32_t* vm = a.vmask != nullptr ? a.vmask + grp * a.mask_words : nullptr;
+  uint32_t* um = a.umask + grp * a.group * a.mask_words;        // the group's heads are consecutive rows
+  uint32_t* vm = a.vmask != nullptr ? a.vmask + grp * a.group * a.mask_words : nullptr;
   int32_t* slot = a.slot + grp * a.slot_stride;
   int32_t* ulist = a.ulist + grp * MAX_UNION;
   const int words = (a.nb + 31) >> 5;
@@ -407,22 +410,34 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   for (int w0 = 0; w0 < words; w0 += 256) {
     const int w = w0 + tid;
     uint32_t kbits = 0u, vbits = 0u;
+    uint32_t kh[4] = {0u, 0u, 0u, 0u}, vh[4] = {0u, 0u, 0u, 0u};   // per head
     if (w < words) {
-      kbits = um[w];
-      um[w] = 0u;
-      if (vm != nullptr) {
-        vbits = vm[w];
-        vm[w] = 0u;
+      for (int i = 0; i < a.group; ++i) {
+        kh[i] = um[i * a.mask_words + w];
+        um[i * a.mask_words + w] = 0u;
+        kbits |= kh[i];
+        if (vm != nullptr) {
+          vh[i] = vm[i * a.mask_words + w];
+          vm[i * a.mask_words + w] = 0u;
+          vbits |= vh[i];
+        }
       }
       if (a.explore_threshold != 0u) {
+        uint32_t ebits = 0u;
 #pragma unroll 4
         for (int j = 0; j < 32; ++j)
           if (explore_mix((uint32_t)(w * 32 + j), (uint32_t)grp, a.explore_seed) < a.explore_threshold)
-            kbits |= 1u << j;
+            ebits |= 1u << j;
+        kbits |= ebits;                          // explored blocks are promoted for every head
+        for (int i = 0; i < a.group; ++i) kh[i] |= ebits;
       }
       if (w == words - 1 && (a.nb & 31)) {      // nothing past nb
         kbits &= (1u << (a.nb & 31)) - 1u;
         vbits &= (1u << (a.nb & 31)) - 1u;
+      }
+      for (int i = 0; i < 4; ++i) {
+        kh[i] = i < a.group ? (a.per_head ? kh[i] & kbits : kbits) : 0u;
+        vh[i] = i < a.group ? (a.per_head ? vh[i] & vbits : vbits) : 0u;
       }
     }
     const uint32_t bits = kbits | vbits;
@@ -444,7 +459,11 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
           // the list cannot overflow (4 heads x MAX_K_LIMIT for keys and as many for values);
           // a block that did not fit would simply stay unpromoted
           const bool fits = pos < MAX_UNION;
-          slot[blk] = fits ? (int)(((kbits >> j) & 1u) | (((vbits >> j) & 1u) << 1)) : 0;
+          uint32_t f = ((kbits >> j) & 1u) | (((vbits >> j) & 1u) << 1);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            f |= (((kh[i] >> j) & 1u) << (SLOT_HK_SHIFT + i)) | (((vh[i] >> j) & 1u) << (SLOT_HV_SHIFT + i));
+          slot[blk] = fits ? (int)f : 0;
           if (fits) ulist[pos] = blk;
           ++pos;
         } else {
@@ -610,6 +629,7 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
   const float delta = ra.cert[row].delta_h;
 
   const float* eta = a.eta + grp * ra.nb;
+  const int kbit = 1 << (SLOT_HK_SHIFT + hq % (ra.n_q / ra.n_kv));   // this head scores the block with FP16 keys
   float best_x = -INFINITY, best_8 = -INFINITY, tail_max = -INFINITY, maxc8 = 0.0f;
   int ix = -1, i8 = -1;
   double tail_mass = 0.0, l8u = 0.0, ev8u = 0.0;
@@ -630,7 +650,7 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
       const int i = base + j * ART + tid;
       if (i >= ra.nb) continue;
       const float v8 = b8[j];
-      if (bs[j] & 1) {
+      if (bs[j] & kbit) {
         const float vx = bx[j];
         if (vx > best_x) {      // ascending scan per thread: strict > keeps the lowest index
           best_x = vx;
@@ -714,7 +734,7 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
     for (int j = 0; j < CAND; ++j) {
       const int i = j * ART + tid;
       const int blk = i < n ? ulist[i] : -1;
-      const bool keyp = blk >= 0 && blk < ra.nb && (slot[blk] & 1);
+      const bool keyp = blk >= 0 && blk < ra.nb && (slot[blk] & kbit);
       cb[j] = keyp ? blk : -1;
       cx[j] = keyp ? lx[blk] : 0.0f;
       c8[j] = keyp ? l8[blk] : 0.0f;
@@ -884,6 +904,8 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   }
   ca.vmask = values ? w.vmask : nullptr;
   ca.umask = w.umask;
+  ca.group = g;
+  ca.per_head = sel.per_head;
   ca.mask_words = w.mask_words;
   ca.slot = w.slot;
   ca.slot_stride = c->nq_cap * 4;

@@ -68,7 +68,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.ad_sel = ad ? rows * MAX_K_LIMIT * 4 : 0;
   s.ad_head = ad ? rows * 4 : 0;
   s.ad_mask_words = (s.nb_cap + 31) / 32;
-  s.ad_mask = ad ? groups * s.ad_mask_words * 4 : 0;
+  s.ad_mask = ad ? rows * s.ad_mask_words * 4 : 0;
   s.ad_slot = ad ? groups * s.nq_cap * 4 * 4 : 0;
   s.ad_group = ad ? groups * 4 : 0;
   s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
@@ -871,7 +871,8 @@ static int32_t check_selector(const cqa_cache* h, const cqa_selector* sel) {
   if (sel == nullptr || !(sel->tau_cov == sel->tau_cov) || sel->k_min < 0 || sel->k_max < sel->k_min ||
       sel->k_limit < sel->k_max || sel->k_limit > MAX_K_LIMIT || sel->v_limit < 0 ||
       sel->v_limit > MAX_K_LIMIT || (sel->v_greedy != 0 && sel->v_greedy != 1) ||
-      (sel->canary != 0 && sel->canary != 1) || !(sel->explore_frac >= 0.0f && sel->explore_frac <= 1.0f))
+      (sel->canary != 0 && sel->canary != 1) || !(sel->explore_frac >= 0.0f && sel->explore_frac <= 1.0f) ||
+      (sel->per_head != 0 && sel->per_head != 1))
     return CQA_ERR_INVALID_ARG;
   if (h->impl.desc.tier2_mode != CQA_TIER2_PINNED) return CQA_ERR_NO_TIER2;
   return CQA_OK;
@@ -1004,7 +1005,7 @@ int32_t cqa_adaptive_step_enqueue(cqa_cache* h, int32_t layer, const void* q_fp1
 }
 
 int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
-                           int32_t* selected_host, uint8_t* promoted_host,
+                           int32_t* selected_host, uint16_t* promoted_host,
                            float* logmass_int8_host, float* logmass_mixed_host,
                            int32_t* v_count_host, int32_t* v_selected_host, float* contrib_host,
                            float* score_dev_host) {
@@ -1052,7 +1053,11 @@ int32_t cqa_adaptive_state(cqa_cache* h, int32_t layer, int32_t* k_star_host,
     for (int64_t gidx = 0; gidx < groups; ++gidx) {
       CQA_HIP(hipMemcpy(slot.data(), c->ad.slot + gidx * c->nq_cap * 4, (size_t)nb * 4,
                         hipMemcpyDeviceToHost));
-      for (int64_t i = 0; i < nb; ++i) promoted_host[gidx * nb + i] = (uint8_t)(slot[(size_t)i] & 3);
+      for (int64_t i = 0; i < nb; ++i) {
+        const uint32_t f = (uint32_t)slot[(size_t)i];
+        promoted_host[gidx * nb + i] =
+            (uint16_t)((f & 3u) | (((f >> SLOT_HK_SHIFT) & 15u) << 4) | (((f >> SLOT_HV_SHIFT) & 15u) << 8));
+      }
     }
   }
   return CQA_OK;

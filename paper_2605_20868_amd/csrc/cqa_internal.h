@@ -100,9 +100,9 @@ struct AdaptiveWs {
   int32_t* sel;      // [Bt][Hq][MAX_K_LIMIT] the head's own selection, best first
   int32_t* kstar;    // [Bt][Hq]              its size after Rung-1 growth
   float* alpha;      // [Bt][Hq]              estimated mass of the blocks its group left in INT8
-  uint32_t* umask;   // [Bt][Hkv][mask_words] union of the group's key selections, one bit per block
-  uint32_t* vmask;   // [Bt][Hkv][mask_words] union of its value selections
-  int32_t* slot;     // [Bt][Hkv][4 nq_cap]   per block: bit 0 = FP16 keys, bit 1 = FP16 values (0 = neither)
+  uint32_t* umask;   // [Bt][Hq][mask_words]  the head's key selection, one bit per block
+  uint32_t* vmask;   // [Bt][Hq][mask_words]  its value selection
+  int32_t* slot;     // [Bt][Hkv][4 nq_cap]   per block: bit 0 = FP16 keys, bit 1 = FP16 values (0 = neither), per-head bits above
   float* eta_blk;    // [Bt][Hkv][nb_cap]     eta_b as read by the pass over all blocks
   float* contrib;    // [Bt][Hq][nb_cap]      estimated contributions p_b eta_b
   int32_t* vsel;     // [Bt][Hq][MAX_K_LIMIT] the head's value selection
@@ -129,6 +129,9 @@ constexpr int SC_MAX_SLOTS = 1024;
 // per-block word of AdaptiveWs::slot: bit 0 FP16 keys, bit 1 FP16 values, bit 2 the keys are to
 // be stored into the scratch slot by the pass that reads them, bits 8.. scratch slot + 1 (0 = none)
 constexpr int SLOT_KEYS = 1, SLOT_VALUES = 2, SLOT_FILL = 4, SLOT_SC_SHIFT = 8;
+// bits 24-27: query head i of the group (i = 0..3) scores this block with FP16 keys; bits 28-31: it
+// attends the block's FP16 values.  With per-group promotion every head's bit follows bits 0 / 1.
+constexpr int SLOT_HK_SHIFT = 24, SLOT_HV_SHIFT = 28;
 
 struct Cache {
   cqa_cache_desc desc;

@@ -114,13 +114,18 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       sraw4[gq] = *reinterpret_cast<const uint4*>(vmb + vo * 64 + g * 8);
       oraw4[gq] = *reinterpret_cast<const uint4*>(vmb + BLK * NG + vo * 64 + g * 8);
     }
-    const bool kfp = PROM && !neg && (pf & 1), vfp = PROM && !neg && (pf & 2);
+    // which heads of the group score this block with FP16 keys / attend its FP16 values (the
+    // per-head bits of the flag word; with per-group promotion they are all alike)
+    const int hkb = (PROM && !neg) ? (pf >> SLOT_HK_SHIFT) & ((1 << G) - 1) : 0;
+    const int hvb = (PROM && !neg) ? (pf >> SLOT_HV_SHIFT) & ((1 << G) - 1) : 0;
+    const bool kfp = hkb != 0, vfp = hvb != 0;
+    const bool kall = hkb == (1 << G) - 1;
     // FP16 keys of the block, [token][128 channels]: from its slot of the device-resident
     // scratch if it is held there, else from the host-resident originals -- and then, if the
     // block has just been given a slot, stored into it on the way
     uint4 k16[2][2];
     if (kfp) {
-      const int sc0 = pf >> SLOT_SC_SHIFT;
+      const int sc0 = (pf >> SLOT_SC_SHIFT) & 0xFFFF;   // bits 8-23: scratch slot + 1
       const int sc = (a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
       const bool fill = sc > 0 && (pf & SLOT_FILL);
       __half* sck = sc > 0 ? a.sc_k + (((grp * a.sc_cap + (sc - 1)) * BLK) + tok) * D : nullptr;
@@ -142,7 +147,6 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       }
     }
     if (vfp) {
-      an.x = 0.0f;     // exact values: the block adds nothing to the value term
       // its FP16 values, row-major [token][128], coalesced into this wave's LDS buffer
       const __half* v16 = a.t2_v + (grp * a.max_tokens + (int64_t)blk * BLK + (l >> 2)) * D + (l & 3) * 32;
       uint4 v16r[4];
@@ -152,33 +156,26 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       for (int j = 0; j < 4; ++j)
         *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) = v16r[j];
     }
-    // ---- scaled query, per-block constant, per-block score-error bound
-    const float2 sg = kfp ? make_float2(1.0f, 1.0f) : sg8;
-    const float2 zz = kfp ? make_float2(0.0f, 0.0f) : zz8;
-    float csum[G], dsum[G];
+    // ---- scores.  Lane (tok, kg) covers channels cq*64 + kg*16 + 0..15, cq = 0, 1.  First from
+    //      the FP16 keys (sigma = 1, z = 0: the query itself in the LDS buffer) when some head asks
+    //      for them, then from the INT8 codes (scaled query q~ = q sigma, block constant
+    //      c_b = q.z, bound Delta_b) when some head keeps them -- or when the score-consistency
+    //      check compares the two.
+    float s16[G], s8[G], dsum[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const float q0 = qv[h][0] * sg.x, q1 = qv[h][1] * sg.y;
-      reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
-      // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
-      csum[h] = kfp ? 0.0f : qv[h][0] * zz.x + qv[h][1] * zz.y - 128.0f * (q0 + q1);
-      dsum[h] = kfp ? 0.0f : fabsf(qv[h][0]) * sg.x + fabsf(qv[h][1]) * sg.y;
+      s16[h] = 0.0f;
+      s8[h] = 0.0f;
+      dsum[h] = 0.0f;
     }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        csum[h] += __shfl_xor(csum[h], m);
-        dsum[h] += __shfl_xor(dsum[h], m);
-      }
-    }
-    wave_sync();
-
-    // ---- scores: lane (tok, kg) covers channels cq*64 + kg*16 + 0..15, cq = 0, 1
-    float dot[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) dot[h] = 0.0f;
     if (kfp) {
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(qv[h][0], qv[h][1]);
+      wave_sync();
+      float dot[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) dot[h] = 0.0f;
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
         const int c0 = cq * 64 + kg * 16;
@@ -192,7 +189,37 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
           for (int h = 0; h < G; ++h) dot[h] = fmaf(qs[w][h][c0 + j], kf, dot[h]);
         }
       }
-    } else {
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        dot[h] += __shfl_xor(dot[h], 16);
+        dot[h] += __shfl_xor(dot[h], 32);
+        s16[h] = dot[h] * inv_sqrt_d;
+      }
+      wave_sync();   // the LDS buffer is rewritten below
+    }
+    const bool canary = PROM && kfp && a.score_dev != nullptr;
+    if (!kfp || !kall || canary) {
+      float csum[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float q0 = qv[h][0] * sg8.x, q1 = qv[h][1] * sg8.y;
+        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
+        // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
+        csum[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y - 128.0f * (q0 + q1);
+        dsum[h] = fabsf(qv[h][0]) * sg8.x + fabsf(qv[h][1]) * sg8.y;
+      }
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          csum[h] += __shfl_xor(csum[h], m);
+          dsum[h] += __shfl_xor(dsum[h], m);
+        }
+      }
+      wave_sync();
+      float dot[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) dot[h] = 0.0f;
 #pragma unroll
       for (int cq = 0; cq < 2; ++cq) {
         const uint32_t wd[4] = {kc8[cq].x, kc8[cq].y, kc8[cq].z, kc8[cq].w};
@@ -204,51 +231,25 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
           for (int h = 0; h < G; ++h) dot[h] = fmaf(qs[w][h][c0 + j], kf, dot[h]);
         }
       }
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        dot[h] += __shfl_xor(dot[h], 16);
+        dot[h] += __shfl_xor(dot[h], 32);
+        s8[h] = (dot[h] + csum[h]) * inv_sqrt_d;
+      }
     }
-    if (PROM && kfp && a.score_dev != nullptr) {
-      // score-consistency check: the same tokens scored from the INT8 codes (scaled query in the
-      // LDS buffer replaced for a moment), compared token by token with the FP16 scores
-      float c8[G], d8[G];
-      wave_sync();
+    if (canary) {
+      // score-consistency check: FP16 against INT8 scores, token by token, for the heads that
+      // score this block from its FP16 keys
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float q0 = qv[h][0] * sg8.x, q1 = qv[h][1] * sg8.y;
-        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
-        c8[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y - 128.0f * (q0 + q1);
-        d8[h] = 0.0f;
-      }
-#pragma unroll
-      for (int m = 1; m < 64; m <<= 1) {
-#pragma unroll
-        for (int h = 0; h < G; ++h) c8[h] += __shfl_xor(c8[h], m);
-      }
-      wave_sync();
-#pragma unroll
-      for (int cq = 0; cq < 2; ++cq) {
-        const uint32_t wd[4] = {kc8[cq].x, kc8[cq].y, kc8[cq].z, kc8[cq].w};
-        const int c0 = cq * 64 + kg * 16;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float kf = (float)((wd[j >> 2] >> (8 * (j & 3))) & 0xffu);
-#pragma unroll
-          for (int h = 0; h < G; ++h) d8[h] = fmaf(qs[w][h][c0 + j], kf, d8[h]);
-        }
-      }
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        d8[h] += __shfl_xor(d8[h], 16);
-        d8[h] += __shfl_xor(d8[h], 32);
-        const float full = dot[h] + __shfl_xor(dot[h], 16);
-        const float s16 = (full + __shfl_xor(full, 32) + csum[h]) * inv_sqrt_d;
-        dev[h] = fmaxf(dev[h], fabsf(s16 - (d8[h] + c8[h]) * inv_sqrt_d));
-      }
+      for (int h = 0; h < G; ++h)
+        if ((hkb >> h) & 1) dev[h] = fmaxf(dev[h], fabsf(s16[h] - s8[h]));
     }
     float p[G], alpha[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      dot[h] += __shfl_xor(dot[h], 16);
-      dot[h] += __shfl_xor(dot[h], 32);
-      const float s = (dot[h] + csum[h]) * inv_sqrt_d;
+      const bool use16 = ((hkb >> h) & 1) != 0;
+      const float s = use16 ? s16[h] : s8[h];
       float mb = s;
 #pragma unroll
       for (int m = 1; m < 16; m <<= 1) mb = fmaxf(mb, __shfl_xor(mb, m));
@@ -262,11 +263,11 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       const float f = __expf(mb - m_new);
       p[h] = pt * f;
       const float sf = sb * f;
-      const float ce = sf * an.x;
+      const float ce = ((hvb >> h) & 1) ? 0.0f : sf * an.x;   // exact values add nothing to the value term
       l_run[h] = l_run[h] * alpha[h] + sf;
       ev[h] = ev[h] * alpha[h] + ce;
       evmax[h] = fmaxf(evmax[h] * alpha[h], ce);
-      dmax[h] = fmaxf(dmax[h], dsum[h] * (0.5f * inv_sqrt_d));
+      dmax[h] = fmaxf(dmax[h], use16 ? 0.0f : dsum[h] * (0.5f * inv_sqrt_d));
       m_run[h] = m_new;
       if (lb > t1[h]) {
         t2[h] = t1[h];
@@ -300,10 +301,10 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       for (int i = 0; i < 8; ++i) {
         const float sc = (i & 1) ? __high2float(sh[i >> 1]) : __low2float(sh[i >> 1]);
         const float of = (i & 1) ? __high2float(oh[i >> 1]) : __low2float(oh[i >> 1]);
-        const float vh = vfp ? __half2float(vst[w][vo * 8 + i][g * 16 + vn])
-                             : fmaf((float)((vw[gq] >> (4 * i)) & 15u), sc, of);
+        const float v4 = fmaf((float)((vw[gq] >> (4 * i)) & 15u), sc, of);
+        const float v16 = vfp ? __half2float(vst[w][vo * 8 + i][g * 16 + vn]) : v4;
 #pragma unroll
-        for (int h = 0; h < G; ++h) acc[gq][h] = fmaf(pi[i][h], vh, acc[gq][h]);
+        for (int h = 0; h < G; ++h) acc[gq][h] = fmaf(pi[i][h], ((hvb >> h) & 1) ? v16 : v4, acc[gq][h]);
       }
     }
     wave_sync();

@@ -43,7 +43,7 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     qd = gc.to_dev(q)
     gtol = to_gpu_tol(cqa, tol)
     gsel = cqa.Selector(sel.tau_cov, sel.k_min, sel.k_max, sel.k_limit, sel.v_limit, sel.v_greedy,
-                        sel.canary, sel.explore_frac, sel.explore_seed)
+                        sel.canary, sel.explore_frac, sel.explore_seed, sel.per_head)
     # the scoring pass on its own first: its certificate (lse, Delta_h, V_max) is what the selector
     # reads inside the adaptive call, bit for bit (same kernel, same inputs)
     gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
@@ -58,7 +58,8 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
     O, cert, flags = gc.results()
     state = cqa.cqa_adaptive_state(gc.h, 0, gc.bt, gc.hq, gc.hkv)
     return dict(O=O, cert=cert, flags=flags, cert0=cert0, rung=rung, k_star=state[0], selected=state[1],
-                promoted=(state[2] & 1).astype(bool), v_promoted=(state[2] & 2).astype(bool), l8=state[3],
+                promoted=(state[2] & 1).astype(bool), v_promoted=(state[2] & 2).astype(bool),
+                head_keys=(state[2] >> 4) & 15, head_values=(state[2] >> 8) & 15, l8=state[3],
                 lx=state[4], v_count=state[5], v_selected=state[6], contrib=state[7], score_dev=state[8])
 
 
@@ -91,10 +92,12 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
                 k = int(out["k_star"][b, h])
             assert out["selected"][b, h, :k].tolist() == s["order"][:k].tolist(), ("selection", b, h)
             picks.append(s["order"][:k])
-        union = ad.group_union(picks, nb) | ad.explored_blocks(nb, b * oc.hkv + kh, sel)
+        explored = ad.explored_blocks(nb, b * oc.hkv + kh, sel)
+        union = ad.group_union(picks, nb) | explored
         assert (out["promoted"][b, kh] == union).all(), ("promoted mask", b, kh)
         # ---- value promotion: decisions on the GPU's own contributions, thresholds as the GPU holds them
         vunion = np.zeros(nb, bool)
+        vpicks = [np.zeros(0, np.int64)] * g
         if sel.v_limit > 0:
             tol32 = att.Tolerances(v_tol=float(np.float32(tol.v_tol)), eps_val=float(np.float32(tol.eps_val)))
             vpicks = []
@@ -111,14 +114,19 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
         assert (out["v_promoted"][b, kh] == vunion).all(), ("value-promoted mask", b, kh)
         for i in range(g):
             h = kh * g + i
+            # the head's own promoted sets: its selections (+ explored blocks), or the group's unions
+            fk = (ad.group_union([picks[i]], nb) | explored) if sel.per_head else union
+            fv = ad.group_union([vpicks[i]], nb) if sel.per_head else vunion
+            assert ((((out["head_keys"][b, kh] >> i) & 1) != 0) == fk).all(), ("head key bits", b, h)
+            assert ((((out["head_values"][b, kh] >> i) & 1) != 0) == fv).all(), ("head value bits", b, h)
             if (b, h) not in heads:
                 continue
             sc = att.certified_head(q[b, h], k_hat, v_hat, oc.sigma[b, kh], oc.eta[b, kh], oc.nu[b, kh],
                                     k_tr, v_tr, att.Tolerances())
             assert np.abs(out["l8"][b, h] - sc["blk_logmass"]).max() <= 1e-4, ("scoring log-masses", b, h)
             ref = ad.mixed_head(q[b, h], k_hat, oc.k16[b, kh, :nb * 16], v_hat, oc.eta[b, kh], oc.nu[b, kh],
-                                k_tr, v_tr, union, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol,
-                                v_promoted=vunion, v16_sealed=oc.v16[b, kh, :nb * 16], canary=sel.canary)
+                                k_tr, v_tr, fk, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol,
+                                v_promoted=fv, v16_sealed=oc.v16[b, kh, :nb * 16], canary=sel.canary)
             if sel.canary:
                 assert abs(float(out["score_dev"][b, h]) - ref["score_dev"]) <= 1e-4, ("score deviation", b, h)
             w = ("adaptive", b, h)
@@ -139,9 +147,9 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
                 assert abs(x - y) <= 1e-4 * abs(y) + 1e-9, (w, name, x, y)
             assert abs(float(ct["lse"]) - ref["lse"]) <= 1e-4 * max(1.0, abs(ref["lse"])), (w, "lse")
             assert np.abs(out["lx"][b, h] - ref["blk_logmass"]).max() <= 1e-4, (w, "attend log-masses")
-            if union.any():
+            if fk.any():
                 rk = ref["ranking"]
-                top2 = np.sort(ref["blk_logmass"][union])[::-1]
+                top2 = np.sort(ref["blk_logmass"][fk])[::-1]
                 if len(top2) < 2 or top2[0] - top2[1] > 1e-3:
                     assert int(ct["top_block"]) == rk["top_fp16"], (w, "top block")
             assert int(out["flags"][b, h]) == ref["flags"], (w, "flags", int(out["flags"][b, h]), ref["flags"])
@@ -669,3 +677,34 @@ def test_adaptive_end_to_end_from_raw_inputs_where_margins_are_clear():
             assert int(out["flags"][b, h]) == r["flags"], (w, "flags", int(out["flags"][b, h]), r["flags"])
             # the key term shrank with the tail
             assert float(ct["E_key"]) < 0.2 * float(out["cert0"]["E_key"][b, h]), w
+
+
+def test_per_head_promoted_sets_against_the_union_variant():
+    """The paper's default (every head promotes its own selection) next to the per-KV-group union:
+    both against the oracle, keys and values, with exploration and the canary on; the head bits
+    differ between the modes, the group-level masks do not."""
+    say("adaptive: per-head promoted sets (the paper's default) and the per-group union")
+    k, v, q = make_case(31, 2, 8, 2, 3000 + 7, peaked=[(0, 1, 333, 0.9), (0, 2, 1900, 1.1), (1, 4, 77, 0.8),
+                                                       (1, 6, 1500, 1.2), (1, 7, 1501, 0.6)])
+    oc = oracle.OracleLayerCache(2, 2)
+    oc.append(k, v)
+    with GpuLayerCache(2, 8, 2, 3100) as gc:
+        gc.append(k, v)
+        outs = {}
+        for per_head in (True, False):
+            for tau, kmin, kmax, vlim in ((0.9, 1, 8, 0), (0.995, 2, 16, 8)):
+                sel = ad.SelectorParams(tau, kmin, kmax, kmax, v_limit=vlim, canary=True, explore_frac=0.02,
+                                        explore_seed=5, per_head=per_head)
+                tol = att.Tolerances(rank_depth=2, v_tol=0.01 if vlim else math.inf)
+                out = gpu_adaptive(gc, q, tol, sel)
+                check_against_oracle(oc, q, tol, sel, out)
+                outs[(per_head, kmax)] = out
+        for kmax in (8, 16):
+            ph, un = outs[(True, kmax)], outs[(False, kmax)]
+            assert (ph["promoted"] == un["promoted"]).all() and (ph["k_star"] == un["k_star"]).all()
+            assert (ph["head_keys"] != un["head_keys"]).any()
+            # a head's own set only loses blocks against the union: its achieved tail is no smaller
+            assert (ph["cert"]["alpha_tail_hat"] >= un["cert"]["alpha_tail_hat"] * (1 - 1e-6)).all()
+            say(f"  K_max {kmax}: (head, block) pairs with FP16 keys per-head "
+                f"{int(sum(bin(int(x)).count('1') for x in ph['head_keys'].ravel()))} / union "
+                f"{int(sum(bin(int(x)).count('1') for x in un['head_keys'].ravel()))}")

@@ -43,7 +43,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(cqa.HeadCert) == 40
     assert ctypes.sizeof(cqa.Tolerances) == 48
     assert ctypes.sizeof(cqa.CacheDesc) == 40
-    assert ctypes.sizeof(cqa.Selector) == 36
+    assert ctypes.sizeof(cqa.Selector) == 40
     assert cqa.CERT_BYTES == 40
 
 

@@ -395,3 +395,56 @@ def test_ranking_check_at_depth_r():
         assert got["boundary"] == (bool(tail) and max(tail) + delta + guard > lxr[by_x[-1]])
         one = ad.ranking_check(l8r, lxr, pr, delta, guard)
         assert one["rank_fp16"] == by_x[:1] and one["top_fp16"] == by_x[0]
+
+
+# ---------------------------------------------------------------- per-head promoted sets
+
+@pytest.mark.parametrize("seed,scale,outlier", [(0, 1.0, False), (1, 2.0, True), (2, 0.5, False)])
+def test_per_head_promoted_sets(seed, scale, outlier):
+    """The paper's default: every head promotes its own selection.  The head's F is exactly its
+    K* best blocks (plus explored ones), lies inside the group's union, its tail is the union
+    variant's tail plus the masses of the union's blocks it did not pick, and every bound that
+    holds for the union holds for it (tail theorem, key term, total)."""
+    oc, q = small_cache(60 + seed, n_tokens=400, scale=scale, outlier=outlier)
+    nb = oc.n_blocks
+    v_hat = qz.dequantize_values(oc.v_codes[0, 0], oc.v_scale[0, 0], oc.v_offset[0, 0]).reshape(nb * 16, 128)
+    v_mixed_all = np.concatenate([v_hat, oc.v16[0, 0, nb * 16:].astype(np.float64)])
+    tol = att.Tolerances(key_bound_mode=1, rank_depth=1, v_tol=0.02)
+    for tau, kmax in ((0.6, 3), (0.9, 6)):
+        ph = ad.SelectorParams(tau_cov=tau, k_min=1, k_max=kmax, k_limit=kmax, v_limit=4, per_head=True,
+                               explore_frac=0.1, explore_seed=3)
+        un = ad.SelectorParams(tau_cov=tau, k_min=1, k_max=kmax, k_limit=kmax, v_limit=4, explore_frac=0.1,
+                               explore_seed=3)
+        rp = ad.adaptive_decode(oc, q, tol, ph)
+        ru = ad.adaptive_decode(oc, q, tol, un)
+        explored = ad.explored_blocks(nb, 0, ph)
+        differs = False
+        for h in range(4):
+            p, u = rp[(0, h)], ru[(0, h)]
+            own = np.zeros(nb, bool)
+            own[p["selected"]] = True
+            assert (p["promoted"] == (own | explored)).all()
+            assert (u["promoted"] >= p["promoted"]).all() and (p["group_promoted"] == u["promoted"]).all()
+            vown = np.zeros(nb, bool)
+            vown[p["v_selected"]] = True
+            assert (p["v_promoted"] == vown).all() and (u["v_promoted"] >= vown).all()
+            differs = differs or (u["promoted"] != p["promoted"]).any()
+            # tail: the union's tail plus the estimated masses of the union's blocks this head left in INT8
+            extra = np.exp(p["scoring"]["blk_logmass"][u["promoted"] & ~p["promoted"]] - p["scoring"]["lse"]).sum()
+            assert abs(p["alpha_tail_hat"] - (u["alpha_tail_hat"] + extra)) < 1e-12
+            # the theorems, with the head's own F
+            qf = q[0, h].astype(np.float64)
+            s_true = oc.k16[0, 0].astype(np.float64) @ qf / math.sqrt(128.0)
+            a_true = np.exp(s_true - s_true.max())
+            a_true /= a_true.sum()
+            tail_tok = np.concatenate([np.repeat(~p["promoted"], 16), np.zeros(oc.length - nb * 16, bool)])
+            assert a_true[tail_tok].sum() <= min(1.0, math.exp(2 * p["delta_h"]) * p["alpha_tail_hat"]) * (1 + 1e-9)
+            v_mix = v_mixed_all.copy()
+            vp_tok = np.repeat(p["v_promoted"], 16)
+            v_mix[:nb * 16][vp_tok] = oc.v16[0, 0, :nb * 16].astype(np.float64)[vp_tok]
+            assert np.linalg.norm(p["O"] - a_true @ v_mix) <= p["E_key"] * (1 + 1e-9) + 1e-12
+            o_ref = att.softmax_attention(q[0, h], oc.k16[0, 0], oc.v16[0, 0])
+            assert np.linalg.norm(p["O"] - o_ref) <= (p["E_key"] + p["E_val"]) * (1 + 1e-9) + 1e-12
+            # ranking check runs over the head's own F
+            assert p["ranking"]["top_fp16"] == -1 or p["promoted"][p["ranking"]["top_fp16"]]
+        assert differs      # the two modes are not the same thing on this data
