@@ -31,14 +31,28 @@ struct SealArgs {
   int layer, batch, n_kv;
 };
 
-// All-reduce over the 16 lanes of a row by DPP moves (quad xor 1, quad xor 2, half-row mirror,
-// row mirror): no LDS round trip.  Minima and maxima do not depend on the order; the FP64 sums
-// below are annotations compared at 1e-6.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float x) {
-  return __uint_as_float(
-      (uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true));
+// Quotient x / d for the quantizers, where only  round-half-even(fl(x / d))  is needed (fl = the
+// correctly rounded binary32 quotient the definition asks for) and |x / d| < 2^8.  One IEEE division
+// costs ten instructions and a block needs 4096 of them, so the quotient is first approximated as
+// x * r with r = 1/d refined by one Newton step: the hardware reciprocal is within one unit in the
+// last place, so after the step r is the rounded value of a number within 2^-44 of 1/d (relative
+// error <= 2^-24), x * r carries one more rounding (2^-24), and |x r - x/d| <= 2^8 * 2^-23 = 2^-15;
+// the exact quotient's own rounding moves it by at most 2^-17.  Unless the approximation lies
+// within 2^-13 of a half-integer, both therefore round to the same integer; the rare lanes that
+// are closer -- and anything not finite -- take the exact division.  Bit-identical to
+// rintf(x / d) by construction.
+__device__ __forceinline__ float refined_rcp(float d) {
+  const float r0 = __builtin_amdgcn_rcpf(d);
+  return fmaf(fmaf(-d, r0, 1.0f), r0, r0);
 }
+__device__ __forceinline__ float rint_quotient(float x, float d, float r) {
+  const float qa = x * r;
+  float q = rintf(qa);
+  if (!(fabsf(qa - q) <= 0.5f - 0.0001220703125f)) q = rintf(x / d);
+  return q;
+}
+
+// DPP moves for the few cross-lane sums of FP64 annotations (lanes of one token are adjacent)
 template <int CTRL>
 __device__ __forceinline__ double dpp_d(double x) {
   const unsigned long long u = (unsigned long long)__double_as_longlong(x);
@@ -46,30 +60,26 @@ __device__ __forceinline__ double dpp_d(double x) {
   const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, true);
   return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
-__device__ __forceinline__ float row_min_f(float x) {
-  x = fminf(x, dpp_f<0xB1>(x));
-  x = fminf(x, dpp_f<0x4E>(x));
-  x = fminf(x, dpp_f<0x141>(x));
-  x = fminf(x, dpp_f<0x140>(x));
-  return x;
-}
-__device__ __forceinline__ float row_max_f(float x) {
-  x = fmaxf(x, dpp_f<0xB1>(x));
-  x = fmaxf(x, dpp_f<0x4E>(x));
-  x = fmaxf(x, dpp_f<0x141>(x));
-  x = fmaxf(x, dpp_f<0x140>(x));
-  return x;
-}
-__device__ __forceinline__ double row_sum_d(double x) {
+// sum over the 8 lanes of an aligned octet: quad xor 1, quad xor 2, half-row mirror
+__device__ __forceinline__ double octet_sum_d(double x) {
   x += dpp_d<0xB1>(x);
   x += dpp_d<0x4E>(x);
   x += dpp_d<0x141>(x);
-  x += dpp_d<0x140>(x);
   return x;
 }
 
+// One workgroup of 128 threads seals one block of 16 tokens.  Two thread roles, so that every
+// reduction the quantizers need runs inside one thread's registers:
+//   keys   : thread = channel c; its 16 values (one per token) give l_c, u_c, sigma_c, z_c and
+//            the 16 codes of the channel;
+//   values : thread = (token t, group g) = (tid >> 3, tid & 7); its 16 values (32 contiguous
+//            bytes) give lo, hi, the FP16 scale and offset, the 16 codes of the group and the
+//            group's share of the token's squared reconstruction error and squared norm (FP64).
+// Codes pass through LDS to reach the physical layout of the Tier-1 record.
+// (Measured and not adopted: fetching the keys as whole rows with 128-bit loads too and handing
+// the columns to the channel threads through LDS -- 0.28 ms against 0.25 ms for the 128K prefill.)
 __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
-  const int c = threadIdx.x;            // channel
+  const int tid = threadIdx.x;
   const int j = blockIdx.x;             // new block index
   const int kvh = blockIdx.y, b = blockIdx.z;
   const int64_t head = ((int64_t)a.layer * a.batch + b) * a.n_kv + kvh;
@@ -77,46 +87,99 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   const int64_t in_head = ((int64_t)b * a.n_kv + kvh) * a.n_new;
 
   __shared__ __align__(16) uint8_t kbuf[KC_BYTES];
-  __shared__ uint8_t vnib[BLK][D];
+  __shared__ __align__(16) uint8_t vnib[BLK][D];
   __shared__ __align__(16) __half vmeta[2 * BLK * NG];
-  __shared__ double red[8][BLK][2];   // [row of 16 channels][token][err^2 | norm^2]
+  __shared__ double red[BLK][2];        // [token][err^2 | norm^2]
 
-  float kf[BLK], vf[BLK];
-#pragma unroll
-  for (int t = 0; t < BLK; ++t) {
-    const int64_t i = (int64_t)j * BLK + t;
-    if (i < a.r) {
-      kf[t] = __half2float(a.trail_k[(head * BLK + i) * D + c]);
-      vf[t] = __half2float(a.trail_v[(head * BLK + i) * D + c]);
-    } else {
-      kf[t] = __half2float(a.k_in[(in_head + (i - a.r)) * D + c]);
-      vf[t] = __half2float(a.v_in[(in_head + (i - a.r)) * D + c]);
-    }
-  }
-
-  // ---- keys: per-channel affine INT8 over the block's 16 tokens
-  float lo = kf[0], hi = kf[0];
-#pragma unroll
-  for (int t = 1; t < BLK; ++t) {
-    lo = fminf(lo, kf[t]);
-    hi = fmaxf(hi, kf[t]);
-  }
-  const float sigma = (hi - lo) / 255.0f;
-  const float z = lo + 128.0f * sigma;
-#pragma unroll
-  for (int t = 0; t < BLK; ++t) {
-    int code = 0;
-    if (sigma != 0.0f) {
-      float q = rintf((kf[t] - z) / sigma);
-      q = fminf(fmaxf(q, -128.0f), 127.0f);
-      code = (int)q;
-    }
-    kbuf[kc_offset(t, c)] = (uint8_t)(code + 128);
-  }
-  float* km = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_KM, KM_BYTES));
-  km[c] = sigma;
-  km[D + c] = z;
+  // token i of this block: one of the r tokens waiting in the trailing block, or a new one
+  const int64_t i0 = (int64_t)j * BLK;
+  // ---- values first (their loads are the wide ones): thread (t, g)
   {
+    const int t = tid >> 3, g = tid & 7;
+    const int64_t i = i0 + t;
+    const __half* src = i < a.r ? a.trail_v + (head * BLK + i) * D : a.v_in + (in_head + (i - a.r)) * D;
+    const uint4 x0 = *reinterpret_cast<const uint4*>(src + g * VG);
+    const uint4 x1 = *reinterpret_cast<const uint4*>(src + g * VG + 8);
+    const __half2* h0 = reinterpret_cast<const __half2*>(&x0);
+    const __half2* h1 = reinterpret_cast<const __half2*>(&x1);
+    float vf[VG];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vf[2 * e] = __low2float(h0[e]);
+      vf[2 * e + 1] = __high2float(h0[e]);
+      vf[8 + 2 * e] = __low2float(h1[e]);
+      vf[8 + 2 * e + 1] = __high2float(h1[e]);
+    }
+    float vlo = vf[0], vhi = vf[0];
+#pragma unroll
+    for (int e = 1; e < VG; ++e) {
+      vlo = fminf(vlo, vf[e]);
+      vhi = fmaxf(vhi, vf[e]);
+    }
+    const __half sh = __float2half_rn((vhi - vlo) / 15.0f);
+    const float sc = __half2float(sh);
+    const float rs = refined_rcp(sc);
+    uint32_t packed[4] = {0u, 0u, 0u, 0u};   // the group's 16 codes, one per byte, channel order
+    double e2 = 0.0, n2 = 0.0;
+    const double dlo = (double)vlo;
+#pragma unroll
+    for (int e = 0; e < VG; ++e) {
+      float q = 0.0f;
+      if (sc != 0.0f) {
+        q = rint_quotient(vf[e] - vlo, sc, rs);
+        q = fminf(fmaxf(q, 0.0f), 15.0f);
+      }
+      packed[e >> 2] |= (uint32_t)(int)q << (8 * (e & 3));
+      // v_hat - v = code * scale + (lo - v): the product is exact in binary32 (4 x 11 bits), the
+      // difference and the sum are taken in double
+      const double dv = (double)vf[e];
+      const double err = (double)(q * sc) + (dlo - dv);
+      e2 += err * err;
+      n2 += dv * dv;
+    }
+    *reinterpret_cast<uint4*>(&vnib[t][g * VG]) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+    vmeta[vm_index(t, g)] = sh;
+    vmeta[BLK * NG + vm_index(t, g)] = __float2half_rn(vlo);  // exact: vlo is an FP16 input
+    e2 = octet_sum_d(e2);
+    n2 = octet_sum_d(n2);
+    if (g == 0) {
+      red[t][0] = e2;
+      red[t][1] = n2;
+    }
+  }
+
+  // ---- keys: thread = channel c, per-channel affine INT8 over the block's 16 tokens
+  {
+    const int c = tid;
+    float kf[BLK];
+#pragma unroll
+    for (int t = 0; t < BLK; ++t) {
+      const int64_t i = i0 + t;
+      kf[t] = __half2float(i < a.r ? a.trail_k[(head * BLK + i) * D + c]
+                                   : a.k_in[(in_head + (i - a.r)) * D + c]);
+    }
+    float lo = kf[0], hi = kf[0];
+#pragma unroll
+    for (int t = 1; t < BLK; ++t) {
+      lo = fminf(lo, kf[t]);
+      hi = fmaxf(hi, kf[t]);
+    }
+    const float sigma = (hi - lo) / 255.0f;
+    const float z = lo + 128.0f * sigma;
+    const float rsig = refined_rcp(sigma);
+#pragma unroll
+    for (int t = 0; t < BLK; ++t) {
+      int code = 0;
+      if (sigma != 0.0f) {
+        float q = rint_quotient(kf[t] - z, sigma, rsig);
+        q = fminf(fmaxf(q, -128.0f), 127.0f);
+        code = (int)q;
+      }
+      kbuf[kc_offset(t, c)] = (uint8_t)(code + 128);
+    }
+    float* km = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_KM, KM_BYTES));
+    km[c] = sigma;
+    km[D + c] = z;
     // running maximum of sigma over the head's blocks (used by the decode pass to pick an
     // overflow-free power-of-two scaling); sigma >= 0, so its bit pattern orders like an int
     float smax = sigma;
@@ -129,38 +192,10 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
       atomicMax(reinterpret_cast<int*>(a.sigmax + head), __float_as_int(smax));
   }
-
-  // ---- values: per-token, per-group asymmetric INT4
-  const int g = c >> 4;
-#pragma unroll
-  for (int t = 0; t < BLK; ++t) {
-    // a value group is one row of 16 lanes
-    const float vlo = row_min_f(vf[t]), vhi = row_max_f(vf[t]);
-    const __half sh = __float2half_rn((vhi - vlo) / 15.0f);
-    const float s = __half2float(sh);
-    int code = 0;
-    if (s != 0.0f) {
-      float q = rintf((vf[t] - vlo) / s);
-      q = fminf(fmaxf(q, 0.0f), 15.0f);
-      code = (int)q;
-    }
-    vnib[t][c] = (uint8_t)code;
-    if ((c & 15) == 0) {
-      vmeta[vm_index(t, g)] = sh;
-      vmeta[BLK * NG + vm_index(t, g)] = __float2half_rn(vlo);  // exact: vlo is an FP16 input
-    }
-    // annotations in double: squared reconstruction error and squared norm of this token
-    const double vh = (double)code * (double)s + (double)vlo;
-    const double e2 = row_sum_d((vh - (double)vf[t]) * (vh - (double)vf[t]));
-    const double n2 = row_sum_d((double)vf[t] * (double)vf[t]);
-    if ((c & 15) == 0) {
-      red[c >> 4][t][0] = e2;
-      red[c >> 4][t][1] = n2;
-    }
-  }
   __syncthreads();
 
   // ---- write out, 16 bytes per thread where possible
+  const int c = tid;
   uint8_t* kc = a.t1 + t1_offset(head * a.nq_cap, blk, Q_KC, KC_BYTES);
   reinterpret_cast<uint4*>(kc)[c] = reinterpret_cast<const uint4*>(kbuf)[c];
 
@@ -181,13 +216,8 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
   if (c == 0) {
     double eta2 = 0.0, nu2 = 0.0;
     for (int t = 0; t < BLK; ++t) {
-      double e = 0.0, n = 0.0;
-      for (int r = 0; r < 8; ++r) {
-        e += red[r][t][0];
-        n += red[r][t][1];
-      }
-      eta2 = fmax(eta2, e);
-      nu2 = fmax(nu2, n);
+      eta2 = fmax(eta2, red[t][0]);
+      nu2 = fmax(nu2, red[t][1]);
     }
     float* an = reinterpret_cast<float*>(a.t1 + t1_offset(head * a.nq_cap, blk, Q_AN, AN_BYTES));
     an[0] = (float)sqrt(eta2);
