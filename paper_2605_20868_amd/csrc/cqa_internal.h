@@ -87,6 +87,9 @@ constexpr int P_I1 = 8;     // block index of the largest (int bits)
 constexpr int P_O = 16;     // o[128]
 constexpr int PART_FLOATS = 16 + D;  // 144
 constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-head)
+constexpr int WPB = 8;               // waves per workgroup of the matrix-core split pass: one workgroup
+                                     // per compute unit (two waves per SIMD), so that all of a
+                                     // launch's waves are dispatched in one sweep
 
 // ---- adaptive key precision ------------------------------------------------------
 constexpr int MAX_K_LIMIT = 512;            // blocks one head may promote (Rung-1 growth included)

@@ -397,22 +397,24 @@ __global__ __launch_bounds__(256) void certified_reduce_kernel(ReduceArgs a) {
 }
 
 // Workgroups ("splits") per (batch, kv-head) and, for the vector-ALU kernel, blocks per split.
-// The launch is sized to ONE resident generation: two workgroups of four waves per compute unit
-// (the matrix-core kernel runs at two waves per SIMD), so no workgroup waits for a slot and the
-// per-wave start-up latency is paid once.  The matrix-core kernel deals the head's quads of
-// blocks evenly over all 4 * nsplit waves; short sequences get fewer workgroups so that every
-// wave still has at least one quad.
+// The launch is sized to ONE resident generation: one workgroup of WPB = 8 waves per compute unit
+// (the matrix-core kernel runs at two waves per SIMD), so no workgroup waits for a slot, the
+// per-wave start-up latency is paid once, and the whole launch is dispatched in one sweep (with
+// two workgroups of four waves per compute unit the second one started ~2 us after the first and
+// finished as much later).  The matrix-core kernel deals the head's quads of blocks evenly over all
+// WPB * nsplit waves; short sequences get fewer workgroups so that every workgroup still has a quad.
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps) {
   *nsplit = 0;
   *bps = 0;
   if (n_blocks <= 0) return;
   const int64_t heads = (int64_t)c->desc.batch * c->desc.n_kv_heads;
-  int64_t want = c->forced_splits > 0 ? c->forced_splits : (2 * (int64_t)c->n_cu + heads - 1) / heads;
+  int64_t want = c->forced_splits > 0 ? c->forced_splits
+                                      : ((8 / WPB) * (int64_t)c->n_cu + heads - 1) / heads;
   if (want < 1) want = 1;
   if (want > c->max_splits) want = c->max_splits;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
   const int64_t quads = (n_blocks + 3) / 4;
-  const int64_t cap = (quads + 3) / 4;   // at least one quad per wave
+  const int64_t cap = (quads + WPB - 1) / WPB;   // at least one quad per workgroup's wave
   if (want > cap) want = cap;
   *nsplit = (int)want;
   *bps = (int)((n_blocks + want - 1) / want);

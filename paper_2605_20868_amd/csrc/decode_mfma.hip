@@ -120,7 +120,7 @@ constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability bu
 //     and scored against the stored key codes by mfma_i32_16x16x64_i8; the block's score bound
 //     grows by the explicit term (128 / sqrt d) sum_c |q~_c - s_q T_c|.
 template <int G, bool LM, bool NT, bool Q8>
-__global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
@@ -137,11 +137,13 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int nquads = (a.nb + 3) >> 2;
   const int L = blockIdx.x;
   const int head = L / a.nsplit, split = L - head * a.nsplit;
-  const bool younger = 2 * L >= (int)gridDim.x;
+  // a SIMD holds waves w and w + 4 of the one workgroup on its compute unit; "younger" names the
+  // second of them in the priority scheme below
+  const bool younger = w >= WPB / 2;
   constexpr int Q_NONE = 0x40000000;   // "no quad": larger than any quad index
   int q_cur, q_next, q_stop;
   {
-    const int nw = 4 * a.nsplit, ci = 4 * split + w;
+    const int nw = WPB * a.nsplit, ci = WPB * split + w;
     const int base = nquads / nw, rem = nquads - base * nw;
     const int nmine = base + (ci < rem ? 1 : 0);
     const int q0 = ci * base + min(ci, rem);
@@ -153,15 +155,15 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   const int64_t head_rec = (int64_t)head * a.nq_cap;
   const float inv_sqrt_d = 0.08838834764831845f;
 
-  __shared__ __align__(16) float kmbuf[4][4][KM_ROW];    // [wave][block of quad][sigma | z]
-  __shared__ __align__(16) __half vmbuf[4][4][VM_ROW];   // [wave][block of quad][scale | offset]
-  __shared__ __align__(16) float pbuf[4][4][P_HEAD];     // [wave][head][block of quad][token]
-  __shared__ __align__(16) float cbuf[4][3][4][4];       // [wave][c_b | Delta_b | s_q][head][block]
-  __shared__ float abuf[4][4];                           // [wave][head] rescale factor of the step
+  __shared__ __align__(16) float kmbuf[WPB][4][KM_ROW];    // [wave][block of quad][sigma | z]
+  __shared__ __align__(16) __half vmbuf[WPB][4][VM_ROW];   // [wave][block of quad][scale | offset]
+  __shared__ __align__(16) float pbuf[WPB][4][P_HEAD];     // [wave][head][block of quad][token]
+  __shared__ __align__(16) float cbuf[WPB][3][4][4];       // [wave][c_b | Delta_b | s_q][head][block]
+  __shared__ float abuf[WPB][4];                           // [wave][head] rescale factor of the step
   __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
   __shared__ float sbuf[4];                              // [head] 1 / S_h
-  __shared__ __align__(16) float mo[4][G][D];
-  __shared__ float ms[4][G][12];
+  __shared__ __align__(16) float mo[WPB][G][D];
+  __shared__ float ms[WPB][G][12];
 
   // A one-token append that rides on this launch: the first wave of each KV group's first
   // workgroup stores the group's new key and value (2 x 256 bytes) into the trailing block and
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
   // elements too small for a normal FP16 low part are negligible against the largest ones.
   // Wave w prepares the row of head w.
   // Lane (h, kg) reads channels (u>>1)*64 + kg*16 + (u&1)*8 + e of head h when it forms slice u.
-  {
+  if (w < 4) {   // qbuf has four rows; the other waves of the workgroup have none to prepare
     float2 qq = __half22float2(q_in);
     float qmax = fmaxf(fabsf(qq.x), fabsf(qq.y));
 #pragma unroll
@@ -654,25 +656,25 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
     m[8] = __int_as_float(i1);
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * D; idx += 64 * WPB) {
     const int hh = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    for (int ww = 0; ww < WPB; ++ww) M = fmaxf(M, ms[ww][hh][0]);
     const float Mr = (M == -INFINITY) ? 0.0f : M;   // a workgroup that drew no quad writes zeros
     float o = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) o += __expf(ms[ww][hh][0] - Mr) * mo[ww][hh][c];
+    for (int ww = 0; ww < WPB; ++ww) o += __expf(ms[ww][hh][0] - Mr) * mo[ww][hh][c];
     a.partials[(((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c] = o;
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
     float M = -INFINITY;
-    for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    for (int ww = 0; ww < WPB; ++ww) M = fmaxf(M, ms[ww][hh][0]);
     const float Mr = (M == -INFINITY) ? 0.0f : M;
     float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f, T1 = -INFINITY, T2 = -INFINITY;
     int I1 = -1;
-    for (int ww = 0; ww < 4; ++ww) {
+    for (int ww = 0; ww < WPB; ++ww) {
       const float fw = __expf(ms[ww][hh][0] - Mr);
       L += fw * ms[ww][hh][1];
       EV += fw * ms[ww][hh][2];
@@ -704,13 +706,13 @@ __global__ __launch_bounds__(256, 2) void certified_split_mfma_kernel(DecodeArgs
 // requested while the current one is consumed) and does nothing else with them.  Its duration is
 // the ceiling the memory system sets for this access pattern.
 template <bool NT>
-__global__ __launch_bounds__(256, 2) void stream_read_kernel(const uint8_t* t1, int64_t nq_cap, int nb,
+__global__ __launch_bounds__(64 * WPB, 1) void stream_read_kernel(const uint8_t* t1, int64_t nq_cap, int nb,
                                                              int nsplit, uint32_t* sink) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int split = blockIdx.x;
   const int64_t head = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
   const int nquads = (nb + 3) >> 2;
-  const int gw = split * 4 + w, nw = nsplit * 4;
+  const int gw = split * WPB + w, nw = nsplit * WPB;
   const int q0 = (int)(((int64_t)gw * nquads) / nw), q1 = (int)(((int64_t)(gw + 1) * nquads) / nw);
   if (q0 >= q1) return;
   const uint8_t* base = t1 + head * nq_cap * QUAD_BYTES;
@@ -733,9 +735,9 @@ __global__ __launch_bounds__(256, 2) void stream_read_kernel(const uint8_t* t1, 
 int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
                            uint32_t* sink, hipStream_t st) {
   if (nt)
-    hipLaunchKernelGGL(stream_read_kernel<true>, grid, dim3(256), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
+    hipLaunchKernelGGL(stream_read_kernel<true>, grid, dim3(64 * WPB), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
   else
-    hipLaunchKernelGGL(stream_read_kernel<false>, grid, dim3(256), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
+    hipLaunchKernelGGL(stream_read_kernel<false>, grid, dim3(64 * WPB), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
   CQA_HIP(hipGetLastError());
   return CQA_OK;
 }
@@ -747,10 +749,10 @@ int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t 
   const bool lm = a.blk_logmass != nullptr;
 #define CQA_LAUNCH_Q(GG, NTV, Q8V)                                                                 \
   if (lm)                                                                                          \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV, Q8V>), grid, dim3(256), 0, st, \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV, Q8V>), grid, dim3(64 * WPB), 0, st, \
                           ev0, ev1, 0, a);                                                         \
   else                                                                                             \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV, Q8V>), grid, dim3(256), 0,   \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV, Q8V>), grid, dim3(64 * WPB), 0,   \
                           st, ev0, ev1, 0, a);
 #define CQA_LAUNCH_NT(GG, NTV)                                                                     \
   if (a.int8_query) { CQA_LAUNCH_Q(GG, NTV, true) } else { CQA_LAUNCH_Q(GG, NTV, false) }

@@ -86,7 +86,7 @@ def test_noalloc_entry_point_matches_the_existing_one_twice_in_a_row():
 
 def test_noalloc_entry_point_rejects_what_does_not_fit_its_scratch():
     cqa = load_binding()
-    bt, hq, hkv, n = 4, 32, 8, 16400
+    bt, hq, hkv, n = 4, 32, 8, 32800     # 513 quads of blocks per head: room for 64 workgroups of 8 waves
     say(f"no-alloc limit: batch {bt}, {hq} q heads, 64 forced splits")
     rng = np.random.default_rng(5)
     k = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
