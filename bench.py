@@ -479,7 +479,7 @@ def main() -> int:
         torch.cuda.synchronize()
         adv_ms = (time.perf_counter() - tv0) * 1e3 / n_ad
         vstate = cqa.cqa_adaptive_state(h, 0, sh.batch, sh.n_q_heads, sh.n_kv_heads)
-        # the optional FP16-key scratch (off above): switched on, the 20 queries once with an empty
+        # the optional FP16 scratch (off above): switched on, the 20 queries once with an empty
         # scratch (every promoted block is read from pinned host RAM and kept) and once more (every
         # promoted block is now held on the device)
         def timed_adaptive(first, tl, sl):
@@ -517,7 +517,7 @@ def main() -> int:
                    "what": f"cqa_adaptive_step_enqueue, wall time, mean of {n_ad} (tau_cov 0.995, K in [2, 128], ranking "
                            "check on, rank_min_mass 0.25; steps that fall back include the dense recompute); "
                            "promoted keys are read from pinned host RAM by the kernel; key_scratch: the same "
-                           "20 queries with the optional device-resident FP16-key scratch switched on, "
+                           "20 queries with the optional device-resident FP16 scratch switched on, "
                            "first filling it, then hitting it"}
 
         # the streaming-read ceiling for this access pattern: the same records, launch shape and load

@@ -153,8 +153,12 @@ int32_t cqa_cache_create_caller_tier2(const cqa_cache_desc* desc, void* t2_k_hos
 int32_t cqa_cache_create(const cqa_cache_desc* desc, cqa_cache** out);
 int32_t cqa_cache_destroy(cqa_cache* c);
 
-/* Bytes the create call allocates: *device_bytes in HBM, *pinned_bytes in pinned
- * host memory.  Either pointer may be NULL. */
+/* Bytes a cache of this shape allocates on a 256-compute-unit device:
+ * *device_bytes in HBM -- every buffer of the create call plus, with Tier 2, what
+ * the first cqa_set_scratch_slots(n > 0) adds at its largest -- and *pinned_bytes
+ * in pinned host memory (library-owned Tier 2 and the flag mirror).  Not counted:
+ * the library's fixed 4 MiB scratch of the no-allocation decode, which every
+ * device holds once per process.  Either pointer may be NULL. */
 int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
                             int64_t* pinned_bytes);
 
@@ -381,19 +385,22 @@ int32_t cqa_adaptive_step_enqueue(cqa_cache* c, int32_t layer, const void* q_fp1
                                   const cqa_tolerances* tol, const cqa_selector* sel, float* O_dev,
                                   cqa_head_cert* cert_dev, uint32_t* flags_dev, void* stream);
 
-/* FP16-key scratch (the paper's VRAM scratch cache of promoted keys, LRU); off
+/* FP16 scratch (the paper's VRAM scratch cache of promoted originals, LRU); off
  * unless switched on here.  Per (layer, batch, kv-head) it keeps up to n_slots
- * blocks of FP16 keys on the device (at most min(1024, capacity in blocks rounded
- * up to a power of two); 4 KB per slot).  An adaptive decode then reads a promoted
- * block's keys from there when it holds them, else from the pinned originals over
- * the host link, and keeps them in the least recently used slot that the step does
- * not use.  Results do not depend on it (the same FP16 bits either way).  On this
- * hardware the kernel's direct reads of pinned host memory are as fast for the few
- * dozen blocks a step promotes, which is why it is off by default.
+ * promoted blocks on the device (at most min(1024, capacity in blocks rounded up
+ * to a power of two)); a slot has a key half and a value half of 4 KB each, and
+ * a half is filled the first time a step needs it.  An adaptive decode then reads
+ * a promoted block's FP16 keys / values from there when the slot holds them, else
+ * from the pinned originals over the host link, and keeps them in the least
+ * recently used slot that the step does not use.  Results do not depend on it (the
+ * same FP16 bits either way).  On this hardware the kernel's direct reads of pinned
+ * host memory are as fast for the few dozen blocks a step promotes, which is why it
+ * is off by default.
  * cqa_set_scratch_slots: 0 = off; the first non-zero call allocates; every call
  * empties the scratch and waits for the device.
  * cqa_scratch_stats: slots per head in use and, since the cache was created, how many
- * key-promoted blocks were found in the scratch / were not; waits for the device.
+ * promoted blocks found every original they needed in the scratch / did not; waits
+ * for the device.
  * Host pointers, may be NULL.  Errors: INVALID_ARG (n_slots out of range), NO_TIER2,
  * OOM_DEVICE, HIP. */
 int32_t cqa_set_scratch_slots(cqa_cache* c, int32_t n_slots);

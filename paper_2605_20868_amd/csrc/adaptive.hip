@@ -5,8 +5,9 @@
 // smallest prefix that covers tau_cov, clamp to [K_min, K_max]), the first rung of its "Fallback
 // Ladder" (grow K while the key term is over its threshold), its total error bound with the
 // achieved INT8-estimated tail mass, and its "Ranking-Consistency Check" with the boundary
-// verification, at depth 1.  Key precision is chosen per KV group (the union of the group's
-// query heads' selections): the paper's per-KV-group selection variant.
+// verification, at depth r <= MAX_RANK_DEPTH.  Key and value precision are chosen per KV group
+// (the union of the group's query heads' selections: the paper's per-KV-group selection variant)
+// or, with cqa_selector.per_head, per query head over the head's own promoted set (its default).
 //
 // Sequence on one stream (launch_adaptive): the certified pass over all sealed blocks in INT8 /
 // INT4 (it emits the block log-masses, eta_b and the usual partial sets, and its reduction the
@@ -381,11 +382,12 @@ struct CompactArgs {
   int32_t* ulist;      // [Bt][Hkv][MAX_UNION]
   int32_t* ucount;     // [Bt][Hkv]
   int nb;
-  // FP16-key scratch of the layer (sc_slots = 0: off)
+  // FP16 scratch of the layer (sc_slots = 0: off)
   int32_t* sc_map;     // [Bt][Hkv][sc_map_stride]
   int64_t sc_map_stride;
   int32_t* sc_tag;     // [Bt][Hkv][sc_cap]
   uint32_t* sc_age;    // [Bt][Hkv][sc_cap]
+  int32_t* sc_have;    // [Bt][Hkv][sc_cap]
   uint32_t* sc_stats;  // [2]
   int sc_cap, sc_slots;
   uint32_t sc_step;    // stamp of this step (larger than every stamp before it, never 0)
@@ -478,20 +480,23 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   if (tid == 0) a.ucount[grp] = min(s_base, MAX_UNION);
   if (a.sc_slots <= 0) return;
 
-  // ---- FP16-key scratch: which listed blocks are held on the device, and where the others go.
-  // A key-promoted block found in the map keeps its slot (stamped with this step).  The others
+  // ---- FP16 scratch: which listed blocks are held on the device, and where the others go.
+  // A promoted block found in the map keeps its slot (stamped with this step); a half of it (keys,
+  // values) that this step needs and the slot does not hold yet is filled on the way.  The others
   // take over the least recently used slots -- found by a radix selection over the slots' stamps,
-  // only in steps that miss -- never one used in this step; the pass that reads
-  // their keys from the host stores them into the slot (SLOT_FILL).  Misses beyond the free
-  // slots are read from the host without being kept.
+  // only in steps that miss -- never one used in this step; the pass that reads their originals
+  // from the host stores them into the slot (SLOT_FILL for the keys, SLOT_VFILL for the values).
+  // Misses beyond the free slots are read from the host without being kept.
   const int n = min(s_base, MAX_UNION);
   int32_t* map = a.sc_map + grp * a.sc_map_stride;
   int32_t* tag = a.sc_tag + grp * (int64_t)a.sc_cap;
   uint32_t* age = a.sc_age + grp * (int64_t)a.sc_cap;
-  __shared__ int s_hits, s_nmiss, s_elig;
+  int32_t* have = a.sc_have + grp * (int64_t)a.sc_cap;
+  __shared__ int s_hits, s_part, s_nmiss, s_elig;
   __shared__ int misslist[SC_MAX_SLOTS];
   if (tid == 0) {
     s_hits = 0;
+    s_part = 0;
     s_nmiss = 0;
     s_elig = 0;
   }
@@ -499,12 +504,16 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   for (int i = tid; i < n; i += 256) {
     const int blk = ulist[i];
     const int f = slot[blk];
-    if (f & SLOT_KEYS) {
+    const int need = f & (SLOT_KEYS | SLOT_VALUES);
+    if (need) {
       const int m = map[blk];
       if (m > 0 && m <= a.sc_slots && tag[m - 1] == blk) {
+        const int missing = need & ~have[m - 1];
         age[m - 1] = a.sc_step;
-        slot[blk] = f | (m << SLOT_SC_SHIFT);
-        atomicAdd(&s_hits, 1);
+        have[m - 1] |= need;
+        slot[blk] = f | (m << SLOT_SC_SHIFT) | ((missing & SLOT_KEYS) ? SLOT_FILL : 0) |
+                    ((missing & SLOT_VALUES) ? SLOT_VFILL : 0);
+        atomicAdd(missing ? &s_part : &s_hits, 1);
       } else {
         const int k = atomicAdd(&s_nmiss, 1);
         if (k < SC_MAX_SLOTS) misslist[k] = blk;
@@ -515,7 +524,7 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   const int nmiss = min(s_nmiss, SC_MAX_SLOTS);
   if (tid == 0) {
     atomicAdd(a.sc_stats + 0, (uint32_t)s_hits);
-    atomicAdd(a.sc_stats + 1, (uint32_t)s_nmiss);
+    atomicAdd(a.sc_stats + 1, (uint32_t)(s_nmiss + s_part));
   }
   if (nmiss == 0) return;
   // The `usable` least recently used slots, ties to the lower slot index: radix selection over
@@ -588,7 +597,10 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
       tag[v] = blk;
       map[blk] = v + 1;
       age[v] = a.sc_step;
-      slot[blk] |= ((v + 1) << SLOT_SC_SHIFT) | SLOT_FILL;
+      const int need = slot[blk] & (SLOT_KEYS | SLOT_VALUES);
+      have[v] = need;
+      slot[blk] |= ((v + 1) << SLOT_SC_SHIFT) | ((need & SLOT_KEYS) ? SLOT_FILL : 0) |
+                   ((need & SLOT_VALUES) ? SLOT_VFILL : 0);
     }
     ++rank;
   }
@@ -920,6 +932,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
     ca.sc_map_stride = c->nb_cap;
     ca.sc_tag = w.sc_tag + layer_head0 * w.sc_cap;
     ca.sc_age = w.sc_age + layer_head0 * w.sc_cap;
+    ca.sc_have = w.sc_have + layer_head0 * w.sc_cap;
     ca.sc_stats = w.sc_stats;
     ca.sc_cap = w.sc_cap;
     ca.sc_step = w.sc_step;
@@ -960,6 +973,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.n_kv = hkv;
   a.slot = w.slot;
   a.sc_k = w.sc_slots > 0 ? w.sc_k + layer_head0 * w.sc_cap * BLK * D : nullptr;
+  a.sc_v = w.sc_slots > 0 ? w.sc_v + layer_head0 * w.sc_cap * BLK * D : nullptr;
   a.sc_cap = w.sc_cap;
   a.ulist = w.ulist;
   a.ucount = w.ucount;

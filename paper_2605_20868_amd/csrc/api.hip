@@ -73,7 +73,7 @@ static Sizes compute_sizes(const cqa_cache_desc* d, int n_cu) {
   s.ad_group = ad ? groups * 4 : 0;
   s.ad_ulist = ad ? groups * MAX_UNION * 4 : 0;
   s.ad_eta = ad ? groups * s.nb_cap * 4 : 0;
-  // FP16-key scratch: a power of two of slots per head, at most SC_MAX_SLOTS, no more than needed
+  // FP16 scratch: a power of two of slots per head, at most SC_MAX_SLOTS, no more than needed
   int cap = 1;
   while (cap < SC_MAX_SLOTS && cap < s.nb_cap) cap <<= 1;
   s.sc_cap = ad ? cap : 0;
@@ -114,6 +114,8 @@ static void release(cqa_cache* h) {
   (void)hipFree(c->ad.vcount);
   (void)hipFree(c->ad.score_dev);
   (void)hipFree(c->ad.sc_k);
+  (void)hipFree(c->ad.sc_v);
+  (void)hipFree(c->ad.sc_have);
   (void)hipFree(c->ad.sc_map);
   (void)hipFree(c->ad.sc_tag);
   (void)hipFree(c->ad.sc_age);
@@ -205,11 +207,20 @@ int32_t cqa_workspace_bytes(const cqa_cache_desc* desc, int64_t* device_bytes,
   const int32_t st = check_desc(desc);
   if (st != CQA_OK) return st;
   const Sizes s = compute_sizes(desc, 256);
-  if (device_bytes)
-    *device_bytes = s.t1 + 2 * s.trail + s.partials + 2 * s.dense_ws + 4 * s.stage + s.select +
-                    s.ladder_ws +
-                    2 * s.ad_lm + s.ad_sel + 2 * s.ad_head + s.ad_mask + s.ad_slot + s.ad_group +
-                    s.ad_ulist + s.ad_mask + s.ad_eta + s.ad_lm + s.ad_sel + 2 * s.ad_head;
+  const bool t2 = desc->tier2_mode == CQA_TIER2_PINNED;
+  const int64_t groups = (int64_t)desc->batch * desc->n_kv_heads;
+  if (device_bytes) {
+    // every device allocation of create_cache, in its order ...
+    int64_t n = s.t1 + s.heads * 4 + 2 * s.trail + s.partials + 2 * s.dense_ws + s.select;
+    if (t2) {
+      n += 3 * s.ad_lm + 2 * s.ad_sel + 4 * s.ad_head + 2 * s.ad_mask + s.ad_slot + s.ad_group + s.ad_ulist +
+           s.ad_eta + 8;
+      n += 4 * s.stage + s.ladder_ws + groups * 4 + 8;
+      // ... and what the first cqa_set_scratch_slots(n > 0) adds: key and value halves, map, three words per slot
+      n += 2 * s.sc_k + s.sc_map + 3 * s.sc_tag;
+    }
+    *device_bytes = n;
+  }
   if (pinned_bytes) *pinned_bytes = 2 * s.t2 + s.select;
   return CQA_OK;
 }
@@ -288,7 +299,7 @@ static int32_t create_cache(const cqa_cache_desc* desc, __half* caller_k, __half
     CQA_TRY(hipMemset(c->ad.vcount, 0, (size_t)s.ad_head));
     CQA_TRY(hipMemset(c->ad.ucount, 0, (size_t)s.ad_group));
     CQA_TRY(hipMemset(c->ad.kstar, 0, (size_t)s.ad_head));
-    // FP16-key scratch: off until cqa_set_scratch_slots asks for it (allocated then)
+    // FP16 scratch: off until cqa_set_scratch_slots asks for it (allocated then)
     CQA_ALLOC_DEV(c->ad.sc_stats, 8);
     CQA_TRY(hipMemset(c->ad.sc_stats, 0, 8));
     c->ad.sc_cap = s.sc_cap;
@@ -402,11 +413,12 @@ int32_t cqa_cache_reset(cqa_cache* h, int32_t layer) {
   CQA_HIP(hipMemset(c->t1 + head_index(c, layer, 0, 0) * c->nq_cap * QUAD_BYTES, 0,
                     (size_t)c->desc.batch * c->desc.n_kv_heads * c->nq_cap * QUAD_BYTES));
   if (c->ad.sc_map != nullptr) {
-    // the layer's blocks are gone: nothing of it stays in the FP16-key scratch
+    // the layer's blocks are gone: nothing of it stays in the FP16 scratch
     const int64_t h0 = head_index(c, layer, 0, 0), nh = (int64_t)c->desc.batch * c->desc.n_kv_heads;
     CQA_HIP(hipMemset(c->ad.sc_map + h0 * c->nb_cap, 0, (size_t)(nh * c->nb_cap) * 4));
     CQA_HIP(hipMemset(c->ad.sc_tag + h0 * c->ad.sc_cap, 0xFF, (size_t)(nh * c->ad.sc_cap) * 4));
     CQA_HIP(hipMemset(c->ad.sc_age + h0 * c->ad.sc_cap, 0, (size_t)(nh * c->ad.sc_cap) * 4));
+    CQA_HIP(hipMemset(c->ad.sc_have + h0 * c->ad.sc_cap, 0, (size_t)(nh * c->ad.sc_cap) * 4));
   }
   c->length[layer] = 0;
   return CQA_OK;
@@ -421,10 +433,12 @@ int32_t cqa_set_scratch_slots(cqa_cache* h, int32_t n_slots) {
   const int64_t cap = c->ad.sc_cap;
   if (n_slots > 0 && c->ad.sc_k == nullptr) {
     // first use: the scratch and its maps
-    __half* k = nullptr;
-    int32_t *map = nullptr, *tag = nullptr;
+    __half *k = nullptr, *v = nullptr;
+    int32_t *map = nullptr, *tag = nullptr, *have = nullptr;
     uint32_t* age = nullptr;
     hipError_t e = hipMalloc((void**)&k, (size_t)(c->heads_total * cap) * BLK * D * 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&v, (size_t)(c->heads_total * cap) * BLK * D * 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&have, (size_t)(c->heads_total * cap) * 4);
     if (e == hipSuccess) e = hipMalloc((void**)&map, (size_t)(c->heads_total * c->nb_cap) * 4);
     if (e == hipSuccess) e = hipMalloc((void**)&tag, (size_t)(c->heads_total * cap) * 4);
     if (e == hipSuccess) e = hipMalloc((void**)&age, (size_t)(c->heads_total * cap) * 4);
@@ -432,12 +446,16 @@ int32_t cqa_set_scratch_slots(cqa_cache* h, int32_t n_slots) {
       g_last_hip_error = (int)e;
       (void)hipGetLastError();
       (void)hipFree(k);
+      (void)hipFree(v);
+      (void)hipFree(have);
       (void)hipFree(map);
       (void)hipFree(tag);
       (void)hipFree(age);
       return e == hipErrorOutOfMemory ? CQA_ERR_OOM_DEVICE : CQA_ERR_HIP;
     }
     c->ad.sc_k = k;
+    c->ad.sc_v = v;
+    c->ad.sc_have = have;
     c->ad.sc_map = map;
     c->ad.sc_tag = tag;
     c->ad.sc_age = age;
@@ -446,6 +464,7 @@ int32_t cqa_set_scratch_slots(cqa_cache* h, int32_t n_slots) {
     CQA_HIP(hipMemset(c->ad.sc_map, 0, (size_t)(c->heads_total * c->nb_cap) * 4));
     CQA_HIP(hipMemset(c->ad.sc_tag, 0xFF, (size_t)(c->heads_total * cap) * 4));   // -1: empty
     CQA_HIP(hipMemset(c->ad.sc_age, 0, (size_t)(c->heads_total * cap) * 4));
+    CQA_HIP(hipMemset(c->ad.sc_have, 0, (size_t)(c->heads_total * cap) * 4));
   }
   c->ad.sc_slots = n_slots;
   return CQA_OK;

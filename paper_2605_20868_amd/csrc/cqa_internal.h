@@ -114,14 +114,17 @@ struct AdaptiveWs {
   int32_t* ucount;   // [Bt][Hkv]             promoted blocks of the group
   int32_t* ulist;    // [Bt][Hkv][MAX_UNION]  their indices, ascending
   int64_t mask_words;
-  // FP16-key scratch (the paper's VRAM scratch cache of promoted keys, LRU): per (layer, batch,
-  // kv-head) `sc_cap` slots of one block's keys each.  sc_map: block -> slot + 1 (0 = not held);
-  // sc_tag: slot -> block (-1 = empty); sc_age: slot -> step stamp of its last use.
+  // FP16 scratch (the paper's VRAM scratch cache of promoted originals, LRU): per (layer, batch,
+  // kv-head) `sc_cap` slots of one block each, a key half and a value half.  sc_map: block ->
+  // slot + 1 (0 = not held); sc_tag: slot -> block (-1 = empty); sc_age: slot -> step stamp of its
+  // last use; sc_have: slot -> which halves hold the block's data (SLOT_KEYS | SLOT_VALUES).
   __half* sc_k;      // [heads_total][sc_cap][16][128]
+  __half* sc_v;      // [heads_total][sc_cap][16][128]
   int32_t* sc_map;   // [heads_total][nb_cap]
   int32_t* sc_tag;   // [heads_total][sc_cap]
   uint32_t* sc_age;  // [heads_total][sc_cap]
-  uint32_t* sc_stats;  // [2] key-promoted blocks found in the scratch / not found, over all steps
+  int32_t* sc_have;  // [heads_total][sc_cap]
+  uint32_t* sc_stats;  // [2] promoted blocks whose originals were all in the scratch / were not, over all steps
   int sc_cap;        // allocated slots per head (a power of two <= SC_MAX_SLOTS)
   int sc_slots;      // slots in use (test hook may lower it; 0 = scratch off)
   uint32_t sc_step;  // stamp of the last adaptive step
@@ -129,9 +132,10 @@ struct AdaptiveWs {
 
 constexpr int MAX_RANK_DEPTH = 8;   // largest depth r of the ranking check (adaptive path)
 constexpr int SC_MAX_SLOTS = 1024;
-// per-block word of AdaptiveWs::slot: bit 0 FP16 keys, bit 1 FP16 values, bit 2 the keys are to
-// be stored into the scratch slot by the pass that reads them, bits 8.. scratch slot + 1 (0 = none)
-constexpr int SLOT_KEYS = 1, SLOT_VALUES = 2, SLOT_FILL = 4, SLOT_SC_SHIFT = 8;
+// per-block word of AdaptiveWs::slot: bit 0 FP16 keys, bit 1 FP16 values, bit 2 / bit 3 the keys /
+// the values are to be stored into the scratch slot by the pass that reads them from the host,
+// bits 8-23 scratch slot + 1 (0 = none)
+constexpr int SLOT_KEYS = 1, SLOT_VALUES = 2, SLOT_FILL = 4, SLOT_VFILL = 8, SLOT_SC_SHIFT = 8;
 // bits 24-27: query head i of the group (i = 0..3) scores this block with FP16 keys; bits 28-31: it
 // attends the block's FP16 values.  With per-group promotion every head's bit follows bits 0 / 1.
 constexpr int SLOT_HK_SHIFT = 24, SLOT_HV_SHIFT = 28;
@@ -199,7 +203,8 @@ struct DecodeArgs {
   int int8_query;      // matrix-core pass: 1 = INT8 x INT8 scoring of the quantised scaled query
   // promoted-block pass of the adaptive decode (null slot = not that pass)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
-  __half* sc_k;             // layer base of the FP16-key scratch [Bt * Hkv][sc_cap][16][128], or null
+  __half* sc_k;             // layer base of the FP16 scratch's key halves [Bt * Hkv][sc_cap][16][128], or null
+  __half* sc_v;             // ... and of its value halves (null exactly when sc_k is)
   int sc_cap;
   const int32_t* ulist;     // [Bt][Hkv][MAX_UNION]: promoted blocks of the group, ascending
   const int32_t* ucount;    // [Bt][Hkv]

@@ -124,9 +124,9 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     // scratch if it is held there, else from the host-resident originals -- and then, if the
     // block has just been given a slot, stored into it on the way
     uint4 k16[2][2];
+    const int sc0 = (pf >> SLOT_SC_SHIFT) & 0xFFFF;   // bits 8-23: scratch slot + 1
+    const int sc = (PROM && a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
     if (kfp) {
-      const int sc0 = (pf >> SLOT_SC_SHIFT) & 0xFFFF;   // bits 8-23: scratch slot + 1
-      const int sc = (a.sc_k != nullptr && sc0 <= a.sc_cap) ? sc0 : 0;   // bounded whatever the word holds
       const bool fill = sc > 0 && (pf & SLOT_FILL);
       __half* sck = sc > 0 ? a.sc_k + (((grp * a.sc_cap + (sc - 1)) * BLK) + tok) * D : nullptr;
       const __half* kf16 = (sc > 0 && !fill) ? sck
@@ -147,11 +147,21 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       }
     }
     if (vfp) {
-      // its FP16 values, row-major [token][128], coalesced into this wave's LDS buffer
-      const __half* v16 = a.t2_v + (grp * a.max_tokens + (int64_t)blk * BLK + (l >> 2)) * D + (l & 3) * 32;
+      // its FP16 values, row-major [token][128], coalesced into this wave's LDS buffer: from the
+      // value half of the block's scratch slot, or from the host-resident originals (and then
+      // into the slot, if the block has just been given one)
+      const bool vfill = sc > 0 && (pf & SLOT_VFILL);
+      const int64_t in_blk = (int64_t)(l >> 2) * D + (l & 3) * 32;
+      __half* scv = sc > 0 ? a.sc_v + (grp * a.sc_cap + (sc - 1)) * (int64_t)(BLK * D) + in_blk : nullptr;
+      const __half* v16 = (sc > 0 && !vfill) ? scv
+                                             : a.t2_v + (grp * a.max_tokens + (int64_t)blk * BLK) * D + in_blk;
       uint4 v16r[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) v16r[j] = *reinterpret_cast<const uint4*>(v16 + j * 8);
+      if (vfill) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4*>(scv + j * 8) = v16r[j];
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         *reinterpret_cast<uint4*>(&vst[w][l >> 2][(l & 3) * 32 + j * 8]) = v16r[j];

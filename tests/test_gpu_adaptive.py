@@ -404,7 +404,7 @@ def test_adaptive_128k_sampled_heads():
 
 
 def test_key_scratch_does_not_change_results_and_holds_recent_blocks():
-    say("adaptive: FP16-key scratch on the device (hits, misses, eviction) gives the same bits as reading the host")
+    say("adaptive: FP16 scratch on the device (hits, misses, eviction) gives the same bits as reading the host")
     k, v, q = make_case(21, 2, 8, 2, 16 * 300 + 9, peaked=[(0, 1, 1500, 0.9), (1, 6, 40, 1.0)])
     rng = np.random.Generator(np.random.Philox(77))
     qs = [q] + [workloads.normal_f16(rng, q.shape) for _ in range(3)]
@@ -459,6 +459,52 @@ def test_key_scratch_does_not_change_results_and_holds_recent_blocks():
         check_against_oracle(oc2, qs[0], tol, sel, out)
         with pytest.raises(cqa.CqaError):
             cqa.cqa_set_scratch_slots(gc.h, 513)
+
+
+def test_scratch_holds_promoted_values_too():
+    say("adaptive: the scratch's value halves (cold, warm, a slot that held only keys, eviction) give the same bits")
+    k, v, q = make_case(23, 2, 8, 2, 16 * 300 + 9, peaked=[(0, 1, 1500, 0.9), (1, 6, 40, 1.0)])
+    rng = np.random.Generator(np.random.Philox(78))
+    qs = [q] + [workloads.normal_f16(rng, q.shape) for _ in range(2)]
+    tol = att.Tolerances(rank_depth=1, v_tol=0.004)
+
+    def same(a, b, w):
+        assert (a["O"] == b["O"]).all() and a["cert"].tobytes() == b["cert"].tobytes(), w
+        assert (a["flags"] == b["flags"]).all() and (a["promoted"] == b["promoted"]).all(), w
+        assert (a["v_promoted"] == b["v_promoted"]).all() and (a["lx"] == b["lx"]).all(), w
+
+    for per_head in (False, True):
+        sel_v = ad.SelectorParams(0.5, 2, 6, 6, v_limit=24, per_head=per_head)
+        with GpuLayerCache(2, 8, 2, 16 * 300 + 64) as gc:
+            cqa = gc.cqa
+            gc.append(k, v)
+            ref = [gpu_adaptive(gc, x, tol, sel_v) for x in qs]
+            ref_k = gpu_adaptive(gc, qs[0], tol, ad.SelectorParams(0.5, 2, 6, 6, per_head=per_head))
+            listed = [int((r["promoted"] | r["v_promoted"]).sum()) for r in ref]
+            assert ref[0]["v_promoted"].sum() > 0 and (ref[0]["v_promoted"] & ~ref[0]["promoted"]).sum() > 0
+            # the value promotion is really on: the value term shrinks against keys-only promotion
+            assert (ref[0]["cert"]["E_val"] < ref_k["cert"]["E_val"]).any()
+            # cold, then warm
+            cqa.cqa_set_scratch_slots(gc.h, 512)
+            same(gpu_adaptive(gc, qs[0], tol, sel_v), ref[0], "cold")
+            assert cqa.cqa_scratch_stats(gc.h) == (512, 0, listed[0])
+            same(gpu_adaptive(gc, qs[0], tol, sel_v), ref[0], "warm")
+            assert cqa.cqa_scratch_stats(gc.h) == (512, listed[0], listed[0])
+            # slots that hold only the keys: a step that also needs the block's values fills the other half
+            cqa.cqa_set_scratch_slots(gc.h, 512)
+            same(gpu_adaptive(gc, qs[0], tol, ad.SelectorParams(0.5, 2, 6, 6, per_head=per_head)), ref_k, "keys only")
+            _, h0, m0 = cqa.cqa_scratch_stats(gc.h)
+            same(gpu_adaptive(gc, qs[0], tol, sel_v), ref[0], "values join")
+            _, h1, m1 = cqa.cqa_scratch_stats(gc.h)
+            assert m1 - m0 >= int(ref[0]["v_promoted"].sum()) and (h1 - h0) + (m1 - m0) == listed[0]
+            same(gpu_adaptive(gc, qs[0], tol, sel_v), ref[0], "both halves held")
+            _, h2, m2 = cqa.cqa_scratch_stats(gc.h)
+            assert (h2 - h1, m2 - m1) == (listed[0], 0)
+            # fewer slots than a step lists: overflow from the host, eviction in later steps
+            cqa.cqa_set_scratch_slots(gc.h, 3)
+            for rep in range(2):
+                for i in (0, 1, 0, 2):
+                    same(gpu_adaptive(gc, qs[i], tol, sel_v), ref[i], ("small scratch", per_head, rep, i))
 
 
 def test_long_context_beyond_the_selector_lds_window():
