@@ -35,6 +35,10 @@ import numpy as np
 import workloads
 
 PEAK_HBM_GBS = 8000.0
+# the arithmetic the path computes in: scores and weighted values are matrix-core contractions whose
+# FP32 operands are split into two FP16 (scores) / two BF16 (values) terms, accumulated in FP32;
+# softmax state and the certificate are FP32
+DTYPE = "f16x2/bf16x2 mfma operands, f32 accumulate"
 ROOF_DISPATCHES = 210          # event-carrying dispatches of the roofline leg ...
 ROOF_DROP = 10                 # ... of which the first ones are dropped
 NO_REUSE_LAYERS = 4            # resident copies of the layer the no-reuse leg alternates over
@@ -177,7 +181,7 @@ def bench_small(args, name) -> int:
         "metric": f"certified decode attention steps/s per layer, workload {name}",
         "value": 1e3 / e2e_ms, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": e2e_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"{name}: 1 layer, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
                                f"context {sh.context}+steps, tolerances +inf", "splits": splits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -267,7 +271,7 @@ def bench_stack(args) -> int:
         "metric": "certified decode attention layer-steps/s, 32-layer stack at 128K ctx, batch 2",
         "value": K * L / (t1 - t0), "unit": "layer-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": (t1 - t0) * 1e3 / K, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"stack: {L} layers, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
                                f"context {ctx}+steps, K ~ Student-t(3), V ~ N(0,1), tolerances +inf",
                    "step": "for each of the 32 layers: append 1 token + decode step with the ladder resolved on the device (cqa_decode_step_enqueue)", "splits": splits},
@@ -576,7 +580,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": DTYPE,
         "data": "synthetic",
         "config": {
             "workload": f"t128k: 1 layer, batch {sh.batch}, {sh.n_q_heads} q / {sh.n_kv_heads} kv heads, "
