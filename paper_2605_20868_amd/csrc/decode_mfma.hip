@@ -126,7 +126,7 @@ __global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(Decod
   const int n = l & 15, kg = l >> 4;
   const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
   // Workgroup -> (head, partial set) and this wave's contiguous run of quads: the head's quads are
-  // dealt evenly over its 4 * nsplit waves, in block order, sizes differing by at most one.
+  // dealt evenly over its WPB * nsplit waves, in block order, sizes differing by at most one.
   // (Measured and not adopted: handing the quads out from per-head counters, so that faster XCDs
   // and earlier workgroups take more -- per-wave clock stamps show the waves of a launch finishing
   // up to 10 us apart.  Atomics on one address are served at ~130 ns each across XCDs, far too
