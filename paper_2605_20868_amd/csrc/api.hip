@@ -666,11 +666,11 @@ int32_t cqa_time_stream_read(cqa_cache* h, int32_t layer, int32_t iters, float* 
   const uint8_t* t1 = c->t1 + head_index(c, layer, 0, 0) * c->nq_cap * QUAD_BYTES;
   const bool nt = stream_nt(c, nb) != 0;
   // the select flags buffer doubles as the (never written) sink
-  int32_t rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, c->select_dev, st);   // warm-up
+  int32_t rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, waves_per_workgroup(c), c->select_dev, st);   // warm-up
   if (rc != CQA_OK) return rc;
   CQA_HIP(hipEventRecord(c->ev_t0, st));
   for (int i = 0; i < iters; ++i) {
-    rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, c->select_dev, st);
+    rc = launch_stream_read(t1, c->nq_cap, (int)nb, grid, nt, waves_per_workgroup(c), c->select_dev, st);
     if (rc != CQA_OK) return rc;
   }
   CQA_HIP(hipEventRecord(c->ev_t1, st));

@@ -87,9 +87,6 @@ constexpr int P_I1 = 8;     // block index of the largest (int bits)
 constexpr int P_O = 16;     // o[128]
 constexpr int PART_FLOATS = 16 + D;  // 144
 constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-head)
-constexpr int WPB = 8;               // waves per workgroup of the matrix-core split pass: one workgroup
-                                     // per compute unit (two waves per SIMD), so that all of a
-                                     // launch's waves are dispatched in one sweep
 
 // ---- adaptive key precision ------------------------------------------------------
 constexpr int MAX_K_LIMIT = 512;            // blocks one head may promote (Rung-1 growth included)
@@ -201,6 +198,7 @@ struct DecodeArgs {
   int n_q, n_kv;
   int pstride;         // partial sets per (batch, q-head) row of `partials` (>= nsplit)
   int int8_query;      // matrix-core pass: 1 = INT8 x INT8 scoring of the quantised scaled query
+  int wpb;             // matrix-core pass: waves per workgroup, 8 or 4 (waves_per_workgroup)
   // promoted-block pass of the adaptive decode (null slot = not that pass)
   const int32_t* slot;      // [Bt][Hkv][4 nq_cap]: bit 0 = FP16 keys, bit 1 = FP16 values, 0 = neither
   __half* sc_k;             // layer base of the FP16 scratch's key halves [Bt * Hkv][sc_cap][16][128], or null
@@ -256,13 +254,14 @@ int32_t static_scratch(int device, void** out);
 int pick_splits(const Cache* c, int64_t n_blocks);
 int stream_nt(const Cache* c, int64_t n_blocks);
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps);
+int waves_per_workgroup(const Cache* c);
 int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
                         const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
                         uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st);
 int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t ev0, hipEvent_t ev1,
                           hipStream_t st);
 
-int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
+int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt, int wpb,
                            uint32_t* sink, hipStream_t st);
 
 int dense_splits(int64_t n_tokens);

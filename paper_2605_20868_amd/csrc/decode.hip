@@ -406,25 +406,35 @@ __global__ __launch_bounds__(256) void certified_reduce_kernel(ReduceArgs a) {
   if (hq < a.n_q) reduce_head_wave(a, b, hq, wsm[w]);
 }
 
+// Waves per workgroup of the matrix-core split pass.  Eight -- one workgroup per compute unit, two
+// waves per SIMD -- as long as there are no more (batch, kv-head) sequences than compute units: all
+// of a launch's waves are then dispatched in one sweep (with two workgroups of four waves per
+// compute unit the second one started ~2 us after the first and finished as much later), and a head
+// has half as many partial sets to merge.  With more sequences than compute units every sequence is
+// one workgroup anyway, and workgroups of four waves, two per compute unit, keep the launch at one
+// resident generation for up to twice as many of them.
+int waves_per_workgroup(const Cache* c) {
+  return (int64_t)c->desc.batch * c->desc.n_kv_heads > c->n_cu ? 4 : 8;
+}
+
 // Workgroups ("splits") per (batch, kv-head) and, for the vector-ALU kernel, blocks per split.
-// The launch is sized to ONE resident generation: one workgroup of WPB = 8 waves per compute unit
-// (the matrix-core kernel runs at two waves per SIMD), so no workgroup waits for a slot, the
-// per-wave start-up latency is paid once, and the whole launch is dispatched in one sweep (with
-// two workgroups of four waves per compute unit the second one started ~2 us after the first and
-// finished as much later).  The matrix-core kernel deals the head's quads of blocks evenly over all
-// WPB * nsplit waves; short sequences get fewer workgroups so that every workgroup still has a quad.
+// The launch is sized to ONE resident generation (the matrix-core kernel runs at two waves per
+// SIMD), so no workgroup waits for a slot and the per-wave start-up latency is paid once.  The
+// matrix-core kernel deals the head's quads of blocks evenly over all wpb * nsplit waves; short
+// sequences get fewer workgroups so that every workgroup still has a quad.
 void split_geometry(const Cache* c, int64_t n_blocks, int* nsplit, int* bps) {
   *nsplit = 0;
   *bps = 0;
   if (n_blocks <= 0) return;
   const int64_t heads = (int64_t)c->desc.batch * c->desc.n_kv_heads;
+  const int wpb = waves_per_workgroup(c);
   int64_t want = c->forced_splits > 0 ? c->forced_splits
-                                      : ((8 / WPB) * (int64_t)c->n_cu + heads - 1) / heads;
+                                      : ((8 / wpb) * (int64_t)c->n_cu + heads - 1) / heads;
   if (want < 1) want = 1;
   if (want > c->max_splits) want = c->max_splits;
   if (want > MAX_SPLITS) want = MAX_SPLITS;
   const int64_t quads = (n_blocks + 3) / 4;
-  const int64_t cap = (quads + WPB - 1) / WPB;   // at least one quad per workgroup's wave
+  const int64_t cap = (quads + wpb - 1) / wpb;   // at least one quad per workgroup's wave
   if (want > cap) want = cap;
   *nsplit = (int)want;
   *bps = (int)((n_blocks + want - 1) / want);
@@ -561,6 +571,7 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.n_kv = hkv;
     a.stream_nt = stream_nt(c, nb);
     a.int8_query = tol.int8_query;
+    a.wpb = waves_per_workgroup(c);
     // the quantised-query scoring exists in the matrix-core pass only
     if (tol.int8_query != 0 && (c->variant != 0 || eta_out != nullptr)) return CQA_ERR_UNSUPPORTED;
     const dim3 grid(nsplit, hkv, bt);

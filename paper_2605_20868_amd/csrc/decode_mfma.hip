@@ -119,14 +119,15 @@ constexpr int P_HEAD = 4 * BLK + 16;    // floats per head in the probability bu
 //     query is quantised to 8 bits with one scale per (head, block) row, s_q = max_c |q~_c| / 127,
 //     and scored against the stored key codes by mfma_i32_16x16x64_i8; the block's score bound
 //     grows by the explicit term (128 / sqrt d) sum_c |q~_c - s_q T_c|.
-template <int G, bool LM, bool NT, bool Q8>
-__global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(DecodeArgs a) {
+// W: waves per workgroup, 8 (one workgroup per compute unit) or 4 (two); either way a SIMD holds two waves.
+template <int G, bool LM, bool NT, bool Q8, int W>
+__global__ __launch_bounds__(64 * W, 8 / W) void certified_split_mfma_kernel(DecodeArgs a) {
   const int l = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
   const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
   // Workgroup -> (head, partial set) and this wave's contiguous run of quads: the head's quads are
-  // dealt evenly over its WPB * nsplit waves, in block order, sizes differing by at most one.
+  // dealt evenly over its W * nsplit waves, in block order, sizes differing by at most one.
   // (Measured and not adopted: handing the quads out from per-head counters, so that faster XCDs
   // and earlier workgroups take more -- per-wave clock stamps show the waves of a launch finishing
   // up to 10 us apart.  Atomics on one address are served at ~130 ns each across XCDs, far too
@@ -137,13 +138,14 @@ __global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(Decod
   const int nquads = (a.nb + 3) >> 2;
   const int L = blockIdx.x;
   const int head = L / a.nsplit, split = L - head * a.nsplit;
-  // a SIMD holds waves w and w + 4 of the one workgroup on its compute unit; "younger" names the
-  // second of them in the priority scheme below
-  const bool younger = w >= WPB / 2;
+  // a SIMD holds two waves: w and w + 4 of the one workgroup on its compute unit (W = 8), or wave w
+  // of each of the two (W = 4; the second half of the launch order presumably arrives later);
+  // "younger" names the second of them in the priority scheme below
+  const bool younger = W == 8 ? w >= 4 : 2 * L >= (int)gridDim.x;
   constexpr int Q_NONE = 0x40000000;   // "no quad": larger than any quad index
   int q_cur, q_next, q_stop;
   {
-    const int nw = WPB * a.nsplit, ci = WPB * split + w;
+    const int nw = W * a.nsplit, ci = W * split + w;
     const int base = nquads / nw, rem = nquads - base * nw;
     const int nmine = base + (ci < rem ? 1 : 0);
     const int q0 = ci * base + min(ci, rem);
@@ -155,15 +157,15 @@ __global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(Decod
   const int64_t head_rec = (int64_t)head * a.nq_cap;
   const float inv_sqrt_d = 0.08838834764831845f;
 
-  __shared__ __align__(16) float kmbuf[WPB][4][KM_ROW];    // [wave][block of quad][sigma | z]
-  __shared__ __align__(16) __half vmbuf[WPB][4][VM_ROW];   // [wave][block of quad][scale | offset]
-  __shared__ __align__(16) float pbuf[WPB][4][P_HEAD];     // [wave][head][block of quad][token]
-  __shared__ __align__(16) float cbuf[WPB][3][4][4];       // [wave][c_b | Delta_b | s_q][head][block]
-  __shared__ float abuf[WPB][4];                           // [wave][head] rescale factor of the step
+  __shared__ __align__(16) float kmbuf[W][4][KM_ROW];    // [wave][block of quad][sigma | z]
+  __shared__ __align__(16) __half vmbuf[W][4][VM_ROW];   // [wave][block of quad][scale | offset]
+  __shared__ __align__(16) float pbuf[W][4][P_HEAD];     // [wave][head][block of quad][token]
+  __shared__ __align__(16) float cbuf[W][3][4][4];       // [wave][c_b | Delta_b | s_q][head][block]
+  __shared__ float abuf[W][4];                           // [wave][head] rescale factor of the step
   __shared__ __align__(16) float qbuf[4][D + 4];         // [head][channel], FP32 query times S_h
   __shared__ float sbuf[4];                              // [head] 1 / S_h
-  __shared__ __align__(16) float mo[WPB][G][D];
-  __shared__ float ms[WPB][G][12];
+  __shared__ __align__(16) float mo[W][G][D];
+  __shared__ float ms[W][G][12];
 
   // A one-token append that rides on this launch: the first wave of each KV group's first
   // workgroup stores the group's new key and value (2 x 256 bytes) into the trailing block and
@@ -656,25 +658,25 @@ __global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(Decod
     m[8] = __int_as_float(i1);
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 64 * WPB) {
+  for (int idx = threadIdx.x; idx < G * D; idx += 64 * W) {
     const int hh = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < WPB; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    for (int ww = 0; ww < W; ++ww) M = fmaxf(M, ms[ww][hh][0]);
     const float Mr = (M == -INFINITY) ? 0.0f : M;   // a workgroup that drew no quad writes zeros
     float o = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < WPB; ++ww) o += __expf(ms[ww][hh][0] - Mr) * mo[ww][hh][c];
+    for (int ww = 0; ww < W; ++ww) o += __expf(ms[ww][hh][0] - Mr) * mo[ww][hh][c];
     a.partials[(((int64_t)b * a.n_q + kvh * G + hh) * a.pstride + split) * PART_FLOATS + P_O + c] = o;
   }
   if (threadIdx.x < G) {
     const int hh = threadIdx.x;
     float M = -INFINITY;
-    for (int ww = 0; ww < WPB; ++ww) M = fmaxf(M, ms[ww][hh][0]);
+    for (int ww = 0; ww < W; ++ww) M = fmaxf(M, ms[ww][hh][0]);
     const float Mr = (M == -INFINITY) ? 0.0f : M;
     float L = 0.0f, EV = 0.0f, EVM = 0.0f, DM = 0.0f, VM = 0.0f, T1 = -INFINITY, T2 = -INFINITY;
     int I1 = -1;
-    for (int ww = 0; ww < WPB; ++ww) {
+    for (int ww = 0; ww < W; ++ww) {
       const float fw = __expf(ms[ww][hh][0] - Mr);
       L += fw * ms[ww][hh][1];
       EV += fw * ms[ww][hh][2];
@@ -705,14 +707,14 @@ __global__ __launch_bounds__(64 * WPB, 1) void certified_split_mfma_kernel(Decod
 // and load instructions as the split kernel (18 x 16 bytes per lane and quad, the next quad
 // requested while the current one is consumed) and does nothing else with them.  Its duration is
 // the ceiling the memory system sets for this access pattern.
-template <bool NT>
-__global__ __launch_bounds__(64 * WPB, 1) void stream_read_kernel(const uint8_t* t1, int64_t nq_cap, int nb,
+template <bool NT, int W>
+__global__ __launch_bounds__(64 * W, 8 / W) void stream_read_kernel(const uint8_t* t1, int64_t nq_cap, int nb,
                                                              int nsplit, uint32_t* sink) {
   const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int split = blockIdx.x;
   const int64_t head = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
   const int nquads = (nb + 3) >> 2;
-  const int gw = split * WPB + w, nw = nsplit * WPB;
+  const int gw = split * W + w, nw = nsplit * W;
   const int q0 = (int)(((int64_t)gw * nquads) / nw), q1 = (int)(((int64_t)(gw + 1) * nquads) / nw);
   if (q0 >= q1) return;
   const uint8_t* base = t1 + head * nq_cap * QUAD_BYTES;
@@ -732,12 +734,17 @@ __global__ __launch_bounds__(64 * WPB, 1) void stream_read_kernel(const uint8_t*
     sink[0] = acc.x;
 }
 
-int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt,
+int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid, bool nt, int wpb,
                            uint32_t* sink, hipStream_t st) {
-  if (nt)
-    hipLaunchKernelGGL(stream_read_kernel<true>, grid, dim3(64 * WPB), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
-  else
-    hipLaunchKernelGGL(stream_read_kernel<false>, grid, dim3(64 * WPB), 0, st, t1, nq_cap, nb, (int)grid.x, sink);
+  if (wpb != 4 && wpb != 8) return CQA_ERR_INVALID_ARG;
+#define CQA_LAUNCH_SR(NTV, WV) \
+  hipLaunchKernelGGL((stream_read_kernel<NTV, WV>), grid, dim3(64 * WV), 0, st, t1, nq_cap, nb, (int)grid.x, sink)
+  if (nt) {
+    if (wpb == 8) CQA_LAUNCH_SR(true, 8); else CQA_LAUNCH_SR(true, 4);
+  } else {
+    if (wpb == 8) CQA_LAUNCH_SR(false, 8); else CQA_LAUNCH_SR(false, 4);
+  }
+#undef CQA_LAUNCH_SR
   CQA_HIP(hipGetLastError());
   return CQA_OK;
 }
@@ -747,13 +754,16 @@ int32_t launch_stream_read(const uint8_t* t1, int64_t nq_cap, int nb, dim3 grid,
 int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t ev0, hipEvent_t ev1,
                           hipStream_t st) {
   const bool lm = a.blk_logmass != nullptr;
-#define CQA_LAUNCH_Q(GG, NTV, Q8V)                                                                 \
+  if (a.wpb != 4 && a.wpb != 8) return CQA_ERR_INVALID_ARG;
+#define CQA_LAUNCH_W(GG, NTV, Q8V, WV)                                                             \
   if (lm)                                                                                          \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV, Q8V>), grid, dim3(64 * WPB), 0, st, \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, true, NTV, Q8V, WV>), grid, dim3(64 * WV), 0, st, \
                           ev0, ev1, 0, a);                                                         \
   else                                                                                             \
-    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV, Q8V>), grid, dim3(64 * WPB), 0,   \
+    hipExtLaunchKernelGGL((certified_split_mfma_kernel<GG, false, NTV, Q8V, WV>), grid, dim3(64 * WV), 0,   \
                           st, ev0, ev1, 0, a);
+#define CQA_LAUNCH_Q(GG, NTV, Q8V)                                                                 \
+  if (a.wpb == 8) { CQA_LAUNCH_W(GG, NTV, Q8V, 8) } else { CQA_LAUNCH_W(GG, NTV, Q8V, 4) }
 #define CQA_LAUNCH_NT(GG, NTV)                                                                     \
   if (a.int8_query) { CQA_LAUNCH_Q(GG, NTV, true) } else { CQA_LAUNCH_Q(GG, NTV, false) }
 #define CQA_LAUNCH(GG)                                                                             \
@@ -767,6 +777,7 @@ int32_t launch_split_mfma(const DecodeArgs& a, int group, dim3 grid, hipEvent_t 
 #undef CQA_LAUNCH
 #undef CQA_LAUNCH_NT
 #undef CQA_LAUNCH_Q
+#undef CQA_LAUNCH_W
   return CQA_OK;
 }
 
