@@ -99,3 +99,29 @@ def test_t128k_sampled_heads_and_error_paths():
         O, cert, flags = gc.results()
         ref = oc.certified_decode(q, oracle.Tolerances(int8_query=True), heads=[(0, 9)])[0]
         assert_head_matches(ref, O[0, 9], cert[0, 9], flags[0, 9], ("t128k enqueue", 9))
+
+
+def test_more_sequences_than_compute_units():
+    """With more (batch, kv-head) sequences than compute units the split pass runs in workgroups of
+    four waves, two per compute unit: both scoring modes, GQA 2, one split and a forced three."""
+    say("280 sequences (batch 70 x 4 kv heads, GQA 2): four-wave workgroups, default and int8 query, 1 and 3 splits")
+    bt, hq, hkv, n = 70, 8, 4, 16 * 23 + 7
+    rng = np.random.default_rng(5)
+    k = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    v = rng.standard_normal((bt, hkv, n, 128)).astype(np.float16)
+    q = (rng.standard_normal((bt, hq, 128)) * 1.5).astype(np.float16)
+    rows = [0, 33, 69]
+    oc = oracle.OracleLayerCache(len(rows), hkv)
+    oc.append(k[rows], v[rows])
+    with GpuLayerCache(bt, hq, hkv, n + 16) as gc:
+        gc.append(k, v)
+        for splits in (0, 3):
+            gc.cqa.cqa_set_splits(gc.h, splits)
+            for tol in (oracle.Tolerances(), oracle.Tolerances(int8_query=True)):
+                O, cert, flags, glm = gc.certified_decode(q, to_gpu_tol(gc.cqa, tol), want_logmass=True)
+                ref = oc.certified_decode(q[rows], tol)
+                for (i, h), r in zip([(i, h) for i in range(len(rows)) for h in range(hq)], ref):
+                    b = rows[i]
+                    assert_head_matches(r, O[b, h], cert[b, h], flags[b, h], (splits, tol.int8_query, b, h))
+                    assert np.abs(glm[b, h] - r["blk_logmass"]).max() <= 1e-4
+        gc.cqa.cqa_set_splits(gc.h, 0)
