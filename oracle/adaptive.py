@@ -50,11 +50,13 @@ Readings where the paper is silent or offers a choice (the HIP path follows the 
   multiply-xorshift mixer with constants 0x7FEB352D / 0x846CA68B applied to
   block * 0x9E3779B1 ^ group * 0x85EBCA77 ^ seed * 0xC2B2AE3D; a block is explored when the
   result is below explore_frac * 2^32.
-* Ranking check at depth r = 1 over the promoted set F of the head's group:
-  (i) the block with the largest FP16 log-mass in F must be the block with the
-  largest INT8 log-mass in F; (ii) boundary: no unpromoted block may have
-  l_b^int8 + Delta_h (+ eps_guard) > the largest FP16 log-mass in F.  Either
-  failure sets RANK.  The optional rank_min_mass gate of the one-pass path
+* Ranking check at depth r (Tolerances.rank_depth, the paper's configurable depth;
+  default 1) over the head's promoted set F (the group's union, or the head's own
+  selection with per_head): (i) the r blocks with the largest FP16 log-masses in F
+  must be, in the same order, the r blocks with the largest INT8 log-masses in F
+  (ties by lower index; fewer than r promoted blocks: r = their number);
+  (ii) boundary: no unpromoted block may have l_b^int8 + Delta_h (+ eps_guard) >
+  the r-th largest FP16 log-mass in F.  Either failure sets RANK.  The optional rank_min_mass gate of the one-pass path
   applies here too (0 = the paper's unconditional check).
 """
 from __future__ import annotations
