@@ -405,79 +405,98 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   int32_t* slot = a.slot + grp * a.slot_stride;
   int32_t* ulist = a.ulist + grp * MAX_UNION;
   const int words = (a.nb + 31) >> 5;
-  __shared__ int scan[256];
+  __shared__ int itot_c[4];
   __shared__ int s_base;
-  if (tid == 0) s_base = 0;
-  __syncthreads();
-  for (int w0 = 0; w0 < words; w0 += 256) {
-    const int w = w0 + tid;
-    uint32_t kbits = 0u, vbits = 0u;
-    uint32_t kh[4] = {0u, 0u, 0u, 0u}, vh[4] = {0u, 0u, 0u, 0u};   // per head
-    if (w < words) {
-      for (int i = 0; i < a.group; ++i) {
-        kh[i] = um[i * a.mask_words + w];
-        um[i * a.mask_words + w] = 0u;
-        kbits |= kh[i];
-        if (vm != nullptr) {
-          vh[i] = vm[i * a.mask_words + w];
-          vm[i * a.mask_words + w] = 0u;
-          vbits |= vh[i];
+  // The flag words of the previous call are taken back through its list (the words of all other
+  // blocks are zero already: at creation every word is, and only listed blocks are ever set), so
+  // a call touches a few dozen words per group instead of one per block.
+  {
+    const int n_prev = min(a.ucount[grp], MAX_UNION);
+    for (int i = tid; i < n_prev; i += 256) {
+      const int blk = ulist[i];
+      if (blk >= 0 && blk < a.slot_stride) slot[blk] = 0;
+    }
+  }
+  __syncthreads();                       // (with its fence) before the same words are set again
+  // thread t owns the contiguous run of mask words [t wpt, (t + 1) wpt): the list comes out ascending
+  constexpr int WPT_MAX = 8;             // up to 256 x 8 x 32 blocks (1M tokens) in one sweep
+  const int wpt = (words + 255) >> 8;
+  int base_total = 0;
+  for (int w00 = 0; w00 < words; w00 += 256 * WPT_MAX) {
+    const int wpt_here = min(wpt, WPT_MAX);
+    uint32_t kb[WPT_MAX], vb[WPT_MAX], khh[WPT_MAX][4], vhh[WPT_MAX][4];
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < WPT_MAX; ++u) {
+      const int w = w00 + tid * wpt_here + u;
+      uint32_t kbits = 0u, vbits = 0u;
+      uint32_t kh[4] = {0u, 0u, 0u, 0u}, vh[4] = {0u, 0u, 0u, 0u};   // per head
+      if (u < wpt_here && w < words) {
+        for (int i = 0; i < a.group; ++i) {
+          kh[i] = um[i * a.mask_words + w];
+          if (kh[i] != 0u) um[i * a.mask_words + w] = 0u;
+          kbits |= kh[i];
+          if (vm != nullptr) {
+            vh[i] = vm[i * a.mask_words + w];
+            if (vh[i] != 0u) vm[i * a.mask_words + w] = 0u;
+            vbits |= vh[i];
+          }
+        }
+        if (a.explore_threshold != 0u) {
+          uint32_t ebits = 0u;
+#pragma unroll 4
+          for (int j = 0; j < 32; ++j)
+            if (explore_mix((uint32_t)(w * 32 + j), (uint32_t)grp, a.explore_seed) < a.explore_threshold)
+              ebits |= 1u << j;
+          kbits |= ebits;                          // explored blocks are promoted for every head
+          for (int i = 0; i < a.group; ++i) kh[i] |= ebits;
+        }
+        if (w == words - 1 && (a.nb & 31)) {      // nothing past nb
+          kbits &= (1u << (a.nb & 31)) - 1u;
+          vbits &= (1u << (a.nb & 31)) - 1u;
+        }
+        for (int i = 0; i < 4; ++i) {
+          kh[i] = i < a.group ? (a.per_head ? kh[i] & kbits : kbits) : 0u;
+          vh[i] = i < a.group ? (a.per_head ? vh[i] & vbits : vbits) : 0u;
         }
       }
-      if (a.explore_threshold != 0u) {
-        uint32_t ebits = 0u;
-#pragma unroll 4
-        for (int j = 0; j < 32; ++j)
-          if (explore_mix((uint32_t)(w * 32 + j), (uint32_t)grp, a.explore_seed) < a.explore_threshold)
-            ebits |= 1u << j;
-        kbits |= ebits;                          // explored blocks are promoted for every head
-        for (int i = 0; i < a.group; ++i) kh[i] |= ebits;
-      }
-      if (w == words - 1 && (a.nb & 31)) {      // nothing past nb
-        kbits &= (1u << (a.nb & 31)) - 1u;
-        vbits &= (1u << (a.nb & 31)) - 1u;
-      }
+      kb[u] = kbits;
+      vb[u] = vbits;
+#pragma unroll
       for (int i = 0; i < 4; ++i) {
-        kh[i] = i < a.group ? (a.per_head ? kh[i] & kbits : kbits) : 0u;
-        vh[i] = i < a.group ? (a.per_head ? vh[i] & vbits : vbits) : 0u;
+        khh[u][i] = kh[i];
+        vhh[u][i] = vh[i];
       }
+      cnt += __popc(kbits | vbits);
     }
-    const uint32_t bits = kbits | vbits;
-    const int cnt = __popc(bits);
-    scan[tid] = cnt;
-    __syncthreads();
-    for (int s = 1; s < 256; s <<= 1) {
-      const int v = tid >= s ? scan[tid - s] : 0;
-      __syncthreads();
-      scan[tid] += v;
-      __syncthreads();
-    }
-    int pos = s_base + scan[tid] - cnt;          // slot of my word's first promoted block
-    if (w < words) {
-      for (int j = 0; j < 32; ++j) {
+    int pos = base_total + block_scan_incl<int>(cnt, itot_c, tid) - cnt;   // slot of my run's first promoted block
+    if (tid == 255) s_base = pos + cnt;
+#pragma unroll
+    for (int u = 0; u < WPT_MAX; ++u) {
+      const int w = w00 + tid * wpt_here + u;
+      uint32_t bits = kb[u] | vb[u];
+      while (bits != 0u) {
+        const int j = __ffs((int)bits) - 1;
+        bits &= bits - 1u;
         const int blk = w * 32 + j;
-        if (blk >= a.nb) break;
-        if ((bits >> j) & 1u) {
-          // the list cannot overflow (4 heads x MAX_K_LIMIT for keys and as many for values);
-          // a block that did not fit would simply stay unpromoted
-          const bool fits = pos < MAX_UNION;
-          uint32_t f = ((kbits >> j) & 1u) | (((vbits >> j) & 1u) << 1);
+        // the list cannot overflow (4 heads x MAX_K_LIMIT for keys and as many for values);
+        // a block that did not fit would simply stay unpromoted
+        if (pos < MAX_UNION) {
+          uint32_t f = ((kb[u] >> j) & 1u) | (((vb[u] >> j) & 1u) << 1);
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            f |= (((kh[i] >> j) & 1u) << (SLOT_HK_SHIFT + i)) | (((vh[i] >> j) & 1u) << (SLOT_HV_SHIFT + i));
-          slot[blk] = fits ? (int)f : 0;
-          if (fits) ulist[pos] = blk;
-          ++pos;
-        } else {
-          slot[blk] = 0;
+            f |= (((khh[u][i] >> j) & 1u) << (SLOT_HK_SHIFT + i)) | (((vhh[u][i] >> j) & 1u) << (SLOT_HV_SHIFT + i));
+          slot[blk] = (int)f;
+          ulist[pos] = blk;
         }
+        ++pos;
       }
     }
     __syncthreads();
-    if (tid == 255) s_base += scan[255];
-    __syncthreads();
+    base_total = s_base;
   }
-  if (tid == 0) a.ucount[grp] = min(s_base, MAX_UNION);
+  const int s_base_final = base_total;
+  if (tid == 0) a.ucount[grp] = min(s_base_final, MAX_UNION);
   if (a.sc_slots <= 0) return;
 
   // ---- FP16 scratch: which listed blocks are held on the device, and where the others go.
@@ -487,7 +506,7 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
   // only in steps that miss -- never one used in this step; the pass that reads their originals
   // from the host stores them into the slot (SLOT_FILL for the keys, SLOT_VFILL for the values).
   // Misses beyond the free slots are read from the host without being kept.
-  const int n = min(s_base, MAX_UNION);
+  const int n = min(s_base_final, MAX_UNION);
   int32_t* map = a.sc_map + grp * a.sc_map_stride;
   int32_t* tag = a.sc_tag + grp * (int64_t)a.sc_cap;
   uint32_t* age = a.sc_age + grp * (int64_t)a.sc_cap;
@@ -686,44 +705,82 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
       }
     }
   }
-  __shared__ float s_bx[ART], s_b8[ART], s_tm[ART], s_mc[ART];
+  // reduce over the workgroup: shuffles inside each wave, then the waves' results through LDS
+  constexpr int NW = ART / 64;
+  __shared__ float s_bx[ART], s_b8[ART];     // (the full-size arrays serve the deeper places below)
   __shared__ int s_ix[ART], s_i8[ART];
-  __shared__ double s_mass[ART], s_l8u[ART], s_ev8u[ART];
+  __shared__ float w_bx[NW], w_b8[NW], w_tm[NW], w_mc[NW];
+  __shared__ int w_ix[NW], w_i8[NW];
+  __shared__ double w_mass[NW], w_l8u[NW], w_ev8u[NW];
+  __shared__ float s_top[4];
+  __shared__ int s_topi[2];
+  __shared__ double s_sum[3];
   __shared__ float wsm[64];
   __shared__ AdaptiveIn s_ad;
-  s_bx[tid] = best_x;
-  s_ix[tid] = ix;
-  s_b8[tid] = best_8;
-  s_i8[tid] = i8;
-  s_tm[tid] = tail_max;
-  s_mc[tid] = maxc8;
-  s_mass[tid] = tail_mass;
-  s_l8u[tid] = l8u;
-  s_ev8u[tid] = ev8u;
-  __syncthreads();
-  for (int s = ART / 2; s > 0; s >>= 1) {
-    if (tid < s) {
-      // larger value wins; equal values: the lower block index (-1 = nothing seen loses)
-      const float ox = s_bx[tid + s];
-      const int oix = s_ix[tid + s];
-      if (oix >= 0 && (s_ix[tid] < 0 || ox > s_bx[tid] || (ox == s_bx[tid] && oix < s_ix[tid]))) {
-        s_bx[tid] = ox;
-        s_ix[tid] = oix;
-      }
-      const float o8 = s_b8[tid + s];
-      const int oi8 = s_i8[tid + s];
-      if (oi8 >= 0 && (s_i8[tid] < 0 || o8 > s_b8[tid] || (o8 == s_b8[tid] && oi8 < s_i8[tid]))) {
-        s_b8[tid] = o8;
-        s_i8[tid] = oi8;
-      }
-      s_tm[tid] = fmaxf(s_tm[tid], s_tm[tid + s]);
-      s_mc[tid] = fmaxf(s_mc[tid], s_mc[tid + s]);
-      s_mass[tid] += s_mass[tid + s];
-      s_l8u[tid] += s_l8u[tid + s];
-      s_ev8u[tid] += s_ev8u[tid + s];
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    // larger value wins; equal values: the lower block index (-1 = nothing seen loses)
+    const float ox = __shfl_xor(best_x, m);
+    const int oix = __shfl_xor(ix, m);
+    if (oix >= 0 && (ix < 0 || ox > best_x || (ox == best_x && oix < ix))) {
+      best_x = ox;
+      ix = oix;
     }
-    __syncthreads();
+    const float o8 = __shfl_xor(best_8, m);
+    const int oi8 = __shfl_xor(i8, m);
+    if (oi8 >= 0 && (i8 < 0 || o8 > best_8 || (o8 == best_8 && oi8 < i8))) {
+      best_8 = o8;
+      i8 = oi8;
+    }
+    tail_max = fmaxf(tail_max, __shfl_xor(tail_max, m));
+    maxc8 = fmaxf(maxc8, __shfl_xor(maxc8, m));
+    tail_mass += __shfl_xor(tail_mass, m);
+    l8u += __shfl_xor(l8u, m);
+    ev8u += __shfl_xor(ev8u, m);
   }
+  if ((tid & 63) == 0) {
+    const int w = tid >> 6;
+    w_bx[w] = best_x;
+    w_ix[w] = ix;
+    w_b8[w] = best_8;
+    w_i8[w] = i8;
+    w_tm[w] = tail_max;
+    w_mc[w] = maxc8;
+    w_mass[w] = tail_mass;
+    w_l8u[w] = l8u;
+    w_ev8u[w] = ev8u;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float bx = w_bx[0], b8 = w_b8[0], tm = w_tm[0], mc = w_mc[0];
+    int jx = w_ix[0], j8 = w_i8[0];
+    double ms = w_mass[0], lu = w_l8u[0], eu = w_ev8u[0];
+    for (int w = 1; w < NW; ++w) {
+      if (w_ix[w] >= 0 && (jx < 0 || w_bx[w] > bx || (w_bx[w] == bx && w_ix[w] < jx))) {
+        bx = w_bx[w];
+        jx = w_ix[w];
+      }
+      if (w_i8[w] >= 0 && (j8 < 0 || w_b8[w] > b8 || (w_b8[w] == b8 && w_i8[w] < j8))) {
+        b8 = w_b8[w];
+        j8 = w_i8[w];
+      }
+      tm = fmaxf(tm, w_tm[w]);
+      mc = fmaxf(mc, w_mc[w]);
+      ms += w_mass[w];
+      lu += w_l8u[w];
+      eu += w_ev8u[w];
+    }
+    s_top[0] = bx;
+    s_top[1] = b8;
+    s_top[2] = tm;
+    s_top[3] = mc;
+    s_topi[0] = jx;
+    s_topi[1] = j8;
+    s_sum[0] = ms;
+    s_sum[1] = lu;
+    s_sum[2] = eu;
+  }
+  __syncthreads();
   // ---- ranking check (the paper's "Ranking-Consistency Check" with its boundary verification)
   //      at depth r: the r best promoted blocks under the FP16 and under the INT8 log-masses must
   //      be the same blocks in the same order, and no unpromoted block may reach the r-th FP16
@@ -731,8 +788,8 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
   //      place is one more arg-max over the group's listed blocks (a few dozen, held in registers),
   //      restricted to what comes after the previous place in the order (larger log-mass first,
   //      equal log-masses by lower index).  Fewer promoted blocks than r: the depth is their number.
-  const float top_x = s_bx[0], top_8 = s_b8[0];
-  const int top_ix = s_ix[0], top_i8 = s_i8[0];
+  const float top_x = s_top[0], top_8 = s_top[1];
+  const int top_ix = s_topi[0], top_i8 = s_topi[1];
   bool disagree = top_ix >= 0 && top_ix != top_i8;
   float kth_x = top_x;
   const int depth = min(ra.tol.rank_depth, MAX_RANK_DEPTH);
@@ -807,21 +864,22 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
   }
   if (tid == 0) {
     AdaptiveIn ad;
-    ad.alpha = (float)s_mass[0];
+    ad.alpha = (float)s_sum[0];
     ad.delta = delta;
     ad.top_block = top_ix;
     ad.top_fp16 = top_ix >= 0 ? top_x : -INFINITY;
     ad.kth_fp16 = top_ix >= 0 ? kth_x : -INFINITY;
-    const bool has_tail = s_tm[0] > -INFINITY;
-    ad.tail_ub = has_tail ? s_tm[0] + delta : -INFINITY;
-    const bool boundary = top_ix >= 0 && has_tail && s_tm[0] + delta + ra.tol.eps_guard > kth_x;
+    const float tmax = s_top[2];
+    const bool has_tail = tmax > -INFINITY;
+    ad.tail_ub = has_tail ? tmax + delta : -INFINITY;
+    const bool boundary = top_ix >= 0 && has_tail && tmax + delta + ra.tol.eps_guard > kth_x;
     ad.rank_fail = (disagree || boundary) ? 1 : 0;
     ad.precond = (a.score_dev != nullptr && a.score_dev[row] > delta + ra.tol.eps_guard) ? 1 : 0;
     ad.pos_set0 = a.pos_set0;
     ad.pos_set1 = a.pos_set1;
-    ad.L8u = (float)s_l8u[0];
-    ad.EV8u = (float)s_ev8u[0];
-    ad.maxc8 = s_mc[0];
+    ad.L8u = (float)s_sum[1];
+    ad.EV8u = (float)s_sum[2];
+    ad.maxc8 = s_top[3];
     ad.lse8 = lse8;
     s_ad = ad;
     a.alpha_out[row] = ad.alpha;
