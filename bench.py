@@ -627,6 +627,12 @@ def main() -> int:
                         "by the memory-side cache)",
             },
         },
+        "step_level": {
+            "achieved": alg_bytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s",
+            "frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "what": "the same algorithmic bytes over the whole step's time (ms_per_step): the split pass plus "
+                    "the reduction, the ladder kernel, the append and their dispatch gaps",
+        },
         "kernel_only": {
             "ms_per_step": ko_ms,
             "steps_per_s": 1e3 / ko_ms,
