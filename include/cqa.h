@@ -225,9 +225,10 @@ int32_t cqa_certified_decode(cqa_cache* c, int32_t layer, const void* q_fp16_dev
  * is resolved when the cache is created).  The call itself allocates nothing and
  * calls no allocating routine; inputs and outputs are the caller's as before.
  * Limit: batch * n_q_heads * splits * 576 bytes must fit the array, where splits
- * is what cqa_decode_splits reports (about compute units / (batch * n_kv_heads),
- * so any shape fits unless a test hook forces more splits); beyond it the call fails
- * with CQA_ERR_SCRATCH and touches nothing.  Every such call on one GPU uses that
+ * is what cqa_decode_splits reports: about compute units / (batch * n_kv_heads),
+ * and 1 once there are more sequences than compute units, so a shape fits up to
+ * batch * n_q_heads = 7281 rows (unless a test hook forces more splits); beyond
+ * it the call fails with CQA_ERR_SCRATCH and touches nothing.  Every such call on one GPU uses that
  * GPU's one array, whatever the cache: calls that overlap on a GPU (two streams,
  * two caches) race and must be ordered by the caller.  The array keeps the last
  * call's contents; every word a call reads it has written first, so nothing needs
