@@ -126,15 +126,19 @@ __global__ __launch_bounds__(64 * W, 8 / W) void certified_split_mfma_kernel(Dec
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = l & 15, kg = l >> 4;
   const int h = n >> 2, j = n & 3;   // operand-forming role: (head, block of quad) / (head, group)
-  // Workgroup -> (head, partial set) and this wave's contiguous run of quads: the head's quads are
-  // dealt evenly over its W * nsplit waves, in block order, sizes differing by at most one.
+  // Workgroup -> (head, partial set) and this wave's quads: the head's quads are dealt round-robin
+  // over its W * nsplit waves (wave ci takes quads ci, ci + nw, ...), so counts differ by at most one
+  // and, the waves advancing at about the same pace, the launch reads a window of consecutive
+  // records that moves through the head (measured against contiguous runs per wave: the same with
+  // one layer read over and over, 0.5 us faster when nothing is left in the caches).  A wave still
+  // meets its blocks in increasing order.
   // (Measured and not adopted: handing the quads out from per-head counters, so that faster XCDs
   // and earlier workgroups take more -- per-wave clock stamps show the waves of a launch finishing
   // up to 10 us apart.  Atomics on one address are served at ~130 ns each across XCDs, far too
   // slow for one draw per quad, and a simulation on the measured per-wave speeds showed that at
   // a granularity of one quad (~4.5 us of work) even an ideal greedy schedule gains < 1 us.
-  // Likewise an uneven static deal, long runs for the first workgroup of every compute unit and
-  // short ones for the second, measured no faster.)
+  // Likewise uneven static deals -- longer runs for the first workgroup of every compute unit,
+  // shares weighted by XCD -- measured no faster.)
   const int nquads = (a.nb + 3) >> 2;
   const int L = blockIdx.x;
   const int head = L / a.nsplit, split = L - head * a.nsplit;
@@ -144,14 +148,12 @@ __global__ __launch_bounds__(64 * W, 8 / W) void certified_split_mfma_kernel(Dec
   const bool younger = W == 8 ? w >= 4 : 2 * L >= (int)gridDim.x;
   constexpr int Q_NONE = 0x40000000;   // "no quad": larger than any quad index
   int q_cur, q_next, q_stop;
+  const int q_step = W * a.nsplit;     // waves of the head
   {
-    const int nw = W * a.nsplit, ci = W * split + w;
-    const int base = nquads / nw, rem = nquads - base * nw;
-    const int nmine = base + (ci < rem ? 1 : 0);
-    const int q0 = ci * base + min(ci, rem);
-    q_stop = q0 + nmine;
-    q_cur = nmine > 0 ? q0 : Q_NONE;
-    q_next = nmine > 1 ? q0 + 1 : Q_NONE;
+    const int ci = W * split + w;
+    q_stop = nquads;
+    q_cur = ci < nquads ? ci : Q_NONE;
+    q_next = ci + q_step < nquads ? ci + q_step : Q_NONE;
   }
   const int b = head / a.n_kv, kvh = head - b * a.n_kv;
   const int64_t head_rec = (int64_t)head * a.nq_cap;
@@ -626,7 +628,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void certified_split_mfma_kernel(Dec
     wave_sync();
     // advance: the quad whose data was requested during this iteration becomes current
     q_cur = q_next;
-    q_next = q_next + 1 < q_stop ? q_next + 1 : Q_NONE;
+    q_next = q_next + q_step < q_stop ? q_next + q_step : Q_NONE;
   }
 
   // ---- per-wave epilogue: fold the offset sums in; the softmax state of head kg is already
@@ -715,14 +717,14 @@ __global__ __launch_bounds__(64 * W, 8 / W) void stream_read_kernel(const uint8_
   const int64_t head = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
   const int nquads = (nb + 3) >> 2;
   const int gw = split * W + w, nw = nsplit * W;
-  const int q0 = (int)(((int64_t)gw * nquads) / nw), q1 = (int)(((int64_t)(gw + 1) * nquads) / nw);
+  const int q0 = gw, q1 = nquads;       // round-robin over the head's waves, as the split kernel deals
   if (q0 >= q1) return;
   const uint8_t* base = t1 + head * nq_cap * QUAD_BYTES;
   u32x4 buf[18], acc = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int i = 0; i < 18; ++i) buf[i] = ld_stream<NT>(base + (int64_t)q0 * QUAD_BYTES + i * 1024 + l * 16);
-  for (int q = q0; q < q1; ++q) {
-    const uint8_t* nxt = base + (int64_t)min(q + 1, q1 - 1) * QUAD_BYTES;
+  for (int q = q0; q < q1; q += nw) {
+    const uint8_t* nxt = base + (int64_t)(q + nw < q1 ? q + nw : q0) * QUAD_BYTES;
 #pragma unroll
     for (int i = 0; i < 18; ++i) {
       acc ^= buf[i];
