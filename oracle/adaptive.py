@@ -50,6 +50,13 @@ Readings where the paper is silent or offers a choice (the HIP path follows the 
   multiply-xorshift mixer with constants 0x7FEB352D / 0x846CA68B applied to
   block * 0x9E3779B1 ^ group * 0x85EBCA77 ^ seed * 0xC2B2AE3D; a block is explored when the
   result is below explore_frac * 2^32.
+* Quantised-query scoring (Tolerances.int8_query, the paper's optional INT8 x INT8 scoring of
+  "Per-Channel Key Scoring"): the scoring pass scores every sealed block with the 8-bit scaled
+  query; selection, Rung 1 and the ranking check read its log-masses, its Delta_h (which
+  contains the explicit third term) is the Delta of the bound, blocks left in INT8 keep its
+  scores in the attend pass, promoted blocks are scored exactly from FP16 keys and the exact
+  query.  The score-consistency check compares a promoted token's FP16 score with the
+  quantised-query score.
 * Ranking check at depth r (Tolerances.rank_depth, the paper's configurable depth;
   default 1) over the head's promoted set F (the group's union, or the head's own
   selection with per_head): (i) the r blocks with the largest FP16 log-masses in F
@@ -210,7 +217,8 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
                eta: np.ndarray, nu: np.ndarray, k_trail16: np.ndarray, v_trail16: np.ndarray,
                promoted: np.ndarray, l_int8: np.ndarray, lse_int8: float, delta_h: float,
                tol: att.Tolerances, v_promoted: np.ndarray | None = None,
-               v16_sealed: np.ndarray | None = None, canary: bool = False) -> dict:
+               v16_sealed: np.ndarray | None = None, canary: bool = False,
+               s_scored: np.ndarray | None = None) -> dict:
     """The attend pass with mask-gated key precision, one head, one step.
 
     k_hat float64 [NB*B, d] INT8 reconstructions; k16_sealed float16 [NB*B, d] the FP16
@@ -218,6 +226,12 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     pass's block log-masses, total log-mass and Delta_h for this head.
     Values are INT4 reconstructions, except in the blocks of v_promoted (bool [NB], optional),
     which use the FP16 originals v16_sealed [NB*B, d] and count with eta_b = 0.
+    s_scored float64 [NB*B] (optional): the scoring pass's own scores of the sealed tokens,
+    given when that pass scored with a quantised scaled query (Tolerances.int8_query): the
+    blocks left in INT8 then keep exactly those scores (scoring and attending are one pass
+    over them), the promoted blocks are scored exactly from their FP16 keys as always, and
+    delta_h already carries the third error term of the quantised query, so the tail theorem
+    and the key bound hold with it unchanged.
     """
     q = q16.astype(np.float64)
     d = q.shape[0]
@@ -227,6 +241,8 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     tok_prom = np.repeat(np.asarray(promoted, dtype=bool), blk)
     k_mix = np.where(tok_prom[:, None], k16_sealed.astype(np.float64), k_hat)
     s_seal = (k_mix @ q) * inv if nb else np.zeros(0)
+    if s_scored is not None and nb:
+        s_seal = np.where(tok_prom, s_seal, np.asarray(s_scored, dtype=np.float64))
     r = k_trail16.shape[0]
     kt = k_trail16.astype(np.float64)
     vt = v_trail16.astype(np.float64)
@@ -264,7 +280,7 @@ def mixed_head(q16: np.ndarray, k_hat: np.ndarray, k16_sealed: np.ndarray, v_hat
     # score-consistency check: FP16 against INT8 scores on the key-promoted tokens
     score_dev = 0.0
     if nb and tok_prom.any():
-        s_int8 = (k_hat[tok_prom] @ q) * inv
+        s_int8 = (k_hat[tok_prom] @ q) * inv if s_scored is None else np.asarray(s_scored, dtype=np.float64)[tok_prom]
         score_dev = float(np.abs(s_seal[tok_prom] - s_int8).max())
     flags = 0
     if canary and score_dev > delta_h + tol.eps_guard:
@@ -315,7 +331,8 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
         for i in range(g):
             h = kh * g + i
             sc = att.certified_head(q16[b, h], k_hat, v_hat, cache.sigma[b, kh], cache.eta[b, kh],
-                                    cache.nu[b, kh], k_tr, v_tr, att.Tolerances())
+                                    cache.nu[b, kh], k_tr, v_tr, att.Tolerances(int8_query=tol.int8_query),
+                                    k_codes=cache.k_codes[b, kh], z=cache.z[b, kh])
             sel = select_blocks(sc["blk_logmass"], sc["lse"], par)
             k = rung1_expand(sel, sc["delta_h"], sc["v_max"], tol, par)
             scoring.append(sc)
@@ -334,7 +351,8 @@ def adaptive_decode(cache, q16: np.ndarray, tol: att.Tolerances, par: SelectorPa
             res = mixed_head(q16[b, h], k_hat, cache.k16[b, kh, :nb * qz.B], v_hat, cache.eta[b, kh],
                              cache.nu[b, kh], k_tr, v_tr, f_keys, sc["blk_logmass"], sc["lse"],
                              sc["delta_h"], tol, v_promoted=f_vals,
-                             v16_sealed=cache.v16[b, kh, :nb * qz.B], canary=par.canary)
+                             v16_sealed=cache.v16[b, kh, :nb * qz.B], canary=par.canary,
+                             s_scored=sc["scores_sealed"] if tol.int8_query else None)
             res.update(k_star=ks[i], selected=picks[i], promoted=f_keys, scoring=sc,
                        v_selected=vpicks[i], v_promoted=f_vals, group_promoted=union,
                        group_v_promoted=vunion)

@@ -146,3 +146,87 @@ def test_total_bound_holds_with_the_quantised_query(seed, n, trail, q_scale, k_s
     s_all = np.concatenate([r["scores_sealed"], K[n:] @ q / math.sqrt(128)])
     assert np.allclose(r["weights"], scipy.special.softmax(s_all), rtol=1e-12, atol=1e-16)
     assert abs(r["lse"] - scipy.special.logsumexp(s_all)) < 1e-10
+
+
+# ---------------------------------------------------------------- the adaptive path in this mode
+
+def _small_cache(seed, n_tokens=300, scale=1.0, outlier=False):
+    import oracle
+    rng = np.random.Generator(np.random.Philox(seed))
+    k = (rng.standard_normal((1, 1, n_tokens, 128)) * scale).astype(np.float32)
+    if outlier:
+        k[..., 5] *= 20.0
+    v = rng.standard_normal((1, 1, n_tokens, 128)).astype(np.float32)
+    q = (rng.standard_normal((1, 4, 128)) * 1.5).astype(np.float16)
+    oc = oracle.OracleLayerCache(1, 1)
+    oc.append(k.astype(np.float16), v.astype(np.float16))
+    return oc, q
+
+
+@pytest.mark.parametrize("seed,scale,outlier", [(0, 1.0, False), (1, 2.5, True), (2, 0.6, False), (3, 4.0, True)])
+def test_adaptive_path_with_the_quantised_query(seed, scale, outlier):
+    """Adaptive precision on top of quantised-query scoring.  Special cases that reduce to known
+    results (nothing promoted = the one-pass result of the mode; everything promoted = textbook
+    attention on the FP16 keys), token-level brute force of the mixed scores, the tail theorem
+    with the widened Delta_h and the end-to-end bound against dense attention on the originals."""
+    from oracle import adaptive as ad
+    oc, q = _small_cache(100 + seed, n_tokens=16 * 18 + 11, scale=scale, outlier=outlier)
+    nb = oc.n_blocks
+    K = oc.k16[0, 0].astype(np.float64)
+    V = oc.v16[0, 0].astype(np.float64)
+    tol8 = Tolerances(int8_query=True, key_bound_mode=1, rank_depth=1)
+    one_pass = oc.certified_decode(q, Tolerances(int8_query=True, key_bound_mode=1))
+    # (i) nothing promoted: the one-pass result of the mode, bit for bit in the oracle's arithmetic
+    none = ad.adaptive_decode(oc, q, tol8, ad.SelectorParams(tau_cov=0.0, k_min=0, k_max=0, k_limit=0))
+    for h in range(4):
+        r = none[(0, h)]
+        assert not r["promoted"].any()
+        assert np.allclose(r["O"], one_pass[h]["O"], rtol=1e-13, atol=1e-15)
+        assert abs(r["E_key"] - one_pass[h]["E_key"]) <= 1e-12 * max(1.0, one_pass[h]["E_key"])
+        assert r["delta_h"] == one_pass[h]["delta_h"] and r["delta_h"] > oc.certified_decode(q, Tolerances())[h]["delta_h"]
+    # (ii) everything promoted: exact keys everywhere, the quantised query no longer matters
+    every = ad.adaptive_decode(oc, q, tol8, ad.SelectorParams(tau_cov=2.0, k_min=nb, k_max=nb, k_limit=nb))
+    v_hat = qz.dequantize_values(oc.v_codes[0, 0], oc.v_scale[0, 0], oc.v_offset[0, 0]).reshape(nb * 16, 128)
+    v_mixed = np.concatenate([v_hat, V[nb * 16:]])
+    for h in range(4):
+        r = every[(0, h)]
+        a = scipy.special.softmax(K @ q[0, h].astype(np.float64) / math.sqrt(128))
+        assert r["promoted"].all() and r["E_key"] == 0.0 and r["alpha_tail_hat"] == 0.0
+        assert np.allclose(r["O"], a @ v_mixed, rtol=1e-12, atol=1e-14)
+    # (iii) partial promotion
+    for tau, kmax in ((0.5, 3), (0.9, 7)):
+        part = ad.adaptive_decode(oc, q, tol8, ad.SelectorParams(tau_cov=tau, k_min=1, k_max=kmax, k_limit=kmax))
+        for h in range(4):
+            r = part[(0, h)]
+            qf = q[0, h].astype(np.float64)
+            sc = r["scoring"]
+            prom = r["promoted"]
+            assert prom.any() and not prom.all()
+            # the selection was made on the quantised-query log-masses
+            assert np.array_equal(sc["blk_logmass"], one_pass[h]["blk_logmass"])
+            # token-level brute force: promoted tokens from the FP16 keys and the exact query, the
+            # rest from integer products of the query codes and the key codes
+            t, s_q = quantize_scaled_query(q[0, h], oc.sigma[0, 0])
+            s = np.empty(nb * 16)
+            for tok in range(nb * 16):
+                b = tok // 16
+                if prom[b]:
+                    s[tok] = sum(float(qf[c]) * float(K[tok, c]) for c in range(128)) / math.sqrt(128)
+                else:
+                    acc = sum(int(t[b, c]) * int(oc.k_codes[0, 0][b, tok % 16, c]) for c in range(0, 128))
+                    cz = float(oc.z[0, 0][b].astype(np.float64) @ qf)
+                    s[tok] = (float(s_q[b]) * acc + cz) / math.sqrt(128)
+            s_all = np.concatenate([s, K[nb * 16:] @ qf / math.sqrt(128)])
+            w = scipy.special.softmax(s_all)
+            assert np.allclose(r["weights"], w, rtol=1e-10, atol=1e-16)
+            assert np.allclose(r["O"], w @ v_mixed, rtol=1e-10, atol=1e-13)
+            # tail theorem with the widened Delta_h: the true mass of the unpromoted blocks
+            a_true = scipy.special.softmax(K @ qf / math.sqrt(128))
+            tail_tok = np.concatenate([np.repeat(~prom, 16), np.zeros(oc.length - nb * 16, bool)])
+            assert a_true[tail_tok].sum() <= math.exp(2 * r["delta_h"]) * r["alpha_tail_hat"] * (1 + 1e-9) + 1e-15
+            # key-side distortion and the total bound, against dense attention on the originals
+            assert 2 * r["v_max"] * 0.5 * np.abs(a_true - r["weights"]).sum() <= r["E_key"] * (1 + 1e-9) + 1e-15
+            assert np.linalg.norm(r["O"] - a_true @ V) <= r["E_key"] + r["E_val"]
+            # the score-consistency figure: FP16 against quantised-query scores on promoted tokens
+            dev = np.abs(s - sc["scores_sealed"])[np.repeat(prom, 16)].max()
+            assert abs(r["score_dev"] - dev) < 1e-12 and r["score_dev"] <= r["delta_h"] * (1 + 2.0 ** -6) + 1e-12
