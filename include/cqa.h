@@ -108,10 +108,12 @@ typedef struct cqa_tolerances {
                                "one more Delta" for this third error source (mass_exp = 3);
                                here the block's score bound also gets the explicit term
                                (128 / sqrt d) sum_c |q~_c - s_q T_c|, so delta_h, E_key and the
-                               ranking test stay valid with mass_exp = 2.  One-pass calls with
-                               the matrix-core kernel only (the adaptive calls and the
-                               vector-ALU cross-check return CQA_ERR_UNSUPPORTED).  0: the
-                               scaled query is used unquantised (default).                */
+                               ranking test stay valid with mass_exp = 2.  In the adaptive
+                               calls the pass over all blocks scores this way, blocks left in
+                               INT8 keep those scores and promoted blocks are scored exactly
+                               from their FP16 keys.  (The vector-ALU cross-check kernel, a
+                               test hook, returns CQA_ERR_UNSUPPORTED.)  0: the scaled query
+                               is used unquantised (default).                            */
 } cqa_tolerances;
 
 /* Per-(batch, query head) certificate of one decode step.  40 bytes. */

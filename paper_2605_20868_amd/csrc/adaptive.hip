@@ -893,9 +893,9 @@ __global__ __launch_bounds__(ART) void adaptive_reduce_kernel(AdaptiveReduceArgs
 int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_tolerances& tol,
                         const cqa_selector& sel, float* O, cqa_head_cert* cert, uint32_t* flags,
                         uint32_t* flags_mirror, uint32_t mirror_tag, hipStream_t st) {
-  // the promoted-block pass re-scores blocks with the unquantised scaled query: the quantised-query
-  // mode exists in the one-pass calls only
-  if (tol.int8_query != 0) return CQA_ERR_UNSUPPORTED;
+  // quantised-query scoring: the pass over all blocks scores on the INT8 matrix cores, the
+  // promoted-block pass reproduces those scores for the blocks (and heads) that stay in INT8
+  if (tol.int8_query != 0 && c->variant != 0) return CQA_ERR_UNSUPPORTED;
   const int bt = c->desc.batch, hq = c->desc.n_q_heads, hkv = c->desc.n_kv_heads;
   const int g = hq / hkv;
   const int64_t len = c->length[layer];
@@ -1039,6 +1039,7 @@ int32_t launch_adaptive(Cache* c, int layer, const __half* q, const cqa_toleranc
   a.t2_v = c->t2_v + layer_head0 * c->desc.max_tokens * D;
   a.eta_out = nullptr;
   a.score_dev = sel.canary ? w.score_dev : nullptr;
+  a.int8_query = tol.int8_query;
   a.max_tokens = c->desc.max_tokens;
   a.split0 = nsplit;
   rc = launch_promoted_pass(a, g, dim3(2 * PROM_SPLITS, hkv, bt), st);

@@ -209,14 +209,37 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
     }
     const bool canary = PROM && kfp && a.score_dev != nullptr;
     if (!kfp || !kall || canary) {
-      float csum[G];
+      // a.int8_query: the scaled query is quantised to 8 bits per (head, block) exactly as the pass
+      // over all blocks does it (binary32 decisions: s_q = max|q~| / 127, T = round-half-even of
+      // q~ * fl(127 / max)), the codes T take the scaled query's place in the dot product, which is
+      // then exact integer arithmetic, and the residual sum |q~ - s_q T| widens the block's bound
+      float csum[G], tsum[G], rsum[G], sqv[G];
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        const float q0 = qv[h][0] * sg8.x, q1 = qv[h][1] * sg8.y;
-        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
-        // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
-        csum[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y - 128.0f * (q0 + q1);
+        float q0 = qv[h][0] * sg8.x, q1 = qv[h][1] * sg8.y;
         dsum[h] = fabsf(qv[h][0]) * sg8.x + fabsf(qv[h][1]) * sg8.y;
+        tsum[h] = 0.0f;
+        rsum[h] = 0.0f;
+        sqv[h] = 1.0f;
+        if (a.int8_query) {
+          float amax = fmaxf(fabsf(q0), fabsf(q1));
+#pragma unroll
+          for (int m = 1; m < 64; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m));
+          const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+          const float sq = amax / 127.0f;
+          const float MAGIC = 12582912.0f;   // 1.5 * 2^23: fl(x + MAGIC) - MAGIC = round-half-even(x)
+          const float t0 = fmaf(q0, inv, MAGIC) - MAGIC, t1 = fmaf(q1, inv, MAGIC) - MAGIC;
+          rsum[h] = fabsf(fmaf(-sq, t0, q0)) + fabsf(fmaf(-sq, t1, q1));
+          q0 = t0;
+          q1 = t1;
+          tsum[h] = t0 + t1;                 // small integers: every partial sum below is exact
+          sqv[h] = sq;
+          csum[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y;
+        } else {
+          // stored bytes are code + 128: fold the -128 * sum(q~) into the block constant
+          csum[h] = qv[h][0] * zz8.x + qv[h][1] * zz8.y - 128.0f * (q0 + q1);
+        }
+        reinterpret_cast<float2*>(&qs[w][h][0])[l] = make_float2(q0, q1);
       }
 #pragma unroll
       for (int m = 1; m < 64; m <<= 1) {
@@ -224,7 +247,15 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
         for (int h = 0; h < G; ++h) {
           csum[h] += __shfl_xor(csum[h], m);
           dsum[h] += __shfl_xor(dsum[h], m);
+          if (a.int8_query) {
+            tsum[h] += __shfl_xor(tsum[h], m);
+            rsum[h] += __shfl_xor(rsum[h], m);
+          }
         }
+      }
+      if (a.int8_query) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) dsum[h] = fmaf(256.0f, rsum[h], dsum[h]);   // (Delta_b + Delta^q_b) * 2 sqrt d
       }
       wave_sync();
       float dot[G];
@@ -245,7 +276,8 @@ __global__ __launch_bounds__(256) void certified_split_kernel(DecodeArgs a) {
       for (int h = 0; h < G; ++h) {
         dot[h] += __shfl_xor(dot[h], 16);
         dot[h] += __shfl_xor(dot[h], 32);
-        s8[h] = (dot[h] + csum[h]) * inv_sqrt_d;
+        // quantised query: s_q * (sum T byte - 128 sum T) + q.z, the bracket in exact integers
+        s8[h] = fmaf(sqv[h], dot[h] - 128.0f * tsum[h], csum[h]) * inv_sqrt_d;
       }
     }
     if (canary) {
@@ -572,8 +604,9 @@ int32_t launch_certified(Cache* c, int layer, const __half* q, const cqa_toleran
     a.stream_nt = stream_nt(c, nb);
     a.int8_query = tol.int8_query;
     a.wpb = waves_per_workgroup(c);
-    // the quantised-query scoring exists in the matrix-core pass only
-    if (tol.int8_query != 0 && (c->variant != 0 || eta_out != nullptr)) return CQA_ERR_UNSUPPORTED;
+    // the quantised-query scoring exists in the matrix-core pass (and in the promoted-block pass of
+    // the adaptive calls), not in the vector-ALU cross-check kernel
+    if (tol.int8_query != 0 && c->variant != 0) return CQA_ERR_UNSUPPORTED;
     const dim3 grid(nsplit, hkv, bt);
     const bool prof = c->prof_ev != nullptr && c->prof_n < c->prof_cap;
     hipEvent_t ev0 = prof ? c->prof_ev[2 * c->prof_n] : nullptr;

@@ -46,7 +46,7 @@ def gpu_adaptive(gc, q, tol, sel, step=False):
                         sel.canary, sel.explore_frac, sel.explore_seed, sel.per_head)
     # the scoring pass on its own first: its certificate (lse, Delta_h, V_max) is what the selector
     # reads inside the adaptive call, bit for bit (same kernel, same inputs)
-    gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(), gc.O, gc.cert, gc.flags, None)
+    gc.cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(int8_query=int(tol.int8_query)), gc.O, gc.cert, gc.flags, None)
     _, cert0, _ = gc.results()
     rung = None
     if step == "enqueue":
@@ -122,11 +122,13 @@ def check_against_oracle(oc, q, tol, sel, out, heads=None, served=None):
             if (b, h) not in heads:
                 continue
             sc = att.certified_head(q[b, h], k_hat, v_hat, oc.sigma[b, kh], oc.eta[b, kh], oc.nu[b, kh],
-                                    k_tr, v_tr, att.Tolerances())
+                                    k_tr, v_tr, att.Tolerances(int8_query=tol.int8_query),
+                                    k_codes=oc.k_codes[b, kh], z=oc.z[b, kh])
             assert np.abs(out["l8"][b, h] - sc["blk_logmass"]).max() <= 1e-4, ("scoring log-masses", b, h)
             ref = ad.mixed_head(q[b, h], k_hat, oc.k16[b, kh, :nb * 16], v_hat, oc.eta[b, kh], oc.nu[b, kh],
                                 k_tr, v_tr, fk, sc["blk_logmass"], sc["lse"], sc["delta_h"], tol,
-                                v_promoted=fv, v16_sealed=oc.v16[b, kh, :nb * 16], canary=sel.canary)
+                                v_promoted=fv, v16_sealed=oc.v16[b, kh, :nb * 16], canary=sel.canary,
+                                s_scored=sc["scores_sealed"] if tol.int8_query else None)
             if sel.canary:
                 assert abs(float(out["score_dev"][b, h]) - ref["score_dev"]) <= 1e-4, ("score deviation", b, h)
             w = ("adaptive", b, h)

@@ -11,7 +11,9 @@ import pytest
 
 import oracle
 import workloads
+from oracle import adaptive as ad
 from helpers import GpuLayerCache, assert_head_matches, to_gpu_tol
+from test_gpu_adaptive import check_against_oracle, gpu_adaptive, make_case
 
 pytestmark = pytest.mark.gpu
 
@@ -84,16 +86,16 @@ def test_t128k_sampled_heads_and_error_paths():
         compare(gc, oc, q, oracle.Tolerances(int8_query=True), "t128k", heads=[(0, 2), (0, 17), (0, 28)])
         cqa = gc.cqa
         qd = gc.to_dev(q)
-        # the vector-ALU cross-check kernel and the adaptive calls do not have the mode
+        # the vector-ALU cross-check kernel does not have the mode
         cqa.cqa_set_kernel_variant(gc.h, 1)
         with pytest.raises(cqa.CqaError) as e:
             cqa.cqa_certified_decode(gc.h, 0, qd, cqa.Tolerances(int8_query=True), gc.O, gc.cert, gc.flags, None)
         assert e.value.status == cqa.ERR_UNSUPPORTED
-        cqa.cqa_set_kernel_variant(gc.h, 0)
         with pytest.raises(cqa.CqaError) as e:
             cqa.cqa_adaptive_decode(gc.h, 0, qd, cqa.Tolerances(int8_query=True), cqa.Selector(), gc.O, gc.cert,
                                     gc.flags)
         assert e.value.status == cqa.ERR_UNSUPPORTED
+        cqa.cqa_set_kernel_variant(gc.h, 0)
         # the enqueue-only step takes it (split pass + reduction + device-resolved ladder)
         cqa.cqa_decode_step_enqueue(gc.h, 0, None, None, qd, cqa.Tolerances(int8_query=True), gc.O, gc.cert, gc.flags)
         O, cert, flags = gc.results()
@@ -125,3 +127,41 @@ def test_more_sequences_than_compute_units():
                     assert_head_matches(r, O[b, h], cert[b, h], flags[b, h], (splits, tol.int8_query, b, h))
                     assert np.abs(glm[b, h] - r["blk_logmass"]).max() <= 1e-4
         gc.cqa.cqa_set_splits(gc.h, 0)
+
+
+def test_adaptive_precision_on_top_of_the_quantised_query():
+    """The adaptive calls in this mode: the pass over all blocks scores with the 8-bit scaled query,
+    the promoted-block pass reproduces those scores for what stays in INT8 (per-group and per-head
+    promoted sets, value promotion, exploration and the score-consistency check on)."""
+    say("int8 query + adaptive precision: small planted case (all heads), both promoted-set modes; t128k sampled heads")
+    k, v, q = make_case(41, 2, 8, 2, 3000 + 5, peaked=[(0, 1, 333, 0.9), (0, 2, 1900, 1.1), (1, 4, 77, 0.8), (1, 6, 1500, 1.2)])
+    oc = oracle.OracleLayerCache(2, 2)
+    oc.append(k, v)
+    with GpuLayerCache(2, 8, 2, 3100) as gc:
+        gc.append(k, v)
+        plain = gpu_adaptive(gc, q, oracle.Tolerances(rank_depth=2), ad.SelectorParams(0.9, 1, 8, 16))
+        for per_head in (False, True):
+            for tau, kmin, kmax, vlim in ((0.9, 1, 8, 0), (0.995, 2, 16, 8)):
+                sel = ad.SelectorParams(tau, kmin, kmax, 2 * kmax, v_limit=vlim, canary=True, explore_frac=0.02,
+                                        explore_seed=7, per_head=per_head)
+                tol = oracle.Tolerances(int8_query=True, rank_depth=2, v_tol=0.01 if vlim else np.inf)
+                out = gpu_adaptive(gc, q, tol, sel)
+                check_against_oracle(oc, q, tol, sel, out)
+                assert (out["cert"]["delta_h"] > plain["cert"]["delta_h"]).all()    # the third term is in
+        # the enqueue-only step (nothing over a threshold and no ranking check: the ladder serves no head)
+        sel = ad.SelectorParams(0.9, 1, 8, 16)
+        tol = oracle.Tolerances(int8_query=True, rank_depth=0)
+        enq = gpu_adaptive(gc, q, tol, sel, step="enqueue")
+        check_against_oracle(oc, q, tol, sel, enq)
+        assert (enq["cert"]["served_rung"] == 0).all()
+    sh = workloads.SHAPES["t128k"]
+    k, v = workloads.make_kv("t128k", seed=0)
+    q = workloads.make_q("t128k", 4, seed=0)
+    oc = oracle.OracleLayerCache(sh.batch, sh.n_kv_heads)
+    oc.append(k, v)
+    with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 64) as gc:
+        gc.append(k, v)
+        sel = ad.SelectorParams(0.995, 2, 128, 128)
+        tol = oracle.Tolerances(int8_query=True, rank_depth=1, rank_min_mass=0.25)
+        out = gpu_adaptive(gc, q, tol, sel)
+        check_against_oracle(oc, q, tol, sel, out, heads=[(0, 4), (0, 5), (0, 7)])
