@@ -611,6 +611,36 @@ def test_random_small_shapes_and_selectors():
                 raise AssertionError(("case", case, bt, hkv, group, n, sel, tol)) from e
 
 
+def test_random_small_shapes_with_quantised_query_and_per_head_sets():
+    say("20 more seeded random small shapes: quantised-query scoring and per-head promoted sets drawn at random too")
+    rng = np.random.default_rng(78)
+    for case in range(20):
+        bt = int(rng.integers(1, 3))
+        hkv = int(rng.integers(1, 3))
+        group = int(rng.choice([1, 2, 4]))
+        hq = hkv * group
+        n = int(rng.choice([16, 31, 48, 161, 500, 1024, 1500]))
+        k, v, q = make_case(2000 + case, bt, hq, hkv, n, student=bool(rng.integers(0, 2)))
+        oc = oracle.OracleLayerCache(bt, hkv)
+        oc.append(k, v)
+        k_min = int(rng.integers(0, 4))
+        k_max = int(k_min + rng.integers(0, 40))
+        sel = ad.SelectorParams(float(rng.choice([0.5, 0.9, 0.995])), k_min, k_max,
+                                int(k_max + rng.integers(0, 64)), v_limit=int(rng.choice([0, 16])),
+                                canary=bool(rng.integers(0, 2)), explore_frac=float(rng.choice([0.0, 0.03])),
+                                explore_seed=case, per_head=bool(rng.integers(0, 2)))
+        tol = att.Tolerances(v_tol=float(rng.choice([np.inf, 0.05])), rank_depth=int(rng.choice([0, 1, 2])),
+                             rank_min_mass=float(rng.choice([0.0, 0.25])), int8_query=bool(case % 4 != 3),
+                             mass_exp=int(rng.choice([2, 3])))
+        with GpuLayerCache(bt, hq, hkv, n + 8) as gc:
+            gc.append(k, v)
+            out = gpu_adaptive(gc, q, tol, sel)
+            try:
+                check_against_oracle(oc, q, tol, sel, out)
+            except AssertionError as e:
+                raise AssertionError(("case", case, bt, hkv, group, n, sel, tol)) from e
+
+
 def test_ranking_check_at_depth_r():
     say("adaptive: ranking check at depths 1..8 on diffuse heads, flags and margins against the oracle")
     k, v, q = make_case(41, 2, 8, 2, 16 * 220 + 5)
