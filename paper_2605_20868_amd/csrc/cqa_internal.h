@@ -91,7 +91,11 @@ constexpr int MAX_SPLITS = 1024;     // upper bound on splits per (batch, kv-hea
 // ---- adaptive key precision ------------------------------------------------------
 constexpr int MAX_K_LIMIT = 512;            // blocks one head may promote (Rung-1 growth included)
 constexpr int MAX_UNION = 8 * MAX_K_LIMIT;  // blocks one KV group may promote (keys and values, <= 4 heads each)
-constexpr int PROM_SPLITS = 32;             // workgroups (= partial sets) per KV group of each half of the promoted-block pass: 128 waves, so a group that promotes K_max = 128 blocks still has about one block per wave
+constexpr int PROM_SPLITS = 16;             // workgroups (= partial sets) per KV group of each half of the promoted-block
+                                            // pass: 64 waves, about two blocks per wave for a group that promotes K_max = 128.
+                                            // With the 32 sets of the pass over all blocks the adaptive reduction then merges
+                                            // 64 sets, one trip of its head wave (measured: 32 per half, two trips, 3.6 us slower;
+                                            // 8 per half, 3.5 us slower: too few waves for the large unions)
 
 // Workspace of the adaptive path, shared by all layers (one decode step at a time).
 struct AdaptiveWs {
