@@ -29,6 +29,12 @@ struct SealArgs {
   int64_t n_new;
   int r;                // tokens in the trailing block before this append
   int layer, batch, n_kv;
+  // short appends that end on a block boundary: the kernel also stores the FP16 originals of the
+  // new tokens into the pinned Tier-2 arrays (null = Tier 2 is written elsewhere)
+  __half* t2_k;         // [heads][t2_cap][128]
+  __half* t2_v;
+  int64_t t2_cap;
+  int64_t len_before;
 };
 
 // Quotient x / d for the quantizers, where only  round-half-even(fl(x / d))  is needed (fl = the
@@ -100,6 +106,11 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
     const __half* src = i < a.r ? a.trail_v + (head * BLK + i) * D : a.v_in + (in_head + (i - a.r)) * D;
     const uint4 x0 = *reinterpret_cast<const uint4*>(src + g * VG);
     const uint4 x1 = *reinterpret_cast<const uint4*>(src + g * VG + 8);
+    if (a.t2_v != nullptr && i >= a.r) {
+      __half* dst = a.t2_v + (head * a.t2_cap + a.len_before + (i - a.r)) * D + g * VG;
+      *reinterpret_cast<uint4*>(dst) = x0;
+      *reinterpret_cast<uint4*>(dst + 8) = x1;
+    }
     const __half2* h0 = reinterpret_cast<const __half2*>(&x0);
     const __half2* h1 = reinterpret_cast<const __half2*>(&x1);
     float vf[VG];
@@ -155,8 +166,9 @@ __global__ __launch_bounds__(128) void seal_kernel(SealArgs a) {
 #pragma unroll
     for (int t = 0; t < BLK; ++t) {
       const int64_t i = i0 + t;
-      kf[t] = __half2float(i < a.r ? a.trail_k[(head * BLK + i) * D + c]
-                                   : a.k_in[(in_head + (i - a.r)) * D + c]);
+      const __half kh = i < a.r ? a.trail_k[(head * BLK + i) * D + c] : a.k_in[(in_head + (i - a.r)) * D + c];
+      kf[t] = __half2float(kh);
+      if (a.t2_k != nullptr && i >= a.r) a.t2_k[(head * a.t2_cap + a.len_before + (i - a.r)) * D + c] = kh;
     }
     float lo = kf[0], hi = kf[0];
 #pragma unroll
@@ -275,6 +287,13 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
     a.layer = layer;
     a.batch = bt;
     a.n_kv = hkv;
+    // an append that ends on a block boundary leaves nothing for the trailing block: its Tier-2
+    // stores ride on the seal launch and the second launch is saved
+    const bool t2_here = tier2_by_kernel && r_new == 0;
+    a.t2_k = t2_here ? c->t2_k : nullptr;
+    a.t2_v = t2_here ? c->t2_v : nullptr;
+    a.t2_cap = c->desc.max_tokens;
+    a.len_before = len_before;
     // grid.x is limited to 2^31-1 blocks; n_seal <= nb_cap is far below that
     hipLaunchKernelGGL(seal_kernel, dim3((unsigned)n_seal, hkv, bt), dim3(128), 0, st, a);
     CQA_HIP(hipGetLastError());
@@ -290,7 +309,7 @@ int32_t launch_seal(Cache* c, int layer, const __half* k_in, const __half* v_in,
     dst_first = 0;
     count = r_new;
   }
-  if (count > 0 || tier2_by_kernel) {
+  if (count > 0 || (tier2_by_kernel && n_seal == 0)) {
     hipLaunchKernelGGL(trail_kernel, dim3(hkv, bt), dim3(128), 0, st, k_in, v_in, c->trail_k,
                        c->trail_v, n_new, src_first, dst_first, count, layer, bt, hkv,
                        tier2_by_kernel ? c->t2_k : nullptr, tier2_by_kernel ? c->t2_v : nullptr,
