@@ -83,9 +83,15 @@ def test_t128k_sampled_heads_and_error_paths():
     oc.append(k, v)
     with GpuLayerCache(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.context + 64) as gc:
         gc.append(k, v)
-        compare(gc, oc, q, oracle.Tolerances(int8_query=True), "t128k", heads=[(0, 2), (0, 17), (0, 28)])
+        O1, c1, f1, _ = compare(gc, oc, q, oracle.Tolerances(int8_query=True), "t128k", heads=[(0, 2), (0, 17), (0, 28)])
         cqa = gc.cqa
         qd = gc.to_dev(q)
+        # the load hint (plain / non-temporal Tier-1 loads) does not change a bit in this mode either
+        for hint in (2, 1):
+            cqa.cqa_set_stream_hint(gc.h, hint)
+            O2, c2, f2 = gc.certified_decode(q, to_gpu_tol(cqa, oracle.Tolerances(int8_query=True)))
+            assert np.array_equal(O1, O2) and c1.tobytes() == c2.tobytes() and (f1 == f2).all(), ("hint", hint)
+        cqa.cqa_set_stream_hint(gc.h, 0)
         # the vector-ALU cross-check kernel does not have the mode
         cqa.cqa_set_kernel_variant(gc.h, 1)
         with pytest.raises(cqa.CqaError) as e:
